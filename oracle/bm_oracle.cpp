@@ -1,0 +1,274 @@
+// CPU oracle for one MoE layer's forward pass with buddy-expert substitution.
+//
+// TEST INFRASTRUCTURE ONLY.  This file is the slow, plain reference that the
+// tests, the smoke check and the benchmark's cpu_baseline leg compare the HIP
+// library against.  It shares no code with the HIP library and the product
+// path never calls it.
+//
+// Precision: inputs are fp32 arrays (bf16 workloads are widened exactly
+// before they get here); every sum, exponential and product is evaluated in
+// fp64; outputs are fp64.  The one place floating point decides an integer is
+// the top-k selection: logits are rounded to fp32 first, because fp32 is the
+// precision the device kernel holds its logits in.
+//
+// Parity pins (tests/test_oracle_*.py): routing against a library argsort and
+// softmax; the substitution against hand-worked cases of Algorithm 1, an
+// independent per-slot checker and the per-expert lookup-table form; the
+// permutation against a library stable sort; the layer output against a
+// brute-force dense evaluation of every expert masked by the gate matrix;
+// TAE against closed forms.  Unpinned by the paper: the error of the
+// substituted layer against the unsubstituted one (no bound is given).
+//
+// Every loop follows the order and notation of the passage it cites; there is
+// no blocking, fusion or reordering.  OpenMP splits the token loop only
+// (tokens are independent).
+
+#include <cmath>
+#include <cstdint>
+#include <cstring>
+#include <vector>
+
+extern "C" {
+
+// Section 3 "Notation and Preliminaries": router logits z(x) in R^E.
+//   z[t][e] = bias[e] + sum_j x[t][j] * w_router[e][j]
+// x [T][d], w_router [E][d], bias [E] or NULL, z [T][E].
+int bm_oracle_router_logits(int T, int d, int E, const float* x, const float* w_router,
+                            const float* bias, double* z) {
+#pragma omp parallel for schedule(static)
+    for (int t = 0; t < T; ++t) {
+        for (int e = 0; e < E; ++e) {
+            double acc = bias ? (double)bias[e] : 0.0;
+            for (int j = 0; j < d; ++j) acc += (double)x[(size_t)t * d + j] * (double)w_router[(size_t)e * d + j];
+            z[(size_t)t * E + e] = acc;
+        }
+    }
+    return 0;
+}
+
+// Section 3 "Notation and Preliminaries": p = softmax(z); S(x) = the k experts
+// of largest probability; p-tilde = p renormalised over S(x).
+// Slot 0 holds the largest logit; equal logits go to the lower expert index.
+// renorm != 0: w = p-tilde (sums to 1 over the K slots); renorm == 0: w = p.
+// ids [T][K], w [T][K].
+int bm_oracle_topk_gates(int T, int E, int K, int renorm, const double* z, int32_t* ids, double* w) {
+    if (K > E) return -1;
+#pragma omp parallel for schedule(static)
+    for (int t = 0; t < T; ++t) {
+        const double* zt = z + (size_t)t * E;
+        std::vector<float> z32(E);
+        std::vector<char> taken(E, 0);
+        for (int e = 0; e < E; ++e) z32[e] = (float)zt[e];
+        double zmax = zt[0];
+        for (int e = 1; e < E; ++e) if (zt[e] > zmax) zmax = zt[e];
+        double sum_all = 0.0;
+        for (int e = 0; e < E; ++e) sum_all += std::exp(zt[e] - zmax);
+        double sum_sel = 0.0;
+        for (int k = 0; k < K; ++k) {
+            int best = -1;
+            for (int e = 0; e < E; ++e) {
+                if (taken[e]) continue;
+                if (best < 0 || z32[e] > z32[best]) best = e;   // strict '>' keeps the lowest index on ties
+            }
+            taken[best] = 1;
+            ids[(size_t)t * K + k] = best;
+            double p = std::exp(zt[best] - zmax);
+            w[(size_t)t * K + k] = p;
+            sum_sel += p;
+        }
+        double denom = renorm ? sum_sel : sum_all;
+        for (int k = 0; k < K; ++k) w[(size_t)t * K + k] /= denom;
+    }
+    return 0;
+}
+
+// Section 3.1 Eq. 1: Token Activating Entropy of the renormalised top-k gates,
+//   TAE = -( sum_{i in S} p~_i log p~_i ) / log k,  in [0,1].
+// w [T][K] must be p-tilde (sum to 1 per token).  For K == 1 the entropy and
+// its normaliser are both 0; the value is defined as 0 here.
+int bm_oracle_tae(int T, int K, const double* w, double* tae) {
+    for (int t = 0; t < T; ++t) {
+        double h = 0.0;
+        for (int k = 0; k < K; ++k) {
+            double p = w[(size_t)t * K + k];
+            if (p > 0.0) h -= p * std::log(p);
+        }
+        tae[t] = (K > 1) ? h / std::log((double)K) : 0.0;
+    }
+    return 0;
+}
+
+// Section 4, Algorithm 1 (BuddySubstitute): per token, walk the K slots in
+// order; a selected expert that is not resident is replaced by the first
+// entry b of its buddy row, among ranks 1..H, that is resident and (unique
+// mode) not yet in the token's set U_t; U_t starts as the token's K selected
+// experts and grows by every accepted buddy.
+//
+// Readings where the algorithm is silent:
+//  * unique == 0 drops the "b not in U_t" test: the substitute is the first
+//    resident entry of the row, whatever the token already holds.
+//  * a table entry outside [0,E) (the -1 padding of short rows) is never
+//    resident; the scan continues past it.
+//  * no acceptable buddy among the first H entries: the slot is dropped
+//    (Section 3.1, the fallback that skips the expert): id -1, gate weight 0,
+//    the other slots' weights are left as they are.
+//  * a substitute inherits the gate weight of the slot it fills.
+// resident [E] (0/1 bytes), table [E][R], ids_in/ids_out [T][K] (may alias),
+// w [T][K] in/out (nullable), stats[3] = {misses, substituted, dropped}.
+int bm_oracle_buddy_remap(int T, int K, int E, int R, int H, int unique, const uint8_t* resident,
+                          const int32_t* table, const int32_t* ids_in, int32_t* ids_out, double* w,
+                          int64_t* stats) {
+    if (H > R || H < 0) return -1;
+    int64_t n_miss = 0, n_sub = 0, n_drop = 0;
+    for (int t = 0; t < T; ++t) {
+        std::vector<char> in_u(E, 0);                       // U_t
+        for (int k = 0; k < K; ++k) {
+            int32_t e = ids_in[(size_t)t * K + k];
+            ids_out[(size_t)t * K + k] = e;                  // S' <- S
+            if (e >= 0 && e < E) in_u[e] = 1;
+        }
+        for (int k = 0; k < K; ++k) {
+            int32_t e = ids_out[(size_t)t * K + k];
+            if (e < 0 || e >= E) {                           // not a routed expert: nothing to run
+                ids_out[(size_t)t * K + k] = -1;
+                if (w) w[(size_t)t * K + k] = 0.0;
+                continue;
+            }
+            if (resident[e]) continue;
+            ++n_miss;
+            int32_t chosen = -1;
+            for (int r = 0; r < H; ++r) {
+                int32_t b = table[(size_t)e * R + r];
+                if (b < 0 || b >= E) continue;
+                if (resident[b] && !(unique && in_u[b])) { chosen = b; break; }
+            }
+            if (chosen >= 0) {
+                ids_out[(size_t)t * K + k] = chosen;
+                in_u[chosen] = 1;
+                ++n_sub;
+            } else {
+                ids_out[(size_t)t * K + k] = -1;
+                if (w) w[(size_t)t * K + k] = 0.0;
+                ++n_drop;
+            }
+        }
+    }
+    if (stats) { stats[0] = n_miss; stats[1] = n_sub; stats[2] = n_drop; }
+    return 0;
+}
+
+// Grouping of the surviving assignments by expert (Section 2.2: each token's
+// selected experts run and their outputs are aggregated; the grouping itself
+// is the execution order of this build): a stable counting sort of the flat
+// assignment indices a = t*K + k with ids[a] >= 0, keyed by ids[a].
+//   offsets [E+1]: offsets[e] = first position of expert e, offsets[E] = live count
+//   perm [T*K]: perm[pos] = a (entries past the live count are -1)
+//   inv_perm [T*K]: inv_perm[a] = pos, or -1 for a dropped assignment
+int bm_oracle_permute(int T, int K, int E, const int32_t* ids, int32_t* offsets, int32_t* perm,
+                      int32_t* inv_perm) {
+    const int A = T * K;
+    std::vector<int32_t> count(E, 0);
+    for (int a = 0; a < A; ++a) if (ids[a] >= 0) ++count[ids[a]];
+    offsets[0] = 0;
+    for (int e = 0; e < E; ++e) offsets[e + 1] = offsets[e] + count[e];
+    std::vector<int32_t> cursor(offsets, offsets + E);
+    for (int a = 0; a < A; ++a) { perm[a] = -1; inv_perm[a] = -1; }
+    for (int a = 0; a < A; ++a) {
+        if (ids[a] < 0) continue;
+        int32_t pos = cursor[ids[a]]++;
+        perm[pos] = a;
+        inv_perm[a] = pos;
+    }
+    return 0;
+}
+
+static inline double silu(double a) { return a / (1.0 + std::exp(-a)); }
+
+// One SwiGLU expert on one token (the expert FFN of Section 2.1, in the gated
+// form the workload configs name):
+//   g = W_g x, u = W_u x, h = silu(g) * u, out = W_d h
+// w_gate, w_up [F][d]; w_down [d][F]; x [d]; out [d].
+int bm_oracle_expert_ffn(int d, int F, const float* w_gate, const float* w_up, const float* w_down,
+                         const float* x, double* out) {
+    std::vector<double> h(F);
+    for (int f = 0; f < F; ++f) {
+        double g = 0.0, u = 0.0;
+        for (int j = 0; j < d; ++j) {
+            g += (double)w_gate[(size_t)f * d + j] * (double)x[j];
+            u += (double)w_up[(size_t)f * d + j] * (double)x[j];
+        }
+        h[f] = silu(g) * u;
+    }
+    for (int i = 0; i < d; ++i) {
+        double acc = 0.0;
+        for (int f = 0; f < F; ++f) acc += (double)w_down[(size_t)i * F + f] * h[f];
+        out[i] = acc;
+    }
+    return 0;
+}
+
+// Expert execution and aggregation (Section 2.2) over rewritten ids:
+//   y[t] = sum_k w[t][k] * FFN_{ids[t][k]}(x[t])   (slots with id -1 skipped)
+//        + sum_{s < n_shared} FFN^shared_s(x[t])   (always on, weight 1)
+// w_gate/w_up [E][F][d], w_down [E][d][F]; shared stacks likewise; y [T][d].
+int bm_oracle_experts_combine(int T, int d, int E, int F, int K, int n_shared, const float* x,
+                              const int32_t* ids, const double* w, const float* w_gate,
+                              const float* w_up, const float* w_down, const float* ws_gate,
+                              const float* ws_up, const float* ws_down, double* y) {
+    const size_t fd = (size_t)F * d;
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int t = 0; t < T; ++t) {
+        std::vector<double> o(d);
+        double* yt = y + (size_t)t * d;
+        for (int i = 0; i < d; ++i) yt[i] = 0.0;
+        for (int k = 0; k < K; ++k) {
+            int32_t e = ids[(size_t)t * K + k];
+            if (e < 0) continue;
+            bm_oracle_expert_ffn(d, F, w_gate + e * fd, w_up + e * fd, w_down + e * fd, x + (size_t)t * d, o.data());
+            double wk = w[(size_t)t * K + k];
+            for (int i = 0; i < d; ++i) yt[i] += wk * o[i];
+        }
+        for (int s = 0; s < n_shared; ++s) {
+            bm_oracle_expert_ffn(d, F, ws_gate + s * fd, ws_up + s * fd, ws_down + s * fd, x + (size_t)t * d, o.data());
+            for (int i = 0; i < d; ++i) yt[i] += o[i];
+        }
+    }
+    return 0;
+}
+
+// The whole layer: logits -> gates -> Algorithm 1 -> experts + aggregation.
+// Optional outputs (any may be NULL): ids, ids_remapped [T][K], w_out [T][K]
+// (after drops), stats[3].
+int bm_oracle_moe_forward(int T, int d, int E, int F, int K, int n_shared, int R, int H, int renorm,
+                          int unique, const float* x, const float* w_router, const float* bias,
+                          const float* w_gate, const float* w_up, const float* w_down,
+                          const float* ws_gate, const float* ws_up, const float* ws_down,
+                          const uint8_t* resident, const int32_t* table, double* y, int32_t* ids_out,
+                          int32_t* ids_remapped_out, double* w_out, int64_t* stats) {
+    std::vector<double> z((size_t)T * E), w((size_t)T * K);
+    std::vector<int32_t> ids((size_t)T * K), ids2((size_t)T * K);
+    int rc = bm_oracle_router_logits(T, d, E, x, w_router, bias, z.data());
+    if (rc) return rc;
+    rc = bm_oracle_topk_gates(T, E, K, renorm, z.data(), ids.data(), w.data());
+    if (rc) return rc;
+    rc = bm_oracle_buddy_remap(T, K, E, R, H, unique, resident, table, ids.data(), ids2.data(), w.data(), stats);
+    if (rc) return rc;
+    rc = bm_oracle_experts_combine(T, d, E, F, K, n_shared, x, ids2.data(), w.data(), w_gate, w_up, w_down,
+                                   ws_gate, ws_up, ws_down, y);
+    if (rc) return rc;
+    if (ids_out) std::memcpy(ids_out, ids.data(), sizeof(int32_t) * ids.size());
+    if (ids_remapped_out) std::memcpy(ids_remapped_out, ids2.data(), sizeof(int32_t) * ids2.size());
+    if (w_out) std::memcpy(w_out, w.data(), sizeof(double) * w.size());
+    return 0;
+}
+
+int bm_oracle_num_threads(void);
+
+}  // extern "C"
+
+#ifdef _OPENMP
+#include <omp.h>
+extern "C" int bm_oracle_num_threads(void) { return omp_get_max_threads(); }
+#else
+extern "C" int bm_oracle_num_threads(void) { return 1; }
+#endif
