@@ -1,0 +1,172 @@
+/* buddymoe.h - C ABI of the MI355X (gfx950) library for one Mixture-of-Experts
+ * layer's forward pass with buddy-expert substitution (BuddyMoE).
+ *
+ * The pass: router logits -> softmax / top-k gates -> substitution of every
+ * selected expert that is not resident in device memory by its highest-ranked
+ * resident buddy (Section 4, Algorithm 1) -> grouping of the surviving
+ * (token, slot) assignments by expert -> SwiGLU expert FFN over resident
+ * experts only -> gate-weighted aggregation (+ always-on shared experts).
+ *
+ * Conventions
+ *  - Plain C.  No hidden allocation, no global state, no host synchronisation:
+ *    every call enqueues its kernels on `stream` (a hipStream_t passed as
+ *    void*; NULL = the default stream) and returns.
+ *  - "device" pointers are HIP device memory owned by the caller, row-major,
+ *    contiguous, 16-byte aligned.  The library never frees or retains them.
+ *    "host" pointers are ordinary memory read during the call.
+ *  - T tokens, d hidden size, E routed experts, F expert FFN width, K experts
+ *    per token, R buddy-table width, H search limit (0 <= H <= R),
+ *    A = T*K assignments.
+ *  - Return value: BM_OK (0) or a negative bm_status.  Shape and pointer
+ *    errors are detected on the host before anything is launched; no kernel
+ *    faults on arbitrary table or id contents (ids outside [0,E) are treated
+ *    as "not resident").
+ */
+#ifndef BUDDYMOE_H
+#define BUDDYMOE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    BM_OK = 0,
+    BM_ERR_NULL = -1,       /* a required pointer is NULL                           */
+    BM_ERR_SHAPE = -2,      /* K>E, H>R, E or K above the supported maximum, d or F
+                               not a multiple of 32 for bf16, non-positive sizes    */
+    BM_ERR_DTYPE = -3,      /* dtype is neither BM_F32 nor BM_BF16                  */
+    BM_ERR_WORKSPACE = -4,  /* workspace NULL, misaligned or smaller than required  */
+    BM_ERR_BAD_TABLE = -5,  /* bm_validate_tables: entry outside [-1,E) or == row   */
+    BM_ERR_HIP = -6         /* a kernel launch failed (hipGetLastError != success)  */
+} bm_status;
+
+typedef enum { BM_F32 = 0, BM_BF16 = 1 } bm_dtype;
+
+enum {
+    BM_RENORM_TOPK  = 1u << 0, /* gate weights are the softmax renormalised over the K
+                                  selected experts (p-tilde of Section 3, "Notation");
+                                  off: the plain softmax probabilities               */
+    BM_REMAP_UNIQUE = 1u << 1, /* Algorithm 1's "b not in U_t" test: a buddy already
+                                  held by the token is skipped.  Off: the substitute
+                                  is the first resident entry of the buddy row        */
+    BM_Y_F32        = 1u << 2  /* bm_moe_forward writes y as fp32 whatever dtype is   */
+};
+
+/* Limits of this build. */
+#define BM_MAX_E 256
+#define BM_MAX_K 32
+#define BM_MAX_R 32
+
+typedef struct {
+    int32_t T, d, E, F, K;
+    int32_t n_shared;   /* always-on experts added with weight 1 (0 for none)        */
+    int32_t R, H;       /* buddy-table width and search limit                         */
+    int32_t dtype;      /* bm_dtype of x, all weights and (unless BM_Y_F32) y         */
+    uint32_t flags;     /* BM_* flag bits                                             */
+} bm_layer_desc;
+
+/* Weights, all device pointers in `dtype`.  The reduction dimension is
+ * contiguous.  Pointers cover all E experts, but rows of an expert that is not
+ * resident are never read. */
+typedef struct {
+    const void *w_router;      /* [E][d]                                  */
+    const float *router_bias;  /* [E] fp32, or NULL                       */
+    const void *w_gate;        /* [E][F][d]                               */
+    const void *w_up;          /* [E][F][d]                               */
+    const void *w_down;        /* [E][d][F]                               */
+    const void *ws_gate;       /* [n_shared][F][d], NULL when n_shared==0 */
+    const void *ws_up;         /* [n_shared][F][d]                        */
+    const void *ws_down;       /* [n_shared][d][F]                        */
+} bm_weights;
+
+typedef struct {
+    int32_t n_miss;         /* selected experts that were not resident  */
+    int32_t n_substituted;  /* of those, replaced by a resident buddy   */
+    int32_t n_dropped;      /* of those, dropped (no acceptable buddy)  */
+} bm_remap_stats;
+
+/* Optional device outputs of bm_moe_forward; any member may be NULL. */
+typedef struct {
+    int32_t *ids;            /* [T][K] router's choice                      */
+    int32_t *ids_remapped;   /* [T][K] after substitution, -1 = dropped     */
+    float *w;                /* [T][K] gate weights after drops             */
+    int32_t *offsets;        /* [E+1]                                       */
+    int32_t *perm;           /* [T*K]                                       */
+    int32_t *inv_perm;       /* [T*K]                                       */
+    bm_remap_stats *stats;   /* one struct                                  */
+} bm_debug_out;
+
+/* Router and gates (Section 3, "Notation and Preliminaries"; Section 2.2):
+ *   z[t][e] = bias[e] + sum_j x[t][j] * w_router[e][j]      (fp32 accumulation)
+ *   p = softmax(z);  ids[t][0..K) = the K experts of largest z, slot 0 the
+ *   largest, equal logits to the lower index;  w[t][k] = p of slot k,
+ *   renormalised over the K slots when BM_RENORM_TOPK is set.
+ * x [T][d] dtype (device), w_router [E][d] dtype (device), bias [E] fp32 or
+ * NULL (device), ids [T][K] int32 and w [T][K] fp32 (device, written).
+ * Uses T, d, E, K, dtype, flags of desc.  T == 0 is a no-op. */
+int bm_route_topk(const bm_layer_desc *desc, const void *x, const void *w_router,
+                  const float *bias, int32_t *ids, float *w, void *stream);
+
+/* Buddy substitution (Section 4, Algorithm 1; fallback of Section 3.1):
+ * per token, slots in order k = 0..K-1; a slot whose expert e is resident is
+ * kept; otherwise it takes the first b = buddy_table[e][r], r < H, that is in
+ * [0,E), resident and - with BM_REMAP_UNIQUE - not in the token's set U_t
+ * (the token's K input ids plus the buddies accepted at earlier slots).  If
+ * none qualifies the slot is dropped: id -1 and, when w is given, w = 0 (the
+ * other slots' weights are not renormalised).  A substitute keeps the slot's
+ * gate weight.  Input ids outside [0,E) come out as -1 / w = 0.
+ * residency_bitmap: ceil(E/64) uint64 words (device), expert e resident iff
+ *   bit (e % 64) of word (e / 64) is set.
+ * buddy_table [E][R] int32 (device), best buddy first, short rows padded -1.
+ * ids_in [T][K] (device); ids_out [T][K] (device, may alias ids_in);
+ * w [T][K] fp32 in/out (device, nullable); stats (device, nullable, written).
+ * Uses T, E, K, R, H, flags of desc. */
+int bm_buddy_remap(const bm_layer_desc *desc, const uint64_t *residency_bitmap,
+                   const int32_t *buddy_table, const int32_t *ids_in, int32_t *ids_out,
+                   float *w, bm_remap_stats *stats, void *stream);
+
+/* Grouping of the surviving assignments by expert, the execution order of the
+ * expert FFNs (Section 2.2: the selected experts run, their outputs are
+ * aggregated): a stable counting sort of the flat indices a = t*K + k with
+ * ids[a] >= 0, keyed by ids[a].
+ *   offsets [E+1]: first position of each expert, offsets[E] = live count
+ *   perm [T*K]: perm[pos] = a for pos < live count, -1 after
+ *   inv_perm [T*K]: position of assignment a, -1 if dropped
+ * All device int32.  workspace: device scratch of at least
+ * bm_workspace_bytes(desc) bytes, 256-byte aligned.  Uses T, E, K of desc. */
+int bm_permute_by_expert(const bm_layer_desc *desc, const int32_t *ids_remapped,
+                         int32_t *offsets, int32_t *perm, int32_t *inv_perm,
+                         void *workspace, size_t workspace_bytes, void *stream);
+
+/* The whole layer (Sections 2.2, 3 and 4 as above) plus expert execution:
+ *   for every surviving slot: h = silu(W_g[e] x) * (W_u[e] x), o = W_d[e] h
+ *   y[t] = sum_k w[t][k] * o[t][k] + sum_{s<n_shared} FFN^shared_s(x[t])
+ * x [T][d] dtype (device), y [T][d] dtype or fp32 with BM_Y_F32 (device,
+ * written; must not alias x).  workspace as above.  dbg may be NULL.
+ * bf16: MFMA with fp32 accumulation, h and o held in bf16 between the two
+ * projections; fp32: fp32 FMA throughout. */
+int bm_moe_forward(const bm_layer_desc *desc, const void *x, const bm_weights *weights,
+                   const uint64_t *residency_bitmap, const int32_t *buddy_table, void *y,
+                   void *workspace, size_t workspace_bytes, const bm_debug_out *dbg,
+                   void *stream);
+
+/* Bytes of device scratch bm_moe_forward / bm_permute_by_expert need for
+ * this desc (host, pure function of desc; 0 if desc is invalid). */
+size_t bm_workspace_bytes(const bm_layer_desc *desc);
+
+/* Host-side check of a residency bitmap and buddy table (host pointers):
+ * every table entry is -1 or in [0,E) and differs from its row index
+ * (Eq. 4: an expert is not its own buddy).  BM_OK or BM_ERR_BAD_TABLE. */
+int bm_validate_tables(const bm_layer_desc *desc, const uint64_t *bitmap_host,
+                       const int32_t *table_host);
+
+/* Static string for a bm_status. */
+const char *bm_strerror(int status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* BUDDYMOE_H */

@@ -1,0 +1,289 @@
+// C ABI of the library: argument checks, workspace carving, kernel sequencing.
+// Nothing here allocates, synchronises or keeps state between calls.
+#include "bm_kernels.h"
+
+namespace {
+
+using namespace bm;
+
+constexpr size_t ALIGN = 256;
+constexpr int MAX_SHARED = 8;
+
+size_t align_up(size_t v) { return (v + ALIGN - 1) / ALIGN * ALIGN; }
+
+// Workspace carving: a pure function of desc.
+struct Layout {
+    size_t ids, ids2, w, tile_counts, tile_base, tile_stats, offsets, perm, inv_perm, row_token;
+    size_t mt_group, mt_row0, n_mtiles, stats, h, o, total;
+    int n_tiles, rows_max, mtiles_max;
+};
+
+int check_desc(const bm_layer_desc *d, bool need_ffn) {
+    if (!d) return BM_ERR_NULL;
+    if (d->dtype != BM_F32 && d->dtype != BM_BF16) return BM_ERR_DTYPE;
+    if (d->T < 0 || d->E <= 0 || d->K <= 0 || d->d <= 0) return BM_ERR_SHAPE;
+    if (d->K > d->E || d->E > BM_MAX_E || d->K > BM_MAX_K) return BM_ERR_SHAPE;
+    if ((long long)d->T * d->K > (1ll << 30)) return BM_ERR_SHAPE;
+    if (d->dtype == BM_BF16 && (d->d % 32)) return BM_ERR_SHAPE;
+    if (need_ffn) {
+        if (d->F <= 0 || d->n_shared < 0 || d->n_shared > MAX_SHARED) return BM_ERR_SHAPE;
+        if (d->dtype == BM_BF16 && (d->F % 32)) return BM_ERR_SHAPE;
+        if (d->dtype == BM_F32 && (d->F > 16000 || d->d > 16000)) return BM_ERR_SHAPE;
+    }
+    return BM_OK;
+}
+
+int check_remap_desc(const bm_layer_desc *d) {
+    if (d->R < 0 || d->R > BM_MAX_R || d->H < 0 || d->H > d->R) return BM_ERR_SHAPE;
+    return BM_OK;
+}
+
+Layout make_layout(const bm_layer_desc *d) {
+    Layout L{};
+    const size_t A = (size_t)d->T * d->K;
+    const int n_shared = d->n_shared > 0 ? d->n_shared : 0;
+    const int G = d->E + n_shared;
+    L.n_tiles = (d->T + TILE_T - 1) / TILE_T;
+    L.rows_max = (int)(A + (size_t)n_shared * d->T);
+    const int BM = gemm_bf16_bm();
+    L.mtiles_max = L.rows_max / BM + G;
+    const size_t esz = d->dtype == BM_BF16 ? 2 : 4;
+    size_t off = 0;
+    auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes); return o; };
+    L.ids = take(A * 4);
+    L.ids2 = take(A * 4);
+    L.w = take(A * 4);
+    L.tile_counts = take((size_t)L.n_tiles * d->E * 4);
+    L.tile_base = take((size_t)L.n_tiles * d->E * 4);
+    L.tile_stats = take((size_t)L.n_tiles * 16);
+    L.offsets = take((size_t)(G + 1) * 4);
+    L.perm = take(A * 4);
+    L.inv_perm = take(A * 4);
+    L.row_token = take((size_t)L.rows_max * 4);
+    L.mt_group = take((size_t)L.mtiles_max * 4);
+    L.mt_row0 = take((size_t)L.mtiles_max * 4);
+    L.n_mtiles = take(16);
+    L.stats = take(16);
+    const size_t F = d->F > 0 ? d->F : 0;
+    L.h = take((size_t)L.rows_max * F * esz);
+    L.o = take((size_t)L.rows_max * d->d * esz);
+    L.total = off;
+    return L;
+}
+
+template <typename T>
+T *at(void *ws, size_t off) { return reinterpret_cast<T *>(static_cast<char *>(ws) + off); }
+
+int check_ws(const bm_layer_desc *d, void *ws, size_t bytes, Layout &L) {
+    L = make_layout(d);
+    if (!ws || (reinterpret_cast<uintptr_t>(ws) % ALIGN) || bytes < L.total) return BM_ERR_WORKSPACE;
+    return BM_OK;
+}
+
+__global__ void copy_ints_kernel(const int32_t *src, int32_t *dst, size_t n) {
+    const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) dst[i] = src[i];
+}
+
+void copy_ints(const void *src, void *dst, size_t n, hipStream_t st) {
+    if (n) hipLaunchKernelGGL(copy_ints_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st,
+                              static_cast<const int32_t *>(src), static_cast<int32_t *>(dst), n);
+}
+
+}  // namespace
+
+extern "C" {
+
+const char *bm_strerror(int status) {
+    switch (status) {
+        case BM_OK: return "ok";
+        case BM_ERR_NULL: return "a required pointer is NULL";
+        case BM_ERR_SHAPE: return "unsupported or inconsistent shape";
+        case BM_ERR_DTYPE: return "unknown dtype";
+        case BM_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
+        case BM_ERR_BAD_TABLE: return "buddy table entry out of range or equal to its row";
+        case BM_ERR_HIP: return "kernel launch failed";
+        default: return "unknown status";
+    }
+}
+
+size_t bm_workspace_bytes(const bm_layer_desc *desc) {
+    if (check_desc(desc, false) != BM_OK) return 0;
+    return make_layout(desc).total;
+}
+
+int bm_validate_tables(const bm_layer_desc *desc, const uint64_t *bitmap_host, const int32_t *table_host) {
+    if (!desc || !bitmap_host || !table_host) return BM_ERR_NULL;
+    if (desc->E <= 0 || desc->E > BM_MAX_E) return BM_ERR_SHAPE;
+    int rc = check_remap_desc(desc);
+    if (rc) return rc;
+    for (int i = 0; i < desc->E; ++i)
+        for (int r = 0; r < desc->R; ++r) {
+            const int32_t b = table_host[(size_t)i * desc->R + r];
+            if (b < -1 || b >= desc->E || b == i) return BM_ERR_BAD_TABLE;
+        }
+    // bits past E must be clear
+    const int words = (desc->E + 63) / 64;
+    if (desc->E % 64) {
+        const uint64_t tail = bitmap_host[words - 1] >> (desc->E % 64);
+        if (tail) return BM_ERR_BAD_TABLE;
+    }
+    return BM_OK;
+}
+
+int bm_route_topk(const bm_layer_desc *desc, const void *x, const void *w_router, const float *bias,
+                  int32_t *ids, float *w, void *stream) {
+    int rc = check_desc(desc, false);
+    if (rc) return rc;
+    if (desc->T == 0) return BM_OK;
+    if (!x || !w_router || !ids || !w) return BM_ERR_NULL;
+    FrontParams p{};
+    p.x = x; p.wr = w_router; p.bias = bias;
+    p.T = desc->T; p.d = desc->d; p.E = desc->E; p.K = desc->K; p.R = 0; p.H = 0;
+    p.flags = desc->flags;
+    p.ids = ids; p.w = w;
+    p.bitmap = nullptr;
+    return launch_front(p, desc->dtype, static_cast<hipStream_t>(stream)) ? BM_ERR_HIP : BM_OK;
+}
+
+int bm_buddy_remap(const bm_layer_desc *desc, const uint64_t *residency_bitmap, const int32_t *buddy_table,
+                   const int32_t *ids_in, int32_t *ids_out, float *w, bm_remap_stats *stats, void *stream) {
+    if (!desc) return BM_ERR_NULL;
+    if (desc->T < 0 || desc->E <= 0 || desc->K <= 0 || desc->E > BM_MAX_E || desc->K > BM_MAX_K) return BM_ERR_SHAPE;
+    int rc = check_remap_desc(desc);
+    if (rc) return rc;
+    if (!residency_bitmap || !ids_in || !ids_out || (!buddy_table && desc->R > 0)) return BM_ERR_NULL;
+    RemapParams p{};
+    p.T = desc->T; p.K = desc->K; p.E = desc->E; p.R = desc->R; p.H = desc->H;
+    p.unique = (desc->flags & BM_REMAP_UNIQUE) ? 1 : 0;
+    p.bitmap = residency_bitmap; p.table = buddy_table;
+    p.ids_in = ids_in; p.ids_out = ids_out; p.w = w;
+    p.stats = reinterpret_cast<int32_t *>(stats);
+    return launch_remap(p, static_cast<hipStream_t>(stream)) ? BM_ERR_HIP : BM_OK;
+}
+
+int bm_permute_by_expert(const bm_layer_desc *desc, const int32_t *ids_remapped, int32_t *offsets,
+                         int32_t *perm, int32_t *inv_perm, void *workspace, size_t workspace_bytes,
+                         void *stream) {
+    if (!desc) return BM_ERR_NULL;
+    if (desc->T < 0 || desc->E <= 0 || desc->K <= 0 || desc->E > BM_MAX_E || desc->K > BM_MAX_K) return BM_ERR_SHAPE;
+    if ((long long)desc->T * desc->K > (1ll << 30)) return BM_ERR_SHAPE;
+    if (!ids_remapped || !offsets || !perm || !inv_perm) return BM_ERR_NULL;
+    bm_layer_desc d2 = *desc;
+    d2.n_shared = 0;
+    Layout L;
+    int rc = check_ws(&d2, workspace, workspace_bytes, L);
+    if (rc) return rc;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    int err = launch_count(ids_remapped, d2.T, d2.K, d2.E, at<int32_t>(workspace, L.tile_counts), st);
+    ScanParams sp{};
+    sp.T = d2.T; sp.E = d2.E; sp.n_shared = 0; sp.n_tiles = L.n_tiles; sp.BM = gemm_bf16_bm();
+    sp.tile_counts = at<int32_t>(workspace, L.tile_counts);
+    sp.tile_base = at<int32_t>(workspace, L.tile_base);
+    sp.tile_stats = nullptr;
+    sp.offsets = offsets;
+    sp.mt_group = at<int32_t>(workspace, L.mt_group);
+    sp.mt_row0 = at<int32_t>(workspace, L.mt_row0);
+    sp.n_mtiles = at<int32_t>(workspace, L.n_mtiles);
+    sp.stats = nullptr;
+    err |= launch_scan(sp, st);
+    ScatterParams cp{};
+    cp.T = d2.T; cp.K = d2.K; cp.E = d2.E; cp.n_shared = 0;
+    cp.ids = ids_remapped; cp.offsets = offsets; cp.tile_base = sp.tile_base;
+    cp.perm = perm; cp.inv_perm = inv_perm; cp.row_token = nullptr;
+    err |= launch_scatter(cp, st);
+    return err ? BM_ERR_HIP : BM_OK;
+}
+
+int bm_moe_forward(const bm_layer_desc *desc, const void *x, const bm_weights *wt,
+                   const uint64_t *residency_bitmap, const int32_t *buddy_table, void *y, void *workspace,
+                   size_t workspace_bytes, const bm_debug_out *dbg, void *stream) {
+    int rc = check_desc(desc, true);
+    if (rc) return rc;
+    rc = check_remap_desc(desc);
+    if (rc) return rc;
+    if (desc->T == 0) return BM_OK;
+    if (!x || !wt || !residency_bitmap || !y || (!buddy_table && desc->R > 0)) return BM_ERR_NULL;
+    if (!wt->w_router || !wt->w_gate || !wt->w_up || !wt->w_down) return BM_ERR_NULL;
+    if (desc->n_shared > 0 && (!wt->ws_gate || !wt->ws_up || !wt->ws_down)) return BM_ERR_NULL;
+    Layout L;
+    rc = check_ws(desc, workspace, workspace_bytes, L);
+    if (rc) return rc;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    void *ws = workspace;
+    const int T = desc->T, K = desc->K, E = desc->E, G = E + desc->n_shared;
+    const bool bf16 = desc->dtype == BM_BF16;
+    int err = 0;
+
+    // 1. router, gates, substitution, per-tile histograms
+    FrontParams fp{};
+    fp.x = x; fp.wr = wt->w_router; fp.bias = wt->router_bias;
+    fp.T = T; fp.d = desc->d; fp.E = E; fp.K = K; fp.R = desc->R; fp.H = desc->H; fp.flags = desc->flags;
+    fp.ids = at<int32_t>(ws, L.ids); fp.w = at<float>(ws, L.w);
+    fp.bitmap = residency_bitmap; fp.table = buddy_table;
+    fp.ids2 = at<int32_t>(ws, L.ids2);
+    fp.tile_counts = at<int32_t>(ws, L.tile_counts);
+    fp.tile_stats = at<int32_t>(ws, L.tile_stats);
+    err |= launch_front(fp, desc->dtype, st);
+
+    // 2. offsets, tile bases, row-tile table, statistics
+    ScanParams sp{};
+    sp.T = T; sp.E = E; sp.n_shared = desc->n_shared; sp.n_tiles = L.n_tiles; sp.BM = gemm_bf16_bm();
+    sp.tile_counts = fp.tile_counts; sp.tile_base = at<int32_t>(ws, L.tile_base);
+    sp.tile_stats = fp.tile_stats;
+    sp.offsets = at<int32_t>(ws, L.offsets);
+    sp.mt_group = at<int32_t>(ws, L.mt_group); sp.mt_row0 = at<int32_t>(ws, L.mt_row0);
+    sp.n_mtiles = at<int32_t>(ws, L.n_mtiles);
+    sp.stats = at<int32_t>(ws, L.stats);
+    err |= launch_scan(sp, st);
+
+    // 3. stable placement
+    ScatterParams cp{};
+    cp.T = T; cp.K = K; cp.E = E; cp.n_shared = desc->n_shared;
+    cp.ids = fp.ids2; cp.offsets = sp.offsets; cp.tile_base = sp.tile_base;
+    cp.perm = at<int32_t>(ws, L.perm); cp.inv_perm = at<int32_t>(ws, L.inv_perm);
+    cp.row_token = at<int32_t>(ws, L.row_token);
+    err |= launch_scatter(cp, st);
+
+    // 4. gate/up projection + SwiGLU, 5. down projection
+    GemmParams gp{};
+    gp.a = x; gp.row_map = cp.row_token;
+    gp.b0 = wt->w_gate; gp.b1 = wt->w_up; gp.sb0 = wt->ws_gate; gp.sb1 = wt->ws_up;
+    gp.c = at<void>(ws, L.h);
+    gp.N = desc->F; gp.Kd = desc->d; gp.E = E; gp.n_groups = G; gp.max_mtiles = L.mtiles_max;
+    gp.mt_group = sp.mt_group; gp.mt_row0 = sp.mt_row0; gp.n_mtiles = sp.n_mtiles; gp.offsets = sp.offsets;
+    GemmParams dp = gp;
+    dp.a = gp.c; dp.row_map = nullptr;
+    dp.b0 = wt->w_down; dp.b1 = nullptr; dp.sb0 = wt->ws_down; dp.sb1 = nullptr;
+    dp.c = at<void>(ws, L.o);
+    dp.N = desc->d; dp.Kd = desc->F;
+    if (bf16) {
+        err |= launch_gateup_bf16(gp, st);
+        err |= launch_down_bf16(dp, st);
+    } else {
+        err |= launch_gateup_f32(gp, L.rows_max, st);
+        err |= launch_down_f32(dp, L.rows_max, st);
+    }
+
+    // 6. aggregation
+    CombineParams mp{};
+    mp.T = T; mp.d = desc->d; mp.K = K; mp.E = E; mp.n_shared = desc->n_shared;
+    mp.o = dp.c; mp.w = fp.w; mp.inv_perm = cp.inv_perm; mp.offsets = sp.offsets;
+    mp.y = y; mp.y_f32 = (!bf16 || (desc->flags & BM_Y_F32)) ? 1 : 0;
+    err |= launch_combine(mp, desc->dtype, st);
+
+    if (dbg) {
+        const size_t A = (size_t)T * K;
+        if (dbg->ids) copy_ints(fp.ids, dbg->ids, A, st);
+        if (dbg->ids_remapped) copy_ints(fp.ids2, dbg->ids_remapped, A, st);
+        if (dbg->w) copy_ints(fp.w, dbg->w, A, st);
+        if (dbg->offsets) copy_ints(sp.offsets, dbg->offsets, (size_t)E + 1, st);
+        if (dbg->perm) copy_ints(cp.perm, dbg->perm, A, st);
+        if (dbg->inv_perm) copy_ints(cp.inv_perm, dbg->inv_perm, A, st);
+        if (dbg->stats) copy_ints(sp.stats, dbg->stats, 3, st);
+        if (hipGetLastError() != hipSuccess) err = 1;
+    }
+    return err ? BM_ERR_HIP : BM_OK;
+}
+
+}  // extern "C"

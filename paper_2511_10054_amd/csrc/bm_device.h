@@ -1,0 +1,71 @@
+// Device-side helpers shared by the gfx950 kernels: bf16 storage, wave64
+// reductions, MFMA operand types.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace bm {
+
+constexpr int WAVE = 64;
+constexpr int TILE_T = 32;      // tokens per front-end tile (one MFMA row block)
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;   // one 16-byte piece
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+
+__device__ __forceinline__ float bf16_to_f32(uint16_t b) {
+    return __builtin_bit_cast(float, (uint32_t)b << 16);
+}
+
+// round-to-nearest-even, NaN kept quiet
+__device__ __forceinline__ uint16_t f32_to_bf16(float f) {
+    uint32_t u = __builtin_bit_cast(uint32_t, f);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x40u);
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return (uint16_t)(u >> 16);
+}
+
+__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
+    return (uint32_t)f32_to_bf16(lo) | ((uint32_t)f32_to_bf16(hi) << 16);
+}
+
+__device__ __forceinline__ bf16x8 as_bf16x8(u32x4 v) { return __builtin_bit_cast(bf16x8, v); }
+
+// Loads and stores through an explicit global-memory pointer.  Pointers that
+// arrive inside a by-value parameter struct are generic to the compiler; the
+// explicit address space turns flat_load/flat_store into global_load/store,
+// which do not tie up the LDS counter.
+#define BM_GLOBAL __attribute__((address_space(1)))
+__device__ __forceinline__ u32x4 ldg128(const void *p) { return *(const BM_GLOBAL u32x4 *)p; }
+__device__ __forceinline__ void stg128(void *p, u32x4 v) { *(BM_GLOBAL u32x4 *)p = v; }
+__device__ __forceinline__ void stg16(void *p, uint16_t v) { *(BM_GLOBAL uint16_t *)p = v; }
+__device__ __forceinline__ int ldg_i32(const void *p) { return *(const BM_GLOBAL int *)p; }
+__device__ __forceinline__ float ldg_f32(const void *p) { return *(const BM_GLOBAL float *)p; }
+
+__device__ __forceinline__ float silu(float a) { return a / (1.0f + __expf(-a)); }
+
+__device__ __forceinline__ int lane_id() { return (int)(threadIdx.x & (WAVE - 1)); }
+
+// butterfly sum over the 64 lanes; every lane ends with the same value and
+// the association order is fixed, so the result is reproducible
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+    for (int m = 32; m >= 1; m >>= 1) v += __shfl_xor(v, m, WAVE);
+    return v;
+}
+
+// (value, index) argmax over the wave: larger value wins, equal values go to
+// the lower index
+__device__ __forceinline__ void wave_argmax(float &v, int &i) {
+#pragma unroll
+    for (int m = 32; m >= 1; m >>= 1) {
+        float ov = __shfl_xor(v, m, WAVE);
+        int oi = __shfl_xor(i, m, WAVE);
+        bool take = (ov > v) || (ov == v && oi < i);
+        v = take ? ov : v;
+        i = take ? oi : i;
+    }
+}
+
+}  // namespace bm

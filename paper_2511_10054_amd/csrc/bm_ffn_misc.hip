@@ -1,0 +1,133 @@
+// fp32 expert projections (plain fp32 FMA, one workgroup per row) and the
+// gate-weighted aggregation  y[t] = sum_k w[t][k] * o[pos(t,k)] + shared rows.
+#include "bm_kernels.h"
+
+namespace bm {
+
+__device__ __forceinline__ float silu_precise(float a) { return a / (1.0f + expf(-a)); }
+
+// group of a row: offsets is non-decreasing with G+1 entries
+__device__ __forceinline__ int find_group(const int32_t *offsets, int G, int pos) {
+    int lo = 0, hi = G;               // offsets[lo] <= pos < offsets[hi]
+    while (hi - lo > 1) {
+        const int mid = (lo + hi) >> 1;
+        if (offsets[mid] <= pos) lo = mid; else hi = mid;
+    }
+    return lo;
+}
+
+template <bool DUAL>
+__global__ void __launch_bounds__(256) rowwise_f32_kernel(GemmParams p) {
+    extern __shared__ float s_row[];
+    __shared__ int s_g;
+    const int pos = blockIdx.x;
+    if (pos >= p.n_mtiles[1]) return;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    if (tid == 0) s_g = find_group(p.offsets, p.n_groups, pos);
+    const int src = p.row_map ? p.row_map[pos] : pos;
+    const float *arow = static_cast<const float *>(p.a) + (size_t)src * p.Kd;
+    for (int j = tid; j < p.Kd; j += blockDim.x) s_row[j] = arow[j];
+    __syncthreads();
+    const int g = s_g;
+    const float *b0 = (g < p.E) ? static_cast<const float *>(p.b0) + (size_t)g * p.N * p.Kd
+                                : static_cast<const float *>(p.sb0) + (size_t)(g - p.E) * p.N * p.Kd;
+    const float *b1 = nullptr;
+    if (DUAL)
+        b1 = (g < p.E) ? static_cast<const float *>(p.b1) + (size_t)g * p.N * p.Kd
+                       : static_cast<const float *>(p.sb1) + (size_t)(g - p.E) * p.N * p.Kd;
+    float *c = static_cast<float *>(p.c) + (size_t)pos * p.N;
+    for (int n = wave; n < p.N; n += 4) {
+        const float *r0 = b0 + (size_t)n * p.Kd;
+        float s0 = 0.0f, s1 = 0.0f;
+        if (DUAL) {
+            const float *r1 = b1 + (size_t)n * p.Kd;
+            for (int j = lane; j < p.Kd; j += WAVE) {
+                s0 = fmaf(r0[j], s_row[j], s0);
+                s1 = fmaf(r1[j], s_row[j], s1);
+            }
+            s0 = wave_sum(s0);
+            s1 = wave_sum(s1);
+            if (lane == 0) c[n] = silu_precise(s0) * s1;
+        } else {
+            for (int j = lane; j < p.Kd; j += WAVE) s0 = fmaf(r0[j], s_row[j], s0);
+            s0 = wave_sum(s0);
+            if (lane == 0) c[n] = s0;
+        }
+    }
+}
+
+int launch_gateup_f32(const GemmParams &p, int max_rows, hipStream_t st) {
+    if (max_rows > 0)
+        hipLaunchKernelGGL(rowwise_f32_kernel<true>, dim3(max_rows), dim3(256), (size_t)p.Kd * sizeof(float), st, p);
+    return hipGetLastError() == hipSuccess ? 0 : -1;
+}
+int launch_down_f32(const GemmParams &p, int max_rows, hipStream_t st) {
+    if (max_rows > 0)
+        hipLaunchKernelGGL(rowwise_f32_kernel<false>, dim3(max_rows), dim3(256), (size_t)p.Kd * sizeof(float), st, p);
+    return hipGetLastError() == hipSuccess ? 0 : -1;
+}
+
+// ---------------------------------------------------------------------------
+// Aggregation: a gather per token in slot order, then the shared experts, so
+// the floating-point sum has one fixed order.
+// ---------------------------------------------------------------------------
+template <bool BF16>
+__global__ void __launch_bounds__(256) combine_kernel(CombineParams p) {
+    __shared__ int s_pos[BM_MAX_K + 8];
+    __shared__ float s_w[BM_MAX_K + 8];
+    const int t = blockIdx.x, tid = threadIdx.x;
+    const int nsrc = p.K + p.n_shared;
+    if (tid < p.K) {
+        s_pos[tid] = p.inv_perm[(size_t)t * p.K + tid];
+        s_w[tid] = p.w[(size_t)t * p.K + tid];
+    } else if (tid < nsrc) {
+        s_pos[tid] = p.offsets[p.E + (tid - p.K)] + t;
+        s_w[tid] = 1.0f;
+    }
+    __syncthreads();
+    for (int j0 = tid * 8; j0 < p.d; j0 += blockDim.x * 8) {
+        float acc[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) acc[i] = 0.0f;
+        for (int k = 0; k < nsrc; ++k) {
+            const int pos = s_pos[k];
+            if (pos < 0) continue;
+            const float wk = s_w[k];
+            if (BF16) {
+                const u32x4 v = ldg128(static_cast<const uint16_t *>(p.o) + (size_t)pos * p.d + j0);
+                const uint32_t u[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    acc[2 * i] = fmaf(wk, bf16_to_f32((uint16_t)(u[i] & 0xffffu)), acc[2 * i]);
+                    acc[2 * i + 1] = fmaf(wk, bf16_to_f32((uint16_t)(u[i] >> 16)), acc[2 * i + 1]);
+                }
+            } else {
+                const float *o = static_cast<const float *>(p.o) + (size_t)pos * p.d + j0;
+#pragma unroll
+                for (int i = 0; i < 8; ++i) if (j0 + i < p.d) acc[i] = fmaf(wk, o[i], acc[i]);
+            }
+        }
+        if (p.y_f32) {
+            float *y = static_cast<float *>(p.y) + (size_t)t * p.d + j0;
+#pragma unroll
+            for (int i = 0; i < 8; ++i) if (j0 + i < p.d) y[i] = acc[i];
+        } else {
+            u32x4 out;
+            out.x = pack_bf16x2(acc[0], acc[1]);
+            out.y = pack_bf16x2(acc[2], acc[3]);
+            out.z = pack_bf16x2(acc[4], acc[5]);
+            out.w = pack_bf16x2(acc[6], acc[7]);
+            stg128(static_cast<uint16_t *>(p.y) + (size_t)t * p.d + j0, out);
+        }
+    }
+}
+
+int launch_combine(const CombineParams &p, int dtype, hipStream_t st) {
+    if (p.T > 0) {
+        if (dtype == BM_BF16) hipLaunchKernelGGL(combine_kernel<true>, dim3(p.T), dim3(256), 0, st, p);
+        else hipLaunchKernelGGL(combine_kernel<false>, dim3(p.T), dim3(256), 0, st, p);
+    }
+    return hipGetLastError() == hipSuccess ? 0 : -1;
+}
+
+}  // namespace bm

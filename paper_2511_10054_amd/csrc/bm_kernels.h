@@ -1,0 +1,94 @@
+// Internal interface between the C-ABI layer (bm_api.hip) and the kernel
+// translation units.  Parameter blocks are plain structs passed by value.
+#pragma once
+#include "../../include/buddymoe.h"
+#include "bm_device.h"
+
+namespace bm {
+
+struct FrontParams {
+    const void *x;          // [T][d]
+    const void *wr;         // [E][d]
+    const float *bias;      // [E] or null
+    int T, d, E, K, R, H;
+    uint32_t flags;
+    int32_t *ids;           // [T][K] router's choice
+    float *w;               // [T][K]
+    const uint64_t *bitmap; // null => routing only (no substitution, no histogram)
+    const int32_t *table;   // [E][R]
+    int32_t *ids2;          // [T][K] after substitution
+    int32_t *tile_counts;   // [n_tiles][E]
+    int32_t *tile_stats;    // [n_tiles][4]
+};
+
+struct RemapParams {
+    int T, K, E, R, H, unique;
+    const uint64_t *bitmap;
+    const int32_t *table;
+    const int32_t *ids_in;
+    int32_t *ids_out;
+    float *w;
+    int32_t *stats;         // 3 ints or null
+};
+
+struct ScanParams {
+    int T, E, n_shared, n_tiles, BM;
+    const int32_t *tile_counts;   // [n_tiles][E]
+    int32_t *tile_base;           // [n_tiles][E]
+    const int32_t *tile_stats;    // [n_tiles][4] or null
+    int32_t *offsets;             // [E + n_shared + 1]
+    int32_t *mt_group, *mt_row0;  // row-tile table
+    int32_t *n_mtiles;            // [2]: number of row tiles, total rows
+    int32_t *stats;               // 3 ints or null
+};
+
+struct ScatterParams {
+    int T, K, E, n_shared;
+    const int32_t *ids;           // [T][K] after substitution
+    const int32_t *offsets;       // [E + n_shared + 1]
+    const int32_t *tile_base;     // [n_tiles][E]
+    int32_t *perm, *inv_perm;     // [T*K]
+    int32_t *row_token;           // [rows] or null
+};
+
+// Grouped projection C[rows][N] = A[rows][Kd] * B_g[N][Kd]^T over row tiles.
+struct GemmParams {
+    const void *a;                // activations: [T][Kd] gathered via row_map, or [rows][Kd]
+    const int32_t *row_map;       // row -> row of a (null: identity)
+    const void *b0, *b1;          // routed weights ([E][N][Kd]); b1 = second matrix (up) or null
+    const void *sb0, *sb1;        // shared-expert weights ([n_shared][N][Kd])
+    void *c;                      // [rows][N]
+    int N, Kd, E;
+    int n_groups;                 // E + n_shared
+    int max_mtiles;               // grid bound on row tiles
+    const int32_t *mt_group, *mt_row0, *n_mtiles, *offsets;
+};
+
+struct CombineParams {
+    int T, d, K, E, n_shared;
+    const void *o;                // [rows][d]
+    const float *w;               // [T][K]
+    const int32_t *inv_perm;      // [T*K]
+    const int32_t *offsets;       // [E + n_shared + 1]
+    void *y;
+    int y_f32;
+};
+
+int launch_front(const FrontParams &p, int dtype, hipStream_t st);
+int launch_remap(const RemapParams &p, hipStream_t st);
+int launch_count(const int32_t *ids, int T, int K, int E, int32_t *tile_counts, hipStream_t st);
+int launch_scan(const ScanParams &p, hipStream_t st);
+int launch_scatter(const ScatterParams &p, hipStream_t st);
+
+// bf16 MFMA grouped projections (row tile height gemm_bf16_bm())
+int gemm_bf16_bm();
+int launch_gateup_bf16(const GemmParams &p, hipStream_t st);   // c = silu(a b0^T) * (a b1^T), bf16
+int launch_down_bf16(const GemmParams &p, hipStream_t st);     // c = a b0^T, bf16
+
+// fp32 FMA projections (one workgroup per row)
+int launch_gateup_f32(const GemmParams &p, int max_rows, hipStream_t st);
+int launch_down_f32(const GemmParams &p, int max_rows, hipStream_t st);
+
+int launch_combine(const CombineParams &p, int dtype, hipStream_t st);
+
+}  // namespace bm

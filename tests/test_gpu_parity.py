@@ -1,0 +1,231 @@
+"""Parity of the HIP library against the CPU oracle, stage by stage and for the
+whole layer, through the C ABI (needs an MI355X)."""
+import numpy as np
+import pytest
+
+import oracle
+import workloads
+from helpers import DeviceLayer, HostLayer, err_metric, to_device
+
+pytestmark = pytest.mark.gpu
+
+TOL = {"bf16": 2e-2, "f32": 1e-5}
+
+
+def _torch():
+    import torch
+    return torch
+
+
+def _say(*a):
+    print(*a, flush=True)
+
+
+# ----------------------------------------------------------------- routing
+
+ROUTE_CASES = [
+    ("c1_tiny", {}, 16),
+    ("c1_tiny", dict(d=200, E=37, K=5), 77),
+    ("c2_mixtral_decode", dict(d=512), 1),
+    ("c2_mixtral_decode", dict(d=512), 100),
+    ("c2_mixtral_decode", dict(d=4096), 64),
+    ("c5_deepseek", dict(d=256), 333),
+    ("c4_qwen3", dict(d=512), 257),
+    ("c4_qwen3", dict(d=256, E=200, K=8, n_resident=100), 65),
+    ("c4_qwen3", dict(d=256, E=256, K=32, n_resident=100), 40),
+]
+
+
+@pytest.mark.parametrize("name,over,T", ROUTE_CASES)
+@pytest.mark.parametrize("renorm", [True, False])
+def test_route_topk(name, over, T, renorm):
+    torch = _torch()
+    import paper_2511_10054_amd as bm
+    spec = workloads.scaled(name, F=32, **over)
+    _say("route", spec.name, over, T, renorm)
+    lay = workloads.get_layer(spec)
+    x, _ = lay.tokens(T)
+    ids_ref, w_ref = oracle.route_topk(lay.as_f32(x), lay.as_f32(lay.w_router), lay.router_bias, spec.K, renorm)
+    desc = bm.LayerDesc(T=T, d=spec.d, E=spec.E, F=0, K=spec.K, n_shared=0, R=0, H=0,
+                        dtype=bm.BM_BF16 if spec.dtype == "bf16" else bm.BM_F32,
+                        flags=bm.BM_RENORM_TOPK if renorm else 0)
+    ids = torch.full((T, spec.K), -9, dtype=torch.int32, device="cuda")
+    w = torch.full((T, spec.K), -9.0, dtype=torch.float32, device="cuda")
+    bm.bm_route_topk(desc, to_device(x), to_device(lay.w_router), to_device(lay.router_bias), ids, w)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(ids.cpu().numpy(), ids_ref)
+    np.testing.assert_allclose(w.cpu().numpy(), w_ref, rtol=2e-5, atol=1e-7)
+
+
+# ------------------------------------------------------------------- remap
+
+
+def _random_problem(seed, T, E, K, R, n_res):
+    g = np.random.default_rng(seed)
+    ids = np.stack([g.permutation(E)[:K] for _ in range(T)]).astype(np.int32)
+    res = np.zeros(E, bool); res[g.permutation(E)[:n_res]] = True
+    table = np.stack([g.permutation([j for j in range(E) if j != i])[:R] for i in range(E)]).astype(np.int32)
+    table[g.random((E, R)) < 0.15] = -1
+    return ids, res, table
+
+
+@pytest.mark.parametrize("T,E,K,R,n_res", [(1, 8, 2, 3, 4), (1000, 24, 4, 6, 9), (513, 64, 6, 8, 16),
+                                           (300, 130, 8, 8, 50), (257, 256, 32, 32, 40), (64, 8, 2, 7, 0)])
+@pytest.mark.parametrize("unique", [False, True])
+def test_buddy_remap(T, E, K, R, n_res, unique):
+    torch = _torch()
+    import paper_2511_10054_amd as bm
+    _say("remap", T, E, K, R, n_res, unique)
+    ids, res, table = _random_problem(T + E, T, E, K, R, n_res)
+    ids[::7, 0] = -1                                   # already-dropped inputs pass through as -1
+    w = np.random.default_rng(1).random((T, K)).astype(np.float32)
+    for H in {R, R // 2, 0}:
+        ref, w_ref, st = oracle.buddy_remap(ids, res, table, H=H, unique=unique, w=w)
+        desc = bm.LayerDesc(T=T, d=32, E=E, F=0, K=K, n_shared=0, R=R, H=H, dtype=bm.BM_BF16,
+                            flags=bm.BM_REMAP_UNIQUE if unique else 0)
+        d_ids = to_device(ids)
+        d_out = torch.full((T, K), -9, dtype=torch.int32, device="cuda")
+        d_w = to_device(w)
+        d_stats = torch.full((3,), -9, dtype=torch.int32, device="cuda")
+        bm.bm_buddy_remap(desc, to_device(workloads.pack_bitmap(res)), to_device(table), d_ids, d_out, d_w, d_stats)
+        torch.cuda.synchronize()
+        np.testing.assert_array_equal(d_out.cpu().numpy(), ref)
+        np.testing.assert_array_equal(d_w.cpu().numpy(), w_ref.astype(np.float32))
+        assert d_stats.cpu().tolist() == [st["n_miss"], st["n_substituted"], st["n_dropped"]]
+        # in place, no weights, no stats
+        bm.bm_buddy_remap(desc, to_device(workloads.pack_bitmap(res)), to_device(table), d_ids, d_ids)
+        torch.cuda.synchronize()
+        np.testing.assert_array_equal(d_ids.cpu().numpy(), ref)
+
+
+# ------------------------------------------------------------- permutation
+
+
+@pytest.mark.parametrize("T,K,E", [(1, 2, 8), (57, 3, 11), (1000, 6, 64), (4096, 8, 128), (33, 32, 256)])
+def test_permute_by_expert(T, K, E):
+    torch = _torch()
+    import paper_2511_10054_amd as bm
+    _say("permute", T, K, E)
+    g = np.random.default_rng(T)
+    ids = g.integers(0, E, size=(T, K)).astype(np.int32)
+    ids[g.random((T, K)) < 0.2] = -1
+    ids[:, 0] = np.minimum(ids[:, 0], 2)               # skew: a few very large groups
+    off_ref, perm_ref, inv_ref = oracle.permute(ids, E)
+    desc = bm.LayerDesc(T=T, d=32, E=E, F=0, K=K, n_shared=0, R=0, H=0, dtype=bm.BM_BF16, flags=0)
+    ws = torch.empty(bm.bm_workspace_bytes(desc), dtype=torch.uint8, device="cuda")
+    off = torch.full((E + 1,), -9, dtype=torch.int32, device="cuda")
+    perm = torch.full((T * K,), -9, dtype=torch.int32, device="cuda")
+    inv = torch.full((T * K,), -9, dtype=torch.int32, device="cuda")
+    bm.bm_permute_by_expert(desc, to_device(ids), off, perm, inv, ws)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(off.cpu().numpy(), off_ref)
+    np.testing.assert_array_equal(perm.cpu().numpy(), perm_ref)
+    np.testing.assert_array_equal(inv.cpu().numpy(), inv_ref)
+
+
+# ------------------------------------------------------------- whole layer
+
+LAYER_CASES = [
+    # name, overrides, T  -- reduced widths, several row tiles and ragged tails
+    ("c1_tiny", {}, 16),
+    ("c1_tiny", dict(d=72, F=100, E=11, K=3, n_resident=5), 45),
+    ("c2_mixtral_decode", dict(d=512, F=1024), 1),
+    ("c2_mixtral_decode", dict(d=512, F=1024), 8),
+    ("c2_mixtral_decode", dict(d=512, F=1024), 64),
+    ("c3_mixtral_prefill", dict(d=512, F=1024), 700),
+    ("c3_mixtral_prefill", dict(d=1024, F=416), 333),     # F not a multiple of the column tile
+    ("c4_qwen3", dict(d=256, F=384), 300),
+    ("c5_deepseek", dict(d=256, F=352), 500),
+]
+
+
+def _check_layer(host, unique, renorm=True, H=None):
+    ref = host.oracle_forward(oracle, unique=unique, renorm=renorm, H=H)
+    dev = DeviceLayer(host, unique=unique, renorm=renorm, H=H)
+    out = dev.forward()
+    spec = host.spec
+    np.testing.assert_array_equal(out["ids"], ref["ids"])
+    np.testing.assert_array_equal(out["ids_remapped"], ref["ids_remapped"])
+    np.testing.assert_allclose(out["w"], ref["w"], rtol=2e-5, atol=1e-7)
+    st = ref["stats"]
+    assert out["stats"].tolist() == [st["n_miss"], st["n_substituted"], st["n_dropped"]]
+    off_ref, perm_ref, inv_ref = oracle.permute(ref["ids_remapped"], spec.E)
+    np.testing.assert_array_equal(out["offsets"], off_ref)
+    np.testing.assert_array_equal(out["perm"], perm_ref)
+    np.testing.assert_array_equal(out["inv_perm"], inv_ref)
+    e = err_metric(out["y"], ref["y"])
+    _say("   err", e, "stats", st)
+    assert e <= TOL[spec.dtype], e
+    return out, ref, dev
+
+
+@pytest.mark.parametrize("name,over,T", LAYER_CASES)
+@pytest.mark.parametrize("unique", [False, True])
+def test_layer_matches_oracle(name, over, T, unique):
+    spec = workloads.scaled(name, **over)
+    _say("layer", name, over, T, "unique" if unique else "first")
+    host = HostLayer(spec, T)
+    _check_layer(host, unique)
+
+
+def test_layer_without_renormalisation_and_short_search():
+    spec = workloads.scaled("c5_deepseek", d=256, F=352)
+    _say("layer no-renorm H=2")
+    _check_layer(HostLayer(spec, 200), unique=True, renorm=False, H=2)
+
+
+def test_all_resident_is_plain_topk_moe():
+    spec = workloads.scaled("c4_qwen3", d=256, F=384)
+    _say("layer all resident")
+    host = HostLayer(spec, 150, mask=np.ones(spec.E, bool))
+    out, ref, _ = _check_layer(host, unique=True)
+    np.testing.assert_array_equal(out["ids"], out["ids_remapped"])
+    assert out["stats"].tolist() == [0, 0, 0]
+
+
+def test_nothing_resident_leaves_only_shared_experts():
+    spec = workloads.scaled("c5_deepseek", d=256, F=352)
+    _say("layer none resident")
+    host = HostLayer(spec, 100, mask=np.zeros(spec.E, bool))
+    out, ref, _ = _check_layer(host, unique=False)
+    assert (out["ids_remapped"] == -1).all() and (out["w"] == 0).all()
+    spec0 = workloads.scaled("c4_qwen3", d=256, F=384)
+    out, _, _ = _check_layer(HostLayer(spec0, 70, mask=np.zeros(spec0.E, bool)), unique=False)
+    assert (out["y"] == 0).all()
+
+
+def test_non_resident_weights_are_never_read():
+    # weights of absent experts are NaN: any read would poison the output
+    spec = workloads.scaled("c3_mixtral_prefill", d=512, F=1024)
+    _say("layer poison")
+    host = HostLayer(spec, 300, only_resident=True, poison=True)
+    assert np.isnan(host.f32(host.wg)).any()
+    out, _, _ = _check_layer(host, unique=False)
+    assert np.isfinite(out["y"]).all()
+
+
+def test_repeated_calls_give_identical_bytes():
+    torch = _torch()
+    spec = workloads.scaled("c5_deepseek", d=256, F=352)
+    _say("layer determinism")
+    dev = DeviceLayer(HostLayer(spec, 400), unique=True)
+    a = dev.forward()
+    dev.workspace.fill_(0xA5)                         # stale workspace contents must not matter
+    b = dev.forward()
+    for k in a:
+        np.testing.assert_array_equal(a[k], b[k])
+
+
+def test_fp32_output_flag_and_empty_batch():
+    torch = _torch()
+    import paper_2511_10054_amd as bm
+    spec = workloads.scaled("c2_mixtral_decode", d=512, F=1024)
+    _say("layer y_f32 / T=0")
+    host = HostLayer(spec, 40)
+    ref = host.oracle_forward(oracle)
+    dev = DeviceLayer(host, y_f32=True)
+    out = dev.forward()
+    assert dev.y.dtype == torch.float32
+    assert err_metric(out["y"], ref["y"]) <= TOL["bf16"]
+    empty = DeviceLayer(HostLayer(spec, 0))
+    empty.forward(debug=False)                         # no-op, must not fault
