@@ -88,7 +88,8 @@ typedef struct {
     int32_t n_dropped;      /* of those, dropped (no acceptable buddy)  */
 } bm_remap_stats;
 
-/* Optional device outputs of bm_moe_forward; any member may be NULL. */
+/* Optional outputs of bm_moe_forward; any member may be NULL.  Pointers are
+ * device memory. */
 typedef struct {
     int32_t *ids;            /* [T][K] router's choice                      */
     int32_t *ids_remapped;   /* [T][K] after substitution, -1 = dropped     */
@@ -97,6 +98,10 @@ typedef struct {
     int32_t *perm;           /* [T*K]                                       */
     int32_t *inv_perm;       /* [T*K]                                       */
     bm_remap_stats *stats;   /* one struct                                  */
+    void *stage_events[5];   /* hipEvent_t handles, all NULL or all set; recorded on
+                                `stream` before the front end, after the grouping,
+                                after the gate/up projection, after the down
+                                projection and after the aggregation (timing only) */
 } bm_debug_out;
 
 /* Router and gates (Section 3, "Notation and Preliminaries"; Section 2.2):

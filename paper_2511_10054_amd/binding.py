@@ -32,7 +32,8 @@ class Weights(ctypes.Structure):
 
 class DebugOut(ctypes.Structure):
     _fields_ = [(n, ctypes.c_void_p) for n in
-                ("ids", "ids_remapped", "w", "offsets", "perm", "inv_perm", "stats")]
+                ("ids", "ids_remapped", "w", "offsets", "perm", "inv_perm", "stats")] + \
+               [("stage_events", ctypes.c_void_p * 5)]
 
 
 def library_path() -> str:
@@ -121,10 +122,13 @@ def bm_permute_by_expert(desc: LayerDesc, ids_remapped, offsets, perm, inv_perm,
 
 def bm_moe_forward(desc: LayerDesc, x, weights: Weights, bitmap, table, y, workspace, dbg: Optional[dict] = None,
                    stream: Optional[int] = None):
-    """dbg: optional dict of device tensors keyed by bm_debug_out member names."""
+    """dbg: optional dict of device tensors keyed by bm_debug_out member names;
+    the key "stage_events" takes a sequence of 5 hipEvent_t handles (ints)."""
     d = None
     if dbg:
-        d = DebugOut(**{k: _ptr(v) for k, v in dbg.items()})
+        d = DebugOut(**{k: _ptr(v) for k, v in dbg.items() if k != "stage_events"})
+        if dbg.get("stage_events") is not None:
+            d.stage_events = (ctypes.c_void_p * 5)(*dbg["stage_events"])
     _check(load_library().bm_moe_forward(ctypes.byref(desc), _ptr(x), ctypes.byref(weights), _ptr(bitmap),
                                          _ptr(table), _ptr(y), _ptr(workspace),
                                          workspace.numel() * workspace.element_size(),

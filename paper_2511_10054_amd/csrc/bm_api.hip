@@ -2,6 +2,17 @@
 // Nothing here allocates, synchronises or keeps state between calls.
 #include "bm_kernels.h"
 
+#include <cstdio>
+
+namespace bm {
+int launch_status(const char *what) {
+    const hipError_t e = hipGetLastError();
+    if (e == hipSuccess) return 0;
+    std::fprintf(stderr, "buddymoe: %s: %s\n", what, hipGetErrorString(e));
+    return -1;
+}
+}  // namespace bm
+
 namespace {
 
 using namespace bm;
@@ -137,6 +148,7 @@ int bm_route_topk(const bm_layer_desc *desc, const void *x, const void *w_router
     if (rc) return rc;
     if (desc->T == 0) return BM_OK;
     if (!x || !w_router || !ids || !w) return BM_ERR_NULL;
+    (void)hipGetLastError();   // errors left by earlier, unrelated HIP calls are not ours
     FrontParams p{};
     p.x = x; p.wr = w_router; p.bias = bias;
     p.T = desc->T; p.d = desc->d; p.E = desc->E; p.K = desc->K; p.R = 0; p.H = 0;
@@ -153,6 +165,7 @@ int bm_buddy_remap(const bm_layer_desc *desc, const uint64_t *residency_bitmap, 
     int rc = check_remap_desc(desc);
     if (rc) return rc;
     if (!residency_bitmap || !ids_in || !ids_out || (!buddy_table && desc->R > 0)) return BM_ERR_NULL;
+    (void)hipGetLastError();
     RemapParams p{};
     p.T = desc->T; p.K = desc->K; p.E = desc->E; p.R = desc->R; p.H = desc->H;
     p.unique = (desc->flags & BM_REMAP_UNIQUE) ? 1 : 0;
@@ -175,6 +188,7 @@ int bm_permute_by_expert(const bm_layer_desc *desc, const int32_t *ids_remapped,
     int rc = check_ws(&d2, workspace, workspace_bytes, L);
     if (rc) return rc;
     hipStream_t st = static_cast<hipStream_t>(stream);
+    (void)hipGetLastError();
     int err = launch_count(ids_remapped, d2.T, d2.K, d2.E, at<int32_t>(workspace, L.tile_counts), st);
     ScanParams sp{};
     sp.T = d2.T; sp.E = d2.E; sp.n_shared = 0; sp.n_tiles = L.n_tiles; sp.BM = gemm_bf16_bm();
@@ -214,8 +228,18 @@ int bm_moe_forward(const bm_layer_desc *desc, const void *x, const bm_weights *w
     const int T = desc->T, K = desc->K, E = desc->E, G = E + desc->n_shared;
     const bool bf16 = desc->dtype == BM_BF16;
     int err = 0;
+    (void)hipGetLastError();   // errors left by earlier, unrelated HIP calls are not ours
+
+    hipEvent_t ev[5] = {nullptr, nullptr, nullptr, nullptr, nullptr};
+    if (dbg && dbg->stage_events[0])
+        for (int i = 0; i < 5; ++i) {
+            if (!dbg->stage_events[i]) return BM_ERR_NULL;
+            ev[i] = static_cast<hipEvent_t>(dbg->stage_events[i]);
+        }
+    auto mark = [&](int i) { if (ev[i]) err |= (hipEventRecord(ev[i], st) != hipSuccess); };
 
     // 1. router, gates, substitution, per-tile histograms
+    mark(0);
     FrontParams fp{};
     fp.x = x; fp.wr = wt->w_router; fp.bias = wt->router_bias;
     fp.T = T; fp.d = desc->d; fp.E = E; fp.K = K; fp.R = desc->R; fp.H = desc->H; fp.flags = desc->flags;
@@ -244,6 +268,7 @@ int bm_moe_forward(const bm_layer_desc *desc, const void *x, const bm_weights *w
     cp.perm = at<int32_t>(ws, L.perm); cp.inv_perm = at<int32_t>(ws, L.inv_perm);
     cp.row_token = at<int32_t>(ws, L.row_token);
     err |= launch_scatter(cp, st);
+    mark(1);
 
     // 4. gate/up projection + SwiGLU, 5. down projection
     GemmParams gp{};
@@ -259,11 +284,14 @@ int bm_moe_forward(const bm_layer_desc *desc, const void *x, const bm_weights *w
     dp.N = desc->d; dp.Kd = desc->F;
     if (bf16) {
         err |= launch_gateup_bf16(gp, st);
+        mark(2);
         err |= launch_down_bf16(dp, st);
     } else {
         err |= launch_gateup_f32(gp, L.rows_max, st);
+        mark(2);
         err |= launch_down_f32(dp, L.rows_max, st);
     }
+    mark(3);
 
     // 6. aggregation
     CombineParams mp{};
@@ -271,6 +299,7 @@ int bm_moe_forward(const bm_layer_desc *desc, const void *x, const bm_weights *w
     mp.o = dp.c; mp.w = fp.w; mp.inv_perm = cp.inv_perm; mp.offsets = sp.offsets;
     mp.y = y; mp.y_f32 = (!bf16 || (desc->flags & BM_Y_F32)) ? 1 : 0;
     err |= launch_combine(mp, desc->dtype, st);
+    mark(4);
 
     if (dbg) {
         const size_t A = (size_t)T * K;
@@ -281,7 +310,7 @@ int bm_moe_forward(const bm_layer_desc *desc, const void *x, const bm_weights *w
         if (dbg->perm) copy_ints(cp.perm, dbg->perm, A, st);
         if (dbg->inv_perm) copy_ints(cp.inv_perm, dbg->inv_perm, A, st);
         if (dbg->stats) copy_ints(sp.stats, dbg->stats, 3, st);
-        if (hipGetLastError() != hipSuccess) err = 1;
+        err |= launch_status("debug copies");
     }
     return err ? BM_ERR_HIP : BM_OK;
 }

@@ -59,12 +59,12 @@ __global__ void __launch_bounds__(256) rowwise_f32_kernel(GemmParams p) {
 int launch_gateup_f32(const GemmParams &p, int max_rows, hipStream_t st) {
     if (max_rows > 0)
         hipLaunchKernelGGL(rowwise_f32_kernel<true>, dim3(max_rows), dim3(256), (size_t)p.Kd * sizeof(float), st, p);
-    return hipGetLastError() == hipSuccess ? 0 : -1;
+    return launch_status(__func__);
 }
 int launch_down_f32(const GemmParams &p, int max_rows, hipStream_t st) {
     if (max_rows > 0)
         hipLaunchKernelGGL(rowwise_f32_kernel<false>, dim3(max_rows), dim3(256), (size_t)p.Kd * sizeof(float), st, p);
-    return hipGetLastError() == hipSuccess ? 0 : -1;
+    return launch_status(__func__);
 }
 
 // ---------------------------------------------------------------------------
@@ -127,7 +127,7 @@ int launch_combine(const CombineParams &p, int dtype, hipStream_t st) {
         if (dtype == BM_BF16) hipLaunchKernelGGL(combine_kernel<true>, dim3(p.T), dim3(256), 0, st, p);
         else hipLaunchKernelGGL(combine_kernel<false>, dim3(p.T), dim3(256), 0, st, p);
     }
-    return hipGetLastError() == hipSuccess ? 0 : -1;
+    return launch_status(__func__);
 }
 
 }  // namespace bm

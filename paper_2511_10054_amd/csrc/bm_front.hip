@@ -426,7 +426,7 @@ int launch_front(const FrontParams &p, int dtype, hipStream_t st) {
         else if (nb <= 4) small ? launch_front_bf16<4, 8>(p, n_tiles, st) : launch_front_bf16<4, 4>(p, n_tiles, st);
         else launch_front_bf16<8, 4>(p, n_tiles, st);
     }
-    return hipGetLastError() == hipSuccess ? 0 : -1;
+    return launch_status(__func__);
 }
 
 int launch_remap(const RemapParams &p, hipStream_t st) {
@@ -435,24 +435,24 @@ int launch_remap(const RemapParams &p, hipStream_t st) {
         const size_t lds = (size_t)p.E * p.R * sizeof(int32_t);
         hipLaunchKernelGGL(remap_kernel, dim3((p.T + 255) / 256), dim3(256), lds, st, p);
     }
-    return hipGetLastError() == hipSuccess ? 0 : -1;
+    return launch_status(__func__);
 }
 
 int launch_count(const int32_t *ids, int T, int K, int E, int32_t *tile_counts, hipStream_t st) {
     const int n_tiles = (T + TILE_T - 1) / TILE_T;
     if (n_tiles) hipLaunchKernelGGL(count_kernel, dim3(n_tiles), dim3(256), 0, st, ids, T, K, E, tile_counts);
-    return hipGetLastError() == hipSuccess ? 0 : -1;
+    return launch_status(__func__);
 }
 
 int launch_scan(const ScanParams &p, hipStream_t st) {
     hipLaunchKernelGGL(scan_kernel, dim3(1), dim3(256), 0, st, p);
-    return hipGetLastError() == hipSuccess ? 0 : -1;
+    return launch_status(__func__);
 }
 
 int launch_scatter(const ScatterParams &p, hipStream_t st) {
     const int n_tiles = (p.T + TILE_T - 1) / TILE_T;
     if (n_tiles) hipLaunchKernelGGL(scatter_kernel, dim3(n_tiles), dim3(256), 0, st, p);
-    return hipGetLastError() == hipSuccess ? 0 : -1;
+    return launch_status(__func__);
 }
 
 }  // namespace bm

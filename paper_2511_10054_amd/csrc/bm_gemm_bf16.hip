@@ -183,12 +183,12 @@ static int grid_for(const GemmParams &p, bool dual) {
 
 int launch_gateup_bf16(const GemmParams &p, hipStream_t st) {
     hipLaunchKernelGGL(grouped_gemm_bf16_kernel<true>, dim3(grid_for(p, true)), dim3(G_THREADS), 0, st, p);
-    return hipGetLastError() == hipSuccess ? 0 : -1;
+    return launch_status(__func__);
 }
 
 int launch_down_bf16(const GemmParams &p, hipStream_t st) {
     hipLaunchKernelGGL(grouped_gemm_bf16_kernel<false>, dim3(grid_for(p, false)), dim3(G_THREADS), 0, st, p);
-    return hipGetLastError() == hipSuccess ? 0 : -1;
+    return launch_status(__func__);
 }
 
 }  // namespace bm

@@ -74,6 +74,10 @@ struct CombineParams {
     int y_f32;
 };
 
+// 0 if the launch just issued was accepted, -1 (and a line on stderr naming
+// the kernel and the HIP error) otherwise
+int launch_status(const char *what);
+
 int launch_front(const FrontParams &p, int dtype, hipStream_t st);
 int launch_remap(const RemapParams &p, hipStream_t st);
 int launch_count(const int32_t *ids, int T, int K, int E, int32_t *tile_counts, hipStream_t st);

@@ -31,7 +31,7 @@ def test_library_exports_every_declared_symbol():
 
 def test_struct_layouts_match_header():
     assert ctypes.sizeof(bm.LayerDesc) == 40
-    assert ctypes.sizeof(Weights) == 64 and ctypes.sizeof(DebugOut) == 56
+    assert ctypes.sizeof(Weights) == 64 and ctypes.sizeof(DebugOut) == 96
 
 
 def test_strerror_and_workspace_bytes():
