@@ -61,14 +61,15 @@ class HipEvents:
             self.hip.hipEventDestroy(ctypes.c_void_p(e))
 
 
-def run_workload(name, T, steps, warmup, with_events=True, unique=False):
+def run_workload(name, T, steps, warmup, with_events=True, unique=False, base=None):
+    """base: result of an earlier run_workload on the same layer (weights are reused)."""
     import torch
     import workloads
     from workloads.harness import DeviceLayer, HostLayer
     spec = workloads.CONFIGS[name]
     t_gen = time.time()
-    host = HostLayer(spec, T, only_resident=True, poison=True)
-    dev = DeviceLayer(host, unique=unique)
+    host = HostLayer(spec, T, only_resident=True, poison=True, base=base["host"] if base else None)
+    dev = DeviceLayer(host, unique=unique, base=base["dev"] if base else None)
     t_gen = time.time() - t_gen
     bm = dev.bm
     E, K = spec.E, spec.K
@@ -168,6 +169,8 @@ def main():
     ap.add_argument("--tokens", type=int, default=None)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--unique", action="store_true", help="Algorithm 1's uniqueness test on")
+    ap.add_argument("--also-tokens", default=None,
+                    help="comma-separated extra batch sizes on the same layer, reported under 'also'")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU: this build has no multi-GPU path (tokens shard "
@@ -207,6 +210,20 @@ def main():
         "stages_us": {k: round(float(v) * 1e3, 2) for k, v in
                       zip(("front_and_grouping", "gate_up", "down", "combine"), r["stage_ms"])},
     }
+    also = args.also_tokens
+    if also is None and args.workload == "c2" and not args.tokens:
+        also = "1,8,32"                                   # the other batch sizes the decode config names
+    if also:
+        out["also"] = {}
+        for t2 in [int(v) for v in also.split(",") if v]:
+            r2 = run_workload(name, t2, args.steps, args.warmup, unique=args.unique, base=r)
+            roof2 = roofline_gateup(r2)
+            out["also"][f"T{t2}"] = {"tokens_per_s": round(t2 / (r2["ms_per_step"] * 1e-3), 1),
+                                     "ms_per_step": round(r2["ms_per_step"], 5),
+                                     "experts_touched": r2["n_touched"],
+                                     "gate_up_frac": roof2["frac"], "gate_up_bound": roof2["bound"],
+                                     "stages_us": {k: round(float(v) * 1e3, 2) for k, v in
+                                                   zip(("front_and_grouping", "gate_up", "down", "combine"), r2["stage_ms"])}}
     if not args.no_cpu_baseline:
         base, err = cpu_baseline(r, 64 if args.workload == "c2" else 256)
         out["cpu_baseline"] = base

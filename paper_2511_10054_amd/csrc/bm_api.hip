@@ -19,6 +19,19 @@ using namespace bm;
 
 constexpr size_t ALIGN = 256;
 constexpr int MAX_SHARED = 8;
+constexpr int SKINNY_MAX_ROWS = 128;   // total rows up to which the weight-streaming path is used
+constexpr int SKINNY_KSPLIT = 8;
+
+// Few rows in total: every expert group is decode-sized and the projections
+// are bound by reading the weights once.
+bool use_skinny(const bm_layer_desc *d) {
+    return d->dtype == BM_BF16 && (long long)d->T * (d->K + (d->n_shared > 0 ? d->n_shared : 0)) <= SKINNY_MAX_ROWS;
+}
+int skinny_ksplit(const bm_layer_desc *d) {
+    const int ksteps = d->F / 32;
+    int s = ksteps / 16;
+    return s < 1 ? 1 : (s > SKINNY_KSPLIT ? SKINNY_KSPLIT : s);
+}
 
 size_t align_up(size_t v) { return (v + ALIGN - 1) / ALIGN * ALIGN; }
 
@@ -77,7 +90,7 @@ Layout make_layout(const bm_layer_desc *d) {
     L.stats = take(16);
     const size_t F = d->F > 0 ? d->F : 0;
     L.h = take((size_t)L.rows_max * F * esz);
-    L.o = take((size_t)L.rows_max * d->d * esz);
+    L.o = take(use_skinny(d) ? (size_t)skinny_ksplit(d) * L.rows_max * d->d * 4 : (size_t)L.rows_max * d->d * esz);
     L.total = off;
     return L;
 }
@@ -252,7 +265,9 @@ int bm_moe_forward(const bm_layer_desc *desc, const void *x, const bm_weights *w
 
     // 2. offsets, tile bases, row-tile table, statistics
     ScanParams sp{};
-    sp.T = T; sp.E = E; sp.n_shared = desc->n_shared; sp.n_tiles = L.n_tiles; sp.BM = gemm_bf16_bm();
+    const bool skinny = use_skinny(desc);
+    sp.T = T; sp.E = E; sp.n_shared = desc->n_shared; sp.n_tiles = L.n_tiles;
+    sp.BM = skinny ? (1 << 20) : gemm_bf16_bm();      // skinny: one table entry per live group
     sp.tile_counts = fp.tile_counts; sp.tile_base = at<int32_t>(ws, L.tile_base);
     sp.tile_stats = fp.tile_stats;
     sp.offsets = at<int32_t>(ws, L.offsets);
@@ -282,7 +297,24 @@ int bm_moe_forward(const bm_layer_desc *desc, const void *x, const bm_weights *w
     dp.b0 = wt->w_down; dp.b1 = nullptr; dp.sb0 = wt->ws_down; dp.sb1 = nullptr;
     dp.c = at<void>(ws, L.o);
     dp.N = desc->d; dp.Kd = desc->F;
-    if (bf16) {
+    int ksplit = 1;
+    if (skinny) {
+        ksplit = skinny_ksplit(desc);
+        SkinnyParams s1{};
+        s1.a = x; s1.row_map = cp.row_token;
+        s1.b0 = wt->w_gate; s1.b1 = wt->w_up; s1.sb0 = wt->ws_gate; s1.sb1 = wt->ws_up;
+        s1.c = gp.c; s1.N = desc->F; s1.Kd = desc->d; s1.E = E;
+        s1.max_groups = G < L.mtiles_max ? G : L.mtiles_max;
+        s1.ksplit = 1; s1.rows_max = L.rows_max; s1.max_rows_per_group = T * K;
+        s1.mt_group = sp.mt_group; s1.n_mtiles = sp.n_mtiles; s1.offsets = sp.offsets;
+        SkinnyParams s2 = s1;
+        s2.a = gp.c; s2.row_map = nullptr;
+        s2.b0 = wt->w_down; s2.b1 = nullptr; s2.sb0 = wt->ws_down; s2.sb1 = nullptr;
+        s2.c = dp.c; s2.N = desc->d; s2.Kd = desc->F; s2.ksplit = ksplit;
+        err |= launch_skinny_gateup_bf16(s1, st);
+        mark(2);
+        err |= launch_skinny_down_bf16(s2, st);
+    } else if (bf16) {
         err |= launch_gateup_bf16(gp, st);
         mark(2);
         err |= launch_down_bf16(dp, st);
@@ -296,9 +328,10 @@ int bm_moe_forward(const bm_layer_desc *desc, const void *x, const bm_weights *w
     // 6. aggregation
     CombineParams mp{};
     mp.T = T; mp.d = desc->d; mp.K = K; mp.E = E; mp.n_shared = desc->n_shared;
+    mp.ksplit = ksplit; mp.slice_stride = (size_t)L.rows_max * desc->d;
     mp.o = dp.c; mp.w = fp.w; mp.inv_perm = cp.inv_perm; mp.offsets = sp.offsets;
     mp.y = y; mp.y_f32 = (!bf16 || (desc->flags & BM_Y_F32)) ? 1 : 0;
-    err |= launch_combine(mp, desc->dtype, st);
+    err |= launch_combine(mp, bf16 && !skinny, st);
     mark(4);
 
     if (dbg) {

@@ -71,7 +71,7 @@ int launch_down_f32(const GemmParams &p, int max_rows, hipStream_t st) {
 // Aggregation: a gather per token in slot order, then the shared experts, so
 // the floating-point sum has one fixed order.
 // ---------------------------------------------------------------------------
-template <bool BF16>
+template <bool O_BF16>
 __global__ void __launch_bounds__(256) combine_kernel(CombineParams p) {
     __shared__ int s_pos[BM_MAX_K + 8];
     __shared__ float s_w[BM_MAX_K + 8];
@@ -85,6 +85,7 @@ __global__ void __launch_bounds__(256) combine_kernel(CombineParams p) {
         s_w[tid] = 1.0f;
     }
     __syncthreads();
+    const bool vec = (p.d & 7) == 0;
     for (int j0 = tid * 8; j0 < p.d; j0 += blockDim.x * 8) {
         float acc[8];
 #pragma unroll
@@ -93,18 +94,31 @@ __global__ void __launch_bounds__(256) combine_kernel(CombineParams p) {
             const int pos = s_pos[k];
             if (pos < 0) continue;
             const float wk = s_w[k];
-            if (BF16) {
+            if (O_BF16) {
                 const u32x4 v = ldg128(static_cast<const uint16_t *>(p.o) + (size_t)pos * p.d + j0);
-                const uint32_t u[4] = {v.x, v.y, v.z, v.w};
 #pragma unroll
                 for (int i = 0; i < 4; ++i) {
-                    acc[2 * i] = fmaf(wk, bf16_to_f32((uint16_t)(u[i] & 0xffffu)), acc[2 * i]);
-                    acc[2 * i + 1] = fmaf(wk, bf16_to_f32((uint16_t)(u[i] >> 16)), acc[2 * i + 1]);
+                    acc[2 * i] = fmaf(wk, bf16_to_f32((uint16_t)(v[i] & 0xffffu)), acc[2 * i]);
+                    acc[2 * i + 1] = fmaf(wk, bf16_to_f32((uint16_t)(v[i] >> 16)), acc[2 * i + 1]);
                 }
             } else {
-                const float *o = static_cast<const float *>(p.o) + (size_t)pos * p.d + j0;
+                // partial sums of the split reduction are added in slice order first
+                float o[8];
 #pragma unroll
-                for (int i = 0; i < 8; ++i) if (j0 + i < p.d) acc[i] = fmaf(wk, o[i], acc[i]);
+                for (int i = 0; i < 8; ++i) o[i] = 0.0f;
+                for (int sl = 0; sl < p.ksplit; ++sl) {
+                    const float *src = static_cast<const float *>(p.o) + sl * p.slice_stride + (size_t)pos * p.d + j0;
+                    if (vec) {
+                        const f32x4 lo = *(const BM_GLOBAL f32x4 *)src, hi = *(const BM_GLOBAL f32x4 *)(src + 4);
+#pragma unroll
+                        for (int i = 0; i < 4; ++i) { o[i] += lo[i]; o[4 + i] += hi[i]; }
+                    } else {
+#pragma unroll
+                        for (int i = 0; i < 8; ++i) if (j0 + i < p.d) o[i] += src[i];
+                    }
+                }
+#pragma unroll
+                for (int i = 0; i < 8; ++i) acc[i] = fmaf(wk, o[i], acc[i]);
             }
         }
         if (p.y_f32) {
@@ -122,9 +136,9 @@ __global__ void __launch_bounds__(256) combine_kernel(CombineParams p) {
     }
 }
 
-int launch_combine(const CombineParams &p, int dtype, hipStream_t st) {
+int launch_combine(const CombineParams &p, bool o_bf16, hipStream_t st) {
     if (p.T > 0) {
-        if (dtype == BM_BF16) hipLaunchKernelGGL(combine_kernel<true>, dim3(p.T), dim3(256), 0, st, p);
+        if (o_bf16) hipLaunchKernelGGL(combine_kernel<true>, dim3(p.T), dim3(256), 0, st, p);
         else hipLaunchKernelGGL(combine_kernel<false>, dim3(p.T), dim3(256), 0, st, p);
     }
     return launch_status(__func__);

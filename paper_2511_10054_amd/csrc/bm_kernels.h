@@ -64,9 +64,24 @@ struct GemmParams {
     const int32_t *mt_group, *mt_row0, *n_mtiles, *offsets;
 };
 
+// Skinny (decode) projections: one weight-row block per wave, see bm_skinny_bf16.hip.
+struct SkinnyParams {
+    const void *a;                // activations [..][Kd] bf16
+    const int32_t *row_map;       // row -> row of a (null: identity)
+    const void *b0, *b1, *sb0, *sb1;
+    void *c;                      // DUAL: bf16 [rows][N]; else fp32 [ksplit][rows_max][N]
+    int N, Kd, E;
+    int max_groups;               // grid bound on live groups
+    int ksplit, rows_max;
+    int max_rows_per_group;       // launch-time bound: T*K routed rows (or T for a shared expert)
+    const int32_t *mt_group, *n_mtiles, *offsets;
+};
+
 struct CombineParams {
     int T, d, K, E, n_shared;
-    const void *o;                // [rows][d]
+    int ksplit;                   // fp32 o: number of partial-sum slices to add (>= 1)
+    size_t slice_stride;          // elements between slices
+    const void *o;                // [rows][d] (bf16), or [ksplit][rows_max][d] (fp32)
     const float *w;               // [T][K]
     const int32_t *inv_perm;      // [T*K]
     const int32_t *offsets;       // [E + n_shared + 1]
@@ -93,6 +108,9 @@ int launch_down_bf16(const GemmParams &p, hipStream_t st);     // c = a b0^T, bf
 int launch_gateup_f32(const GemmParams &p, int max_rows, hipStream_t st);
 int launch_down_f32(const GemmParams &p, int max_rows, hipStream_t st);
 
-int launch_combine(const CombineParams &p, int dtype, hipStream_t st);
+int launch_skinny_gateup_bf16(const SkinnyParams &p, hipStream_t st);
+int launch_skinny_down_bf16(const SkinnyParams &p, hipStream_t st);
+
+int launch_combine(const CombineParams &p, bool o_bf16, hipStream_t st);
 
 }  // namespace bm

@@ -19,7 +19,8 @@ def err_metric(y, ref):
 class HostLayer:
     """Host-side view of one workload: storage arrays and fp32 views for the oracle."""
 
-    def __init__(self, spec, T, stream=0, mask=None, only_resident=False, poison=False):
+    def __init__(self, spec, T, stream=0, mask=None, only_resident=False, poison=False, base=None):
+        """base: another HostLayer of the same spec whose weight arrays are reused."""
         self.spec = spec
         lay = _get_layer(spec)
         if mask is not None:
@@ -27,10 +28,13 @@ class HostLayer:
         self.lay = lay
         self.T = T
         self.x, self.redraws = lay.tokens(T, stream) if T > 0 else (np.zeros((0, spec.d), np.uint16 if spec.dtype == "bf16" else np.float32), 0)
-        self.wg, self.wu, self.wd = lay.stacked_experts(only_resident=only_resident, poison=poison)
-        self.sg = self.su = self.sd = None
-        if spec.n_shared:
-            self.sg, self.su, self.sd = lay.stacked_experts(shared=True)
+        if base is not None:
+            self.wg, self.wu, self.wd, self.sg, self.su, self.sd = base.wg, base.wu, base.wd, base.sg, base.su, base.sd
+        else:
+            self.wg, self.wu, self.wd = lay.stacked_experts(only_resident=only_resident, poison=poison)
+            self.sg = self.su = self.sd = None
+            if spec.n_shared:
+                self.sg, self.su, self.sd = lay.stacked_experts(shared=True)
         self.mask = lay.resident_mask
         self.bitmap = lay.bitmap
         self.table = lay.buddy_table
@@ -67,7 +71,8 @@ def to_device(a, device="cuda"):
 class DeviceLayer:
     """Uploads a HostLayer and runs the library through the Python binding."""
 
-    def __init__(self, host: HostLayer, unique=False, renorm=True, H=None, y_f32=False):
+    def __init__(self, host: HostLayer, unique=False, renorm=True, H=None, y_f32=False, base=None):
+        """base: another DeviceLayer whose uploaded weights are reused."""
         import torch
         import paper_2511_10054_amd as bm
         self.bm = bm
@@ -80,8 +85,11 @@ class DeviceLayer:
         self.x = to_device(host.x)
         self.w_router = to_device(host.w_router)
         self.bias = to_device(host.bias)
-        self.wg, self.wu, self.wd = to_device(host.wg), to_device(host.wu), to_device(host.wd)
-        self.sg, self.su, self.sd = to_device(host.sg), to_device(host.su), to_device(host.sd)
+        if base is not None:
+            self.wg, self.wu, self.wd, self.sg, self.su, self.sd = base.wg, base.wu, base.wd, base.sg, base.su, base.sd
+        else:
+            self.wg, self.wu, self.wd = to_device(host.wg), to_device(host.wu), to_device(host.wd)
+            self.sg, self.su, self.sd = to_device(host.sg), to_device(host.su), to_device(host.sd)
         self.bitmap = to_device(host.bitmap)
         self.table = to_device(host.table)
         from paper_2511_10054_amd.binding import make_weights
