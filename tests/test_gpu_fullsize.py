@@ -1,0 +1,79 @@
+"""Parity at the full benchmark sizes, in the launch configuration bench.py times:
+all index outputs on every token, layer outputs on a seeded sample of tokens that
+the oracle can compute one by one (tokens are independent).  Needs an MI355X."""
+import numpy as np
+import pytest
+
+import oracle
+import workloads
+from helpers import DeviceLayer, HostLayer, err_metric
+
+pytestmark = pytest.mark.gpu
+
+_cache = {}
+
+
+def _layers(name):
+    """Host + device weights of a config, built once per test session."""
+    if name not in _cache:
+        _cache.clear()                       # one big layer at a time
+        spec = workloads.CONFIGS[name]
+        host = HostLayer(spec, 1, only_resident=True, poison=True)
+        _cache[name] = (host, DeviceLayer(host))
+    return _cache[name]
+
+
+def _check(name, T, n_sample, unique=False):
+    spec = workloads.CONFIGS[name]
+    base_host, base_dev = _layers(name)
+    print(f"fullsize {name} T={T} unique={unique}", flush=True)
+    host = HostLayer(spec, T, base=base_host)
+    dev = DeviceLayer(host, unique=unique, base=base_dev)
+    out = dev.forward()
+    # indices on all tokens
+    lay = host.lay
+    ids_ref, w_ref = oracle.route_topk(host.f32(host.x), host.f32(host.w_router), host.bias, spec.K)
+    ids2_ref, w2_ref, st = oracle.buddy_remap(ids_ref, host.mask, host.table, H=spec.H, unique=unique, w=w_ref)
+    off_ref, perm_ref, inv_ref = oracle.permute(ids2_ref, spec.E)
+    np.testing.assert_array_equal(out["ids"], ids_ref)
+    np.testing.assert_array_equal(out["ids_remapped"], ids2_ref)
+    np.testing.assert_allclose(out["w"], w2_ref, rtol=2e-5, atol=1e-7)
+    assert out["stats"].tolist() == [st["n_miss"], st["n_substituted"], st["n_dropped"]]
+    np.testing.assert_array_equal(out["offsets"], off_ref)
+    np.testing.assert_array_equal(out["perm"], perm_ref)
+    np.testing.assert_array_equal(out["inv_perm"], inv_ref)
+    assert host.mask[ids2_ref[ids2_ref >= 0]].all()
+    # outputs on a seeded sample that touches every expert in use
+    g = np.random.default_rng(1234 + T)
+    rows = g.permutation(T)[: min(T, n_sample)]
+    used = np.unique(ids2_ref[ids2_ref >= 0])
+    extra = [int(np.nonzero((ids2_ref == e).any(1))[0][0]) for e in used]
+    rows = np.unique(np.concatenate([rows, np.array(extra, dtype=rows.dtype)]))
+    ref = host.oracle_forward(oracle, unique=unique, rows=rows)
+    np.testing.assert_array_equal(ref["ids_remapped"], ids2_ref[rows])
+    err = err_metric(out["y"][rows], ref["y"])
+    print(f"   sample {len(rows)} tokens, err {err:.3e}, stats {st}", flush=True)
+    assert np.isfinite(out["y"]).all()
+    assert err <= 2e-2, err
+
+
+@pytest.mark.parametrize("T", [1, 8, 32, 64])
+def test_c2_mixtral_decode(T):
+    _check("c2_mixtral_decode", T, 64)
+
+
+def test_c2_mixtral_decode_unique():
+    _check("c2_mixtral_decode", 64, 64, unique=True)
+
+
+def test_c3_mixtral_prefill():
+    _check("c3_mixtral_prefill", 4096, 96)
+
+
+def test_c4_qwen3():
+    _check("c4_qwen3", 2048, 256)
+
+
+def test_c5_deepseek():
+    _check("c5_deepseek", 8192, 256)
+    _check("c5_deepseek", 8192, 64, unique=True)
