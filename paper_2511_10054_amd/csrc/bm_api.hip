@@ -27,7 +27,17 @@ constexpr int SKINNY_KSPLIT = 8;
 bool use_skinny(const bm_layer_desc *d) {
     return d->dtype == BM_BF16 && (long long)d->T * (d->K + (d->n_shared > 0 ? d->n_shared : 0)) <= SKINNY_MAX_ROWS;
 }
+// Reduction slices of the decode down projection (each slice is a workgroup
+// whose 4 waves split it once more): prefer a count that fits the
+// quarter-split kernel, else up to 8 slices of at least 16 k-steps.
 int skinny_ksplit(const bm_layer_desc *d) {
+    // small groups: the persistent kernel splits the reduction inside one workgroup, no slices
+    if ((long long)d->T * d->K <= 32 && (bm::skinny_p_ok(d->F, 14) || bm::skinny_p_ok(d->F, 8))) return 1;
+    if ((long long)d->T * d->K > 32)
+        for (int s = SKINNY_KSPLIT; s > 1; --s)
+            if (bm::skinny_lds_ok(d->F, s) && d->F / (512 * s) >= 2) return s;
+    for (int s = SKINNY_KSPLIT; s >= 1; --s)
+        if (bm::skinny_q_ok(d->F, s)) return s;
     const int ksteps = d->F / 32;
     int s = ksteps / 16;
     return s < 1 ? 1 : (s > SKINNY_KSPLIT ? SKINNY_KSPLIT : s);

@@ -108,6 +108,9 @@ int launch_down_bf16(const GemmParams &p, hipStream_t st);     // c = a b0^T, bf
 int launch_gateup_f32(const GemmParams &p, int max_rows, hipStream_t st);
 int launch_down_f32(const GemmParams &p, int max_rows, hipStream_t st);
 
+bool skinny_p_ok(int Kd, int ch);       // shape fits the persistent decode kernel with ring depth ch
+bool skinny_lds_ok(int Kd, int ksplit); // shape fits the LDS-staged decode kernel
+bool skinny_q_ok(int Kd, int ksplit);   // shape fits the quarter-split decode kernel
 int launch_skinny_gateup_bf16(const SkinnyParams &p, hipStream_t st);
 int launch_skinny_down_bf16(const SkinnyParams &p, hipStream_t st);
 

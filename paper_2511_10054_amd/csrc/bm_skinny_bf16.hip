@@ -135,6 +135,499 @@ __global__ void __launch_bounds__(256) skinny_bf16_kernel(SkinnyParams p) {
     }
 }
 
+// ---------------------------------------------------------------------------
+// Main decode kernel.  One workgroup = 16 weight rows (of each matrix); its 4
+// waves split the reduction into 4 contiguous quarters and meet in LDS at the
+// end (partials added in wave order).  Work items are therefore small (a
+// quarter of a row block per wave) and numerous, so the last round of
+// workgroups on the chip is short - with whole row blocks per wave the tail
+// round cost up to a third of the kernel.  No barrier inside the main loop.
+// Weights and activations run through a rotating set of CH register slots: a
+// slot is refilled with the k-step CH ahead right after the MFMAs that
+// consumed it, so CH-1 of every CH slots are in flight.
+// Needs (Kd / 32) divisible by 4 * CH * ksplit; other shapes use the kernel above.
+// ---------------------------------------------------------------------------
+constexpr int QCH = 8;
+
+template <bool DUAL, int NBT>
+__device__ __forceinline__ void skinny_q_pass(const SkinnyParams &p, const uint16_t *w0, const uint16_t *w1,
+                                              f32x4 *red, int row_begin, int row_end, int k_begin, int k_end,
+                                              int n0, int kslice) {
+    constexpr int CH = QCH;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, lr = lane & 15, lk = lane >> 4;
+    const uint16_t *a = static_cast<const uint16_t *>(p.a);
+    const uint16_t *xa[NBT];
+#pragma unroll
+    for (int tb = 0; tb < NBT; ++tb) {
+        const int pos = min(row_begin + tb * 16 + lr, row_end - 1);
+        const int src = p.row_map ? ldg_i32(p.row_map + pos) : pos;
+        xa[tb] = a + (size_t)src * p.Kd + lk * 8;
+    }
+    f32x4 acc0[NBT], acc1[NBT];
+#pragma unroll
+    for (int tb = 0; tb < NBT; ++tb) {
+        acc0[tb] = f32x4{0.f, 0.f, 0.f, 0.f};
+        acc1[tb] = f32x4{0.f, 0.f, 0.f, 0.f};
+    }
+    u32x4 s0[CH], s1[CH], sx[NBT][CH];
+#pragma unroll
+    for (int u = 0; u < CH; ++u) {
+        s0[u] = ldg128_stream(w0 + k_begin + u * 32);
+        if (DUAL) s1[u] = ldg128_stream(w1 + k_begin + u * 32);
+#pragma unroll
+        for (int tb = 0; tb < NBT; ++tb) sx[tb][u] = ldg128(xa[tb] + k_begin + u * 32);
+    }
+    // steady state: unconditional refills (branches around the loads would make the
+    // order of outstanding loads ambiguous to the wait-count insertion)
+    int k = k_begin;
+    for (; k + 2 * CH * 32 <= k_end; k += CH * 32) {
+#pragma unroll
+        for (int u = 0; u < CH; ++u) {
+#pragma unroll
+            for (int tb = 0; tb < NBT; ++tb) {
+                acc0[tb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(s0[u]), as_bf16x8(sx[tb][u]), acc0[tb], 0, 0, 0);
+                if (DUAL)
+                    acc1[tb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(s1[u]), as_bf16x8(sx[tb][u]), acc1[tb], 0, 0, 0);
+            }
+            const int kn = k + (CH + u) * 32;
+            s0[u] = ldg128_stream(w0 + kn);
+            if (DUAL) s1[u] = ldg128_stream(w1 + kn);
+#pragma unroll
+            for (int tb = 0; tb < NBT; ++tb) sx[tb][u] = ldg128(xa[tb] + kn);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    }
+    // last chunk: drain
+#pragma unroll
+    for (int u = 0; u < CH; ++u)
+#pragma unroll
+        for (int tb = 0; tb < NBT; ++tb) {
+            acc0[tb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(s0[u]), as_bf16x8(sx[tb][u]), acc0[tb], 0, 0, 0);
+            if (DUAL)
+                acc1[tb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(s1[u]), as_bf16x8(sx[tb][u]), acc1[tb], 0, 0, 0);
+        }
+
+    // reduction over the 4 reduction quarters, in wave order
+    if (wave > 0) {
+#pragma unroll
+        for (int tb = 0; tb < NBT; ++tb) {
+            red[((wave - 1) * NBT + tb) * 2 * 64 + lane] = acc0[tb];
+            if (DUAL) red[((wave - 1) * NBT + tb) * 2 * 64 + 64 + lane] = acc1[tb];
+        }
+    }
+    __syncthreads();
+    if (wave == 0) {
+#pragma unroll
+        for (int tb = 0; tb < NBT; ++tb) {
+#pragma unroll
+            for (int w = 0; w < 3; ++w) {
+                acc0[tb] += red[(w * NBT + tb) * 2 * 64 + lane];
+                if (DUAL) acc1[tb] += red[(w * NBT + tb) * 2 * 64 + 64 + lane];
+            }
+            const int pos = row_begin + tb * 16 + lr;
+            if (pos >= row_end) continue;
+            const int n = n0 + lk * 4;
+            if (DUAL) {
+                u16x4 h;
+#pragma unroll
+                for (int i = 0; i < 4; ++i) h[i] = f32_to_bf16(silu(acc0[tb][i]) * acc1[tb][i]);
+                *(BM_GLOBAL u16x4 *)(static_cast<uint16_t *>(p.c) + (size_t)pos * p.N + n) = h;
+            } else {
+                float *c = static_cast<float *>(p.c) + ((size_t)kslice * p.rows_max + pos) * p.N + n;
+                *(BM_GLOBAL f32x4 *)c = acc0[tb];
+            }
+        }
+    }
+}
+
+// grid.x = 16-row blocks of the weight matrix, grid.y = live-group slots, grid.z = reduction slices
+template <bool DUAL, int MAXNBT>
+__global__ void __launch_bounds__(256) skinny_q_bf16_kernel(SkinnyParams p) {
+    __shared__ f32x4 red[3 * MAXNBT * 2 * 64];
+    const int gi = blockIdx.y;
+    if (gi >= p.n_mtiles[0]) return;
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, lr = lane & 15, lk = lane >> 4;
+    const int n0 = blockIdx.x * 16;
+    const int g = p.mt_group[gi];
+    const int row_begin = p.offsets[g], row_end = p.offsets[g + 1];
+    const int kslice = blockIdx.z;
+    const int per_wave = p.Kd / (4 * p.ksplit);        // host guarantees a multiple of 32 * QCH
+    const int k_begin = (kslice * 4 + wave) * per_wave, k_end = k_begin + per_wave;
+
+    const size_t gofs = (size_t)(g < p.E ? g : g - p.E) * p.N * p.Kd;
+    const uint16_t *b0 = static_cast<const uint16_t *>(g < p.E ? p.b0 : p.sb0) + gofs;
+    const uint16_t *w0 = b0 + (size_t)(n0 + lr) * p.Kd + lk * 8;
+    const uint16_t *w1 = nullptr;
+    if (DUAL) {
+        const uint16_t *b1 = static_cast<const uint16_t *>(g < p.E ? p.b1 : p.sb1) + gofs;
+        w1 = b1 + (size_t)(n0 + lr) * p.Kd + lk * 8;
+    }
+    constexpr int PASS_ROWS = 16 * MAXNBT;
+    for (int rb = row_begin; rb < row_end; rb += PASS_ROWS) {
+        const int re = min(row_end, rb + PASS_ROWS);
+        const int n_rows = re - rb;
+        if (MAXNBT == 1 || n_rows <= 16) skinny_q_pass<DUAL, 1>(p, w0, w1, red, rb, re, k_begin, k_end, n0, kslice);
+        else if (MAXNBT == 2 || n_rows <= 32) skinny_q_pass<DUAL, 2>(p, w0, w1, red, rb, re, k_begin, k_end, n0, kslice);
+        else skinny_q_pass<DUAL, 4>(p, w0, w1, red, rb, re, k_begin, k_end, n0, kslice);
+        __syncthreads();                               // the next pass reuses the reduction buffer
+    }
+}
+
+bool skinny_q_ok(int Kd, int ksplit) { return Kd % (4 * ksplit * 32 * QCH) == 0; }
+
+template <bool DUAL>
+static void launch_skinny_q(const SkinnyParams &p, hipStream_t st) {
+    dim3 grid(p.N / 16, p.max_groups, p.ksplit);
+    if (p.max_rows_per_group <= 16) hipLaunchKernelGGL((skinny_q_bf16_kernel<DUAL, 1>), grid, dim3(256), 0, st, p);
+    else if (p.max_rows_per_group <= 32) hipLaunchKernelGGL((skinny_q_bf16_kernel<DUAL, 2>), grid, dim3(256), 0, st, p);
+    else hipLaunchKernelGGL((skinny_q_bf16_kernel<DUAL, 4>), grid, dim3(256), 0, st, p);
+}
+
+// ---------------------------------------------------------------------------
+// Decode kernel for larger groups (up to 64 rows per pass).  A workgroup's 4
+// waves own 4 different 16-row weight blocks and walk the whole reduction
+// together; the activation rows are staged by the workgroup in LDS in chunks
+// of CH k-steps, already in MFMA B-operand order (one 1 KB fragment per
+// k-step and 16-row block: contiguous ds_read_b128), double-buffered, so they
+// cost each wave a quarter of the loads and no ring registers.  Weights run
+// through the same rotating register ring as above.
+// Needs Kd divisible by 512 * ksplit.
+// ---------------------------------------------------------------------------
+template <int NBT> struct SkinnyChunk { static constexpr int CH = NBT == 1 ? 16 : 8; };
+constexpr int KUNIT = 512;
+
+template <bool DUAL, int NBT>
+__device__ __forceinline__ void skinny_lds_pass(const SkinnyParams &p, const uint16_t *w0, const uint16_t *w1,
+                                                u32x4 *xs, int row_begin, int row_end, int k_begin,
+                                                int k_end, int n0, int kslice, bool active) {
+    constexpr int CH = SkinnyChunk<NBT>::CH;
+    constexpr int XW = CH / 4;                          // k-steps of a chunk each wave stages
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, lr = lane & 15, lk = lane >> 4;
+    const uint16_t *a = static_cast<const uint16_t *>(p.a);
+    const uint16_t *xa[NBT];
+#pragma unroll
+    for (int tb = 0; tb < NBT; ++tb) {
+        const int pos = min(row_begin + tb * 16 + lr, row_end - 1);
+        const int src = p.row_map ? ldg_i32(p.row_map + pos) : pos;
+        xa[tb] = a + (size_t)src * p.Kd + lk * 8 + (XW * wave) * 32;
+    }
+    f32x4 acc0[NBT], acc1[NBT];
+#pragma unroll
+    for (int tb = 0; tb < NBT; ++tb) {
+        acc0[tb] = f32x4{0.f, 0.f, 0.f, 0.f};
+        acc1[tb] = f32x4{0.f, 0.f, 0.f, 0.f};
+    }
+    u32x4 s0[CH], s1[CH], xr[XW * NBT];
+    const int nch = (k_end - k_begin) / (CH * 32);
+
+#define BM_LOAD_X(k_)                                                                      \
+    _Pragma("unroll") for (int i = 0; i < XW; ++i)                                         \
+        _Pragma("unroll") for (int tb = 0; tb < NBT; ++tb) xr[i * NBT + tb] = ldg128(xa[tb] + (k_) + i * 32);
+#define BM_STORE_X(buf_)                                                                   \
+    _Pragma("unroll") for (int i = 0; i < XW; ++i)                                         \
+        _Pragma("unroll") for (int tb = 0; tb < NBT; ++tb)                                 \
+            xs[(((buf_) * CH + XW * wave + i) * NBT + tb) * 64 + lane] = xr[i * NBT + tb];
+
+    BM_LOAD_X(k_begin);
+#pragma unroll
+    for (int u = 0; u < CH; ++u) {
+        s0[u] = ldg128_stream(w0 + k_begin + u * 32);
+        if (DUAL) s1[u] = ldg128_stream(w1 + k_begin + u * 32);
+    }
+    BM_STORE_X(0);
+    __syncthreads();
+
+// one chunk: consume slot u, then (REFILL_) refill it with the k-step CH ahead; the refill is
+// unconditional inside the steady-state loop (see the note on wait counts in the kernel above)
+#define BM_CHUNK(c_, REFILL_)                                                                        \
+    {                                                                                                \
+        const int kn_ = k_begin + ((c_) + 1) * (CH * 32);                                            \
+        if (REFILL_) { BM_LOAD_X(kn_); }                                                             \
+        {                                                                                            \
+            const u32x4 *xc = xs + (size_t)((c_) & 1) * CH * NBT * 64 + lane;                        \
+            _Pragma("unroll") for (int u = 0; u < CH; ++u) {                                         \
+                bf16x8 xb[NBT];                                                                      \
+                _Pragma("unroll") for (int tb = 0; tb < NBT; ++tb)                                   \
+                    xb[tb] = as_bf16x8(xc[(u * NBT + tb) * 64]);                                     \
+                _Pragma("unroll") for (int tb = 0; tb < NBT; ++tb) {                                 \
+                    acc0[tb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(s0[u]), xb[tb],     \
+                                                                       acc0[tb], 0, 0, 0);           \
+                    if (DUAL)                                                                        \
+                        acc1[tb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(s1[u]), xb[tb], \
+                                                                           acc1[tb], 0, 0, 0);       \
+                }                                                                                    \
+                if (REFILL_) {                                                                       \
+                    s0[u] = ldg128_stream(w0 + kn_ + u * 32);                                        \
+                    if (DUAL) s1[u] = ldg128_stream(w1 + kn_ + u * 32);                              \
+                }                                                                                    \
+                __builtin_amdgcn_sched_barrier(0);                                                   \
+            }                                                                                        \
+        }                                                                                            \
+        if (REFILL_) { BM_STORE_X(((c_) + 1) & 1); }                                                 \
+        __syncthreads();                                                                             \
+    }
+
+    for (int c = 0; c + 1 < nch; ++c) BM_CHUNK(c, true);
+    BM_CHUNK(nch - 1, false);
+#undef BM_CHUNK
+#undef BM_LOAD_X
+#undef BM_STORE_X
+    if (!active) return;
+#pragma unroll
+    for (int tb = 0; tb < NBT; ++tb) {
+        const int pos = row_begin + tb * 16 + lr;
+        if (pos >= row_end) continue;
+        const int n = n0 + lk * 4;
+        if (DUAL) {
+            u16x4 h;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) h[i] = f32_to_bf16(silu(acc0[tb][i]) * acc1[tb][i]);
+            *(BM_GLOBAL u16x4 *)(static_cast<uint16_t *>(p.c) + (size_t)pos * p.N + n) = h;
+        } else {
+            float *c = static_cast<float *>(p.c) + ((size_t)kslice * p.rows_max + pos) * p.N + n;
+            *(BM_GLOBAL f32x4 *)c = acc0[tb];
+        }
+    }
+}
+
+template <bool DUAL, int MAXNBT>
+__global__ void __launch_bounds__(256) skinny_lds_bf16_kernel(SkinnyParams p) {
+    __shared__ u32x4 xs[2 * 8 * MAXNBT * 64 * (MAXNBT == 1 ? 2 : 1)];
+    const int gi = blockIdx.y;
+    if (gi >= p.n_mtiles[0]) return;
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, lr = lane & 15, lk = lane >> 4;
+    const int n0w = (blockIdx.x * 4 + wave) * 16;
+    const bool active = n0w < p.N;                    // a wave past the last weight row recomputes block 0 and stores nothing
+    const int n0 = active ? n0w : 0;
+    const int g = p.mt_group[gi];
+    const int row_begin = p.offsets[g], row_end = p.offsets[g + 1];
+    const int kslice = blockIdx.z;
+    const int per = (p.Kd / KUNIT) / p.ksplit;        // the host picks ksplit as a divisor
+    const int k_begin = kslice * per * KUNIT, k_end = k_begin + per * KUNIT;
+
+    const size_t gofs = (size_t)(g < p.E ? g : g - p.E) * p.N * p.Kd;
+    const uint16_t *b0 = static_cast<const uint16_t *>(g < p.E ? p.b0 : p.sb0) + gofs;
+    const uint16_t *w0 = b0 + (size_t)(n0 + lr) * p.Kd + lk * 8;
+    const uint16_t *w1 = nullptr;
+    if (DUAL) {
+        const uint16_t *b1 = static_cast<const uint16_t *>(g < p.E ? p.b1 : p.sb1) + gofs;
+        w1 = b1 + (size_t)(n0 + lr) * p.Kd + lk * 8;
+    }
+    constexpr int PASS_ROWS = 16 * MAXNBT;
+    for (int rb = row_begin; rb < row_end; rb += PASS_ROWS) {
+        const int re = min(row_end, rb + PASS_ROWS);
+        const int n_rows = re - rb;
+        if (MAXNBT == 1 || n_rows <= 16) skinny_lds_pass<DUAL, 1>(p, w0, w1, xs, rb, re, k_begin, k_end, n0, kslice, active);
+        else if (MAXNBT == 2 || n_rows <= 32) skinny_lds_pass<DUAL, 2>(p, w0, w1, xs, rb, re, k_begin, k_end, n0, kslice, active);
+        else skinny_lds_pass<DUAL, 4>(p, w0, w1, xs, rb, re, k_begin, k_end, n0, kslice, active);
+        __syncthreads();                              // the next pass restages the LDS buffers
+    }
+}
+
+bool skinny_lds_ok(int Kd, int ksplit) { return Kd % (KUNIT * ksplit) == 0; }
+
+template <bool DUAL>
+static void launch_skinny_lds(const SkinnyParams &p, hipStream_t st) {
+    dim3 grid((p.N / 16 + 3) / 4, p.max_groups, p.ksplit);
+    hipLaunchKernelGGL((skinny_lds_bf16_kernel<DUAL, 4>), grid, dim3(256), 0, st, p);
+}
+
+// ---------------------------------------------------------------------------
+// Persistent decode kernel for small groups (at most 16*NBT rows each).
+// Measured on MI355X, a streaming read is capped per compute unit (about
+// 24 GB/s each, 6 TB/s over 256), so the bytes must be spread evenly: one
+// workgroup of 8 waves per compute unit walks items (group, 16-row block of
+// the weight matrix) with stride gridDim.x; the 8 waves split the reduction
+// into contiguous eighths.  The register ring (CH k-steps of weights and
+// activation fragments, refilled right after use) runs across item
+// boundaries, so the stream never drains; at the end of an item the eight
+// partial tiles meet in a double-buffered LDS area, are added in wave order,
+// and each wave finishes an eighth of the 16 x 16*NBT outputs.
+// Needs Kd divisible by 8 * 32 * CH.
+// ---------------------------------------------------------------------------
+struct PItem {
+    const uint16_t *w0, *w1;
+    int g, row_begin, row_end, n0;
+};
+
+template <bool DUAL>
+__device__ __forceinline__ PItem p_setup(const SkinnyParams &p, int it, int NRB, int lr, int lk, int k0) {
+    PItem r;
+    const int gi = it / NRB, rb = it - gi * NRB;
+    r.g = p.mt_group[gi];
+    r.row_begin = p.offsets[r.g];
+    r.row_end = p.offsets[r.g + 1];
+    r.n0 = rb * 16;
+    const size_t gofs = (size_t)(r.g < p.E ? r.g : r.g - p.E) * p.N * p.Kd;
+    const size_t rofs = gofs + (size_t)(r.n0 + lr) * p.Kd + lk * 8 + k0;
+    r.w0 = static_cast<const uint16_t *>(r.g < p.E ? p.b0 : p.sb0) + rofs;
+    r.w1 = DUAL ? static_cast<const uint16_t *>(r.g < p.E ? p.b1 : p.sb1) + rofs : nullptr;
+    return r;
+}
+
+template <bool DUAL, int NBT, int CH>
+__global__ void __launch_bounds__(512) skinny_p_kernel(SkinnyParams p) {
+    constexpr int NM = DUAL ? 2 : 1;
+    constexpr int RED = 2 * 8 * NBT * NM * 64;                 // f32x4 entries of the reduction area
+    constexpr int PAD = RED * 16 < 84 * 1024 ? (84 * 1024 - RED * 16) / 16 : 0;
+    __shared__ f32x4 red[RED + PAD];                           // > half the LDS: one workgroup per compute unit
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, lr = lane & 15, lk = lane >> 4;
+    const int NRB = p.N >> 4;
+    const int n_items = p.n_mtiles[0] * NRB;
+    if ((int)blockIdx.x >= n_items) return;
+    const int my_items = (n_items - 1 - (int)blockIdx.x) / (int)gridDim.x + 1;
+    const int kq = p.Kd >> 3;
+    const int k0 = wave * kq;
+    const int cpi = kq / (CH * 32);                            // chunks per item
+    const int total = my_items * cpi;
+    const uint16_t *a = static_cast<const uint16_t *>(p.a);
+
+    int it = blockIdx.x;
+    PItem cur = p_setup<DUAL>(p, it, NRB, lr, lk, k0);
+    const uint16_t *xa[NBT];
+#pragma unroll
+    for (int tb = 0; tb < NBT; ++tb) {
+        const int pos = min(cur.row_begin + tb * 16 + lr, cur.row_end - 1);
+        const int src = p.row_map ? ldg_i32(p.row_map + pos) : pos;
+        xa[tb] = a + (size_t)src * p.Kd + lk * 8 + k0;
+    }
+    f32x4 acc0[NBT], acc1[NBT];
+#pragma unroll
+    for (int tb = 0; tb < NBT; ++tb) {
+        acc0[tb] = f32x4{0.f, 0.f, 0.f, 0.f};
+        acc1[tb] = f32x4{0.f, 0.f, 0.f, 0.f};
+    }
+    u32x4 s0[CH], s1[CH], sx[NBT][CH];
+#pragma unroll
+    for (int u = 0; u < CH; ++u) {
+        s0[u] = ldg128_stream(cur.w0 + u * 32);
+        if (DUAL) s1[u] = ldg128_stream(cur.w1 + u * 32);
+#pragma unroll
+        for (int tb = 0; tb < NBT; ++tb) sx[tb][u] = ldg128(xa[tb] + u * 32);
+    }
+
+#define BM_CONSUME(u_)                                                                                  \
+    _Pragma("unroll") for (int tb = 0; tb < NBT; ++tb) {                                                \
+        acc0[tb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(s0[u_]), as_bf16x8(sx[tb][u_]),    \
+                                                           acc0[tb], 0, 0, 0);                          \
+        if (DUAL)                                                                                       \
+            acc1[tb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(s1[u_]), as_bf16x8(sx[tb][u_]),\
+                                                               acc1[tb], 0, 0, 0);                      \
+    }
+// partial tiles -> LDS, barrier, every wave adds up and finishes an eighth of the outputs
+#define BM_FINALIZE()                                                                                   \
+    {                                                                                                   \
+        f32x4 *rbuf = red + par * (8 * NBT * NM * 64);                                                  \
+        _Pragma("unroll") for (int tb = 0; tb < NBT; ++tb) {                                            \
+            rbuf[((wave * NBT + tb) * NM + 0) * 64 + lane] = acc0[tb];                                  \
+            if (DUAL) rbuf[((wave * NBT + tb) * NM + 1) * 64 + lane] = acc1[tb];                        \
+            acc0[tb] = f32x4{0.f, 0.f, 0.f, 0.f};                                                       \
+            acc1[tb] = f32x4{0.f, 0.f, 0.f, 0.f};                                                       \
+        }                                                                                               \
+        __syncthreads();                                                                                \
+        if (lane < 8 * NBT) {                                                                           \
+            const int q = wave * 8 * NBT + lane, tb = q >> 6, ln = q & 63;                              \
+            f32x4 t0 = f32x4{0.f, 0.f, 0.f, 0.f}, t1 = f32x4{0.f, 0.f, 0.f, 0.f};                       \
+            _Pragma("unroll") for (int sw = 0; sw < 8; ++sw) {                                          \
+                t0 += rbuf[((sw * NBT + tb) * NM + 0) * 64 + ln];                                       \
+                if (DUAL) t1 += rbuf[((sw * NBT + tb) * NM + 1) * 64 + ln];                             \
+            }                                                                                           \
+            const int pos = cur.row_begin + tb * 16 + (ln & 15);                                        \
+            const int n = cur.n0 + (ln >> 4) * 4;                                                       \
+            if (pos < cur.row_end) {                                                                    \
+                if (DUAL) {                                                                             \
+                    u16x4 h;                                                                            \
+                    _Pragma("unroll") for (int i = 0; i < 4; ++i) h[i] = f32_to_bf16(silu(t0[i]) * t1[i]); \
+                    *(BM_GLOBAL u16x4 *)(static_cast<uint16_t *>(p.c) + (size_t)pos * p.N + n) = h;     \
+                } else {                                                                                \
+                    *(BM_GLOBAL f32x4 *)(static_cast<float *>(p.c) + (size_t)pos * p.N + n) = t0;       \
+                }                                                                                       \
+            }                                                                                           \
+        }                                                                                               \
+        par ^= 1;                                                                                       \
+    }
+
+    int c_in_item = 0, par = 0;
+    for (int j = 0; j + 1 < total; ++j) {
+        // where chunk j+1 comes from: the same item, or the first chunk of this workgroup's next item
+        const bool last_in_item = (c_in_item + 1 == cpi);
+        PItem nxt = cur;
+        const uint16_t *rw0, *rw1, *rx[NBT];
+        if (last_in_item) {
+            nxt = p_setup<DUAL>(p, it + gridDim.x, NRB, lr, lk, k0);
+            rw0 = nxt.w0;
+            rw1 = nxt.w1;
+            if (nxt.g != cur.g) {                       // rare: the next item belongs to another group
+#pragma unroll
+                for (int tb = 0; tb < NBT; ++tb) {
+                    const int pos = min(nxt.row_begin + tb * 16 + lr, nxt.row_end - 1);
+                    const int src = p.row_map ? ldg_i32(p.row_map + pos) : pos;
+                    xa[tb] = a + (size_t)src * p.Kd + lk * 8 + k0;
+                }
+            }
+#pragma unroll
+            for (int tb = 0; tb < NBT; ++tb) rx[tb] = xa[tb];
+        } else {
+            const int ofs = (c_in_item + 1) * (CH * 32);
+            rw0 = cur.w0 + ofs;
+            rw1 = DUAL ? cur.w1 + ofs : nullptr;
+#pragma unroll
+            for (int tb = 0; tb < NBT; ++tb) rx[tb] = xa[tb] + ofs;
+        }
+        // consume slot u, refill it with the k-step CH ahead (always: a branch around the refills
+        // would make the order of outstanding loads ambiguous and drain the ring)
+#pragma unroll
+        for (int u = 0; u < CH; ++u) {
+            BM_CONSUME(u);
+            s0[u] = ldg128_stream(rw0 + u * 32);
+            if (DUAL) s1[u] = ldg128_stream(rw1 + u * 32);
+#pragma unroll
+            for (int tb = 0; tb < NBT; ++tb) sx[tb][u] = ldg128(rx[tb] + u * 32);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        if (last_in_item) {
+            BM_FINALIZE();
+            it += gridDim.x;
+            cur = nxt;
+            c_in_item = 0;
+        } else {
+            ++c_in_item;
+        }
+    }
+    // last chunk of the last item: drain the ring
+#pragma unroll
+    for (int u = 0; u < CH; ++u) { BM_CONSUME(u); }
+    BM_FINALIZE();
+#undef BM_CONSUME
+#undef BM_FINALIZE
+}
+
+bool skinny_p_ok(int Kd, int ch) { return Kd % (8 * 32 * ch) == 0; }
+
+// launches the persistent kernel if a ring depth fits the shape; false otherwise
+template <bool DUAL>
+static bool launch_skinny_p(const SkinnyParams &p, hipStream_t st) {
+    if (p.max_rows_per_group > 32) return false;
+    int dev = 0, cus = 0;
+    if (hipGetDevice(&dev) != hipSuccess ||
+        hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0)
+        return false;
+    const dim3 grid(cus), block(512);
+    const bool one = p.max_rows_per_group <= 16;
+    if (DUAL) {
+        if (one && skinny_p_ok(p.Kd, 8)) hipLaunchKernelGGL((skinny_p_kernel<true, 1, 8>), grid, block, 0, st, p);
+        else if (!one && skinny_p_ok(p.Kd, 8)) hipLaunchKernelGGL((skinny_p_kernel<true, 2, 8>), grid, block, 0, st, p);
+        else return false;
+    } else {
+        if (one && skinny_p_ok(p.Kd, 14)) hipLaunchKernelGGL((skinny_p_kernel<false, 1, 14>), grid, block, 0, st, p);
+        else if (one && skinny_p_ok(p.Kd, 8)) hipLaunchKernelGGL((skinny_p_kernel<false, 1, 8>), grid, block, 0, st, p);
+        else if (!one && skinny_p_ok(p.Kd, 14)) hipLaunchKernelGGL((skinny_p_kernel<false, 2, 14>), grid, block, 0, st, p);
+        else if (!one && skinny_p_ok(p.Kd, 8)) hipLaunchKernelGGL((skinny_p_kernel<false, 2, 8>), grid, block, 0, st, p);
+        else return false;
+    }
+    return true;
+}
+
 template <bool DUAL>
 static void launch_skinny(const SkinnyParams &p, dim3 grid, hipStream_t st) {
     if (p.max_rows_per_group <= 16) hipLaunchKernelGGL((skinny_bf16_kernel<DUAL, 1>), grid, dim3(256), 0, st, p);
@@ -143,14 +636,28 @@ static void launch_skinny(const SkinnyParams &p, dim3 grid, hipStream_t st) {
 }
 
 int launch_skinny_gateup_bf16(const SkinnyParams &p, hipStream_t st) {
-    dim3 grid((p.N / 16 + 3) / 4, p.max_groups, 1);
-    launch_skinny<true>(p, grid, st);
+    if (launch_skinny_p<true>(p, st)) {
+    } else if (p.max_rows_per_group > 32 && skinny_lds_ok(p.Kd, 1)) {
+        launch_skinny_lds<true>(p, st);
+    } else if (skinny_q_ok(p.Kd, 1)) {
+        launch_skinny_q<true>(p, st);
+    } else {
+        dim3 grid((p.N / 16 + 3) / 4, p.max_groups, 1);
+        launch_skinny<true>(p, grid, st);
+    }
     return launch_status(__func__);
 }
 
 int launch_skinny_down_bf16(const SkinnyParams &p, hipStream_t st) {
-    dim3 grid((p.N / 16 + 3) / 4, p.max_groups, p.ksplit);
-    launch_skinny<false>(p, grid, st);
+    if (p.ksplit == 1 && launch_skinny_p<false>(p, st)) {
+    } else if (p.max_rows_per_group > 32 && skinny_lds_ok(p.Kd, p.ksplit)) {
+        launch_skinny_lds<false>(p, st);
+    } else if (skinny_q_ok(p.Kd, p.ksplit)) {
+        launch_skinny_q<false>(p, st);
+    } else {
+        dim3 grid((p.N / 16 + 3) / 4, p.max_groups, p.ksplit);
+        launch_skinny<false>(p, grid, st);
+    }
     return launch_status(__func__);
 }
 
