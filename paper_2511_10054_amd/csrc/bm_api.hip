@@ -22,6 +22,12 @@ constexpr int MAX_SHARED = 8;
 constexpr int SKINNY_MAX_ROWS = 128;   // total rows up to which the weight-streaming path is used
 constexpr int SKINNY_KSPLIT = 8;
 
+// Row-tile height of the grouped GEMM: 256 rows when the average group is large
+// (measured on routed experts; shared experts always have T rows), else 128.
+int gemm_tile_rows(const bm_layer_desc *d) {
+    return ((long long)d->T * d->K / d->E >= 512) ? 256 : 128;
+}
+
 // Few rows in total: every expert group is decode-sized and the projections
 // are bound by reading the weights once.
 bool use_skinny(const bm_layer_desc *d) {
@@ -79,8 +85,7 @@ Layout make_layout(const bm_layer_desc *d) {
     const int G = d->E + n_shared;
     L.n_tiles = (d->T + TILE_T - 1) / TILE_T;
     L.rows_max = (int)(A + (size_t)n_shared * d->T);
-    const int BM = gemm_bf16_bm();
-    L.mtiles_max = L.rows_max / BM + G;
+    L.mtiles_max = L.rows_max / 128 + G;         // bound for the smaller of the two row-tile heights
     const size_t esz = d->dtype == BM_BF16 ? 2 : 4;
     size_t off = 0;
     auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes); return o; };
@@ -214,7 +219,7 @@ int bm_permute_by_expert(const bm_layer_desc *desc, const int32_t *ids_remapped,
     (void)hipGetLastError();
     int err = launch_count(ids_remapped, d2.T, d2.K, d2.E, at<int32_t>(workspace, L.tile_counts), st);
     ScanParams sp{};
-    sp.T = d2.T; sp.E = d2.E; sp.n_shared = 0; sp.n_tiles = L.n_tiles; sp.BM = gemm_bf16_bm();
+    sp.T = d2.T; sp.E = d2.E; sp.n_shared = 0; sp.n_tiles = L.n_tiles; sp.BM = 128;
     sp.tile_counts = at<int32_t>(workspace, L.tile_counts);
     sp.tile_base = at<int32_t>(workspace, L.tile_base);
     sp.tile_stats = nullptr;
@@ -277,7 +282,7 @@ int bm_moe_forward(const bm_layer_desc *desc, const void *x, const bm_weights *w
     ScanParams sp{};
     const bool skinny = use_skinny(desc);
     sp.T = T; sp.E = E; sp.n_shared = desc->n_shared; sp.n_tiles = L.n_tiles;
-    sp.BM = skinny ? (1 << 20) : gemm_bf16_bm();      // skinny: one table entry per live group
+    sp.BM = skinny ? (1 << 20) : gemm_tile_rows(desc);   // skinny: one table entry per live group
     sp.tile_counts = fp.tile_counts; sp.tile_base = at<int32_t>(ws, L.tile_base);
     sp.tile_stats = fp.tile_stats;
     sp.offsets = at<int32_t>(ws, L.offsets);
@@ -300,7 +305,7 @@ int bm_moe_forward(const bm_layer_desc *desc, const void *x, const bm_weights *w
     gp.a = x; gp.row_map = cp.row_token;
     gp.b0 = wt->w_gate; gp.b1 = wt->w_up; gp.sb0 = wt->ws_gate; gp.sb1 = wt->ws_up;
     gp.c = at<void>(ws, L.h);
-    gp.N = desc->F; gp.Kd = desc->d; gp.E = E; gp.n_groups = G; gp.max_mtiles = L.mtiles_max;
+    gp.N = desc->F; gp.Kd = desc->d; gp.E = E; gp.n_groups = G; gp.max_mtiles = L.mtiles_max; gp.BM = sp.BM;
     gp.mt_group = sp.mt_group; gp.mt_row0 = sp.mt_row0; gp.n_mtiles = sp.n_mtiles; gp.offsets = sp.offsets;
     GemmParams dp = gp;
     dp.a = gp.c; dp.row_map = nullptr;

@@ -2,43 +2,69 @@
 //
 // Rows are the surviving assignments, grouped by expert; a row-tile table
 // built on the device says which group each tile of BM rows belongs to.  One
-// workgroup (4 waves, 2x2) computes BM=128 rows x 256 weight rows with
-// v_mfma_f32_32x32x16_bf16 and fp32 accumulators:
+// workgroup computes BM rows x 256 weight rows with v_mfma_f32_32x32x16_bf16
+// and fp32 accumulators:
 //   DUAL  : the 256 weight rows are 128 rows of W_gate and the same 128 rows
 //           of W_up; the epilogue writes h = silu(g) * u as bf16.
 //   !DUAL : 256 rows of W_down; the epilogue writes the product as bf16.
+// Four waves (2 x 2) per workgroup, two shapes: BM = 256 (wave tile 128 x 128,
+// all 256 accumulator registers) for large groups - per flop it needs a third
+// less LDS and L2 traffic than the smaller tile, and LDS bandwidth is what
+// bounds these kernels first - and BM = 128 (wave tile 64 x 128) when groups
+// are small and a 256-row tile would be mostly padding.
 // Both operands have the reduction dimension contiguous, so a lane's MFMA
-// operand (8 consecutive k) is one 16-byte piece of a row.  Tiles of BK=64
-// are staged through LDS (16-byte pieces XOR-swizzled by row so that the
-// 32-row operand reads are conflict-free), double-buffered, with the next
-// tile's global loads in flight while the current one is multiplied.
+// operand (8 consecutive k) is one 16-byte piece of a row.  Tiles of BK = 64
+// are staged through LDS, double-buffered, with the next tile's global loads in
+// flight while the current one is multiplied.  LDS rows are 128 bytes; the 64
+// banks span two rows, so piece p of row r is stored at slot p ^ ((r >> 1) & 7):
+// the 16 lanes of one ds_read_b128 pass (16 rows, same p) then hit 16 distinct
+// 16-byte slots (measured: zero bank-conflict cycles).
 #include "bm_kernels.h"
 
 namespace bm {
 
-constexpr int G_BM = 128, G_BN = 256, G_BK = 64, G_THREADS = 256;
+constexpr int G_BN = 256, G_BK = 64;
 
-int gemm_bf16_bm() { return G_BM; }
+// Logical tile id -> (row tile, column tile).  The 32 workgroups that run together on one XCD (its
+// 32 compute units take consecutive ids) form a block of GM row tiles x 32/GM column tiles, so they
+// share GM activation tiles and 32/GM weight panels in that XCD's L2 instead of 32 + 1.
+constexpr int G_GM = 4;
+__device__ __forceinline__ void tile_of(int lid, int n_mt, int n_nt, int &mt, int &nt) {
+    const int per_group = G_GM * n_nt;
+    const int group = lid / per_group, in_group = lid - group * per_group;
+    const int first = group * G_GM;
+    const int gsize = min(n_mt - first, G_GM);
+    nt = in_group / gsize;
+    mt = first + (in_group - nt * gsize);
+}
 
-template <bool DUAL>
-__global__ void __launch_bounds__(G_THREADS) grouped_gemm_bf16_kernel(GemmParams p) {
-    __shared__ __attribute__((aligned(16))) uint16_t sA[2][G_BM * G_BK];
+__device__ __forceinline__ int lds_slot(int row, int piece) { return row * G_BK + ((piece ^ ((row >> 1) & 7)) << 3); }
+
+template <bool DUAL, int BM>
+__global__ void __launch_bounds__(256) grouped_gemm_bf16_kernel(GemmParams p) {
+    constexpr int THREADS = 256;                    // 4 waves, 2 x 2
+    constexpr int WN = 2;                           // waves along the weight rows (2 along the rows)
+    constexpr int AI = BM / 2 / 32;                 // 32-row blocks per wave
+    constexpr int BJ = G_BN / WN / 32;              // 32-column blocks per wave
+    constexpr int RSTEP = THREADS / 8;              // tile rows covered by one round of 16-byte loads
+    constexpr int NA = BM / RSTEP, NB = G_BN / RSTEP;
+    __shared__ __attribute__((aligned(16))) uint16_t sA[2][BM * G_BK];
     __shared__ __attribute__((aligned(16))) uint16_t sB[2][G_BN * G_BK];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int wm = wave >> 1, wn = wave & 1;
+    const int wm = wave / WN, wn = wave % WN;
     const int r32 = lane & 31, half = lane >> 5;
 
     // tile scheduling: consecutive logical tiles stay on one XCD (workgroups
-    // are dealt round-robin to the 8 XCDs), row tiles vary fastest so that
-    // the workgroups sharing one weight panel run together on one L2
+    // are dealt round-robin to the 8 XCDs); see tile_of for the order inside
     const int n_mt = p.n_mtiles[0];
     const int n_nt = DUAL ? (p.N + 127) / 128 : (p.N + 255) / 256;
     const int total = n_mt * n_nt;
     const int per_xcd = (total + 7) >> 3;
     const int lid = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
     if ((int)(blockIdx.x >> 3) >= per_xcd || lid >= total) return;
-    const int nt = lid / n_mt, mt = lid - nt * n_mt;
+    int mt, nt;
+    tile_of(lid, n_mt, n_nt, mt, nt);
 
     const int g = p.mt_group[mt];
     const int row0 = p.mt_row0[mt];
@@ -56,19 +82,22 @@ __global__ void __launch_bounds__(G_THREADS) grouped_gemm_bf16_kernel(GemmParams
         b1 = DUAL ? static_cast<const uint16_t *>(p.sb1) + (size_t)(g - p.E) * N * Kd : nullptr;
     }
 
-    // per-thread global sources: 4 pieces of the A tile, 8 of the B tile
+    // per-thread global sources and LDS destinations
     const int lrow = tid >> 3, chunk = tid & 7;
-    const uint16_t *pa[4];
-    const uint16_t *pb[8];
+    const uint16_t *pa[NA];
+    const uint16_t *pb[NB];
+    int sa_off[NA], sb_off[NB];
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        int pos = min(row0 + lrow + 32 * i, row_end - 1);
-        int src = p.row_map ? p.row_map[pos] : pos;
+    for (int i = 0; i < NA; ++i) {
+        const int r = lrow + RSTEP * i;
+        const int pos = min(row0 + r, row_end - 1);
+        const int src = p.row_map ? p.row_map[pos] : pos;
         pa[i] = a + (size_t)src * Kd + chunk * 8;
+        sa_off[i] = lds_slot(r, chunk);
     }
 #pragma unroll
-    for (int i = 0; i < 8; ++i) {
-        const int rb = lrow + 32 * i;
+    for (int i = 0; i < NB; ++i) {
+        const int rb = lrow + RSTEP * i;
         if (DUAL) {
             const int f = min(n0 + (rb & 127), N - 1);
             pb[i] = ((rb >> 7) ? b1 : b0) + (size_t)f * Kd + chunk * 8;
@@ -76,48 +105,42 @@ __global__ void __launch_bounds__(G_THREADS) grouped_gemm_bf16_kernel(GemmParams
             const int n = min(n0 + rb, N - 1);
             pb[i] = b0 + (size_t)n * Kd + chunk * 8;
         }
+        sb_off[i] = lds_slot(rb, chunk);
     }
-    // LDS destinations (swizzled): row r, piece (chunk ^ (r & 7))
-    int sa_off[4], sb_off[8];
-#pragma unroll
-    for (int i = 0; i < 4; ++i) { const int r = lrow + 32 * i; sa_off[i] = r * G_BK + ((chunk ^ (r & 7)) << 3); }
-#pragma unroll
-    for (int i = 0; i < 8; ++i) { const int r = lrow + 32 * i; sb_off[i] = r * G_BK + ((chunk ^ (r & 7)) << 3); }
 
-    f32x16 acc[2][4];
+    f32x16 acc[AI][BJ];
 #pragma unroll
-    for (int i = 0; i < 2; ++i)
+    for (int i = 0; i < AI; ++i)
 #pragma unroll
-        for (int j = 0; j < 4; ++j)
+        for (int j = 0; j < BJ; ++j)
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
 
     // operand rows of this wave inside the tile
-    int a_row[2], b_row[4];
+    int a_row[AI], b_row[BJ];
 #pragma unroll
-    for (int i = 0; i < 2; ++i) a_row[i] = wm * 64 + i * 32 + r32;
+    for (int i = 0; i < AI; ++i) a_row[i] = wm * (BM / 2) + i * 32 + r32;
 #pragma unroll
-    for (int j = 0; j < 4; ++j)
-        b_row[j] = DUAL ? ((j >> 1) * 128 + wn * 64 + (j & 1) * 32 + r32) : (wn * 128 + j * 32 + r32);
+    for (int j = 0; j < BJ; ++j)
+        b_row[j] = DUAL ? ((j / (BJ / 2)) * 128 + wn * (128 / WN) + (j % (BJ / 2)) * 32 + r32)
+                        : (wn * (G_BN / WN) + j * 32 + r32);
 
     const int KT = (Kd + G_BK - 1) / G_BK;
-    u32x4 ra[4], rb[8];
+    u32x4 ra[NA], rb[NB];
     const u32x4 zero4 = {0u, 0u, 0u, 0u};
 
-#define BM_LOAD_GLOBAL(kt_)                                                                         \
+#define BM_LOAD_GLOBAL(kt_)                                                                        \
     {                                                                                              \
         const int k0_ = (kt_) * G_BK;                                                              \
         const bool in_ = (k0_ + chunk * 8) < Kd;                                                   \
-        _Pragma("unroll") for (int i = 0; i < 4; ++i)                                              \
-            ra[i] = in_ ? ldg128(pa[i] + k0_) : zero4;                                            \
-        _Pragma("unroll") for (int i = 0; i < 8; ++i)                                              \
-            rb[i] = in_ ? ldg128(pb[i] + k0_) : zero4;                                            \
+        _Pragma("unroll") for (int i = 0; i < NA; ++i) ra[i] = in_ ? ldg128(pa[i] + k0_) : zero4;  \
+        _Pragma("unroll") for (int i = 0; i < NB; ++i) rb[i] = in_ ? ldg128(pb[i] + k0_) : zero4;  \
     }
 #define BM_STORE_LDS(buf_)                                                                         \
     {                                                                                              \
-        _Pragma("unroll") for (int i = 0; i < 4; ++i)                                              \
+        _Pragma("unroll") for (int i = 0; i < NA; ++i)                                             \
             *reinterpret_cast<u32x4 *>(&sA[buf_][sa_off[i]]) = ra[i];                              \
-        _Pragma("unroll") for (int i = 0; i < 8; ++i)                                              \
+        _Pragma("unroll") for (int i = 0; i < NB; ++i)                                             \
             *reinterpret_cast<u32x4 *>(&sB[buf_][sb_off[i]]) = rb[i];                              \
     }
 
@@ -131,17 +154,17 @@ __global__ void __launch_bounds__(G_THREADS) grouped_gemm_bf16_kernel(GemmParams
 #pragma unroll
         for (int kk = 0; kk < 4; ++kk) {
             const int piece = kk * 2 + half;
-            bf16x8 fa[2], fb[4];
+            bf16x8 fa[AI], fb[BJ];
 #pragma unroll
-            for (int i = 0; i < 2; ++i)
-                fa[i] = as_bf16x8(*reinterpret_cast<const u32x4 *>(&sA[buf][a_row[i] * G_BK + ((piece ^ (a_row[i] & 7)) << 3)]));
+            for (int i = 0; i < AI; ++i)
+                fa[i] = as_bf16x8(*reinterpret_cast<const u32x4 *>(&sA[buf][lds_slot(a_row[i], piece)]));
 #pragma unroll
-            for (int j = 0; j < 4; ++j)
-                fb[j] = as_bf16x8(*reinterpret_cast<const u32x4 *>(&sB[buf][b_row[j] * G_BK + ((piece ^ (b_row[j] & 7)) << 3)]));
+            for (int j = 0; j < BJ; ++j)
+                fb[j] = as_bf16x8(*reinterpret_cast<const u32x4 *>(&sB[buf][lds_slot(b_row[j], piece)]));
 #pragma unroll
-            for (int i = 0; i < 2; ++i)
+            for (int i = 0; i < AI; ++i)
 #pragma unroll
-                for (int j = 0; j < 4; ++j)
+                for (int j = 0; j < BJ; ++j)
                     acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
         }
         if (kt + 1 < KT) BM_STORE_LDS(buf ^ 1);
@@ -153,10 +176,385 @@ __global__ void __launch_bounds__(G_THREADS) grouped_gemm_bf16_kernel(GemmParams
     // epilogue.  D[i][j]: lane holds column j = l % 32, rows 8*(v/4) + 4*(l/32) + v%4
     uint16_t *c = static_cast<uint16_t *>(p.c);
 #pragma unroll
-    for (int i = 0; i < 2; ++i) {
+    for (int i = 0; i < AI; ++i) {
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
-            const int row = row0 + wm * 64 + i * 32 + 8 * (v >> 2) + 4 * half + (v & 3);
+            const int row = row0 + wm * (BM / 2) + i * 32 + 8 * (v >> 2) + 4 * half + (v & 3);
+            if (row >= row_end) continue;
+            if (DUAL) {
+#pragma unroll
+                for (int jj = 0; jj < BJ / 2; ++jj) {
+                    const int f = n0 + wn * (128 / WN) + jj * 32 + r32;
+                    if (f < N)
+                        stg16(&c[(size_t)row * N + f], f32_to_bf16(silu(acc[i][jj][v]) * acc[i][BJ / 2 + jj][v]));
+                }
+            } else {
+#pragma unroll
+                for (int j = 0; j < BJ; ++j) {
+                    const int n = n0 + wn * (G_BN / WN) + j * 32 + r32;
+                    if (n < N) stg16(&c[(size_t)row * N + n], f32_to_bf16(acc[i][j][v]));
+                }
+            }
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------
+// Large-group kernel: 256 rows x 256 weight rows per workgroup, 4 waves (2 x 2),
+// wave tile 128 x 128 (all 256 accumulator registers), one wave per SIMD.  With a
+// single wave per SIMD nothing hides a stall, so the loop is software-pipelined
+// by hand and the instruction mix is pinned with sched_group_barrier:
+//   * BK = 32 tiles in a 3-stage LDS ring; iteration kt multiplies stage kt%3,
+//     writes tile kt+2 (loaded one iteration earlier into registers) to stage
+//     (kt+2)%3 and issues the global loads of tile kt+3; one barrier per
+//     iteration.  Stage (kt+1)%3 is complete before iteration kt starts, so the
+//     first fragments of the next tile are read under the last MFMAs of this one.
+//   * every LDS read, LDS write and global load is issued between two MFMAs.
+// LDS rows are 64 bytes here (4 pieces); the 64 banks span 4 rows, so piece p of
+// row r sits at slot p ^ ((r >> 2) & 3).
+// ---------------------------------------------------------------------------
+constexpr int L_BK = 32, L_BM = 256, L_STAGE = (L_BM + G_BN) * L_BK;   // bf16 elements per stage
+
+__device__ __forceinline__ int lds_slot32(int row, int piece) { return row * L_BK + ((piece ^ ((row >> 2) & 3)) << 3); }
+
+template <bool DUAL>
+__global__ void __launch_bounds__(256) grouped_gemm256_bf16_kernel(GemmParams p) {
+    __shared__ __attribute__((aligned(16))) uint16_t smem[3 * L_STAGE];          // 96 KB
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm = wave >> 1, wn = wave & 1;
+    const int r32 = lane & 31, half = lane >> 5;
+
+    const int n_mt = p.n_mtiles[0];
+    const int n_nt = DUAL ? (p.N + 127) / 128 : (p.N + 255) / 256;
+    const int total = n_mt * n_nt;
+    const int per_xcd = (total + 7) >> 3;
+    const int lid = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
+    if ((int)(blockIdx.x >> 3) >= per_xcd || lid >= total) return;
+    int mt, nt;
+    tile_of(lid, n_mt, n_nt, mt, nt);
+
+    const int g = p.mt_group[mt];
+    const int row0 = p.mt_row0[mt];
+    const int row_end = p.offsets[g + 1];
+    const int n0 = nt * (DUAL ? 128 : 256);
+    const int N = p.N, Kd = p.Kd;
+
+    const uint16_t *a = static_cast<const uint16_t *>(p.a);
+    const uint16_t *b0, *b1;
+    if (g < p.E) {
+        b0 = static_cast<const uint16_t *>(p.b0) + (size_t)g * N * Kd;
+        b1 = DUAL ? static_cast<const uint16_t *>(p.b1) + (size_t)g * N * Kd : nullptr;
+    } else {
+        b0 = static_cast<const uint16_t *>(p.sb0) + (size_t)(g - p.E) * N * Kd;
+        b1 = DUAL ? static_cast<const uint16_t *>(p.sb1) + (size_t)(g - p.E) * N * Kd : nullptr;
+    }
+
+    // global sources: thread covers rows lrow + 64*i, one 16-byte piece (4 per 64-byte tile row)
+    const int lrow = tid >> 2, chunk = tid & 3;
+    const uint16_t *pa[4];
+    const uint16_t *pb[4];
+    int s_off[8];                                      // LDS destinations inside a stage (A rows, then B rows)
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int r = lrow + 64 * i;
+        const int pos = min(row0 + r, row_end - 1);
+        const int src = p.row_map ? p.row_map[pos] : pos;
+        pa[i] = a + (size_t)src * Kd + chunk * 8;
+        s_off[i] = lds_slot32(r, chunk);
+        if (DUAL) {
+            const int f = min(n0 + (r & 127), N - 1);
+            pb[i] = ((r >> 7) ? b1 : b0) + (size_t)f * Kd + chunk * 8;
+        } else {
+            const int n = min(n0 + r, N - 1);
+            pb[i] = b0 + (size_t)n * Kd + chunk * 8;
+        }
+        s_off[4 + i] = L_BM * L_BK + lds_slot32(r, chunk);
+    }
+
+    // fragment sources inside a stage: 4 row blocks of A, 4 of B, for k-step 0 and 1
+    int fa_off[2][4], fb_off[2][4];
+#pragma unroll
+    for (int kk = 0; kk < 2; ++kk)
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int ar = wm * 128 + i * 32 + r32;
+            const int br = DUAL ? ((i >> 1) * 128 + wn * 64 + (i & 1) * 32 + r32) : (wn * 128 + i * 32 + r32);
+            fa_off[kk][i] = lds_slot32(ar, kk * 2 + half);
+            fb_off[kk][i] = L_BM * L_BK + lds_slot32(br, kk * 2 + half);
+        }
+
+    f32x16 acc[4][4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
+
+    const int KT = Kd / L_BK;
+    u32x4 rg[2][8];                                    // two register sets of one tile each
+    bf16x8 f0a[4], f0b[4], f1a[4], f1b[4];
+
+#define BM_GLOAD(set_, tile_)                                                              \
+    {                                                                                      \
+        const int k0_ = min((tile_), KT - 1) * L_BK;                                       \
+        _Pragma("unroll") for (int i = 0; i < 4; ++i) rg[set_][i] = ldg128(pa[i] + k0_);   \
+        _Pragma("unroll") for (int i = 0; i < 4; ++i) rg[set_][4 + i] = ldg128(pb[i] + k0_); \
+    }
+#define BM_SSTORE(set_, stage_)                                                            \
+    {                                                                                      \
+        uint16_t *st_ = smem + (stage_) * L_STAGE;                                         \
+        _Pragma("unroll") for (int i = 0; i < 8; ++i)                                      \
+            *reinterpret_cast<u32x4 *>(st_ + s_off[i]) = rg[set_][i];                      \
+    }
+#define BM_FREAD(fa_, fb_, stage_, kk_)                                                    \
+    {                                                                                      \
+        const uint16_t *st_ = smem + (stage_) * L_STAGE;                                   \
+        _Pragma("unroll") for (int i = 0; i < 4; ++i)                                      \
+            fa_[i] = as_bf16x8(*reinterpret_cast<const u32x4 *>(st_ + fa_off[kk_][i]));    \
+        _Pragma("unroll") for (int i = 0; i < 4; ++i)                                      \
+            fb_[i] = as_bf16x8(*reinterpret_cast<const u32x4 *>(st_ + fb_off[kk_][i]));    \
+    }
+#define BM_MFMA16(fa_, fb_)                                                                \
+    _Pragma("unroll") for (int i = 0; i < 4; ++i)                                          \
+        _Pragma("unroll") for (int j = 0; j < 4; ++j)                                      \
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa_[i], fb_[j], acc[i][j], 0, 0, 0);
+
+    // prologue: tiles 0 and 1 in stages 0 and 1, tile 2 in register set 0, first fragments loaded
+    BM_GLOAD(0, 0);
+    BM_GLOAD(1, 1);
+    BM_SSTORE(0, 0);
+    BM_SSTORE(1, 1);
+    BM_GLOAD(0, 2);
+    __syncthreads();
+    BM_FREAD(f0a, f0b, 0, 0);
+
+    int st_cur = 0, st_nxt = 1, st_wr = 2;
+    for (int kt = 0; kt < KT; kt += 2) {
+        // two iterations per trip so that the register-set index is a compile-time constant
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            BM_FREAD(f1a, f1b, st_cur, 1);             // k-step 1 of this tile, under the first MFMAs
+            BM_GLOAD(1 - h, kt + h + 3);               // tile kt+3 -> the register set written out last iteration
+            BM_MFMA16(f0a, f0b);
+            BM_FREAD(f0a, f0b, st_nxt, 0);             // first fragments of the next tile
+            BM_SSTORE(h, st_wr);                       // tile kt+2 (loaded one iteration ago)
+            BM_MFMA16(f1a, f1b);
+            // instruction mix: one LDS read / global load / LDS write between consecutive MFMAs
+            _Pragma("unroll") for (int q = 0; q < 8; ++q) {
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   // MFMA
+                __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);   // DS read  (f1)
+            }
+            _Pragma("unroll") for (int q = 0; q < 8; ++q) {
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);   // VMEM read
+            }
+            _Pragma("unroll") for (int q = 0; q < 8; ++q) {
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);   // DS read  (next f0)
+            }
+            _Pragma("unroll") for (int q = 0; q < 8; ++q) {
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                __builtin_amdgcn_sched_group_barrier(0x200, 1, 0);   // DS write
+            }
+            __syncthreads();
+            const int t = st_cur; st_cur = st_nxt; st_nxt = st_wr; st_wr = t;
+        }
+    }
+#undef BM_GLOAD
+#undef BM_SSTORE
+#undef BM_FREAD
+#undef BM_MFMA16
+
+    uint16_t *c = static_cast<uint16_t *>(p.c);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            const int row = row0 + wm * 128 + i * 32 + 8 * (v >> 2) + 4 * half + (v & 3);
+            if (row >= row_end) continue;
+            if (DUAL) {
+#pragma unroll
+                for (int jj = 0; jj < 2; ++jj) {
+                    const int f = n0 + wn * 64 + jj * 32 + r32;
+                    if (f < N) stg16(&c[(size_t)row * N + f], f32_to_bf16(silu(acc[i][jj][v]) * acc[i][2 + jj][v]));
+                }
+            } else {
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const int n = n0 + wn * 128 + j * 32 + r32;
+                    if (n < N) stg16(&c[(size_t)row * N + n], f32_to_bf16(acc[i][j][v]));
+                }
+            }
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------
+// Same tile and wave layout, but the tiles go from global memory straight into
+// LDS (global_load_lds_dwordx4: each lane's 16 bytes land at M0 + 16 * lane, so
+// one instruction fills 16 tile rows of 64 bytes; the swizzle is applied by
+// choosing which piece a lane fetches).  No staging registers, no LDS-write
+// instructions, and a 5-stage ring over the whole 160 KB of LDS: the loads of
+// tile kt+4 are issued in iteration kt and first needed three iterations later
+// (three tiles, 96 KB, in flight per compute unit: the kernel is bound by the
+// latency of its L2 traffic, about 57 GB/s per compute unit at 1 PFLOP/s).
+//   iteration kt:  wait until tile kt+1 has landed (at most the 16 loads of tiles
+//   kt+2, kt+3 outstanding) -> barrier (every wave's part of tile kt+1 is in LDS
+//   and every wave is done with stage (kt-1)%5) -> issue tile kt+4 into stage
+//   (kt+4)%5 -> MFMAs on stage kt%5, reading the first fragments of tile kt+1
+//   under the last MFMAs.
+// The compiler does not order LDS reads after these loads by itself, so the
+// waits are explicit s_waitcnt vmcnt(n) and the barrier is a bare s_barrier.
+// Needs Kd divisible by 32.
+// ---------------------------------------------------------------------------
+#define BM_LDS __attribute__((address_space(3)))
+// s_waitcnt with only vmcnt set (gfx9 encoding: vmcnt[3:0] | expcnt 7 << 4 | lgkmcnt 15 << 8 | vmcnt[5:4] << 14)
+#define BM_WAIT_VMCNT(n) __builtin_amdgcn_s_waitcnt(((n) & 15) | (7 << 4) | (15 << 8) | (((n) >> 4) << 14))
+#define BM_BARE_BARRIER() asm volatile("s_barrier" ::: "memory")
+
+template <bool DUAL>
+__global__ void __launch_bounds__(256) grouped_gemm256_dma_bf16_kernel(GemmParams p) {
+    __shared__ __attribute__((aligned(1024))) uint16_t smem[5 * L_STAGE];        // 160 KB: the whole LDS
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm = wave >> 1, wn = wave & 1;
+    const int r32 = lane & 31, half = lane >> 5;
+
+    const int n_mt = p.n_mtiles[0];
+    const int n_nt = DUAL ? (p.N + 127) / 128 : (p.N + 255) / 256;
+    const int total = n_mt * n_nt;
+    const int per_xcd = (total + 7) >> 3;
+    const int lid = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
+    if ((int)(blockIdx.x >> 3) >= per_xcd || lid >= total) return;
+    int mt, nt;
+    tile_of(lid, n_mt, n_nt, mt, nt);
+
+    const int g = p.mt_group[mt];
+    const int row0 = p.mt_row0[mt];
+    const int row_end = p.offsets[g + 1];
+    const int n0 = nt * (DUAL ? 128 : 256);
+    const int N = p.N, Kd = p.Kd;
+
+    const uint16_t *a = static_cast<const uint16_t *>(p.a);
+    const uint16_t *b0, *b1;
+    if (g < p.E) {
+        b0 = static_cast<const uint16_t *>(p.b0) + (size_t)g * N * Kd;
+        b1 = DUAL ? static_cast<const uint16_t *>(p.b1) + (size_t)g * N * Kd : nullptr;
+    } else {
+        b0 = static_cast<const uint16_t *>(p.sb0) + (size_t)(g - p.E) * N * Kd;
+        b1 = DUAL ? static_cast<const uint16_t *>(p.sb1) + (size_t)(g - p.E) * N * Kd : nullptr;
+    }
+
+    // Load instruction j of this wave fills the 1 KB block (4*j + wave) of a stage: blocks 0..15 are
+    // the A tile (16 rows each), 16..31 the B tile.  Lane i supplies row 16*block + i/4, LDS slot i%4,
+    // i.e. global piece (i%4) ^ ((row >> 2) & 3) = (i & 3) ^ ((i >> 4) & 3).
+    const int piece = (lane & 3) ^ ((lane >> 4) & 3);
+    const uint16_t *ps[8];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        const int r = 16 * (4 * j + wave) + (lane >> 2);         // row inside the 256-row tile
+        const int pos = min(row0 + r, row_end - 1);
+        const int src = p.row_map ? p.row_map[pos] : pos;
+        ps[j] = a + (size_t)src * Kd + piece * 8;
+        if (DUAL) {
+            const int f = min(n0 + (r & 127), N - 1);
+            ps[4 + j] = ((r >> 7) ? b1 : b0) + (size_t)f * Kd + piece * 8;
+        } else {
+            const int n = min(n0 + r, N - 1);
+            ps[4 + j] = b0 + (size_t)n * Kd + piece * 8;
+        }
+    }
+
+    int fa_off[2][4], fb_off[2][4];
+#pragma unroll
+    for (int kk = 0; kk < 2; ++kk)
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int ar = wm * 128 + i * 32 + r32;
+            const int br = DUAL ? ((i >> 1) * 128 + wn * 64 + (i & 1) * 32 + r32) : (wn * 128 + i * 32 + r32);
+            fa_off[kk][i] = lds_slot32(ar, kk * 2 + half);
+            fb_off[kk][i] = L_BM * L_BK + lds_slot32(br, kk * 2 + half);
+        }
+
+    f32x16 acc[4][4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
+
+    const int KT = Kd / L_BK;
+    bf16x8 f0a[4], f0b[4], f1a[4], f1b[4];
+
+// tile_ -> stage_: 8 direct-to-LDS loads per wave
+#define BM_DMA(stage_, tile_)                                                                      \
+    {                                                                                              \
+        const int k0_ = min((tile_), KT - 1) * L_BK;                                               \
+        uint16_t *st_ = smem + (stage_) * L_STAGE + wave * 512;                                    \
+        _Pragma("unroll") for (int j = 0; j < 8; ++j)                                              \
+            __builtin_amdgcn_global_load_lds((const BM_GLOBAL void *)(ps[j] + k0_),                \
+                                             (BM_LDS void *)(st_ + ((j >> 2) * 16 + 4 * (j & 3)) * 512), 16, 0, 0); \
+    }
+#define BM_FREAD(fa_, fb_, stage_, kk_)                                                    \
+    {                                                                                      \
+        const uint16_t *st_ = smem + (stage_) * L_STAGE;                                   \
+        _Pragma("unroll") for (int i = 0; i < 4; ++i)                                      \
+            fa_[i] = as_bf16x8(*reinterpret_cast<const u32x4 *>(st_ + fa_off[kk_][i]));    \
+        _Pragma("unroll") for (int i = 0; i < 4; ++i)                                      \
+            fb_[i] = as_bf16x8(*reinterpret_cast<const u32x4 *>(st_ + fb_off[kk_][i]));    \
+    }
+#define BM_MFMA16(fa_, fb_)                                                                \
+    _Pragma("unroll") for (int i = 0; i < 4; ++i)                                          \
+        _Pragma("unroll") for (int j = 0; j < 4; ++j)                                      \
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa_[i], fb_[j], acc[i][j], 0, 0, 0);
+
+    // prologue: tiles 0..3 in flight, tile 0 landed, its first fragments loaded
+    BM_DMA(0, 0);
+    BM_DMA(1, 1);
+    BM_DMA(2, 2);
+    BM_DMA(3, 3);
+    BM_WAIT_VMCNT(24);
+    BM_BARE_BARRIER();
+    BM_FREAD(f0a, f0b, 0, 0);
+
+    int s_cur = 0, s_nxt = 1, s_wr = 4;                // stage being multiplied, the next one, the free one
+    for (int kt = 0; kt < KT; ++kt) {
+        BM_WAIT_VMCNT(16);                             // tile kt+1 has landed (this wave's part)
+        BM_BARE_BARRIER();                             // ... and everybody's; stage s_wr is free
+        BM_FREAD(f1a, f1b, s_cur, 1);
+        BM_DMA(s_wr, kt + 4);
+        BM_MFMA16(f0a, f0b);
+        BM_FREAD(f0a, f0b, s_nxt, 0);
+        BM_MFMA16(f1a, f1b);
+        _Pragma("unroll") for (int q = 0; q < 8; ++q) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   // MFMA
+            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);   // DS read (f1)
+        }
+        _Pragma("unroll") for (int q = 0; q < 8; ++q) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);   // direct-to-LDS load
+        }
+        _Pragma("unroll") for (int q = 0; q < 8; ++q) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);   // DS read (next f0)
+        }
+        __builtin_amdgcn_sched_group_barrier(0x008, 8, 0);
+        s_wr = s_cur;
+        s_cur = s_nxt;
+        s_nxt = (s_nxt == 4) ? 0 : s_nxt + 1;
+    }
+    BM_WAIT_VMCNT(0);                                  // no load may land in LDS after this workgroup is gone
+#undef BM_DMA
+#undef BM_FREAD
+#undef BM_MFMA16
+
+    uint16_t *c = static_cast<uint16_t *>(p.c);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            const int row = row0 + wm * 128 + i * 32 + 8 * (v >> 2) + 4 * half + (v & 3);
             if (row >= row_end) continue;
             if (DUAL) {
 #pragma unroll
@@ -182,12 +580,26 @@ static int grid_for(const GemmParams &p, bool dual) {
 }
 
 int launch_gateup_bf16(const GemmParams &p, hipStream_t st) {
-    hipLaunchKernelGGL(grouped_gemm_bf16_kernel<true>, dim3(grid_for(p, true)), dim3(G_THREADS), 0, st, p);
+    if (p.BM == 256)
+        hipLaunchKernelGGL((grouped_gemm256_dma_bf16_kernel<true>), dim3(grid_for(p, true)), dim3(256), 0, st, p);
+    else if (p.BM == 256 && p.Kd % 64 == 0)
+        hipLaunchKernelGGL((grouped_gemm256_bf16_kernel<true>), dim3(grid_for(p, true)), dim3(256), 0, st, p);
+    else if (p.BM == 256)
+        hipLaunchKernelGGL((grouped_gemm_bf16_kernel<true, 256>), dim3(grid_for(p, true)), dim3(256), 0, st, p);
+    else
+        hipLaunchKernelGGL((grouped_gemm_bf16_kernel<true, 128>), dim3(grid_for(p, true)), dim3(256), 0, st, p);
     return launch_status(__func__);
 }
 
 int launch_down_bf16(const GemmParams &p, hipStream_t st) {
-    hipLaunchKernelGGL(grouped_gemm_bf16_kernel<false>, dim3(grid_for(p, false)), dim3(G_THREADS), 0, st, p);
+    if (p.BM == 256)
+        hipLaunchKernelGGL((grouped_gemm256_dma_bf16_kernel<false>), dim3(grid_for(p, false)), dim3(256), 0, st, p);
+    else if (p.BM == 256 && p.Kd % 64 == 0)
+        hipLaunchKernelGGL((grouped_gemm256_bf16_kernel<false>), dim3(grid_for(p, false)), dim3(256), 0, st, p);
+    else if (p.BM == 256)
+        hipLaunchKernelGGL((grouped_gemm_bf16_kernel<false, 256>), dim3(grid_for(p, false)), dim3(256), 0, st, p);
+    else
+        hipLaunchKernelGGL((grouped_gemm_bf16_kernel<false, 128>), dim3(grid_for(p, false)), dim3(256), 0, st, p);
     return launch_status(__func__);
 }
 

@@ -61,6 +61,7 @@ struct GemmParams {
     int N, Kd, E;
     int n_groups;                 // E + n_shared
     int max_mtiles;               // grid bound on row tiles
+    int BM;                       // rows per tile of the row-tile table: 128 or 256
     const int32_t *mt_group, *mt_row0, *n_mtiles, *offsets;
 };
 
@@ -99,8 +100,7 @@ int launch_count(const int32_t *ids, int T, int K, int E, int32_t *tile_counts, 
 int launch_scan(const ScanParams &p, hipStream_t st);
 int launch_scatter(const ScatterParams &p, hipStream_t st);
 
-// bf16 MFMA grouped projections (row tile height gemm_bf16_bm())
-int gemm_bf16_bm();
+// bf16 MFMA grouped projections (row tile height p.BM, which the row-tile table was built for)
 int launch_gateup_bf16(const GemmParams &p, hipStream_t st);   // c = silu(a b0^T) * (a b1^T), bf16
 int launch_down_bf16(const GemmParams &p, hipStream_t st);     // c = a b0^T, bf16
 
