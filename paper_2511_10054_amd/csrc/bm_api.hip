@@ -276,7 +276,6 @@ int bm_moe_forward(const bm_layer_desc *desc, const void *x, const bm_weights *w
     fp.ids2 = at<int32_t>(ws, L.ids2);
     fp.tile_counts = at<int32_t>(ws, L.tile_counts);
     fp.tile_stats = at<int32_t>(ws, L.tile_stats);
-    err |= launch_front(fp, desc->dtype, st);
 
     // 2. offsets, tile bases, row-tile table, statistics
     ScanParams sp{};
@@ -289,7 +288,6 @@ int bm_moe_forward(const bm_layer_desc *desc, const void *x, const bm_weights *w
     sp.mt_group = at<int32_t>(ws, L.mt_group); sp.mt_row0 = at<int32_t>(ws, L.mt_row0);
     sp.n_mtiles = at<int32_t>(ws, L.n_mtiles);
     sp.stats = at<int32_t>(ws, L.stats);
-    err |= launch_scan(sp, st);
 
     // 3. stable placement
     ScatterParams cp{};
@@ -297,7 +295,16 @@ int bm_moe_forward(const bm_layer_desc *desc, const void *x, const bm_weights *w
     cp.ids = fp.ids2; cp.offsets = sp.offsets; cp.tile_base = sp.tile_base;
     cp.perm = at<int32_t>(ws, L.perm); cp.inv_perm = at<int32_t>(ws, L.inv_perm);
     cp.row_token = at<int32_t>(ws, L.row_token);
-    err |= launch_scatter(cp, st);
+    if (front_can_fuse(T, desc->dtype)) {      // decode-sized batch: one kernel does steps 1-3
+        fp.fused = 1;
+        fp.scan = sp;
+        fp.scat = cp;
+        err |= launch_front(fp, desc->dtype, st);
+    } else {
+        err |= launch_front(fp, desc->dtype, st);
+        err |= launch_scan(sp, st);
+        err |= launch_scatter(cp, st);
+    }
     mark(1);
 
     // 4. gate/up projection + SwiGLU, 5. down projection

@@ -77,6 +77,7 @@ struct FrontLds {
     int32_t ids[TILE_T * BM_MAX_K];
     float w[TILE_T * BM_MAX_K];
     int32_t counts[BM_MAX_E];
+    int32_t lut[BM_MAX_E];
     int32_t stats[4];
     uint64_t bitmap[4];
 };
@@ -84,6 +85,7 @@ struct FrontLds {
 // Ranks the tile's tokens from the logits in LDS and finishes the tile.
 // logits: [TILE_T][stride] fp32, bias already added.  The logits region is
 // reused for the buddy table once ranking is done (cap = its size in ints).
+template <int EC>   // EC = ceil(E / 64) experts per lane (compile-time bound)
 __device__ void tile_epilogue(const FrontParams &p, float *logits, int stride, int cap_ints,
                               FrontLds &s, int tile) {
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, nw = blockDim.x >> 6;
@@ -92,44 +94,50 @@ __device__ void tile_epilogue(const FrontParams &p, float *logits, int stride, i
     const int E = p.E, K = p.K;
     const int ec = (E + 63) >> 6;
 
+    // Ranking by counting: lane l owns experts l, l+64, ...; the rank of an expert is the number of
+    // experts that beat it (larger logit, or equal logit and lower index), found with E broadcast
+    // reads of the logit row - no cross-lane traffic.  Experts of rank < K are the selection,
+    // slot = rank.
     for (int i = wave; i < ntok; i += nw) {
-        float vals[4], orig[4];
+        const float *zr = logits + i * stride;
+        float myv[EC];
+        int rank[EC];
 #pragma unroll
-        for (int c = 0; c < 4; ++c) {
+        for (int c = 0; c < EC; ++c) {
             const int e = lane + 64 * c;
-            vals[c] = (c < ec && e < E) ? logits[i * stride + e] : -INFINITY;
-            orig[c] = vals[c];
+            myv[c] = (e < E) ? zr[e] : -INFINITY;
+            rank[c] = 0;
         }
-        float my_z = -INFINITY;
-        int my_id = -1;
-        for (int k = 0; k < K; ++k) {
-            float bv = vals[0];
-            int bi = lane;
+#pragma unroll 16
+        for (int j = 0; j < E; ++j) {                  // branch-free body, unrolled: the LDS reads go out in batches
+            const float zj = zr[j];
 #pragma unroll
-            for (int c = 1; c < 4; ++c) {
-                if (vals[c] > bv) { bv = vals[c]; bi = lane + 64 * c; }   // lower index wins ties
-            }
-            wave_argmax(bv, bi);
-            if ((bi & 63) == lane) {
-#pragma unroll
-                for (int c = 0; c < 4; ++c) if ((bi >> 6) == c) vals[c] = -INFINITY;
-            }
-            if (lane == k) { my_z = bv; my_id = bi; }
+            for (int c = 0; c < EC; ++c)
+                rank[c] += (int)(zj > myv[c]) | ((int)(zj == myv[c]) & (int)(j < lane + 64 * c));
         }
-        const float zmax = __shfl(my_z, 0, WAVE);
-        const float pk = (lane < K) ? expf(my_z - zmax) : 0.0f;
-        float denom;
+#pragma unroll
+        for (int c = 0; c < EC; ++c) {
+            const int e = lane + 64 * c;
+            if (e < E && rank[c] < K) {
+                s.ids[i * K + rank[c]] = e;
+                s.w[i * K + rank[c]] = myv[c];            // the logit for now; replaced by the gate weight below
+            }
+        }
+        __builtin_amdgcn_wave_barrier();
+        const float zmax = s.w[i * K];
+        float denom = 0.0f;
         if (p.flags & BM_RENORM_TOPK) {
-            denom = wave_sum(pk);
+            for (int k = 0; k < K; ++k) denom += expf(s.w[i * K + k] - zmax);     // same order in every lane
         } else {
-            float acc = 0.0f;
+            float part = 0.0f;
 #pragma unroll
-            for (int c = 0; c < 4; ++c) acc += (orig[c] == -INFINITY) ? 0.0f : expf(orig[c] - zmax);
-            denom = wave_sum(acc);
+            for (int c = 0; c < EC; ++c) part += (myv[c] == -INFINITY) ? 0.0f : expf(myv[c] - zmax);
+            denom = wave_sum(part);
         }
+        const float pk = (lane < K) ? expf(s.w[i * K + lane] - zmax) : 0.0f;
+        __builtin_amdgcn_wave_barrier();
         if (lane < K) {
-            p.ids[(size_t)(t0 + i) * K + lane] = my_id;
-            s.ids[i * K + lane] = my_id;
+            p.ids[(size_t)(t0 + i) * K + lane] = s.ids[i * K + lane];
             s.w[i * K + lane] = pk / denom;
         }
     }
@@ -150,18 +158,51 @@ __device__ void tile_epilogue(const FrontParams &p, float *logits, int stride, i
     if (tid < 4) { s.bitmap[tid] = (tid < ec) ? p.bitmap[tid] : 0ull; s.stats[tid] = 0; }
     __syncthreads();
 
-    if (tid < ntok) {
-        int n_miss = 0, n_sub = 0, n_drop = 0;
-        int32_t *tok_ids = &s.ids[tid * K];
-        float *tok_w = &s.w[tid * K];
-        remap_token(K, E, p.R, p.H, (p.flags & BM_REMAP_UNIQUE) != 0, s.bitmap,
-                    tab_in_lds ? s_table : p.table, tok_ids, tok_ids, tok_w, n_miss, n_sub, n_drop);
-        if (n_miss) atomicAdd(&s.stats[0], n_miss);
-        if (n_sub) atomicAdd(&s.stats[1], n_sub);
-        if (n_drop) atomicAdd(&s.stats[2], n_drop);
-        for (int k = 0; k < K; ++k) {
-            const int e = tok_ids[k];
-            if (e >= 0) atomicAdd(&s.counts[e], 1);
+    if (p.flags & BM_REMAP_UNIQUE) {
+        // Algorithm 1 proper: a lane walks its token's slots in order
+        if (tid < ntok) {
+            int n_miss = 0, n_sub = 0, n_drop = 0;
+            int32_t *tok_ids = &s.ids[tid * K];
+            float *tok_w = &s.w[tid * K];
+            remap_token(K, E, p.R, p.H, true, s.bitmap, tab_in_lds ? s_table : p.table, tok_ids, tok_ids, tok_w,
+                        n_miss, n_sub, n_drop);
+            if (n_miss) atomicAdd(&s.stats[0], n_miss);
+            if (n_sub) atomicAdd(&s.stats[1], n_sub);
+            if (n_drop) atomicAdd(&s.stats[2], n_drop);
+            for (int k = 0; k < K; ++k) {
+                const int e = tok_ids[k];
+                if (e >= 0) atomicAdd(&s.counts[e], 1);
+            }
+        }
+    } else {
+        // without the U_t test the substitute depends on the expert alone: one lane per expert scans
+        // its buddy row once (same fixed-trip select scan), then every assignment is a table lookup
+        const int32_t *tab = tab_in_lds ? s_table : p.table;
+        for (int e = tid; e < E; e += blockDim.x) {
+            const bool res = (s.bitmap[e >> 6] >> (e & 63)) & 1ull;
+            int out = res ? e : -1;
+            bool found = res;
+            for (int r = 0; r < p.H; ++r) {
+                const int b = tab[e * p.R + r];
+                const bool bvalid = (unsigned)b < (unsigned)E;
+                const int bc = bvalid ? b : 0;
+                const bool ok = bvalid && ((s.bitmap[bc >> 6] >> (bc & 63)) & 1ull);
+                out = (ok && !found) ? b : out;
+                found = found || ok;
+            }
+            s.lut[e] = out | (res ? 0 : 0x40000000);       // bit 30 marks "was not resident"
+        }
+        __syncthreads();
+        for (int idx = tid; idx < n; idx += blockDim.x) {
+            const int v = s.lut[s.ids[idx]];
+            const bool miss = (v & 0x40000000) != 0 || v < 0;
+            const int out = v < 0 ? -1 : (v & 0x3fffffff);
+            s.ids[idx] = out;
+            if (out < 0) s.w[idx] = 0.0f;
+            if (miss) atomicAdd(&s.stats[0], 1);
+            if (miss && out >= 0) atomicAdd(&s.stats[1], 1);
+            if (out < 0) atomicAdd(&s.stats[2], 1);
+            if (out >= 0) atomicAdd(&s.counts[out], 1);
         }
     }
     __syncthreads();
@@ -175,65 +216,207 @@ __device__ void tile_epilogue(const FrontParams &p, float *logits, int stride, i
 }
 
 // ---------------------------------------------------------------------------
+// Tail of the front end when one workgroup owns every tile (at most
+// FUSED_TILES tiles, i.e. decode-sized batches): group offsets, row-tile table,
+// statistics and the stable placement, from the per-tile histograms and
+// substituted ids kept in LDS.  Saves the scan and scatter launches.
+// ---------------------------------------------------------------------------
+constexpr int FUSED_TILES = 2;
+
+struct FusedLds {
+    int32_t ids[FUSED_TILES][TILE_T * BM_MAX_K];   // substituted ids of every tile
+    int32_t counts[FUSED_TILES][BM_MAX_E];         // per-tile histograms
+    int32_t stats[FUSED_TILES][4];
+    int32_t start[BM_MAX_E + 16];                  // group offsets
+    int32_t tstart[BM_MAX_E + 16];                 // first row tile of each group
+};
+
+// exclusive prefix sum over the wave; `total` = sum over all lanes
+__device__ __forceinline__ int wave_excl_scan(int v, int &total) {
+    const int lane = threadIdx.x & 63;
+    int incl = v;
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+        const int o = __shfl_up(incl, d, WAVE);
+        if (lane >= d) incl += o;
+    }
+    total = __shfl(incl, 63, WAVE);
+    return incl - v;
+}
+
+__device__ void fused_tail(const FrontParams &p, FusedLds &fs, int n_tiles) {
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int E = p.E, K = p.K, n_shared = p.scan.n_shared, G = E + n_shared, BM = p.scan.BM;
+    // group offsets and row-tile starts: one wave, up to 5 consecutive groups per lane
+    if (wave == 0) {
+        constexpr int PER = (BM_MAX_E + 8 + 63) / 64;
+        int cnt[PER], nt[PER], sum_c = 0, sum_t = 0;
+#pragma unroll
+        for (int i = 0; i < PER; ++i) {
+            const int g = lane * PER + i;
+            int c = 0;
+            if (g < E) { for (int t = 0; t < n_tiles; ++t) c += fs.counts[t][g]; }
+            else if (g < G) c = p.T;
+            cnt[i] = c;
+            nt[i] = (c + BM - 1) / BM;
+            sum_c += c;
+            sum_t += nt[i];
+        }
+        int tot_c, tot_t;
+        int run_c = wave_excl_scan(sum_c, tot_c), run_t = wave_excl_scan(sum_t, tot_t);
+#pragma unroll
+        for (int i = 0; i < PER; ++i) {
+            const int g = lane * PER + i;
+            if (g <= G) { fs.start[g] = run_c; fs.tstart[g] = run_t; }
+            run_c += cnt[i];
+            run_t += nt[i];
+        }
+        if (lane == 0) { p.scan.n_mtiles[0] = tot_t; p.scan.n_mtiles[1] = tot_c; }
+    }
+    __syncthreads();
+    for (int g = tid; g <= G; g += blockDim.x) p.scan.offsets[g] = fs.start[g];
+    for (int g = tid; g < G; g += blockDim.x) {
+        const int ntile = fs.tstart[g + 1] - fs.tstart[g];
+        for (int i = 0; i < ntile; ++i) {
+            p.scan.mt_group[fs.tstart[g] + i] = g;
+            p.scan.mt_row0[fs.tstart[g] + i] = fs.start[g] + i * BM;
+        }
+    }
+    if (p.scan.stats != nullptr && tid < 3) {
+        int sum = 0;
+        for (int t = 0; t < n_tiles; ++t) sum += fs.stats[t][tid];
+        p.scan.stats[tid] = sum;
+    }
+    // stable placement
+    const int live = fs.start[E];
+    for (int tile = 0; tile < n_tiles; ++tile) {
+        const int t0 = tile * TILE_T, ntok = min(TILE_T, p.T - t0), n = ntok * K;
+        for (int idx = tid; idx < n; idx += blockDim.x) {
+            const int e = fs.ids[tile][idx];
+            const int a = t0 * K + idx;
+            int pos = -1;
+            if (e >= 0) {
+                int rank = 0;
+                for (int j = 0; j < idx; ++j) rank += (fs.ids[tile][j] == e) ? 1 : 0;
+                int base = fs.start[e];
+                for (int t = 0; t < tile; ++t) base += fs.counts[t][e];
+                pos = base + rank;
+                p.scat.perm[pos] = a;
+                if (p.scat.row_token) p.scat.row_token[pos] = a / K;
+            }
+            p.scat.inv_perm[a] = pos;
+        }
+    }
+    for (int pos = live + tid; pos < p.T * K; pos += blockDim.x) p.scat.perm[pos] = -1;
+    if (p.scat.row_token)
+        for (int sidx = 0; sidx < n_shared; ++sidx)
+            for (int t = tid; t < p.T; t += blockDim.x) p.scat.row_token[fs.start[E + sidx] + t] = t;
+}
+
+// ---------------------------------------------------------------------------
 // bf16 front kernel: router product on MFMA 32x32x16 (tokens x experts),
 // operands read from global memory directly in the instruction's layout:
 // lane l supplies row/column (l % 32) and the 8 consecutive k values starting
-// at 8 * (l / 32), i.e. one 16-byte load per operand per k-step.
-// NB = number of 32-expert column blocks, NW = waves per workgroup (k split).
+// at 8 * (l / 32), i.e. one 16-byte load per operand per k-step.  The waves
+// split the hidden dimension in batches of U k-steps; the loads of a batch are
+// all issued before its MFMAs.  The partial logit tiles of the waves are
+// written to LDS side by side and added in wave order (reproducible sum), or,
+// when NW tiles do not fit, added into one tile wave after wave.
+// NB = number of 32-expert column blocks, NW = waves per workgroup.
+// FUSED: one workgroup walks all (<= FUSED_TILES) tiles and finishes the
+// grouping itself.
 // ---------------------------------------------------------------------------
-template <int NB, int NW>
+template <int NB, int NW, int U, bool FUSED>
 __global__ void __launch_bounds__(NW * 64) front_bf16_kernel(FrontParams p) {
     constexpr int STRIDE = NB * 32 + 1;
-    __shared__ float logits[TILE_T * STRIDE];
+    constexpr int TILE = TILE_T * STRIDE;
+    constexpr int NS_FIT = (68 * 1024) / (TILE * 4);
+    constexpr int NS = NS_FIT >= NW ? NW : (NS_FIT < 1 ? 1 : NS_FIT);   // partial tiles kept side by side
+    __shared__ float part[NS * TILE];
     __shared__ FrontLds s;
+    __shared__ FusedLds fs_store[FUSED ? 1 : 0 + 1];
+    FusedLds &fs = fs_store[0];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int tile = blockIdx.x, t0 = tile * TILE_T;
     const int r32 = lane & 31, half = lane >> 5;
     const uint16_t *x = static_cast<const uint16_t *>(p.x);
     const uint16_t *wr = static_cast<const uint16_t *>(p.wr);
+    const int n_tiles = (p.T + TILE_T - 1) / TILE_T;
+    const int tile_begin = FUSED ? 0 : blockIdx.x, tile_end = FUSED ? n_tiles : blockIdx.x + 1;
 
-    const int trow = min(t0 + r32, p.T - 1);
-    const uint16_t *xa = x + (size_t)trow * p.d + half * 8;
     const uint16_t *wb[NB];
 #pragma unroll
     for (int nb = 0; nb < NB; ++nb) wb[nb] = wr + (size_t)min(nb * 32 + r32, p.E - 1) * p.d + half * 8;
-
-    f32x16 acc[NB];
-#pragma unroll
-    for (int nb = 0; nb < NB; ++nb)
-#pragma unroll
-        for (int v = 0; v < 16; ++v) acc[nb][v] = 0.0f;
-
     const int ksteps = p.d >> 4;
-#pragma unroll 4
-    for (int ks = wave; ks < ksteps; ks += NW) {
-        const bf16x8 a = as_bf16x8(ldg128(xa + ks * 16));
-#pragma unroll
-        for (int nb = 0; nb < NB; ++nb) {
-            const bf16x8 b = as_bf16x8(ldg128(wb[nb] + ks * 16));
-            acc[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, acc[nb], 0, 0, 0);
-        }
-    }
+    const int nbatch = ksteps / U;
 
-    // D[i][j]: lane holds column j = l % 32 and rows i = 8*(v/4) + 4*(l/32) + v%4.
-    // Waves add their partial sums in wave order, so the sum is reproducible.
-    for (int w = 0; w < NW; ++w) {
-        if (wave == w) {
+    for (int tile = tile_begin; tile < tile_end; ++tile) {
+        const int t0 = tile * TILE_T;
+        const int trow = min(t0 + r32, p.T - 1);
+        const uint16_t *xa = x + (size_t)trow * p.d + half * 8;
+        f32x16 acc[NB];
 #pragma unroll
-            for (int nb = 0; nb < NB; ++nb) {
-                const int e = nb * 32 + r32;
-                const float b0 = (w == 0) ? ((p.bias != nullptr && e < p.E) ? p.bias[e] : 0.0f) : 0.0f;
+        for (int nb = 0; nb < NB; ++nb)
 #pragma unroll
-                for (int v = 0; v < 16; ++v) {
-                    const int i = 8 * (v >> 2) + 4 * half + (v & 3);
-                    float *q = &logits[i * STRIDE + e];
-                    *q = (w == 0 ? b0 : *q) + acc[nb][v];
-                }
+            for (int v = 0; v < 16; ++v) acc[nb][v] = 0.0f;
+
+        for (int bt = wave; bt < nbatch; bt += NW) {
+            const int k0 = bt * U * 16;
+            u32x4 ra[U], rb[NB][U];
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                ra[u] = ldg128(xa + k0 + u * 16);
+#pragma unroll
+                for (int nb = 0; nb < NB; ++nb) rb[nb][u] = ldg128(wb[nb] + k0 + u * 16);
             }
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int u = 0; u < U; ++u)
+#pragma unroll
+                for (int nb = 0; nb < NB; ++nb)
+                    acc[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(ra[u]), as_bf16x8(rb[nb][u]), acc[nb], 0, 0, 0);
+        }
+        for (int ks = nbatch * U + wave; ks < ksteps; ks += NW) {       // k-steps past the last full batch
+            const bf16x8 a = as_bf16x8(ldg128(xa + ks * 16));
+#pragma unroll
+            for (int nb = 0; nb < NB; ++nb)
+                acc[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, as_bf16x8(ldg128(wb[nb] + ks * 16)), acc[nb], 0, 0, 0);
+        }
+
+        // D[i][j]: lane holds column j = l % 32 and rows i = 8*(v/4) + 4*(l/32) + v%4.
+        // NS partial tiles sit side by side in LDS; wave w adds into slot w % NS in round w / NS,
+        // then the slots are added in slot order: one fixed association, reproducible.
+        for (int r = 0; r < (NW + NS - 1) / NS; ++r) {
+            if (wave / NS == r) {
+                float *mine = part + (wave % NS) * TILE;
+#pragma unroll
+                for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) {
+                        float *q = &mine[(8 * (v >> 2) + 4 * half + (v & 3)) * STRIDE + nb * 32 + r32];
+                        *q = (r == 0 ? 0.0f : *q) + acc[nb][v];
+                    }
+            }
+            __syncthreads();
+        }
+        for (int idx = tid; idx < TILE_T * NB * 32; idx += NW * 64) {
+            const int i = idx / (NB * 32), e = idx - i * (NB * 32);
+            float sum = (p.bias != nullptr && e < p.E) ? p.bias[e] : 0.0f;
+#pragma unroll
+            for (int w = 0; w < NS; ++w) sum += part[w * TILE + i * STRIDE + e];
+            part[i * STRIDE + e] = sum;                // slot 0 becomes the logit tile (own element only)
         }
         __syncthreads();
+        tile_epilogue<(NB + 1) / 2>(p, part, STRIDE, TILE, s, tile);
+        if (FUSED) {
+            __syncthreads();
+            const int n = min(TILE_T, p.T - t0) * p.K;
+            for (int idx = tid; idx < n; idx += NW * 64) fs.ids[tile][idx] = s.ids[idx];
+            for (int e = tid; e < p.E; e += NW * 64) fs.counts[tile][e] = s.counts[e];
+            if (tid < 3) fs.stats[tile][tid] = s.stats[tid];
+            __syncthreads();
+        }
     }
-    tile_epilogue(p, logits, STRIDE, TILE_T * STRIDE, s, tile);
+    if (FUSED) fused_tail(p, fs, n_tiles);
 }
 
 // ---------------------------------------------------------------------------
@@ -258,7 +441,7 @@ __global__ void __launch_bounds__(256) front_f32_kernel(FrontParams p) {
         if (lane == 0) logits[i * STRIDE + e] = acc + (p.bias ? p.bias[e] : 0.0f);
     }
     __syncthreads();
-    tile_epilogue(p, logits, STRIDE, TILE_T * STRIDE, s, tile);
+    tile_epilogue<4>(p, logits, STRIDE, TILE_T * STRIDE, s, tile);
 }
 
 // ---------------------------------------------------------------------------
@@ -316,20 +499,24 @@ __global__ void __launch_bounds__(256) count_kernel(const int32_t *ids, int T, i
 // rows each), the row-tile table of the grouped GEMMs, and the summed
 // substitution statistics.
 // ---------------------------------------------------------------------------
-__global__ void __launch_bounds__(256) scan_kernel(ScanParams p) {
+__global__ void __launch_bounds__(1024) scan_kernel(ScanParams p) {
     __shared__ int32_t total[BM_MAX_E + 8];
     __shared__ int32_t start[BM_MAX_E + 9];
     __shared__ int32_t tstart[BM_MAX_E + 9];
-    const int tid = threadIdx.x;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, nw = blockDim.x >> 6;
     const int G = p.E + p.n_shared;
-    for (int e = tid; e < p.E; e += blockDim.x) {
+    // per expert: exclusive scan of its counts over the tiles, 64 tiles per wave step
+    for (int e = wave; e < p.E; e += nw) {
         int run = 0;
-        for (int t = 0; t < p.n_tiles; ++t) {
-            const int c = p.tile_counts[(size_t)t * p.E + e];
-            p.tile_base[(size_t)t * p.E + e] = run;
-            run += c;
+        for (int tb = 0; tb < p.n_tiles; tb += WAVE) {
+            const int t = tb + lane;
+            const int c = (t < p.n_tiles) ? p.tile_counts[(size_t)t * p.E + e] : 0;
+            int tot;
+            const int ex = wave_excl_scan(c, tot);
+            if (t < p.n_tiles) p.tile_base[(size_t)t * p.E + e] = run + ex;
+            run += tot;
         }
-        total[e] = run;
+        if (lane == 0) total[e] = run;
     }
     for (int g = p.E + tid; g < G; g += blockDim.x) total[g] = p.T;
     __syncthreads();
@@ -355,11 +542,13 @@ __global__ void __launch_bounds__(256) scan_kernel(ScanParams p) {
             p.mt_row0[tstart[g] + i] = start[g] + i * p.BM;
         }
     }
-    if (p.stats != nullptr && tid < 3) {
+    if (p.stats != nullptr && wave < 3) {          // one wave per counter, lanes over the tiles
         int sum = 0;
         if (p.tile_stats != nullptr)
-            for (int t = 0; t < p.n_tiles; ++t) sum += p.tile_stats[t * 4 + tid];
-        p.stats[tid] = sum;
+            for (int t = lane; t < p.n_tiles; t += WAVE) sum += p.tile_stats[t * 4 + wave];
+#pragma unroll
+        for (int m = 32; m >= 1; m >>= 1) sum += __shfl_xor(sum, m, WAVE);
+        if (lane == 0) p.stats[wave] = sum;
     }
 }
 
@@ -408,10 +597,14 @@ __global__ void __launch_bounds__(256) scatter_kernel(ScatterParams p) {
 // ---------------------------------------------------------------------------
 // Host-side launchers
 // ---------------------------------------------------------------------------
-template <int NB, int NW>
+template <int NB, int NW, int U>
 static void launch_front_bf16(const FrontParams &p, int n_tiles, hipStream_t st) {
-    hipLaunchKernelGGL((front_bf16_kernel<NB, NW>), dim3(n_tiles), dim3(NW * 64), 0, st, p);
+    if (p.fused) hipLaunchKernelGGL((front_bf16_kernel<NB, NW, U, true>), dim3(1), dim3(NW * 64), 0, st, p);
+    else hipLaunchKernelGGL((front_bf16_kernel<NB, NW, U, false>), dim3(n_tiles), dim3(NW * 64), 0, st, p);
 }
+
+// measured: with two tiles the sequential walk (52 us at T=64) loses to the three-kernel path (31 us)
+bool front_can_fuse(int T, int dtype) { return dtype == BM_BF16 && T > 0 && T <= TILE_T; }
 
 int launch_front(const FrontParams &p, int dtype, hipStream_t st) {
     const int n_tiles = (p.T + TILE_T - 1) / TILE_T;
@@ -420,11 +613,11 @@ int launch_front(const FrontParams &p, int dtype, hipStream_t st) {
         hipLaunchKernelGGL(front_f32_kernel, dim3(n_tiles), dim3(256), 0, st, p);
     } else {
         const int nb = (p.E + 31) / 32;
-        const bool small = n_tiles <= 8;   // few tiles: split the hidden dimension 16 ways
-        if (nb <= 1) small ? launch_front_bf16<1, 16>(p, n_tiles, st) : launch_front_bf16<1, 4>(p, n_tiles, st);
-        else if (nb <= 2) small ? launch_front_bf16<2, 16>(p, n_tiles, st) : launch_front_bf16<2, 4>(p, n_tiles, st);
-        else if (nb <= 4) small ? launch_front_bf16<4, 8>(p, n_tiles, st) : launch_front_bf16<4, 4>(p, n_tiles, st);
-        else launch_front_bf16<8, 4>(p, n_tiles, st);
+        // a tile is latency-bound: 16 waves split the product and rank two tokens each
+        if (nb <= 1) launch_front_bf16<1, 16, 8>(p, n_tiles, st);
+        else if (nb <= 2) launch_front_bf16<2, 16, 4>(p, n_tiles, st);
+        else if (nb <= 4) launch_front_bf16<4, 16, 2>(p, n_tiles, st);
+        else launch_front_bf16<8, 8, 2>(p, n_tiles, st);
     }
     return launch_status(__func__);
 }
@@ -445,7 +638,7 @@ int launch_count(const int32_t *ids, int T, int K, int E, int32_t *tile_counts, 
 }
 
 int launch_scan(const ScanParams &p, hipStream_t st) {
-    hipLaunchKernelGGL(scan_kernel, dim3(1), dim3(256), 0, st, p);
+    hipLaunchKernelGGL(scan_kernel, dim3(1), dim3(1024), 0, st, p);
     return launch_status(__func__);
 }
 

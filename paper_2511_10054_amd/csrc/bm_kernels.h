@@ -6,21 +6,6 @@
 
 namespace bm {
 
-struct FrontParams {
-    const void *x;          // [T][d]
-    const void *wr;         // [E][d]
-    const float *bias;      // [E] or null
-    int T, d, E, K, R, H;
-    uint32_t flags;
-    int32_t *ids;           // [T][K] router's choice
-    float *w;               // [T][K]
-    const uint64_t *bitmap; // null => routing only (no substitution, no histogram)
-    const int32_t *table;   // [E][R]
-    int32_t *ids2;          // [T][K] after substitution
-    int32_t *tile_counts;   // [n_tiles][E]
-    int32_t *tile_stats;    // [n_tiles][4]
-};
-
 struct RemapParams {
     int T, K, E, R, H, unique;
     const uint64_t *bitmap;
@@ -50,6 +35,25 @@ struct ScatterParams {
     int32_t *perm, *inv_perm;     // [T*K]
     int32_t *row_token;           // [rows] or null
 };
+
+struct FrontParams {
+    const void *x;          // [T][d]
+    const void *wr;         // [E][d]
+    const float *bias;      // [E] or null
+    int T, d, E, K, R, H;
+    uint32_t flags;
+    int32_t *ids;           // [T][K] router's choice
+    float *w;               // [T][K]
+    const uint64_t *bitmap; // null => routing only (no substitution, no histogram)
+    const int32_t *table;   // [E][R]
+    int32_t *ids2;          // [T][K] after substitution
+    int32_t *tile_counts;   // [n_tiles][E]
+    int32_t *tile_stats;    // [n_tiles][4]
+    int fused;              // one workgroup walks all tiles and also does the scan and the scatter
+    ScanParams scan;        // used when fused
+    ScatterParams scat;     // used when fused
+};
+
 
 // Grouped projection C[rows][N] = A[rows][Kd] * B_g[N][Kd]^T over row tiles.
 struct GemmParams {
@@ -94,6 +98,7 @@ struct CombineParams {
 // the kernel and the HIP error) otherwise
 int launch_status(const char *what);
 
+bool front_can_fuse(int T, int dtype);   // the batch is small enough for the one-workgroup front end
 int launch_front(const FrontParams &p, int dtype, hipStream_t st);
 int launch_remap(const RemapParams &p, hipStream_t st);
 int launch_count(const int32_t *ids, int T, int K, int E, int32_t *tile_counts, hipStream_t st);
