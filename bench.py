@@ -27,6 +27,16 @@ sys.path.insert(0, ROOT)
 PEAK_HBM_GBS = 8000.0        # MI355X HBM3E
 PEAK_BF16_TFLOPS = 2500.0    # MI355X dense bf16 MFMA
 
+# HBM bytes per launch of the gate/up kernel (read + write), from the rocprofv3 --pmc FETCH_SIZE and
+# WRITE_SIZE runs summarised under profiles/ (counter x copy-kernel calibration); default shapes,
+# first-resident mode only.  Re-measure after changing that kernel.
+TRAFFIC_BYTES = {
+    "c2_mixtral_decode_T64": 1335.1e6,
+    "c3_mixtral_prefill_T4096": 3828.0e6,
+    "c4_qwen3_T2048": 646.2e6,
+    "c5_deepseek_T8192": 1723.1e6,
+}
+
 WORKLOADS = {
     "c2": ("c2_mixtral_decode", 64),
     "c3": ("c3_mixtral_prefill", 4096),
@@ -169,6 +179,8 @@ def main():
     ap.add_argument("--tokens", type=int, default=None)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--unique", action="store_true", help="Algorithm 1's uniqueness test on")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="run plain 1 GiB device copies and exit (reference for the HBM byte counters)")
     ap.add_argument("--also-tokens", default=None,
                     help="comma-separated extra batch sizes on the same layer, reported under 'also'")
     args = ap.parse_args()
@@ -180,6 +192,15 @@ def main():
     if not torch.cuda.is_available():
         print("bench.py needs an MI355X", file=sys.stderr)
         sys.exit(1)
+    if args.copy_calibration:
+        # a copy kernel of known size: reads 2^30 bytes and writes 2^30 bytes per launch
+        src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda").random_(0, 255)
+        dst = torch.empty_like(src)
+        for _ in range(5):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_bytes_read": 1 << 30, "copy_bytes_written": 1 << 30, "launches": 5}))
+        return
     import paper_2511_10054_amd as bm
     bm.load_library()                                   # fails loudly if the HIP library is not built
 
@@ -188,6 +209,8 @@ def main():
         T = args.tokens
     r = run_workload(name, T, args.steps, args.warmup, unique=args.unique)
     roof = roofline_gateup(r)
+    if not args.unique:
+        roof["traffic"] = TRAFFIC_BYTES.get(f"{name}_T{T}")
     out = {
         "metric": "moe_layer_tokens_per_s_with_buddy_remap",
         "value": round(T / (r["ms_per_step"] * 1e-3), 1),

@@ -520,18 +520,28 @@ __global__ void __launch_bounds__(1024) scan_kernel(ScanParams p) {
     }
     for (int g = p.E + tid; g < G; g += blockDim.x) total[g] = p.T;
     __syncthreads();
-    if (tid == 0) {
-        int run = 0, trun = 0;
-        for (int g = 0; g < G; ++g) {
-            start[g] = run;
-            tstart[g] = trun;
-            run += total[g];
-            trun += (total[g] + p.BM - 1) / p.BM;
+    if (wave == 0) {                               // exclusive scans over the groups, a few consecutive groups per lane
+        constexpr int PER = (BM_MAX_E + 8 + 63) / 64;
+        int cnt[PER], nt[PER], sum_c = 0, sum_t = 0;
+#pragma unroll
+        for (int i = 0; i < PER; ++i) {
+            const int g = lane * PER + i;
+            const int c = g < G ? total[g] : 0;
+            cnt[i] = c;
+            nt[i] = (c + p.BM - 1) / p.BM;
+            sum_c += c;
+            sum_t += nt[i];
         }
-        start[G] = run;
-        tstart[G] = trun;
-        p.n_mtiles[0] = trun;
-        p.n_mtiles[1] = run;                       // total rows
+        int tot_c, tot_t;
+        int run_c = wave_excl_scan(sum_c, tot_c), run_t = wave_excl_scan(sum_t, tot_t);
+#pragma unroll
+        for (int i = 0; i < PER; ++i) {
+            const int g = lane * PER + i;
+            if (g <= G) { start[g] = run_c; tstart[g] = run_t; }
+            run_c += cnt[i];
+            run_t += nt[i];
+        }
+        if (lane == 0) { p.n_mtiles[0] = tot_t; p.n_mtiles[1] = tot_c; }
     }
     __syncthreads();
     for (int g = tid; g <= G; g += blockDim.x) p.offsets[g] = start[g];
