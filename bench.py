@@ -71,7 +71,7 @@ class HipEvents:
             self.hip.hipEventDestroy(ctypes.c_void_p(e))
 
 
-def run_workload(name, T, steps, warmup, with_events=True, unique=False, base=None):
+def run_workload(name, T, steps, warmup, with_events=True, unique=False, base=None, pack=False):
     """base: result of an earlier run_workload on the same layer (weights are reused)."""
     import torch
     import workloads
@@ -79,7 +79,7 @@ def run_workload(name, T, steps, warmup, with_events=True, unique=False, base=No
     spec = workloads.CONFIGS[name]
     t_gen = time.time()
     host = HostLayer(spec, T, only_resident=True, poison=True, base=base["host"] if base else None)
-    dev = DeviceLayer(host, unique=unique, base=base["dev"] if base else None)
+    dev = DeviceLayer(host, unique=unique, base=base["dev"] if base else None, pack=pack)
     t_gen = time.time() - t_gen
     bm = dev.bm
     E, K = spec.E, spec.K
@@ -179,6 +179,8 @@ def main():
     ap.add_argument("--tokens", type=int, default=None)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--unique", action="store_true", help="Algorithm 1's uniqueness test on")
+    ap.add_argument("--no-pack", action="store_true",
+                    help="decode workload: stream the public weight layout instead of the packed copy")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="run plain 1 GiB device copies and exit (reference for the HBM byte counters)")
     ap.add_argument("--also-tokens", default=None,
@@ -207,7 +209,8 @@ def main():
     name, T = WORKLOADS[args.workload]
     if args.tokens:
         T = args.tokens
-    r = run_workload(name, T, args.steps, args.warmup, unique=args.unique)
+    pack = (args.workload == "c2") and not args.no_pack     # decode: weights repacked once at load time
+    r = run_workload(name, T, args.steps, args.warmup, unique=args.unique, pack=pack)
     roof = roofline_gateup(r)
     if not args.unique:
         roof["traffic"] = TRAFFIC_BYTES.get(f"{name}_T{T}")
@@ -227,6 +230,7 @@ def main():
         "config": {"workload": f"{name}_T{T}", "T": T, "d": r["spec"].d, "E": r["spec"].E, "F": r["spec"].F,
                    "K": r["spec"].K, "n_shared": r["spec"].n_shared, "resident": r["spec"].n_resident,
                    "remap": "unique" if args.unique else "first_resident",
+                   "weights": "fragment-major copy made once by bm_pack_weights (untimed)" if pack else "public layout",
                    "a_live": r["a_live"], "experts_touched": r["n_touched"],
                    "n_miss": r["stats"][0], "n_substituted": r["stats"][1], "n_dropped": r["stats"][2]},
         "roofline": roof,
@@ -239,7 +243,7 @@ def main():
     if also:
         out["also"] = {}
         for t2 in [int(v) for v in also.split(",") if v]:
-            r2 = run_workload(name, t2, args.steps, args.warmup, unique=args.unique, base=r)
+            r2 = run_workload(name, t2, args.steps, args.warmup, unique=args.unique, base=r, pack=pack)
             roof2 = roofline_gateup(r2)
             out["also"][f"T{t2}"] = {"tokens_per_s": round(t2 / (r2["ms_per_step"] * 1e-3), 1),
                                      "ms_per_step": round(r2["ms_per_step"], 5),

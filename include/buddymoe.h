@@ -80,6 +80,13 @@ typedef struct {
     const void *ws_gate;       /* [n_shared][F][d], NULL when n_shared==0 */
     const void *ws_up;         /* [n_shared][F][d]                        */
     const void *ws_down;       /* [n_shared][d][F]                        */
+    /* Optional fragment-major copies written by bm_pack_weights (bf16 only; NULL =
+     * not available).  When all copies a layer needs are given, the decode-sized
+     * path streams them instead of the arrays above; results are identical. */
+    const void *wp_gateup;     /* routed gate+up, bm_packed_bytes(desc, 0) bytes */
+    const void *wp_down;       /* routed down,    bm_packed_bytes(desc, 1) bytes */
+    const void *wsp_gateup;    /* shared gate+up, bm_packed_bytes(desc, 2) bytes */
+    const void *wsp_down;      /* shared down,    bm_packed_bytes(desc, 3) bytes */
 } bm_weights;
 
 typedef struct {
@@ -157,6 +164,23 @@ int bm_moe_forward(const bm_layer_desc *desc, const void *x, const bm_weights *w
                    const uint64_t *residency_bitmap, const int32_t *buddy_table, void *y,
                    void *workspace, size_t workspace_bytes, const bm_debug_out *dbg,
                    void *stream);
+
+/* One-time repacking of the expert weights for decode-sized batches (model
+ * load time, not part of the forward pass).  The public layout above stays the
+ * reference; the packed copy holds, for every block of 16 weight rows and every
+ * 32 values of the reduction dimension, the 1 KB MFMA operand fragment
+ * contiguously (gate and up fragments interleaved), so a wave streams its rows
+ * as one contiguous run.  bf16 only; needs F % 32 == 0 and d % 32 == 0.
+ * which: 0 routed gate+up, 1 routed down, 2 shared gate+up, 3 shared down. */
+size_t bm_packed_bytes(const bm_layer_desc *desc, int which);
+
+/* Fills the packed buffers named in weights->wp_* / wsp_* (device, caller-owned,
+ * at least bm_packed_bytes each; a NULL member is skipped) from the public
+ * arrays of the same struct.  residency_bitmap (device, nullable): only routed
+ * experts whose bit is set are read and packed - weights of absent experts are
+ * not touched; NULL packs all.  Shared experts are always packed. */
+int bm_pack_weights(const bm_layer_desc *desc, const bm_weights *weights,
+                    const uint64_t *residency_bitmap, void *stream);
 
 /* Bytes of device scratch bm_moe_forward / bm_permute_by_expert need for
  * this desc (host, pure function of desc; 0 if desc is invalid). */

@@ -27,7 +27,8 @@ class LayerDesc(ctypes.Structure):
 
 class Weights(ctypes.Structure):
     _fields_ = [(n, ctypes.c_void_p) for n in
-                ("w_router", "router_bias", "w_gate", "w_up", "w_down", "ws_gate", "ws_up", "ws_down")]
+                ("w_router", "router_bias", "w_gate", "w_up", "w_down", "ws_gate", "ws_up", "ws_down",
+                 "wp_gateup", "wp_down", "wsp_gateup", "wsp_down")]
 
 
 class DebugOut(ctypes.Structure):
@@ -55,6 +56,10 @@ def load_library() -> ctypes.CDLL:
         lib.bm_workspace_bytes.restype = ctypes.c_size_t
         lib.bm_workspace_bytes.argtypes = [ctypes.POINTER(LayerDesc)]
         lib.bm_validate_tables.argtypes = [ctypes.POINTER(LayerDesc), vp, vp]
+        lib.bm_packed_bytes.restype = ctypes.c_size_t
+        lib.bm_packed_bytes.argtypes = [ctypes.POINTER(LayerDesc), i32]
+        lib.bm_pack_weights.argtypes = [ctypes.POINTER(LayerDesc), ctypes.POINTER(Weights), vp, vp]
+        lib.bm_pack_weights.restype = i32
         lib.bm_route_topk.argtypes = [ctypes.POINTER(LayerDesc), vp, vp, vp, vp, vp, vp]
         lib.bm_buddy_remap.argtypes = [ctypes.POINTER(LayerDesc), vp, vp, vp, vp, vp, vp, vp]
         lib.bm_permute_by_expert.argtypes = [ctypes.POINTER(LayerDesc), vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
@@ -136,5 +141,17 @@ def bm_moe_forward(desc: LayerDesc, x, weights: Weights, bitmap, table, y, works
                                          _stream() if stream is None else stream), "bm_moe_forward")
 
 
-def make_weights(w_router, router_bias, w_gate, w_up, w_down, ws_gate=None, ws_up=None, ws_down=None) -> Weights:
-    return Weights(*[_ptr(t) for t in (w_router, router_bias, w_gate, w_up, w_down, ws_gate, ws_up, ws_down)])
+def make_weights(w_router, router_bias, w_gate, w_up, w_down, ws_gate=None, ws_up=None, ws_down=None,
+                 wp_gateup=None, wp_down=None, wsp_gateup=None, wsp_down=None) -> Weights:
+    return Weights(*[_ptr(t) for t in (w_router, router_bias, w_gate, w_up, w_down, ws_gate, ws_up, ws_down,
+                                       wp_gateup, wp_down, wsp_gateup, wsp_down)])
+
+
+def bm_packed_bytes(desc: LayerDesc, which: int) -> int:
+    return int(load_library().bm_packed_bytes(ctypes.byref(desc), which))
+
+
+def bm_pack_weights(desc: LayerDesc, weights: Weights, bitmap=None, stream: Optional[int] = None):
+    """Fills the packed buffers named in `weights` (wp_*/wsp_*) from its public arrays."""
+    _check(load_library().bm_pack_weights(ctypes.byref(desc), ctypes.byref(weights), _ptr(bitmap),
+                                          _stream() if stream is None else stream), "bm_pack_weights")

@@ -151,6 +151,45 @@ size_t bm_workspace_bytes(const bm_layer_desc *desc) {
     return make_layout(desc).total;
 }
 
+size_t bm_packed_bytes(const bm_layer_desc *desc, int which) {
+    if (check_desc(desc, true) != BM_OK || desc->dtype != BM_BF16 || which < 0 || which > 3) return 0;
+    const size_t per = (size_t)desc->F * desc->d * 2;            // one matrix of one expert
+    const size_t n = which < 2 ? (size_t)desc->E : (size_t)desc->n_shared;
+    return n * per * ((which & 1) ? 1 : 2);
+}
+
+int bm_pack_weights(const bm_layer_desc *desc, const bm_weights *wt, const uint64_t *residency_bitmap,
+                    void *stream) {
+    int rc = check_desc(desc, true);
+    if (rc) return rc;
+    if (desc->dtype != BM_BF16) return BM_ERR_DTYPE;
+    if (!wt) return BM_ERR_NULL;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    (void)hipGetLastError();
+    int err = 0;
+    if (wt->wp_gateup) {
+        if (!wt->w_gate || !wt->w_up) return BM_ERR_NULL;
+        err |= launch_pack(wt->w_gate, wt->w_up, const_cast<void *>(wt->wp_gateup), desc->E, desc->F, desc->d,
+                           residency_bitmap, st);
+    }
+    if (wt->wp_down) {
+        if (!wt->w_down) return BM_ERR_NULL;
+        err |= launch_pack(wt->w_down, nullptr, const_cast<void *>(wt->wp_down), desc->E, desc->d, desc->F,
+                           residency_bitmap, st);
+    }
+    if (desc->n_shared > 0 && wt->wsp_gateup) {
+        if (!wt->ws_gate || !wt->ws_up) return BM_ERR_NULL;
+        err |= launch_pack(wt->ws_gate, wt->ws_up, const_cast<void *>(wt->wsp_gateup), desc->n_shared, desc->F,
+                           desc->d, nullptr, st);
+    }
+    if (desc->n_shared > 0 && wt->wsp_down) {
+        if (!wt->ws_down) return BM_ERR_NULL;
+        err |= launch_pack(wt->ws_down, nullptr, const_cast<void *>(wt->wsp_down), desc->n_shared, desc->d, desc->F,
+                           nullptr, st);
+    }
+    return err ? BM_ERR_HIP : BM_OK;
+}
+
 int bm_validate_tables(const bm_layer_desc *desc, const uint64_t *bitmap_host, const int32_t *table_host) {
     if (!desc || !bitmap_host || !table_host) return BM_ERR_NULL;
     if (desc->E <= 0 || desc->E > BM_MAX_E) return BM_ERR_SHAPE;
@@ -325,6 +364,10 @@ int bm_moe_forward(const bm_layer_desc *desc, const void *x, const bm_weights *w
         SkinnyParams s1{};
         s1.a = x; s1.row_map = cp.row_token;
         s1.b0 = wt->w_gate; s1.b1 = wt->w_up; s1.sb0 = wt->ws_gate; s1.sb1 = wt->ws_up;
+        // packed copies are used only when every group of the layer has one
+        const bool pk_gu = wt->wp_gateup && (desc->n_shared == 0 || wt->wsp_gateup);
+        const bool pk_dn = wt->wp_down && (desc->n_shared == 0 || wt->wsp_down);
+        s1.pk = pk_gu ? wt->wp_gateup : nullptr; s1.spk = pk_gu ? wt->wsp_gateup : nullptr;
         s1.c = gp.c; s1.N = desc->F; s1.Kd = desc->d; s1.E = E;
         s1.max_groups = G < L.mtiles_max ? G : L.mtiles_max;
         s1.ksplit = 1; s1.rows_max = L.rows_max; s1.max_rows_per_group = T * K;
@@ -332,6 +375,7 @@ int bm_moe_forward(const bm_layer_desc *desc, const void *x, const bm_weights *w
         SkinnyParams s2 = s1;
         s2.a = gp.c; s2.row_map = nullptr;
         s2.b0 = wt->w_down; s2.b1 = nullptr; s2.sb0 = wt->ws_down; s2.sb1 = nullptr;
+        s2.pk = pk_dn ? wt->wp_down : nullptr; s2.spk = pk_dn ? wt->wsp_down : nullptr;
         s2.c = dp.c; s2.N = desc->d; s2.Kd = desc->F; s2.ksplit = ksplit;
         err |= launch_skinny_gateup_bf16(s1, st);
         mark(2);

@@ -74,6 +74,7 @@ struct SkinnyParams {
     const void *a;                // activations [..][Kd] bf16
     const int32_t *row_map;       // row -> row of a (null: identity)
     const void *b0, *b1, *sb0, *sb1;
+    const void *pk, *spk;         // fragment-major copies (routed, shared) from bm_pack_weights, or null
     void *c;                      // DUAL: bf16 [rows][N]; else fp32 [ksplit][rows_max][N]
     int N, Kd, E;
     int max_groups;               // grid bound on live groups
@@ -120,5 +121,9 @@ int launch_skinny_gateup_bf16(const SkinnyParams &p, hipStream_t st);
 int launch_skinny_down_bf16(const SkinnyParams &p, hipStream_t st);
 
 int launch_combine(const CombineParams &p, bool o_bf16, hipStream_t st);
+
+// fragment-major repacking of n matrices [N][Kd] (two interleaved when src1 is given)
+int launch_pack(const void *src0, const void *src1, void *dst, int n, int N, int Kd, const uint64_t *bitmap,
+                hipStream_t st);
 
 }  // namespace bm

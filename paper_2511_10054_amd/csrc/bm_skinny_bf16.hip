@@ -296,11 +296,15 @@ static void launch_skinny_q(const SkinnyParams &p, hipStream_t st) {
 template <int NBT> struct SkinnyChunk { static constexpr int CH = NBT == 1 ? 16 : 8; };
 constexpr int KUNIT = 512;
 
-template <bool DUAL, int NBT>
+// PACKED: the weights come from bm_pack_weights' fragment-major copy, where the 1 KB operand
+// fragment of every (16-row block, k-step) is contiguous (gate and up fragments interleaved), so a
+// wave's stream is one contiguous run; otherwise from the public row-major layout.
+template <bool DUAL, int NBT, bool PACKED>
 __device__ __forceinline__ void skinny_lds_pass(const SkinnyParams &p, const uint16_t *w0, const uint16_t *w1,
                                                 u32x4 *xs, int row_begin, int row_end, int k_begin,
                                                 int k_end, int n0, int kslice, bool active) {
     constexpr int CH = SkinnyChunk<NBT>::CH;
+    constexpr int KSTEP = PACKED ? 512 * (DUAL ? 2 : 1) : 32;   // weight elements between consecutive k-steps
     constexpr int XW = CH / 4;                          // k-steps of a chunk each wave stages
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, lr = lane & 15, lk = lane >> 4;
     const uint16_t *a = static_cast<const uint16_t *>(p.a);
@@ -331,8 +335,8 @@ __device__ __forceinline__ void skinny_lds_pass(const SkinnyParams &p, const uin
     BM_LOAD_X(k_begin);
 #pragma unroll
     for (int u = 0; u < CH; ++u) {
-        s0[u] = ldg128_stream(w0 + k_begin + u * 32);
-        if (DUAL) s1[u] = ldg128_stream(w1 + k_begin + u * 32);
+        s0[u] = ldg128_stream(w0 + (k_begin >> 5) * KSTEP + u * KSTEP);
+        if (DUAL) s1[u] = ldg128_stream(w1 + (k_begin >> 5) * KSTEP + u * KSTEP);
     }
     BM_STORE_X(0);
     __syncthreads();
@@ -357,8 +361,8 @@ __device__ __forceinline__ void skinny_lds_pass(const SkinnyParams &p, const uin
                                                                            acc1[tb], 0, 0, 0);       \
                 }                                                                                    \
                 if (REFILL_) {                                                                       \
-                    s0[u] = ldg128_stream(w0 + kn_ + u * 32);                                        \
-                    if (DUAL) s1[u] = ldg128_stream(w1 + kn_ + u * 32);                              \
+                    s0[u] = ldg128_stream(w0 + (kn_ >> 5) * KSTEP + u * KSTEP);                      \
+                    if (DUAL) s1[u] = ldg128_stream(w1 + (kn_ >> 5) * KSTEP + u * KSTEP);            \
                 }                                                                                    \
                 __builtin_amdgcn_sched_barrier(0);                                                   \
             }                                                                                        \
@@ -390,7 +394,7 @@ __device__ __forceinline__ void skinny_lds_pass(const SkinnyParams &p, const uin
     }
 }
 
-template <bool DUAL, int MAXNBT>
+template <bool DUAL, int MAXNBT, bool PACKED>
 __global__ void __launch_bounds__(256) skinny_lds_bf16_kernel(SkinnyParams p) {
     __shared__ u32x4 xs[2 * 8 * MAXNBT * 64 * (MAXNBT == 1 ? 2 : 1)];
     const int gi = blockIdx.y;
@@ -405,21 +409,25 @@ __global__ void __launch_bounds__(256) skinny_lds_bf16_kernel(SkinnyParams p) {
     const int per = (p.Kd / KUNIT) / p.ksplit;        // the host picks ksplit as a divisor
     const int k_begin = kslice * per * KUNIT, k_end = k_begin + per * KUNIT;
 
-    const size_t gofs = (size_t)(g < p.E ? g : g - p.E) * p.N * p.Kd;
-    const uint16_t *b0 = static_cast<const uint16_t *>(g < p.E ? p.b0 : p.sb0) + gofs;
-    const uint16_t *w0 = b0 + (size_t)(n0 + lr) * p.Kd + lk * 8;
-    const uint16_t *w1 = nullptr;
-    if (DUAL) {
-        const uint16_t *b1 = static_cast<const uint16_t *>(g < p.E ? p.b1 : p.sb1) + gofs;
-        w1 = b1 + (size_t)(n0 + lr) * p.Kd + lk * 8;
+    const int gl = g < p.E ? g : g - p.E;             // index inside the routed or the shared stack
+    const uint16_t *w0, *w1 = nullptr;
+    if (PACKED) {
+        constexpr int NM = DUAL ? 2 : 1;
+        const uint16_t *base = static_cast<const uint16_t *>(g < p.E ? p.pk : p.spk);
+        w0 = base + ((size_t)gl * (p.N >> 4) + (n0 >> 4)) * (size_t)(p.Kd >> 5) * (512 * NM) + lane * 8;
+        if (DUAL) w1 = w0 + 512;
+    } else {
+        const size_t gofs = (size_t)gl * p.N * p.Kd;
+        w0 = static_cast<const uint16_t *>(g < p.E ? p.b0 : p.sb0) + gofs + (size_t)(n0 + lr) * p.Kd + lk * 8;
+        if (DUAL) w1 = static_cast<const uint16_t *>(g < p.E ? p.b1 : p.sb1) + gofs + (size_t)(n0 + lr) * p.Kd + lk * 8;
     }
     constexpr int PASS_ROWS = 16 * MAXNBT;
     for (int rb = row_begin; rb < row_end; rb += PASS_ROWS) {
         const int re = min(row_end, rb + PASS_ROWS);
         const int n_rows = re - rb;
-        if (MAXNBT == 1 || n_rows <= 16) skinny_lds_pass<DUAL, 1>(p, w0, w1, xs, rb, re, k_begin, k_end, n0, kslice, active);
-        else if (MAXNBT == 2 || n_rows <= 32) skinny_lds_pass<DUAL, 2>(p, w0, w1, xs, rb, re, k_begin, k_end, n0, kslice, active);
-        else skinny_lds_pass<DUAL, 4>(p, w0, w1, xs, rb, re, k_begin, k_end, n0, kslice, active);
+        if (MAXNBT == 1 || n_rows <= 16) skinny_lds_pass<DUAL, 1, PACKED>(p, w0, w1, xs, rb, re, k_begin, k_end, n0, kslice, active);
+        else if (MAXNBT == 2 || n_rows <= 32) skinny_lds_pass<DUAL, 2, PACKED>(p, w0, w1, xs, rb, re, k_begin, k_end, n0, kslice, active);
+        else skinny_lds_pass<DUAL, 4, PACKED>(p, w0, w1, xs, rb, re, k_begin, k_end, n0, kslice, active);
         __syncthreads();                              // the next pass restages the LDS buffers
     }
 }
@@ -429,7 +437,8 @@ bool skinny_lds_ok(int Kd, int ksplit) { return Kd % (KUNIT * ksplit) == 0; }
 template <bool DUAL>
 static void launch_skinny_lds(const SkinnyParams &p, hipStream_t st) {
     dim3 grid((p.N / 16 + 3) / 4, p.max_groups, p.ksplit);
-    hipLaunchKernelGGL((skinny_lds_bf16_kernel<DUAL, 4>), grid, dim3(256), 0, st, p);
+    if (p.pk != nullptr) hipLaunchKernelGGL((skinny_lds_bf16_kernel<DUAL, 4, true>), grid, dim3(256), 0, st, p);
+    else hipLaunchKernelGGL((skinny_lds_bf16_kernel<DUAL, 4, false>), grid, dim3(256), 0, st, p);
 }
 
 // ---------------------------------------------------------------------------
@@ -450,7 +459,7 @@ struct PItem {
     int g, row_begin, row_end, n0;
 };
 
-template <bool DUAL>
+template <bool DUAL, bool PACKED>
 __device__ __forceinline__ PItem p_setup(const SkinnyParams &p, int it, int NRB, int lr, int lk, int k0) {
     PItem r;
     const int gi = it / NRB, rb = it - gi * NRB;
@@ -458,16 +467,24 @@ __device__ __forceinline__ PItem p_setup(const SkinnyParams &p, int it, int NRB,
     r.row_begin = p.offsets[r.g];
     r.row_end = p.offsets[r.g + 1];
     r.n0 = rb * 16;
-    const size_t gofs = (size_t)(r.g < p.E ? r.g : r.g - p.E) * p.N * p.Kd;
-    const size_t rofs = gofs + (size_t)(r.n0 + lr) * p.Kd + lk * 8 + k0;
-    r.w0 = static_cast<const uint16_t *>(r.g < p.E ? p.b0 : p.sb0) + rofs;
-    r.w1 = DUAL ? static_cast<const uint16_t *>(r.g < p.E ? p.b1 : p.sb1) + rofs : nullptr;
+    const int gl = r.g < p.E ? r.g : r.g - p.E;
+    if (PACKED) {
+        constexpr int NM = DUAL ? 2 : 1;
+        const uint16_t *base = static_cast<const uint16_t *>(r.g < p.E ? p.pk : p.spk);
+        r.w0 = base + (((size_t)gl * NRB + rb) * (size_t)(p.Kd >> 5) + (k0 >> 5)) * (512 * NM) + (lk * 16 + lr) * 8;
+        r.w1 = DUAL ? r.w0 + 512 : nullptr;
+    } else {
+        const size_t rofs = (size_t)gl * p.N * p.Kd + (size_t)(r.n0 + lr) * p.Kd + lk * 8 + k0;
+        r.w0 = static_cast<const uint16_t *>(r.g < p.E ? p.b0 : p.sb0) + rofs;
+        r.w1 = DUAL ? static_cast<const uint16_t *>(r.g < p.E ? p.b1 : p.sb1) + rofs : nullptr;
+    }
     return r;
 }
 
-template <bool DUAL, int NBT, int CH>
+template <bool DUAL, int NBT, int CH, bool PACKED>
 __global__ void __launch_bounds__(512) skinny_p_kernel(SkinnyParams p) {
     constexpr int NM = DUAL ? 2 : 1;
+    constexpr int KSTEP = PACKED ? 512 * NM : 32;              // weight elements between consecutive k-steps
     constexpr int RED = 2 * 8 * NBT * NM * 64;                 // f32x4 entries of the reduction area
     constexpr int PAD = RED * 16 < 84 * 1024 ? (84 * 1024 - RED * 16) / 16 : 0;
     __shared__ f32x4 red[RED + PAD];                           // > half the LDS: one workgroup per compute unit
@@ -483,7 +500,7 @@ __global__ void __launch_bounds__(512) skinny_p_kernel(SkinnyParams p) {
     const uint16_t *a = static_cast<const uint16_t *>(p.a);
 
     int it = blockIdx.x;
-    PItem cur = p_setup<DUAL>(p, it, NRB, lr, lk, k0);
+    PItem cur = p_setup<DUAL, PACKED>(p, it, NRB, lr, lk, k0);
     const uint16_t *xa[NBT];
 #pragma unroll
     for (int tb = 0; tb < NBT; ++tb) {
@@ -500,8 +517,8 @@ __global__ void __launch_bounds__(512) skinny_p_kernel(SkinnyParams p) {
     u32x4 s0[CH], s1[CH], sx[NBT][CH];
 #pragma unroll
     for (int u = 0; u < CH; ++u) {
-        s0[u] = ldg128_stream(cur.w0 + u * 32);
-        if (DUAL) s1[u] = ldg128_stream(cur.w1 + u * 32);
+        s0[u] = ldg128_stream(cur.w0 + u * KSTEP);
+        if (DUAL) s1[u] = ldg128_stream(cur.w1 + u * KSTEP);
 #pragma unroll
         for (int tb = 0; tb < NBT; ++tb) sx[tb][u] = ldg128(xa[tb] + u * 32);
     }
@@ -554,7 +571,7 @@ __global__ void __launch_bounds__(512) skinny_p_kernel(SkinnyParams p) {
         PItem nxt = cur;
         const uint16_t *rw0, *rw1, *rx[NBT];
         if (last_in_item) {
-            nxt = p_setup<DUAL>(p, it + gridDim.x, NRB, lr, lk, k0);
+            nxt = p_setup<DUAL, PACKED>(p, it + gridDim.x, NRB, lr, lk, k0);
             rw0 = nxt.w0;
             rw1 = nxt.w1;
             if (nxt.g != cur.g) {                       // rare: the next item belongs to another group
@@ -569,8 +586,8 @@ __global__ void __launch_bounds__(512) skinny_p_kernel(SkinnyParams p) {
             for (int tb = 0; tb < NBT; ++tb) rx[tb] = xa[tb];
         } else {
             const int ofs = (c_in_item + 1) * (CH * 32);
-            rw0 = cur.w0 + ofs;
-            rw1 = DUAL ? cur.w1 + ofs : nullptr;
+            rw0 = cur.w0 + (c_in_item + 1) * (CH * KSTEP);
+            rw1 = DUAL ? cur.w1 + (c_in_item + 1) * (CH * KSTEP) : nullptr;
 #pragma unroll
             for (int tb = 0; tb < NBT; ++tb) rx[tb] = xa[tb] + ofs;
         }
@@ -579,8 +596,8 @@ __global__ void __launch_bounds__(512) skinny_p_kernel(SkinnyParams p) {
 #pragma unroll
         for (int u = 0; u < CH; ++u) {
             BM_CONSUME(u);
-            s0[u] = ldg128_stream(rw0 + u * 32);
-            if (DUAL) s1[u] = ldg128_stream(rw1 + u * 32);
+            s0[u] = ldg128_stream(rw0 + u * KSTEP);
+            if (DUAL) s1[u] = ldg128_stream(rw1 + u * KSTEP);
 #pragma unroll
             for (int tb = 0; tb < NBT; ++tb) sx[tb][u] = ldg128(rx[tb] + u * 32);
             __builtin_amdgcn_sched_barrier(0);
@@ -614,17 +631,23 @@ static bool launch_skinny_p(const SkinnyParams &p, hipStream_t st) {
         return false;
     const dim3 grid(cus), block(512);
     const bool one = p.max_rows_per_group <= 16;
+#define BM_LAUNCH_P(D_, NBT_, CH_)                                                                         \
+    {                                                                                                      \
+        if (p.pk != nullptr) hipLaunchKernelGGL((skinny_p_kernel<D_, NBT_, CH_, true>), grid, block, 0, st, p); \
+        else hipLaunchKernelGGL((skinny_p_kernel<D_, NBT_, CH_, false>), grid, block, 0, st, p);           \
+    }
     if (DUAL) {
-        if (one && skinny_p_ok(p.Kd, 8)) hipLaunchKernelGGL((skinny_p_kernel<true, 1, 8>), grid, block, 0, st, p);
-        else if (!one && skinny_p_ok(p.Kd, 8)) hipLaunchKernelGGL((skinny_p_kernel<true, 2, 8>), grid, block, 0, st, p);
+        if (one && skinny_p_ok(p.Kd, 8)) BM_LAUNCH_P(true, 1, 8)
+        else if (!one && skinny_p_ok(p.Kd, 8)) BM_LAUNCH_P(true, 2, 8)
         else return false;
     } else {
-        if (one && skinny_p_ok(p.Kd, 14)) hipLaunchKernelGGL((skinny_p_kernel<false, 1, 14>), grid, block, 0, st, p);
-        else if (one && skinny_p_ok(p.Kd, 8)) hipLaunchKernelGGL((skinny_p_kernel<false, 1, 8>), grid, block, 0, st, p);
-        else if (!one && skinny_p_ok(p.Kd, 14)) hipLaunchKernelGGL((skinny_p_kernel<false, 2, 14>), grid, block, 0, st, p);
-        else if (!one && skinny_p_ok(p.Kd, 8)) hipLaunchKernelGGL((skinny_p_kernel<false, 2, 8>), grid, block, 0, st, p);
+        if (one && skinny_p_ok(p.Kd, 14)) BM_LAUNCH_P(false, 1, 14)
+        else if (one && skinny_p_ok(p.Kd, 8)) BM_LAUNCH_P(false, 1, 8)
+        else if (!one && skinny_p_ok(p.Kd, 14)) BM_LAUNCH_P(false, 2, 14)
+        else if (!one && skinny_p_ok(p.Kd, 8)) BM_LAUNCH_P(false, 2, 8)
         else return false;
     }
+#undef BM_LAUNCH_P
     return true;
 }
 

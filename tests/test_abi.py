@@ -31,7 +31,7 @@ def test_library_exports_every_declared_symbol():
 
 def test_struct_layouts_match_header():
     assert ctypes.sizeof(bm.LayerDesc) == 40
-    assert ctypes.sizeof(Weights) == 64 and ctypes.sizeof(DebugOut) == 96
+    assert ctypes.sizeof(Weights) == 96 and ctypes.sizeof(DebugOut) == 96
 
 
 def test_strerror_and_workspace_bytes():
@@ -48,6 +48,21 @@ def test_strerror_and_workspace_bytes():
     n = bm.bm_workspace_bytes(_desc(T=8192, d=2048, E=64, F=1408, K=6, n_shared=2, R=8, H=8, dtype=bm.BM_BF16))
     rows = 8192 * 8
     assert n >= rows * (1408 + 2048) * 2
+
+
+def test_packed_bytes_and_pack_argument_errors():
+    lib = bm.load_library()
+    d = _desc(T=8, d=4096, E=8, F=14336, K=2, R=7, H=7, dtype=bm.BM_BF16, n_shared=1)
+    one = 14336 * 4096 * 2
+    assert bm.bm_packed_bytes(d, 0) == 8 * 2 * one and bm.bm_packed_bytes(d, 1) == 8 * one
+    assert bm.bm_packed_bytes(d, 2) == 2 * one and bm.bm_packed_bytes(d, 3) == one
+    assert bm.bm_packed_bytes(d, 4) == 0 and bm.bm_packed_bytes(_desc(), 0) == 0      # fp32 layers are not packed
+    w = Weights(*([256] * 8 + [0] * 4))
+    assert lib.bm_pack_weights(ctypes.byref(_desc()), ctypes.byref(w), None, None) == -3   # dtype
+    assert lib.bm_pack_weights(ctypes.byref(d), None, None, None) == -1
+    assert lib.bm_pack_weights(ctypes.byref(d), ctypes.byref(w), None, None) == 0          # nothing to fill
+    w3 = Weights(256, 0, 0, 256, 256, 0, 0, 0, 256, 0, 0, 0)
+    assert lib.bm_pack_weights(ctypes.byref(d), ctypes.byref(w3), None, None) == -1        # source missing
 
 
 def test_validate_tables():
@@ -83,12 +98,12 @@ def test_host_side_argument_errors_launch_nothing():
     assert lib.bm_permute_by_expert(ctypes.byref(d), one, one, one, one, None, 1 << 20, None) == -4
     assert lib.bm_permute_by_expert(ctypes.byref(d), one, one, one, one, one, 16, None) == -4
     assert lib.bm_permute_by_expert(ctypes.byref(d), one, one, one, one, ctypes.c_void_p(264), 1 << 20, None) == -4
-    w = Weights(*([256] * 8))
+    w = Weights(*([256] * 8 + [0] * 4))
     assert lib.bm_moe_forward(ctypes.byref(d), one, ctypes.byref(w), one, one, one, one, 16, None, None) == -4
     assert lib.bm_moe_forward(ctypes.byref(d), one, None, one, one, one, one, 1 << 30, None, None) == -1
     assert lib.bm_moe_forward(ctypes.byref(_desc(n_shared=9)), one, ctypes.byref(w), one, one, one, one, 1 << 30, None, None) == -2
     assert lib.bm_moe_forward(ctypes.byref(_desc(T=0)), None, None, None, None, None, None, 0, None, None) == 0
-    w2 = Weights(256, 0, 256, 256, 256, 0, 0, 0)
+    w2 = Weights(256, 0, 256, 256, 256, 0, 0, 0, 0, 0, 0, 0)
     assert lib.bm_moe_forward(ctypes.byref(_desc(n_shared=1)), one, ctypes.byref(w2), one, one, one, one, 1 << 30, None, None) == -1
 
 

@@ -19,7 +19,7 @@ def _layers(name):
         _cache.clear()                       # one big layer at a time
         spec = workloads.CONFIGS[name]
         host = HostLayer(spec, 1, only_resident=True, poison=True)
-        _cache[name] = (host, DeviceLayer(host))
+        _cache[name] = (host, DeviceLayer(host, pack=name.startswith("c2")))   # decode config: packed weights, as bench.py
     return _cache[name]
 
 

@@ -168,6 +168,37 @@ def test_layer_matches_oracle(name, over, T, unique):
     _check_layer(host, unique)
 
 
+DECODE_CASES = [
+    ("c2_mixtral_decode", dict(d=512, F=1024), 1),
+    ("c2_mixtral_decode", dict(d=2048, F=2048), 8),       # persistent kernel shapes
+    ("c2_mixtral_decode", dict(d=2048, F=3584), 16),
+    ("c2_mixtral_decode", dict(d=1024, F=2048), 64),      # LDS-staged kernel, several passes possible
+    ("c5_deepseek", dict(d=2048, F=1792, E=16, n_resident=4), 4),    # shared experts on the decode path
+    ("c4_qwen3", dict(d=256, F=96), 12),                  # odd widths: generic decode kernel
+]
+
+
+@pytest.mark.parametrize("name,over,T", DECODE_CASES)
+@pytest.mark.parametrize("pack", [False, True])
+def test_decode_path_matches_oracle(name, over, T, pack):
+    """Decode-sized batches, public and fragment-major (packed) weights; absent experts are NaN."""
+    spec = workloads.scaled(name, **over)
+    _say("decode", name, over, T, "packed" if pack else "public")
+    host = HostLayer(spec, T, only_resident=True, poison=True)
+    ref = host.oracle_forward(oracle)
+    dev = DeviceLayer(host, pack=pack)
+    out = dev.forward()
+    np.testing.assert_array_equal(out["ids_remapped"], ref["ids_remapped"])
+    assert np.isfinite(out["y"]).all()
+    e = err_metric(out["y"], ref["y"])
+    _say("   err", e)
+    assert e <= TOL["bf16"], e
+    if pack:
+        # packed and public weights give the same bytes
+        out2 = DeviceLayer(host).forward()
+        np.testing.assert_array_equal(out["y"], out2["y"])
+
+
 def test_layer_without_renormalisation_and_short_search():
     spec = workloads.scaled("c5_deepseek", d=256, F=352)
     _say("layer no-renorm H=2")

@@ -71,8 +71,9 @@ def to_device(a, device="cuda"):
 class DeviceLayer:
     """Uploads a HostLayer and runs the library through the Python binding."""
 
-    def __init__(self, host: HostLayer, unique=False, renorm=True, H=None, y_f32=False, base=None):
-        """base: another DeviceLayer whose uploaded weights are reused."""
+    def __init__(self, host: HostLayer, unique=False, renorm=True, H=None, y_f32=False, base=None, pack=False):
+        """base: another DeviceLayer whose uploaded (and packed) weights are reused.
+        pack: also build the fragment-major weight copies (bm_pack_weights), once."""
         import torch
         import paper_2511_10054_amd as bm
         self.bm = bm
@@ -93,7 +94,17 @@ class DeviceLayer:
         self.bitmap = to_device(host.bitmap)
         self.table = to_device(host.table)
         from paper_2511_10054_amd.binding import make_weights
-        self.weights = make_weights(self.w_router, self.bias, self.wg, self.wu, self.wd, self.sg, self.su, self.sd)
+        self.packed = None
+        if base is not None and base.packed is not None:
+            self.packed = base.packed
+        elif pack and s.dtype == "bf16":
+            self.packed = [torch.empty(max(bm.bm_packed_bytes(self.desc, i), 16), dtype=torch.uint8, device="cuda")
+                           if (i < 2 or s.n_shared) else None for i in range(4)]
+        pk = self.packed or [None] * 4
+        self.weights = make_weights(self.w_router, self.bias, self.wg, self.wu, self.wd, self.sg, self.su, self.sd, *pk)
+        if self.packed is not None and not (base is not None and base.packed is not None):
+            bm.bm_pack_weights(self.desc, self.weights, self.bitmap)      # only resident experts are read
+            torch.cuda.synchronize()
         nbytes = bm.bm_workspace_bytes(self.desc)
         self.workspace = torch.empty(max(nbytes, 256), dtype=torch.uint8, device="cuda")
         self.y_dtype = torch.float32 if (y_f32 or s.dtype == "f32") else torch.bfloat16
