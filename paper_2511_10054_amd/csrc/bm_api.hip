@@ -25,7 +25,7 @@ constexpr int SKINNY_KSPLIT = 8;
 // Row-tile height of the grouped GEMM: 256 rows when the average group is large
 // (measured on routed experts; shared experts always have T rows), else 128.
 int gemm_tile_rows(const bm_layer_desc *d) {
-    return ((long long)d->T * d->K / d->E >= 512) ? 256 : 128;
+    return ((long long)d->T * d->K / d->E >= 128) ? 256 : 128;
 }
 
 // Few rows in total: every expert group is decode-sized and the projections
