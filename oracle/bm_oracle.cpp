@@ -157,6 +157,77 @@ int bm_oracle_buddy_remap(int T, int K, int E, int R, int H, int unique, const u
     return 0;
 }
 
+// Section 3.1 (TAE gate, optional margin gate) and Section 5.1 (replacement
+// budget rho) in front of Algorithm 1.  Per token, from its gate weights
+// renormalised over the K slots (p~):
+//   TAE = -(sum p~ log p~) / log K  (Eq. 1);  m = p~_max - p~_2nd  (0 for the
+//   missing second value when K == 1).
+//   Replacement is forbidden for the token when (use_tae and TAE <= tau) or
+//   (use_margin and m >= gamma).
+//   With use_budget, at most rho slots of a token are replaced, counted in slot
+//   order.
+// Reading (the paper lets such a miss be fetched from host memory, which this
+// layer cannot do): a miss that may not be replaced - forbidden token, or
+// budget used up - is dropped exactly like a miss without an acceptable buddy.
+// Everything else is bm_oracle_buddy_remap.  w [T][K] is required (read for
+// the gates before any drop, then updated).
+int bm_oracle_buddy_remap_gated(int T, int K, int E, int R, int H, int unique, int use_tae, double tau,
+                                int use_margin, double gamma, int use_budget, int rho,
+                                const uint8_t* resident, const int32_t* table, const int32_t* ids_in,
+                                int32_t* ids_out, double* w, int64_t* stats) {
+    if (H > R || H < 0 || !w) return -1;
+    int64_t n_miss = 0, n_sub = 0, n_drop = 0;
+    for (int t = 0; t < T; ++t) {
+        double* wt = w + (size_t)t * K;
+        double sum = 0.0;
+        for (int k = 0; k < K; ++k) sum += wt[k];
+        double h = 0.0, p1 = 0.0, p2 = 0.0;                  // entropy, largest and second largest p~
+        for (int k = 0; k < K; ++k) {
+            double pk = wt[k] / sum;
+            if (pk > 0.0) h -= pk * std::log(pk);
+            if (pk > p1) { p2 = p1; p1 = pk; } else if (pk > p2) { p2 = pk; }
+        }
+        const double tae = (K > 1) ? h / std::log((double)K) : 0.0;
+        bool allowed = true;
+        if (use_tae && tae <= tau) allowed = false;
+        if (use_margin && (p1 - p2) >= gamma) allowed = false;
+        int replaced = 0;
+
+        std::vector<char> in_u(E, 0);
+        for (int k = 0; k < K; ++k) {
+            int32_t e = ids_in[(size_t)t * K + k];
+            ids_out[(size_t)t * K + k] = e;
+            if (e >= 0 && e < E) in_u[e] = 1;
+        }
+        for (int k = 0; k < K; ++k) {
+            int32_t e = ids_out[(size_t)t * K + k];
+            if (e < 0 || e >= E) { ids_out[(size_t)t * K + k] = -1; wt[k] = 0.0; continue; }
+            if (resident[e]) continue;
+            ++n_miss;
+            int32_t chosen = -1;
+            if (allowed && !(use_budget && replaced >= rho)) {
+                for (int r = 0; r < H; ++r) {
+                    int32_t b = table[(size_t)e * R + r];
+                    if (b < 0 || b >= E) continue;
+                    if (resident[b] && !(unique && in_u[b])) { chosen = b; break; }
+                }
+            }
+            if (chosen >= 0) {
+                ids_out[(size_t)t * K + k] = chosen;
+                in_u[chosen] = 1;
+                ++replaced;
+                ++n_sub;
+            } else {
+                ids_out[(size_t)t * K + k] = -1;
+                wt[k] = 0.0;
+                ++n_drop;
+            }
+        }
+    }
+    if (stats) { stats[0] = n_miss; stats[1] = n_sub; stats[2] = n_drop; }
+    return 0;
+}
+
 // Grouping of the surviving assignments by expert (Section 2.2: each token's
 // selected experts run and their outputs are aggregated; the grouping itself
 // is the execution order of this build): a stable counting sort of the flat
@@ -252,6 +323,33 @@ int bm_oracle_moe_forward(int T, int d, int E, int F, int K, int n_shared, int R
     rc = bm_oracle_topk_gates(T, E, K, renorm, z.data(), ids.data(), w.data());
     if (rc) return rc;
     rc = bm_oracle_buddy_remap(T, K, E, R, H, unique, resident, table, ids.data(), ids2.data(), w.data(), stats);
+    if (rc) return rc;
+    rc = bm_oracle_experts_combine(T, d, E, F, K, n_shared, x, ids2.data(), w.data(), w_gate, w_up, w_down,
+                                   ws_gate, ws_up, ws_down, y);
+    if (rc) return rc;
+    if (ids_out) std::memcpy(ids_out, ids.data(), sizeof(int32_t) * ids.size());
+    if (ids_remapped_out) std::memcpy(ids_remapped_out, ids2.data(), sizeof(int32_t) * ids2.size());
+    if (w_out) std::memcpy(w_out, w.data(), sizeof(double) * w.size());
+    return 0;
+}
+
+// The whole layer with the gates of Section 3.1 / budget of Section 5.1 in front of Algorithm 1.
+int bm_oracle_moe_forward_gated(int T, int d, int E, int F, int K, int n_shared, int R, int H, int renorm,
+                                int unique, int use_tae, double tau, int use_margin, double gamma,
+                                int use_budget, int rho, const float* x, const float* w_router,
+                                const float* bias, const float* w_gate, const float* w_up,
+                                const float* w_down, const float* ws_gate, const float* ws_up,
+                                const float* ws_down, const uint8_t* resident, const int32_t* table,
+                                double* y, int32_t* ids_out, int32_t* ids_remapped_out, double* w_out,
+                                int64_t* stats) {
+    std::vector<double> z((size_t)T * E), w((size_t)T * K);
+    std::vector<int32_t> ids((size_t)T * K), ids2((size_t)T * K);
+    int rc = bm_oracle_router_logits(T, d, E, x, w_router, bias, z.data());
+    if (rc) return rc;
+    rc = bm_oracle_topk_gates(T, E, K, renorm, z.data(), ids.data(), w.data());
+    if (rc) return rc;
+    rc = bm_oracle_buddy_remap_gated(T, K, E, R, H, unique, use_tae, tau, use_margin, gamma, use_budget, rho,
+                                     resident, table, ids.data(), ids2.data(), w.data(), stats);
     if (rc) return rc;
     rc = bm_oracle_experts_combine(T, d, E, F, K, n_shared, x, ids2.data(), w.data(), w_gate, w_up, w_down,
                                    ws_gate, ws_up, ws_down, y);
