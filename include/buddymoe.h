@@ -52,8 +52,20 @@ enum {
     BM_REMAP_UNIQUE = 1u << 1, /* Algorithm 1's "b not in U_t" test: a buddy already
                                   held by the token is skipped.  Off: the substitute
                                   is the first resident entry of the buddy row        */
-    BM_Y_F32        = 1u << 2  /* bm_moe_forward writes y as fp32 whatever dtype is   */
+    BM_Y_F32        = 1u << 2, /* bm_moe_forward writes y as fp32 whatever dtype is   */
+    /* Gates in front of the substitution, decided per token from its K gate weights
+     * renormalised to sum 1 (p-tilde), before any drop.  A miss of a token that may
+     * not be given a substitute is dropped like a miss without an acceptable buddy
+     * (the paper fetches such an expert from host memory instead; a single layer's
+     * forward pass has no such channel). */
+    BM_GATE_TAE       = 1u << 3, /* Section 3.1, Eq. 1: no substitution for a token whose
+                                    TAE = -(sum p~ log p~)/log K is <= desc.tae_tau       */
+    BM_GATE_MARGIN    = 1u << 4, /* Section 3.1: nor when p~_max - p~_2nd >= desc.margin_gamma
+                                    (second value 0 when K == 1)                          */
+    BM_REPLACE_BUDGET = 1u << 5  /* Section 5.1: at most desc.rho substitutions per token,
+                                    counted in slot order; later misses are dropped      */
 };
+#define BM_GATE_ANY (BM_GATE_TAE | BM_GATE_MARGIN | BM_REPLACE_BUDGET)
 
 /* Limits of this build. */
 #define BM_MAX_E 256
@@ -66,6 +78,9 @@ typedef struct {
     int32_t R, H;       /* buddy-table width and search limit                         */
     int32_t dtype;      /* bm_dtype of x, all weights and (unless BM_Y_F32) y         */
     uint32_t flags;     /* BM_* flag bits                                             */
+    float tae_tau;      /* read only with BM_GATE_TAE                                 */
+    float margin_gamma; /* read only with BM_GATE_MARGIN                              */
+    int32_t rho;        /* read only with BM_REPLACE_BUDGET; >= 0                     */
 } bm_layer_desc;
 
 /* Weights, all device pointers in `dtype`.  The reduction dimension is
@@ -135,7 +150,11 @@ int bm_route_topk(const bm_layer_desc *desc, const void *x, const void *w_router
  * buddy_table [E][R] int32 (device), best buddy first, short rows padded -1.
  * ids_in [T][K] (device); ids_out [T][K] (device, may alias ids_in);
  * w [T][K] fp32 in/out (device, nullable); stats (device, nullable, written).
- * Uses T, E, K, R, H, flags of desc. */
+ * With BM_GATE_TAE / BM_GATE_MARGIN / BM_REPLACE_BUDGET (Section 3.1, Section 5.1)
+ * the gates are evaluated per token in fp32 from w as passed in (w is then
+ * required: BM_ERR_NULL without it); a miss of a gated token, or one beyond the
+ * token's budget, counts as a miss and as dropped.
+ * Uses T, E, K, R, H, flags, tae_tau, margin_gamma, rho of desc. */
 int bm_buddy_remap(const bm_layer_desc *desc, const uint64_t *residency_bitmap,
                    const int32_t *buddy_table, const int32_t *ids_in, int32_t *ids_out,
                    float *w, bm_remap_stats *stats, void *stream);

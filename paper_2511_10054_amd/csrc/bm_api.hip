@@ -75,6 +75,9 @@ int check_desc(const bm_layer_desc *d, bool need_ffn) {
 
 int check_remap_desc(const bm_layer_desc *d) {
     if (d->R < 0 || d->R > BM_MAX_R || d->H < 0 || d->H > d->R) return BM_ERR_SHAPE;
+    if ((d->flags & BM_REPLACE_BUDGET) && d->rho < 0) return BM_ERR_SHAPE;
+    if ((d->flags & BM_GATE_TAE) && !(d->tae_tau == d->tae_tau)) return BM_ERR_SHAPE;            // NaN
+    if ((d->flags & BM_GATE_MARGIN) && !(d->margin_gamma == d->margin_gamma)) return BM_ERR_SHAPE;
     return BM_OK;
 }
 
@@ -232,10 +235,11 @@ int bm_buddy_remap(const bm_layer_desc *desc, const uint64_t *residency_bitmap, 
     int rc = check_remap_desc(desc);
     if (rc) return rc;
     if (!residency_bitmap || !ids_in || !ids_out || (!buddy_table && desc->R > 0)) return BM_ERR_NULL;
+    if ((desc->flags & (BM_GATE_TAE | BM_GATE_MARGIN)) && !w) return BM_ERR_NULL;   // the gates read the weights
     (void)hipGetLastError();
     RemapParams p{};
     p.T = desc->T; p.K = desc->K; p.E = desc->E; p.R = desc->R; p.H = desc->H;
-    p.unique = (desc->flags & BM_REMAP_UNIQUE) ? 1 : 0;
+    p.flags = desc->flags; p.tau = desc->tae_tau; p.gamma = desc->margin_gamma; p.rho = desc->rho;
     p.bitmap = residency_bitmap; p.table = buddy_table;
     p.ids_in = ids_in; p.ids_out = ids_out; p.w = w;
     p.stats = reinterpret_cast<int32_t *>(stats);
@@ -310,6 +314,7 @@ int bm_moe_forward(const bm_layer_desc *desc, const void *x, const bm_weights *w
     FrontParams fp{};
     fp.x = x; fp.wr = wt->w_router; fp.bias = wt->router_bias;
     fp.T = T; fp.d = desc->d; fp.E = E; fp.K = K; fp.R = desc->R; fp.H = desc->H; fp.flags = desc->flags;
+    fp.tau = desc->tae_tau; fp.gamma = desc->margin_gamma; fp.rho = desc->rho;
     fp.ids = at<int32_t>(ws, L.ids); fp.w = at<float>(ws, L.w);
     fp.bitmap = residency_bitmap; fp.table = buddy_table;
     fp.ids2 = at<int32_t>(ws, L.ids2);

@@ -36,10 +36,38 @@ __device__ __forceinline__ void set_bit4(uint64_t (&m)[4], int b) {
     m[3] |= wi == 3 ? bit : 0ull;
 }
 
-__device__ __forceinline__ void remap_token(int K, int E, int R, int H, bool unique,
-                                            const uint64_t *bitmap, const int32_t *table,
+// Gates in front of the substitution (Section 3.1: TAE, Eq. 1, and probability margin;
+// Section 5.1: replacement budget).  From the token's K gate weights renormalised to sum 1:
+// the token may be given substitutes unless (BM_GATE_TAE and TAE <= tau) or (BM_GATE_MARGIN and
+// largest - second largest >= gamma); returns how many slots may be replaced (0 = none).
+__device__ __forceinline__ int replacement_budget(int K, uint32_t flags, float tau, float gamma, int rho,
+                                                  const float *w) {
+    int budget = (flags & BM_REPLACE_BUDGET) ? rho : 0x7fffffff;
+    if (flags & (BM_GATE_TAE | BM_GATE_MARGIN)) {
+        float sum = 0.0f;
+        for (int k = 0; k < K; ++k) sum += w[k];
+        float h = 0.0f, p1 = 0.0f, p2 = 0.0f;
+        for (int k = 0; k < K; ++k) {
+            const float pk = w[k] / sum;
+            h -= pk > 0.0f ? pk * logf(pk) : 0.0f;
+            const float lo = fminf(p1, pk);
+            p1 = fmaxf(p1, pk);
+            p2 = fmaxf(p2, lo);
+        }
+        const float tae = K > 1 ? h / logf((float)K) : 0.0f;
+        if ((flags & BM_GATE_TAE) && tae <= tau) budget = 0;
+        if ((flags & BM_GATE_MARGIN) && (p1 - p2) >= gamma) budget = 0;
+    }
+    return budget;
+}
+
+__device__ __forceinline__ void remap_token(int K, int E, int R, int H, uint32_t flags, float tau, float gamma,
+                                            int rho, const uint64_t *bitmap, const int32_t *table,
                                             const int32_t *ids_in, int32_t *ids_out, float *w,
                                             int &n_miss, int &n_sub, int &n_drop) {
+    const bool unique = (flags & BM_REMAP_UNIQUE) != 0;
+    int budget = 0x7fffffff;
+    if (flags & BM_GATE_ANY) budget = replacement_budget(K, flags, tau, gamma, rho, w);   // before any drop
     uint64_t used[4] = {0ull, 0ull, 0ull, 0ull};   // U_t
     for (int k = 0; k < K; ++k) {
         int e = ids_in[k];
@@ -54,7 +82,8 @@ __device__ __forceinline__ void remap_token(int K, int E, int R, int H, bool uni
             ++n_miss;
             bool found = false;
             const int32_t *row = table + (size_t)e * R;
-            for (int r = 0; r < H; ++r) {
+            const int depth = budget > 0 ? H : 0;          // budget used up or token gated: no search
+            for (int r = 0; r < depth; ++r) {
                 const int b = row[r];
                 const bool bvalid = (unsigned)b < (unsigned)E;
                 const int bc = bvalid ? b : 0;
@@ -63,7 +92,7 @@ __device__ __forceinline__ void remap_token(int K, int E, int R, int H, bool uni
                 out = (ok && !found) ? b : out;
                 found = found || ok;
             }
-            if (found) { ++n_sub; set_bit4(used, out); } else { ++n_drop; }
+            if (found) { ++n_sub; --budget; set_bit4(used, out); } else { ++n_drop; }
         }
         ids_out[k] = out;
         if (w != nullptr && out < 0) w[k] = 0.0f;
@@ -158,14 +187,14 @@ __device__ void tile_epilogue(const FrontParams &p, float *logits, int stride, i
     if (tid < 4) { s.bitmap[tid] = (tid < ec) ? p.bitmap[tid] : 0ull; s.stats[tid] = 0; }
     __syncthreads();
 
-    if (p.flags & BM_REMAP_UNIQUE) {
-        // Algorithm 1 proper: a lane walks its token's slots in order
+    if (p.flags & (BM_REMAP_UNIQUE | BM_GATE_ANY)) {
+        // Algorithm 1 proper (and its per-token gates): a lane walks its token's slots in order
         if (tid < ntok) {
             int n_miss = 0, n_sub = 0, n_drop = 0;
             int32_t *tok_ids = &s.ids[tid * K];
             float *tok_w = &s.w[tid * K];
-            remap_token(K, E, p.R, p.H, true, s.bitmap, tab_in_lds ? s_table : p.table, tok_ids, tok_ids, tok_w,
-                        n_miss, n_sub, n_drop);
+            remap_token(K, E, p.R, p.H, p.flags, p.tau, p.gamma, p.rho, s.bitmap,
+                        tab_in_lds ? s_table : p.table, tok_ids, tok_ids, tok_w, n_miss, n_sub, n_drop);
             if (n_miss) atomicAdd(&s.stats[0], n_miss);
             if (n_sub) atomicAdd(&s.stats[1], n_sub);
             if (n_drop) atomicAdd(&s.stats[2], n_drop);
@@ -463,7 +492,8 @@ __global__ void __launch_bounds__(256) remap_kernel(RemapParams p) {
         const int32_t *in = p.ids_in + (size_t)t * p.K;
         int32_t *out = p.ids_out + (size_t)t * p.K;
         float *w = p.w ? p.w + (size_t)t * p.K : nullptr;
-        remap_token(p.K, p.E, p.R, p.H, p.unique != 0, s_bitmap, s_table, in, out, w, n_miss, n_sub, n_drop);
+        remap_token(p.K, p.E, p.R, p.H, p.flags, p.tau, p.gamma, p.rho, s_bitmap, s_table, in, out, w, n_miss,
+                    n_sub, n_drop);
         if (n_miss) atomicAdd(&s_stats[0], n_miss);
         if (n_sub) atomicAdd(&s_stats[1], n_sub);
         if (n_drop) atomicAdd(&s_stats[2], n_drop);

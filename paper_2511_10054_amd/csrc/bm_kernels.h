@@ -7,7 +7,10 @@
 namespace bm {
 
 struct RemapParams {
-    int T, K, E, R, H, unique;
+    int T, K, E, R, H;
+    uint32_t flags;         // BM_REMAP_UNIQUE and the gate bits
+    float tau, gamma;       // TAE and margin thresholds
+    int rho;                // replacement budget per token
     const uint64_t *bitmap;
     const int32_t *table;
     const int32_t *ids_in;
@@ -42,6 +45,8 @@ struct FrontParams {
     const float *bias;      // [E] or null
     int T, d, E, K, R, H;
     uint32_t flags;
+    float tau, gamma;       // TAE and margin thresholds (gate bits of flags)
+    int rho;                // replacement budget per token
     int32_t *ids;           // [T][K] router's choice
     float *w;               // [T][K]
     const uint64_t *bitmap; // null => routing only (no substitution, no histogram)

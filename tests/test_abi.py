@@ -29,9 +29,28 @@ def test_library_exports_every_declared_symbol():
         assert hasattr(lib, n), n
 
 
-def test_struct_layouts_match_header():
-    assert ctypes.sizeof(bm.LayerDesc) == 40
-    assert ctypes.sizeof(Weights) == 96 and ctypes.sizeof(DebugOut) == 96
+def test_struct_layouts_match_header(tmp_path):
+    # sizes and member offsets as the C compiler sees the header, against the ctypes mirrors
+    import subprocess
+    hdr = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "include")
+    members = {"bm_layer_desc": [f[0] for f in bm.LayerDesc._fields_],
+               "bm_weights": [f[0] for f in Weights._fields_],
+               "bm_debug_out": [f[0] for f in DebugOut._fields_]}
+    lines = []
+    for st, names in members.items():
+        lines.append(f'printf("{st} %zu\\n", sizeof({st}));')
+        lines += [f'printf("{st}.{m} %zu\\n", offsetof({st}, {m}));' for m in names]
+    src = tmp_path / "layout.c"
+    src.write_text('#include <stdio.h>\n#include <stddef.h>\n#include "buddymoe.h"\nint main(void){'
+                   + "".join(lines) + "return 0;}\n")
+    exe = tmp_path / "layout"
+    subprocess.run(["gcc", "-I", hdr, "-o", str(exe), str(src)], check=True)
+    got = dict(l.split() for l in subprocess.run([str(exe)], check=True, capture_output=True,
+                                                 text=True).stdout.splitlines())
+    for st, cls in (("bm_layer_desc", bm.LayerDesc), ("bm_weights", Weights), ("bm_debug_out", DebugOut)):
+        assert int(got[st]) == ctypes.sizeof(cls)
+        for m in members[st]:
+            assert int(got[f"{st}.{m}"]) == getattr(cls, m).offset, (st, m)
 
 
 def test_strerror_and_workspace_bytes():
@@ -95,6 +114,12 @@ def test_host_side_argument_errors_launch_nothing():
     assert lib.bm_buddy_remap(ctypes.byref(_desc(H=4)), one, one, one, one, None, None, None) == -2
     assert lib.bm_buddy_remap(ctypes.byref(d), None, one, one, one, None, None, None) == -1
     assert lib.bm_buddy_remap(ctypes.byref(_desc(R=33, H=1)), one, one, one, one, None, None, None) == -2
+    gated = _desc(flags=bm.BM_GATE_TAE, tae_tau=0.5)
+    assert lib.bm_buddy_remap(ctypes.byref(gated), one, one, one, one, None, None, None) == -1   # gates read w
+    assert lib.bm_buddy_remap(ctypes.byref(_desc(flags=bm.BM_REPLACE_BUDGET, rho=-1)), one, one, one, one, one,
+                              None, None) == -2
+    assert lib.bm_buddy_remap(ctypes.byref(_desc(flags=bm.BM_GATE_MARGIN, margin_gamma=float("nan"))), one, one,
+                              one, one, one, None, None) == -2
     assert lib.bm_permute_by_expert(ctypes.byref(d), one, one, one, one, None, 1 << 20, None) == -4
     assert lib.bm_permute_by_expert(ctypes.byref(d), one, one, one, one, one, 16, None) == -4
     assert lib.bm_permute_by_expert(ctypes.byref(d), one, one, one, one, ctypes.c_void_p(264), 1 << 20, None) == -4

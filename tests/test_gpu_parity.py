@@ -139,9 +139,9 @@ LAYER_CASES = [
 ]
 
 
-def _check_layer(host, unique, renorm=True, H=None):
-    ref = host.oracle_forward(oracle, unique=unique, renorm=renorm, H=H)
-    dev = DeviceLayer(host, unique=unique, renorm=renorm, H=H)
+def _check_layer(host, unique, renorm=True, H=None, **gates):
+    ref = host.oracle_forward(oracle, unique=unique, renorm=renorm, H=H, **gates)
+    dev = DeviceLayer(host, unique=unique, renorm=renorm, H=H, **gates)
     out = dev.forward()
     spec = host.spec
     np.testing.assert_array_equal(out["ids"], ref["ids"])
@@ -260,3 +260,98 @@ def test_fp32_output_flag_and_empty_batch():
     assert err_metric(out["y"], ref["y"]) <= TOL["bf16"]
     empty = DeviceLayer(HostLayer(spec, 0))
     empty.forward(debug=False)                         # no-op, must not fault
+
+
+# ------------------------------------------------ gates in front of Algorithm 1
+
+
+def _tae_margin(w):
+    """TAE (Eq. 1) and top-two margin of gate weights, numpy fp64 - used only to place thresholds."""
+    p = w / w.sum(1, keepdims=True)
+    K = p.shape[1]
+    tae = -(np.where(p > 0, p * np.log(np.where(p > 0, p, 1.0)), 0.0)).sum(1) / np.log(K)
+    top = -np.sort(-p, axis=1)
+    return tae, top[:, 0] - top[:, 1]
+
+
+def _threshold(values, q):
+    """A threshold near the q-quantile of `values` in the middle of the widest nearby gap, so that the
+    fp32 device value and the fp64 oracle value of every token fall on the same side of it."""
+    v = np.unique(values)
+    if len(v) < 2:
+        return float(v[0]) + 0.25
+    i = int(q * (len(v) - 1))
+    lo, hi = max(0, i - 8), min(len(v) - 1, i + 8)
+    j = lo + int(np.argmax(np.diff(v[lo:hi + 1])))
+    assert v[j + 1] - v[j] > 2e-5, "no safe gap"
+    return float(0.5 * (v[j] + v[j + 1]))
+
+
+@pytest.mark.parametrize("T,E,K,R,n_res", [(1, 8, 2, 3, 4), (1000, 24, 4, 6, 9), (513, 64, 6, 8, 16),
+                                           (257, 256, 32, 32, 40)])
+@pytest.mark.parametrize("unique", [False, True])
+def test_buddy_remap_gated(T, E, K, R, n_res, unique):
+    torch = _torch()
+    import paper_2511_10054_amd as bm
+    _say("remap gated", T, E, K, R, n_res, unique)
+    ids, res, table = _random_problem(T + E, T, E, K, R, n_res)
+    g = np.random.default_rng(T)
+    z = g.normal(size=(T, K)) * 2.0
+    w = (np.exp(z) / np.exp(z).sum(1, keepdims=True) * g.uniform(0.2, 1.0, size=(T, 1))).astype(np.float32)
+    tae, margin = _tae_margin(w.astype(np.float64))
+    tau, gamma = _threshold(tae, 0.4), _threshold(margin, 0.7)
+    base = bm.BM_REMAP_UNIQUE if unique else 0
+    for gates in (dict(tau=tau), dict(gamma=gamma), dict(rho=1), dict(rho=0), dict(tau=tau, gamma=gamma, rho=2)):
+        ref, w_ref, st = oracle.buddy_remap_gated(ids, res, table, w, H=R, unique=unique, **gates)
+        flags = base | (bm.BM_GATE_TAE if "tau" in gates else 0) | (bm.BM_GATE_MARGIN if "gamma" in gates else 0) \
+            | (bm.BM_REPLACE_BUDGET if "rho" in gates else 0)
+        desc = bm.LayerDesc(T=T, d=32, E=E, F=0, K=K, n_shared=0, R=R, H=R, dtype=bm.BM_BF16, flags=flags,
+                            tae_tau=gates.get("tau", 0.0), margin_gamma=gates.get("gamma", 0.0),
+                            rho=gates.get("rho", 0))
+        d_out = torch.full((T, K), -9, dtype=torch.int32, device="cuda")
+        d_w = to_device(w)
+        d_stats = torch.full((3,), -9, dtype=torch.int32, device="cuda")
+        bm.bm_buddy_remap(desc, to_device(workloads.pack_bitmap(res)), to_device(table), to_device(ids), d_out,
+                          d_w, d_stats)
+        torch.cuda.synchronize()
+        np.testing.assert_array_equal(d_out.cpu().numpy(), ref, err_msg=str(gates))
+        np.testing.assert_array_equal(d_w.cpu().numpy(), w_ref.astype(np.float32))
+        assert d_stats.cpu().tolist() == [st["n_miss"], st["n_substituted"], st["n_dropped"]]
+        if T > 100 and ("tau" in gates or "gamma" in gates):
+            assert 0 < st["n_substituted"] and 0 < st["n_dropped"]
+
+
+def test_gates_need_weights():
+    import paper_2511_10054_amd as bm
+    torch = _torch()
+    desc = bm.LayerDesc(T=4, d=32, E=8, F=0, K=2, n_shared=0, R=2, H=2, dtype=bm.BM_BF16, flags=bm.BM_GATE_TAE,
+                        tae_tau=0.5)
+    ids = torch.zeros((4, 2), dtype=torch.int32, device="cuda")
+    with pytest.raises(bm.BuddyMoEError):
+        bm.bm_buddy_remap(desc, torch.zeros(1, dtype=torch.int64, device="cuda"),
+                          torch.zeros((8, 2), dtype=torch.int32, device="cuda"), ids, ids)
+
+
+GATED_LAYER_CASES = [
+    ("c1_tiny", {}, 16, False),
+    ("c2_mixtral_decode", dict(d=512, F=1024), 8, False),       # fused one-workgroup front end
+    ("c2_mixtral_decode", dict(d=512, F=1024), 64, True),
+    ("c3_mixtral_prefill", dict(d=512, F=1024), 700, False),
+    ("c4_qwen3", dict(d=256, F=384), 300, True),
+    ("c5_deepseek", dict(d=256, F=352), 500, True),
+]
+
+
+@pytest.mark.parametrize("name,over,T,unique", GATED_LAYER_CASES)
+def test_gated_layer_matches_oracle(name, over, T, unique):
+    spec = workloads.scaled(name, **over)
+    _say("gated layer", name, over, T, unique)
+    host = HostLayer(spec, T)
+    _, w = oracle.route_topk(host.f32(host.x), host.f32(host.w_router), host.bias, spec.K)
+    tae, margin = _tae_margin(w)
+    tau, gamma = _threshold(tae, 0.35), _threshold(margin, 0.75)
+    _check_layer(host, unique, tau=tau)
+    _check_layer(host, unique, gamma=gamma, rho=max(1, spec.K // 2))
+    out, ref, _ = _check_layer(host, unique, tau=tau, gamma=gamma, rho=1)
+    replaced = (ref["ids_remapped"] != ref["ids"]) & (ref["ids_remapped"] >= 0)
+    assert (replaced.sum(1) <= 1).all()
