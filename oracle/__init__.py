@@ -106,10 +106,37 @@ def buddy_remap(ids, resident_mask, table, H: Optional[int] = None, unique: bool
     return out, w2, dict(n_miss=int(stats[0]), n_substituted=int(stats[1]), n_dropped=int(stats[2]))
 
 
-def buddy_remap_gated(ids, resident_mask, table, w, H: Optional[int] = None, unique: bool = False,
-                      tau: Optional[float] = None, gamma: Optional[float] = None, rho: Optional[int] = None):
-    """Algorithm 1 behind the TAE gate (tau), the margin gate (gamma) and the budget (rho);
-    a None switches that gate off.  Returns (ids_remapped, w_after_drops, stats dict)."""
+def distribution_delta(ids, resident_mask):
+    """Eq. 2: (delta, |R(B)|, offloaded among R(B)) for the batch of routed ids [T][K]."""
+    ids = np.ascontiguousarray(ids, dtype=np.int32)
+    T, K = ids.shape
+    res = np.ascontiguousarray(np.asarray(resident_mask, dtype=bool).astype(np.uint8))
+    counts = np.zeros(2, dtype=np.int64)
+    f = lib().bm_oracle_distribution_delta
+    f.restype = ctypes.c_double
+    f.argtypes = [ctypes.c_int] * 3 + [ctypes.c_void_p] * 3
+    delta = f(T, K, len(res), res.ctypes.data, ids.ctypes.data, counts.ctypes.data)
+    return float(delta), int(counts[0]), int(counts[1])
+
+
+def _stats_dict(stats):
+    return dict(n_miss=int(stats[0]), n_substituted=int(stats[1]), n_dropped=int(stats[2]),
+                n_requested=int(stats[3]), n_requested_offloaded=int(stats[4]), bypassed=int(stats[5]))
+
+
+_GATE_ARGS = [ctypes.c_int, _D, ctypes.c_int, _D, ctypes.c_int, ctypes.c_int, ctypes.c_int, _D]
+
+
+def _gate_values(tau, gamma, rho, beta):
+    return (int(tau is not None), float(tau or 0.0), int(gamma is not None), float(gamma or 0.0),
+            int(rho is not None), int(rho or 0), int(beta is not None), float(beta or 0.0))
+
+
+def buddy_remap_gated(ids, resident_mask, table, w=None, H: Optional[int] = None, unique: bool = False,
+                      tau: Optional[float] = None, gamma: Optional[float] = None, rho: Optional[int] = None,
+                      beta: Optional[float] = None):
+    """Algorithm 1 behind the TAE gate (tau), the margin gate (gamma), the distribution gate (beta) and
+    the budget (rho); a None switches that gate off.  Returns (ids_remapped, w_after_drops, stats dict)."""
     ids = np.ascontiguousarray(ids, dtype=np.int32)
     T, K = ids.shape
     res = np.ascontiguousarray(np.asarray(resident_mask, dtype=bool).astype(np.uint8))
@@ -118,16 +145,15 @@ def buddy_remap_gated(ids, resident_mask, table, w, H: Optional[int] = None, uni
     R = table.shape[1]
     H = R if H is None else H
     out = np.empty_like(ids)
-    w2 = np.array(w, dtype=np.float64, order="C", copy=True)
-    stats = np.zeros(3, dtype=np.int64)
+    w2 = None if w is None else np.array(w, dtype=np.float64, order="C", copy=True)
+    stats = np.zeros(6, dtype=np.int64)
     f = lib().bm_oracle_buddy_remap_gated
-    f.argtypes = [ctypes.c_int] * 7 + [_D, ctypes.c_int, _D, ctypes.c_int, ctypes.c_int] + [ctypes.c_void_p] * 6
-    rc = f(T, K, E, R, H, int(unique), int(tau is not None), float(tau or 0.0), int(gamma is not None),
-           float(gamma or 0.0), int(rho is not None), int(rho or 0), res.ctypes.data, table.ctypes.data,
-           ids.ctypes.data, out.ctypes.data, w2.ctypes.data, stats.ctypes.data)
+    f.argtypes = [ctypes.c_int] * 6 + _GATE_ARGS + [ctypes.c_void_p] * 6
+    rc = f(T, K, E, R, H, int(unique), *_gate_values(tau, gamma, rho, beta), res.ctypes.data, table.ctypes.data,
+           ids.ctypes.data, out.ctypes.data, None if w2 is None else w2.ctypes.data, stats.ctypes.data)
     if rc:
-        raise ValueError("H must be in [0, R]")
-    return out, w2, dict(n_miss=int(stats[0]), n_substituted=int(stats[1]), n_dropped=int(stats[2]))
+        raise ValueError("H must be in [0, R]; the TAE and margin gates need w")
+    return out, w2, _stats_dict(stats)
 
 
 def permute(ids, E: int):
@@ -169,9 +195,9 @@ def experts_combine(x, ids, w, w_gate, w_up, w_down, ws_gate=None, ws_up=None, w
 
 def moe_forward(x, w_router, bias, w_gate, w_up, w_down, resident_mask, table, K: int,
                 H: Optional[int] = None, renorm: bool = True, unique: bool = False,
-                ws_gate=None, ws_up=None, ws_down=None, tau=None, gamma=None, rho=None):
+                ws_gate=None, ws_up=None, ws_down=None, tau=None, gamma=None, rho=None, beta=None):
     """Whole layer. Returns dict(y, ids, ids_remapped, w, stats).  tau / gamma / rho: the TAE gate,
-    margin gate and replacement budget in front of Algorithm 1 (None = off)."""
+    margin gate, replacement budget and distribution gate (beta) in front of Algorithm 1 (None = off)."""
     x, w_router, bias = _f32(x), _f32(w_router), _f32(bias)
     w_gate, w_up, w_down = _f32(w_gate), _f32(w_up), _f32(w_down)
     ws_gate, ws_up, ws_down = _f32(ws_gate), _f32(ws_up), _f32(ws_down)
@@ -186,8 +212,8 @@ def moe_forward(x, w_router, bias, w_gate, w_up, w_down, resident_mask, table, K
     ids = np.empty((T, K), dtype=np.int32)
     ids2 = np.empty((T, K), dtype=np.int32)
     w = np.empty((T, K), dtype=np.float64)
-    stats = np.zeros(3, dtype=np.int64)
-    if tau is None and gamma is None and rho is None:
+    stats = np.zeros(6, dtype=np.int64)
+    if tau is None and gamma is None and rho is None and beta is None:
         rc = lib().bm_oracle_moe_forward(T, d, E, F, K, n_shared, R, H, int(renorm), int(unique),
                                          _p(x, _F), _p(w_router, _F), _p(bias, _F),
                                          _p(w_gate, _F), _p(w_up, _F), _p(w_down, _F),
@@ -196,15 +222,12 @@ def moe_forward(x, w_router, bias, w_gate, w_up, w_down, resident_mask, table, K
                                          _p(ids2, _I32), _p(w, _D), _p(stats, _I64))
     else:
         f = lib().bm_oracle_moe_forward_gated
-        f.argtypes = ([ctypes.c_int] * 11 + [_D, ctypes.c_int, _D, ctypes.c_int, ctypes.c_int]
-                      + [ctypes.c_void_p] * 16)
+        f.argtypes = [ctypes.c_int] * 10 + _GATE_ARGS + [ctypes.c_void_p] * 16
         vp = lambda a: None if a is None else a.ctypes.data
-        rc = f(T, d, E, F, K, n_shared, R, H, int(renorm), int(unique), int(tau is not None), float(tau or 0.0),
-               int(gamma is not None), float(gamma or 0.0), int(rho is not None), int(rho or 0),
+        rc = f(T, d, E, F, K, n_shared, R, H, int(renorm), int(unique), *_gate_values(tau, gamma, rho, beta),
                vp(x), vp(w_router), vp(bias), vp(w_gate), vp(w_up), vp(w_down), vp(ws_gate), vp(ws_up),
                vp(ws_down), vp(res), vp(table), vp(y), vp(ids), vp(ids2), vp(w), vp(stats))
     if rc:
         raise ValueError("bad shape")
-    return dict(y=y, ids=ids, ids_remapped=ids2, w=w,
-                stats=dict(n_miss=int(stats[0]), n_substituted=int(stats[1]), n_dropped=int(stats[2])))
+    return dict(y=y, ids=ids, ids_remapped=ids2, w=w, stats=_stats_dict(stats))
 

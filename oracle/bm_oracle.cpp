@@ -157,40 +157,69 @@ int bm_oracle_buddy_remap(int T, int K, int E, int R, int H, int unique, const u
     return 0;
 }
 
-// Section 3.1 (TAE gate, optional margin gate) and Section 5.1 (replacement
-// budget rho) in front of Algorithm 1.  Per token, from its gate weights
-// renormalised over the K slots (p~):
+// Section 3.1 Eq. 2, Expert Distribution Gate: over the micro-batch (here: the
+// T tokens of the call) R(B) = the set of distinct experts some token selected;
+//   delta = |{i in R(B) : i not resident}| / |R(B)|.
+// counts[0] = |R(B)|, counts[1] = the numerator.  Returns delta (0 for an empty
+// batch).  Ids outside [0,E) request nothing.
+double bm_oracle_distribution_delta(int T, int K, int E, const uint8_t* resident, const int32_t* ids,
+                                    int64_t* counts) {
+    std::vector<char> requested(E, 0);
+    for (size_t a = 0; a < (size_t)T * K; ++a)
+        if (ids[a] >= 0 && ids[a] < E) requested[ids[a]] = 1;
+    int64_t n_req = 0, n_cpu = 0;
+    for (int e = 0; e < E; ++e) {
+        if (!requested[e]) continue;
+        ++n_req;
+        if (!resident[e]) ++n_cpu;
+    }
+    if (counts) { counts[0] = n_req; counts[1] = n_cpu; }
+    return n_req ? (double)n_cpu / (double)n_req : 0.0;
+}
+
+// Section 3.1 (the three-stage decision: TAE gate with optional margin gate,
+// distribution gate, buddy selection) and Section 5.1 (replacement budget rho)
+// around Algorithm 1.
+// Per token, from its gate weights renormalised over the K slots (p~):
 //   TAE = -(sum p~ log p~) / log K  (Eq. 1);  m = p~_max - p~_2nd  (0 for the
 //   missing second value when K == 1).
 //   Replacement is forbidden for the token when (use_tae and TAE <= tau) or
 //   (use_margin and m >= gamma).
-//   With use_budget, at most rho slots of a token are replaced, counted in slot
-//   order.
+// Per batch: with use_dist, replacement is bypassed for every token when
+//   delta >= beta (Eq. 2).
+// With use_budget, at most rho slots of a token are replaced, counted in slot
+// order.
 // Reading (the paper lets such a miss be fetched from host memory, which this
-// layer cannot do): a miss that may not be replaced - forbidden token, or
-// budget used up - is dropped exactly like a miss without an acceptable buddy.
-// Everything else is bm_oracle_buddy_remap.  w [T][K] is required (read for
-// the gates before any drop, then updated).
+// layer cannot do): a miss that may not be replaced - forbidden token, bypassed
+// batch, or budget used up - is dropped exactly like a miss without an
+// acceptable buddy.  Everything else is bm_oracle_buddy_remap.  w [T][K] is
+// required with use_tae / use_margin (read for the gates before any drop, then
+// updated).  stats[6] = {misses, substituted, dropped, |R(B)|, offloaded among
+// R(B), bypassed 0/1}; the last three are 0 without use_dist.
 int bm_oracle_buddy_remap_gated(int T, int K, int E, int R, int H, int unique, int use_tae, double tau,
-                                int use_margin, double gamma, int use_budget, int rho,
-                                const uint8_t* resident, const int32_t* table, const int32_t* ids_in,
-                                int32_t* ids_out, double* w, int64_t* stats) {
-    if (H > R || H < 0 || !w) return -1;
-    int64_t n_miss = 0, n_sub = 0, n_drop = 0;
+                                int use_margin, double gamma, int use_budget, int rho, int use_dist,
+                                double beta, const uint8_t* resident, const int32_t* table,
+                                const int32_t* ids_in, int32_t* ids_out, double* w, int64_t* stats) {
+    if (H > R || H < 0 || ((use_tae || use_margin) && !w)) return -1;
+    int64_t n_miss = 0, n_sub = 0, n_drop = 0, dist[2] = {0, 0};
+    bool bypass = false;
+    if (use_dist) bypass = bm_oracle_distribution_delta(T, K, E, resident, ids_in, dist) >= beta && dist[0] > 0;
     for (int t = 0; t < T; ++t) {
-        double* wt = w + (size_t)t * K;
-        double sum = 0.0;
-        for (int k = 0; k < K; ++k) sum += wt[k];
-        double h = 0.0, p1 = 0.0, p2 = 0.0;                  // entropy, largest and second largest p~
-        for (int k = 0; k < K; ++k) {
-            double pk = wt[k] / sum;
-            if (pk > 0.0) h -= pk * std::log(pk);
-            if (pk > p1) { p2 = p1; p1 = pk; } else if (pk > p2) { p2 = pk; }
+        double* wt = w ? w + (size_t)t * K : nullptr;
+        bool allowed = !bypass;
+        if (use_tae || use_margin) {
+            double sum = 0.0;
+            for (int k = 0; k < K; ++k) sum += wt[k];
+            double h = 0.0, p1 = 0.0, p2 = 0.0;              // entropy, largest and second largest p~
+            for (int k = 0; k < K; ++k) {
+                double pk = wt[k] / sum;
+                if (pk > 0.0) h -= pk * std::log(pk);
+                if (pk > p1) { p2 = p1; p1 = pk; } else if (pk > p2) { p2 = pk; }
+            }
+            const double tae = (K > 1) ? h / std::log((double)K) : 0.0;
+            if (use_tae && tae <= tau) allowed = false;
+            if (use_margin && (p1 - p2) >= gamma) allowed = false;
         }
-        const double tae = (K > 1) ? h / std::log((double)K) : 0.0;
-        bool allowed = true;
-        if (use_tae && tae <= tau) allowed = false;
-        if (use_margin && (p1 - p2) >= gamma) allowed = false;
         int replaced = 0;
 
         std::vector<char> in_u(E, 0);
@@ -201,7 +230,11 @@ int bm_oracle_buddy_remap_gated(int T, int K, int E, int R, int H, int unique, i
         }
         for (int k = 0; k < K; ++k) {
             int32_t e = ids_out[(size_t)t * K + k];
-            if (e < 0 || e >= E) { ids_out[(size_t)t * K + k] = -1; wt[k] = 0.0; continue; }
+            if (e < 0 || e >= E) {
+                ids_out[(size_t)t * K + k] = -1;
+                if (wt) wt[k] = 0.0;
+                continue;
+            }
             if (resident[e]) continue;
             ++n_miss;
             int32_t chosen = -1;
@@ -219,12 +252,15 @@ int bm_oracle_buddy_remap_gated(int T, int K, int E, int R, int H, int unique, i
                 ++n_sub;
             } else {
                 ids_out[(size_t)t * K + k] = -1;
-                wt[k] = 0.0;
+                if (wt) wt[k] = 0.0;
                 ++n_drop;
             }
         }
     }
-    if (stats) { stats[0] = n_miss; stats[1] = n_sub; stats[2] = n_drop; }
+    if (stats) {
+        stats[0] = n_miss; stats[1] = n_sub; stats[2] = n_drop;
+        stats[3] = dist[0]; stats[4] = dist[1]; stats[5] = bypass ? 1 : 0;
+    }
     return 0;
 }
 
@@ -333,10 +369,12 @@ int bm_oracle_moe_forward(int T, int d, int E, int F, int K, int n_shared, int R
     return 0;
 }
 
-// The whole layer with the gates of Section 3.1 / budget of Section 5.1 in front of Algorithm 1.
+// The whole layer with the gates of Section 3.1 / budget of Section 5.1 in front of Algorithm 1
+// (stats[6] as in bm_oracle_buddy_remap_gated).
 int bm_oracle_moe_forward_gated(int T, int d, int E, int F, int K, int n_shared, int R, int H, int renorm,
                                 int unique, int use_tae, double tau, int use_margin, double gamma,
-                                int use_budget, int rho, const float* x, const float* w_router,
+                                int use_budget, int rho, int use_dist, double beta, const float* x,
+                                const float* w_router,
                                 const float* bias, const float* w_gate, const float* w_up,
                                 const float* w_down, const float* ws_gate, const float* ws_up,
                                 const float* ws_down, const uint8_t* resident, const int32_t* table,
@@ -349,7 +387,7 @@ int bm_oracle_moe_forward_gated(int T, int d, int E, int F, int K, int n_shared,
     rc = bm_oracle_topk_gates(T, E, K, renorm, z.data(), ids.data(), w.data());
     if (rc) return rc;
     rc = bm_oracle_buddy_remap_gated(T, K, E, R, H, unique, use_tae, tau, use_margin, gamma, use_budget, rho,
-                                     resident, table, ids.data(), ids2.data(), w.data(), stats);
+                                     use_dist, beta, resident, table, ids.data(), ids2.data(), w.data(), stats);
     if (rc) return rc;
     rc = bm_oracle_experts_combine(T, d, E, F, K, n_shared, x, ids2.data(), w.data(), w_gate, w_up, w_down,
                                    ws_gate, ws_up, ws_down, y);

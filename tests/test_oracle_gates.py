@@ -9,6 +9,14 @@ import oracle
 from tests.test_oracle_remap import _random_problem
 
 
+def _same(a, b):
+    """(ids, w, stats) triples agree; stats compared on the keys both have."""
+    np.testing.assert_array_equal(a[0], b[0])
+    np.testing.assert_array_equal(a[1], b[1])
+    for k in set(a[2]) & set(b[2]):
+        assert a[2][k] == b[2][k], k
+
+
 def _gates(seed, T, K, sharp=3.0):
     g = np.random.default_rng(seed)
     z = g.normal(size=(T, K)) * sharp
@@ -22,10 +30,10 @@ def test_gates_off_equals_algorithm1():
     for unique in (False, True):
         a = oracle.buddy_remap(ids, res, table, H=4, unique=unique, w=w)
         b = oracle.buddy_remap_gated(ids, res, table, w, H=4, unique=unique)
-        np.testing.assert_array_equal(a[0], b[0]); np.testing.assert_array_equal(a[1], b[1]); assert a[2] == b[2]
+        _same(a, b)
         # thresholds no token can reach, budget no token can use up: the gates are there but never fire
         c = oracle.buddy_remap_gated(ids, res, table, w, H=4, unique=unique, tau=-1.0, gamma=2.0, rho=ids.shape[1])
-        np.testing.assert_array_equal(a[0], c[0]); np.testing.assert_array_equal(a[1], c[1]); assert a[2] == c[2]
+        _same(a, c)
 
 
 @pytest.mark.parametrize("kw", [dict(tau=1.0), dict(gamma=0.0), dict(rho=0)])
@@ -36,7 +44,7 @@ def test_gate_that_forbids_everything_equals_empty_search(kw):
     w = _gates(14, *ids.shape)
     a = oracle.buddy_remap(ids, res, table, H=0, w=w)
     b = oracle.buddy_remap_gated(ids, res, table, w, H=5, **kw)
-    np.testing.assert_array_equal(a[0], b[0]); np.testing.assert_array_equal(a[1], b[1]); assert a[2] == b[2]
+    _same(a, b)
 
 
 def test_tae_gate_splits_tokens_at_the_threshold():
@@ -75,7 +83,7 @@ def test_tae_closed_forms_decide():
     out, w2, st = oracle.buddy_remap_gated(ids, res, table, w, tau=0.5)
     np.testing.assert_array_equal(out, [[-1, 2], [1, 2]])
     np.testing.assert_array_equal(w2, [[0.0, 0.90], [0.12, 0.88]])
-    assert st == dict(n_miss=2, n_substituted=1, n_dropped=1)
+    assert (st["n_miss"], st["n_substituted"], st["n_dropped"]) == (2, 1, 1)
     # uniform gates have TAE = 1 > any tau < 1; a one-hot token has TAE = 0 <= tau = 0
     w = np.array([[0.5, 0.5], [1.0, 0.0]])
     out, _, _ = oracle.buddy_remap_gated(ids, res, table, w, tau=0.0)
@@ -158,3 +166,70 @@ def test_gated_layer_equals_stages():
     np.testing.assert_array_equal(out["y"], y)
     assert out["stats"] == st
     assert 0 < st["n_substituted"] and 0 < st["n_dropped"]
+
+
+# ------------------------------------------------------------ distribution gate (Eq. 2)
+
+
+def test_delta_hand_cases():
+    # E = 6, experts 0..2 resident.  Batch requests {0, 1, 3, 5}: two of four offloaded.
+    res = np.array([1, 1, 1, 0, 0, 0], bool)
+    ids = np.array([[0, 3], [1, 3], [5, 0], [3, 1]], np.int32)
+    assert oracle.distribution_delta(ids, res) == (0.5, 4, 2)
+    # repeated requests count once (a set, not a multiset): 100 tokens asking for (0, 4)
+    assert oracle.distribution_delta(np.tile(np.array([[0, 4]], np.int32), (100, 1)), res) == (0.5, 2, 1)
+    # all requested resident -> 0; none resident -> 1; slots already dropped (-1) request nothing
+    assert oracle.distribution_delta(np.array([[0, 1], [2, 1]], np.int32), res)[0] == 0.0
+    assert oracle.distribution_delta(np.array([[3, 4], [5, -1]], np.int32), res) == (1.0, 3, 3)
+    assert oracle.distribution_delta(np.zeros((0, 2), np.int32), res) == (0.0, 0, 0)
+
+
+def test_delta_against_numpy_sets():
+    ids, res, _ = _random_problem(31, T=37, E=24, K=4)
+    req = np.unique(ids)
+    d, n_req, n_cpu = oracle.distribution_delta(ids, res)
+    assert n_req == len(req) and n_cpu == int((~res[req]).sum()) and d == n_cpu / n_req
+    # delta depends on the set only: permuting tokens and slots changes nothing
+    g = np.random.default_rng(0)
+    assert oracle.distribution_delta(g.permuted(ids[g.permutation(len(ids))], axis=1), res) == (d, n_req, n_cpu)
+
+
+def test_distribution_gate_is_all_or_nothing():
+    ids, res, table = _random_problem(33, T=64, E=24, K=4, n_res=9)
+    w = _gates(34, *ids.shape)
+    d, n_req, n_cpu = oracle.distribution_delta(ids, res)
+    full = oracle.buddy_remap(ids, res, table, H=4, unique=True, w=w)
+    none = oracle.buddy_remap(ids, res, table, H=0, unique=True, w=w)
+    for beta, want, byp in [(d + 1e-9, full, 0), (d, none, 1), (d - 1e-9, none, 1), (1.01, full, 0), (0.0, none, 1)]:
+        got = oracle.buddy_remap_gated(ids, res, table, w, H=4, unique=True, beta=beta)
+        _same(got, want)
+        assert (got[2]["n_requested"], got[2]["n_requested_offloaded"], got[2]["bypassed"]) == (n_req, n_cpu, byp)
+    # the gate needs no weights
+    got = oracle.buddy_remap_gated(ids, res, table, None, H=4, unique=True, beta=d)
+    np.testing.assert_array_equal(got[0], none[0])
+
+
+def test_distribution_gate_sees_the_whole_batch():
+    # one token alone: it requests {0 (resident), 3 (offloaded)} -> delta = 1/2.  Together with a token
+    # that requests two more resident experts the batch has delta = 1/4: beta = 0.4 bypasses the first
+    # batch and not the second, so the same token gets a different result depending on its batch.
+    res = np.array([1, 1, 1, 0, 0, 0], bool)
+    table = np.array([[1], [0], [0], [2], [2], [2]], np.int32)
+    a = oracle.buddy_remap_gated(np.array([[0, 3]], np.int32), res, table, beta=0.4)
+    b = oracle.buddy_remap_gated(np.array([[0, 3], [1, 2]], np.int32), res, table, beta=0.4)
+    np.testing.assert_array_equal(a[0], [[0, -1]])
+    np.testing.assert_array_equal(b[0], [[0, 2], [1, 2]])
+    assert a[2]["bypassed"] == 1 and b[2]["bypassed"] == 0
+
+
+def test_three_stage_order():
+    # TAE gate closes token 0, distribution gate open: token 1 is still served.  Then the distribution
+    # gate closes: nobody is served, although token 1 passed its own gate.
+    res = np.array([1, 1, 0, 0], bool)
+    table = np.array([[1], [0], [0], [1]], np.int32)
+    ids = np.array([[2, 0], [3, 0]], np.int32)
+    w = np.array([[0.95, 0.05], [0.5, 0.5]])
+    got = oracle.buddy_remap_gated(ids, res, table, w, tau=0.5, beta=0.9)        # delta = 2/3
+    np.testing.assert_array_equal(got[0], [[-1, 0], [1, 0]])
+    got = oracle.buddy_remap_gated(ids, res, table, w, tau=0.5, beta=0.6)
+    np.testing.assert_array_equal(got[0], [[-1, 0], [-1, 0]])
