@@ -85,7 +85,7 @@ def run_workload(name, T, steps, warmup, with_events=True, unique=False, base=No
     E, K = spec.E, spec.K
     i32 = dict(dtype=torch.int32, device="cuda")
     offsets = torch.zeros(E + 1, **i32)
-    stats = torch.zeros(3, **i32)
+    stats = torch.zeros(6, **i32)
     ids2 = torch.zeros((T, K), **i32)
     hipev = HipEvents()
     events = [hipev.create(5) for _ in range(steps)] if with_events else None

@@ -62,10 +62,15 @@ enum {
                                     TAE = -(sum p~ log p~)/log K is <= desc.tae_tau       */
     BM_GATE_MARGIN    = 1u << 4, /* Section 3.1: nor when p~_max - p~_2nd >= desc.margin_gamma
                                     (second value 0 when K == 1)                          */
-    BM_REPLACE_BUDGET = 1u << 5  /* Section 5.1: at most desc.rho substitutions per token,
+    BM_REPLACE_BUDGET = 1u << 5, /* Section 5.1: at most desc.rho substitutions per token,
                                     counted in slot order; later misses are dropped      */
+    BM_GATE_DIST      = 1u << 6  /* Section 3.1, Eq. 2: over the batch of the call (its T
+                                    tokens), delta = share of the distinct routed experts
+                                    that are not resident; no substitution for any token
+                                    when delta >= desc.dist_beta.  Decided exactly
+                                    (offloaded >= beta * requested, in fp64)              */
 };
-#define BM_GATE_ANY (BM_GATE_TAE | BM_GATE_MARGIN | BM_REPLACE_BUDGET)
+#define BM_GATE_ANY (BM_GATE_TAE | BM_GATE_MARGIN | BM_REPLACE_BUDGET)   /* the per-token ones */
 
 /* Limits of this build. */
 #define BM_MAX_E 256
@@ -81,6 +86,7 @@ typedef struct {
     float tae_tau;      /* read only with BM_GATE_TAE                                 */
     float margin_gamma; /* read only with BM_GATE_MARGIN                              */
     int32_t rho;        /* read only with BM_REPLACE_BUDGET; >= 0                     */
+    float dist_beta;    /* read only with BM_GATE_DIST                                */
 } bm_layer_desc;
 
 /* Weights, all device pointers in `dtype`.  The reduction dimension is
@@ -108,6 +114,10 @@ typedef struct {
     int32_t n_miss;         /* selected experts that were not resident  */
     int32_t n_substituted;  /* of those, replaced by a resident buddy   */
     int32_t n_dropped;      /* of those, dropped (no acceptable buddy)  */
+    /* Distribution gate (Eq. 2); all three are 0 without BM_GATE_DIST */
+    int32_t n_requested;            /* distinct experts routed to by the batch       */
+    int32_t n_requested_offloaded;  /* of those, not resident                        */
+    int32_t bypassed;               /* 1 if delta >= beta switched substitution off  */
 } bm_remap_stats;
 
 /* Optional outputs of bm_moe_forward; any member may be NULL.  Pointers are
@@ -153,8 +163,11 @@ int bm_route_topk(const bm_layer_desc *desc, const void *x, const void *w_router
  * With BM_GATE_TAE / BM_GATE_MARGIN / BM_REPLACE_BUDGET (Section 3.1, Section 5.1)
  * the gates are evaluated per token in fp32 from w as passed in (w is then
  * required: BM_ERR_NULL without it); a miss of a gated token, or one beyond the
- * token's budget, counts as a miss and as dropped.
- * Uses T, E, K, R, H, flags, tae_tau, margin_gamma, rho of desc. */
+ * token's budget, counts as a miss and as dropped.  BM_GATE_DIST takes the
+ * T tokens of the call as the batch; with it and ids_out == ids_in the call
+ * runs in a single workgroup (the request set has to be read before any id is
+ * overwritten).
+ * Uses T, E, K, R, H, flags, tae_tau, margin_gamma, rho, dist_beta of desc. */
 int bm_buddy_remap(const bm_layer_desc *desc, const uint64_t *residency_bitmap,
                    const int32_t *buddy_table, const int32_t *ids_in, int32_t *ids_out,
                    float *w, bm_remap_stats *stats, void *stream);

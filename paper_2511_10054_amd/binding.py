@@ -11,7 +11,7 @@ _lib = None
 
 BM_F32, BM_BF16 = 0, 1
 BM_RENORM_TOPK, BM_REMAP_UNIQUE, BM_Y_F32 = 1, 2, 4
-BM_GATE_TAE, BM_GATE_MARGIN, BM_REPLACE_BUDGET = 8, 16, 32
+BM_GATE_TAE, BM_GATE_MARGIN, BM_REPLACE_BUDGET, BM_GATE_DIST = 8, 16, 32, 64
 
 
 class BuddyMoEError(RuntimeError):
@@ -24,7 +24,7 @@ class LayerDesc(ctypes.Structure):
     _fields_ = [("T", ctypes.c_int32), ("d", ctypes.c_int32), ("E", ctypes.c_int32), ("F", ctypes.c_int32),
                 ("K", ctypes.c_int32), ("n_shared", ctypes.c_int32), ("R", ctypes.c_int32), ("H", ctypes.c_int32),
                 ("dtype", ctypes.c_int32), ("flags", ctypes.c_uint32), ("tae_tau", ctypes.c_float),
-                ("margin_gamma", ctypes.c_float), ("rho", ctypes.c_int32)]
+                ("margin_gamma", ctypes.c_float), ("rho", ctypes.c_int32), ("dist_beta", ctypes.c_float)]
 
 
 class Weights(ctypes.Structure):

@@ -78,6 +78,7 @@ int check_remap_desc(const bm_layer_desc *d) {
     if ((d->flags & BM_REPLACE_BUDGET) && d->rho < 0) return BM_ERR_SHAPE;
     if ((d->flags & BM_GATE_TAE) && !(d->tae_tau == d->tae_tau)) return BM_ERR_SHAPE;            // NaN
     if ((d->flags & BM_GATE_MARGIN) && !(d->margin_gamma == d->margin_gamma)) return BM_ERR_SHAPE;
+    if ((d->flags & BM_GATE_DIST) && !(d->dist_beta == d->dist_beta)) return BM_ERR_SHAPE;
     return BM_OK;
 }
 
@@ -105,7 +106,7 @@ Layout make_layout(const bm_layer_desc *d) {
     L.mt_group = take((size_t)L.mtiles_max * 4);
     L.mt_row0 = take((size_t)L.mtiles_max * 4);
     L.n_mtiles = take(16);
-    L.stats = take(16);
+    L.stats = take(32);
     const size_t F = d->F > 0 ? d->F : 0;
     L.h = take((size_t)L.rows_max * F * esz);
     L.o = take(use_skinny(d) ? (size_t)skinny_ksplit(d) * L.rows_max * d->d * 4 : (size_t)L.rows_max * d->d * esz);
@@ -240,6 +241,7 @@ int bm_buddy_remap(const bm_layer_desc *desc, const uint64_t *residency_bitmap, 
     RemapParams p{};
     p.T = desc->T; p.K = desc->K; p.E = desc->E; p.R = desc->R; p.H = desc->H;
     p.flags = desc->flags; p.tau = desc->tae_tau; p.gamma = desc->margin_gamma; p.rho = desc->rho;
+    p.beta = desc->dist_beta;
     p.bitmap = residency_bitmap; p.table = buddy_table;
     p.ids_in = ids_in; p.ids_out = ids_out; p.w = w;
     p.stats = reinterpret_cast<int32_t *>(stats);
@@ -314,7 +316,7 @@ int bm_moe_forward(const bm_layer_desc *desc, const void *x, const bm_weights *w
     FrontParams fp{};
     fp.x = x; fp.wr = wt->w_router; fp.bias = wt->router_bias;
     fp.T = T; fp.d = desc->d; fp.E = E; fp.K = K; fp.R = desc->R; fp.H = desc->H; fp.flags = desc->flags;
-    fp.tau = desc->tae_tau; fp.gamma = desc->margin_gamma; fp.rho = desc->rho;
+    fp.tau = desc->tae_tau; fp.gamma = desc->margin_gamma; fp.rho = desc->rho; fp.beta = desc->dist_beta;
     fp.ids = at<int32_t>(ws, L.ids); fp.w = at<float>(ws, L.w);
     fp.bitmap = residency_bitmap; fp.table = buddy_table;
     fp.ids2 = at<int32_t>(ws, L.ids2);
@@ -344,6 +346,23 @@ int bm_moe_forward(const bm_layer_desc *desc, const void *x, const bm_weights *w
         fp.scan = sp;
         fp.scat = cp;
         err |= launch_front(fp, desc->dtype, st);
+    } else if (desc->flags & BM_GATE_DIST) {
+        // the distribution gate needs every token's routing before the first substitution: route,
+        // then substitute (each workgroup derives the batch's request set itself), then count
+        FrontParams rp = fp;
+        rp.bitmap = nullptr;
+        err |= launch_front(rp, desc->dtype, st);
+        RemapParams mp{};
+        mp.T = T; mp.K = K; mp.E = E; mp.R = desc->R; mp.H = desc->H;
+        mp.flags = desc->flags; mp.tau = fp.tau; mp.gamma = fp.gamma; mp.rho = fp.rho; mp.beta = fp.beta;
+        mp.bitmap = residency_bitmap; mp.table = buddy_table;
+        mp.ids_in = fp.ids; mp.ids_out = fp.ids2; mp.w = fp.w; mp.stats = sp.stats;
+        err |= launch_remap(mp, st);
+        err |= launch_count(fp.ids2, T, K, E, fp.tile_counts, st);
+        ScanParams sq = sp;
+        sq.tile_stats = nullptr; sq.stats = nullptr;      // written by the substitution kernel
+        err |= launch_scan(sq, st);
+        err |= launch_scatter(cp, st);
     } else {
         err |= launch_front(fp, desc->dtype, st);
         err |= launch_scan(sp, st);
@@ -413,7 +432,7 @@ int bm_moe_forward(const bm_layer_desc *desc, const void *x, const bm_weights *w
         if (dbg->offsets) copy_ints(sp.offsets, dbg->offsets, (size_t)E + 1, st);
         if (dbg->perm) copy_ints(cp.perm, dbg->perm, A, st);
         if (dbg->inv_perm) copy_ints(cp.inv_perm, dbg->inv_perm, A, st);
-        if (dbg->stats) copy_ints(sp.stats, dbg->stats, 3, st);
+        if (dbg->stats) copy_ints(sp.stats, dbg->stats, 6, st);
         err |= launch_status("debug copies");
     }
     return err ? BM_ERR_HIP : BM_OK;

@@ -61,6 +61,12 @@ __device__ __forceinline__ int replacement_budget(int K, uint32_t flags, float t
     return budget;
 }
 
+// Distribution gate (Section 3.1, Eq. 2): delta = n_cpu / n_req >= beta, decided without rounding
+// (both products are exact in fp64 for counts up to BM_MAX_E and an fp32 threshold).
+__device__ __forceinline__ bool dist_bypass(int n_req, int n_cpu, float beta) {
+    return n_req > 0 && (double)n_cpu >= (double)beta * (double)n_req;
+}
+
 __device__ __forceinline__ void remap_token(int K, int E, int R, int H, uint32_t flags, float tau, float gamma,
                                             int rho, const uint64_t *bitmap, const int32_t *table,
                                             const int32_t *ids_in, int32_t *ids_out, float *w,
@@ -108,7 +114,9 @@ struct FrontLds {
     int32_t counts[BM_MAX_E];
     int32_t lut[BM_MAX_E];
     int32_t stats[4];
+    int32_t dist[4];         // distribution gate: requested, requested and offloaded, bypassed
     uint64_t bitmap[4];
+    unsigned long long req[4];
 };
 
 // Ranks the tile's tokens from the logits in LDS and finishes the tile.
@@ -184,8 +192,27 @@ __device__ void tile_epilogue(const FrontParams &p, float *logits, int stride, i
     if (tab_in_lds)
         for (int idx = tid; idx < E * p.R; idx += blockDim.x) s_table[idx] = p.table[idx];
     for (int idx = tid; idx < BM_MAX_E; idx += blockDim.x) s.counts[idx] = 0;
-    if (tid < 4) { s.bitmap[tid] = (tid < ec) ? p.bitmap[tid] : 0ull; s.stats[tid] = 0; }
+    if (tid < 4) { s.bitmap[tid] = (tid < ec) ? p.bitmap[tid] : 0ull; s.stats[tid] = 0; s.req[tid] = 0ull; s.dist[tid] = 0; }
     __syncthreads();
+
+    int H = p.H;
+    if (p.flags & BM_GATE_DIST) {
+        // this tile holds the whole batch (the host guarantees it): set of requested experts, Eq. 2
+        for (int idx = tid; idx < n; idx += blockDim.x) {
+            const int e = s.ids[idx];
+            atomicOr(&s.req[e >> 6], 1ull << (e & 63));
+        }
+        __syncthreads();
+        int n_req = 0, n_cpu = 0;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            n_req += __popcll(s.req[i]);
+            n_cpu += __popcll(s.req[i] & ~s.bitmap[i]);
+        }
+        const bool bypass = dist_bypass(n_req, n_cpu, p.beta);
+        if (bypass) H = 0;                       // every miss is dropped
+        if (tid == 0) { s.dist[0] = n_req; s.dist[1] = n_cpu; s.dist[2] = bypass ? 1 : 0; }
+    }
 
     if (p.flags & (BM_REMAP_UNIQUE | BM_GATE_ANY)) {
         // Algorithm 1 proper (and its per-token gates): a lane walks its token's slots in order
@@ -193,7 +220,7 @@ __device__ void tile_epilogue(const FrontParams &p, float *logits, int stride, i
             int n_miss = 0, n_sub = 0, n_drop = 0;
             int32_t *tok_ids = &s.ids[tid * K];
             float *tok_w = &s.w[tid * K];
-            remap_token(K, E, p.R, p.H, p.flags, p.tau, p.gamma, p.rho, s.bitmap,
+            remap_token(K, E, p.R, H, p.flags, p.tau, p.gamma, p.rho, s.bitmap,
                         tab_in_lds ? s_table : p.table, tok_ids, tok_ids, tok_w, n_miss, n_sub, n_drop);
             if (n_miss) atomicAdd(&s.stats[0], n_miss);
             if (n_sub) atomicAdd(&s.stats[1], n_sub);
@@ -211,7 +238,7 @@ __device__ void tile_epilogue(const FrontParams &p, float *logits, int stride, i
             const bool res = (s.bitmap[e >> 6] >> (e & 63)) & 1ull;
             int out = res ? e : -1;
             bool found = res;
-            for (int r = 0; r < p.H; ++r) {
+            for (int r = 0; r < H; ++r) {
                 const int b = tab[e * p.R + r];
                 const bool bvalid = (unsigned)b < (unsigned)E;
                 const int bc = bvalid ? b : 0;
@@ -256,6 +283,7 @@ struct FusedLds {
     int32_t ids[FUSED_TILES][TILE_T * BM_MAX_K];   // substituted ids of every tile
     int32_t counts[FUSED_TILES][BM_MAX_E];         // per-tile histograms
     int32_t stats[FUSED_TILES][4];
+    int32_t dist[4];                               // distribution gate counters (single-tile batches)
     int32_t start[BM_MAX_E + 16];                  // group offsets
     int32_t tstart[BM_MAX_E + 16];                 // first row tile of each group
 };
@@ -315,6 +343,7 @@ __device__ void fused_tail(const FrontParams &p, FusedLds &fs, int n_tiles) {
         int sum = 0;
         for (int t = 0; t < n_tiles; ++t) sum += fs.stats[t][tid];
         p.scan.stats[tid] = sum;
+        p.scan.stats[3 + tid] = (p.flags & BM_GATE_DIST) ? fs.dist[tid] : 0;
     }
     // stable placement
     const int live = fs.start[E];
@@ -441,7 +470,7 @@ __global__ void __launch_bounds__(NW * 64) front_bf16_kernel(FrontParams p) {
             const int n = min(TILE_T, p.T - t0) * p.K;
             for (int idx = tid; idx < n; idx += NW * 64) fs.ids[tile][idx] = s.ids[idx];
             for (int e = tid; e < p.E; e += NW * 64) fs.counts[tile][e] = s.counts[e];
-            if (tid < 3) fs.stats[tile][tid] = s.stats[tid];
+            if (tid < 3) { fs.stats[tile][tid] = s.stats[tid]; fs.dist[tid] = s.dist[tid]; }
             __syncthreads();
         }
     }
@@ -479,25 +508,54 @@ __global__ void __launch_bounds__(256) front_f32_kernel(FrontParams p) {
 __global__ void __launch_bounds__(256) remap_kernel(RemapParams p) {
     extern __shared__ int32_t s_table[];
     __shared__ uint64_t s_bitmap[4];
+    __shared__ unsigned long long s_req[4];
     __shared__ int32_t s_stats[3];
     const int tid = threadIdx.x;
     const int ec = (p.E + 63) >> 6;
     for (int idx = tid; idx < p.E * p.R; idx += blockDim.x) s_table[idx] = p.table[idx];
-    if (tid < 4) s_bitmap[tid] = (tid < ec) ? p.bitmap[tid] : 0ull;
+    if (tid < 4) { s_bitmap[tid] = (tid < ec) ? p.bitmap[tid] : 0ull; s_req[tid] = 0ull; }
     if (tid < 3) s_stats[tid] = 0;
     __syncthreads();
-    const int t = blockIdx.x * blockDim.x + tid;
-    if (t < p.T) {
-        int n_miss = 0, n_sub = 0, n_drop = 0;
+    int H = p.H;
+    if (p.flags & BM_GATE_DIST) {
+        // Eq. 2 over the whole batch, recomputed by every workgroup (no scratch memory, no grid-wide wait)
+        const size_t n = (size_t)p.T * p.K;
+        unsigned long long mine[4] = {0ull, 0ull, 0ull, 0ull};
+        for (size_t a = tid; a < n; a += blockDim.x) {
+            const int e = p.ids_in[a];
+            if ((unsigned)e < (unsigned)p.E) {
+                const unsigned long long bit = 1ull << (e & 63);
+                const int wi = e >> 6;
+                mine[0] |= wi == 0 ? bit : 0ull; mine[1] |= wi == 1 ? bit : 0ull;
+                mine[2] |= wi == 2 ? bit : 0ull; mine[3] |= wi == 3 ? bit : 0ull;
+            }
+        }
+#pragma unroll
+        for (int i = 0; i < 4; ++i) if (mine[i]) atomicOr(&s_req[i], mine[i]);
+        __syncthreads();
+        int n_req = 0, n_cpu = 0;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            n_req += __popcll(s_req[i]);
+            n_cpu += __popcll(s_req[i] & ~s_bitmap[i]);
+        }
+        const bool bypass = dist_bypass(n_req, n_cpu, p.beta);
+        if (bypass) H = 0;
+        if (p.stats != nullptr && blockIdx.x == 0 && tid == 0) {
+            p.stats[3] = n_req; p.stats[4] = n_cpu; p.stats[5] = bypass ? 1 : 0;
+        }
+    }
+    int n_miss = 0, n_sub = 0, n_drop = 0;
+    for (int t = blockIdx.x * blockDim.x + tid; t < p.T; t += gridDim.x * blockDim.x) {
         const int32_t *in = p.ids_in + (size_t)t * p.K;
         int32_t *out = p.ids_out + (size_t)t * p.K;
         float *w = p.w ? p.w + (size_t)t * p.K : nullptr;
-        remap_token(p.K, p.E, p.R, p.H, p.flags, p.tau, p.gamma, p.rho, s_bitmap, s_table, in, out, w, n_miss,
+        remap_token(p.K, p.E, p.R, H, p.flags, p.tau, p.gamma, p.rho, s_bitmap, s_table, in, out, w, n_miss,
                     n_sub, n_drop);
-        if (n_miss) atomicAdd(&s_stats[0], n_miss);
-        if (n_sub) atomicAdd(&s_stats[1], n_sub);
-        if (n_drop) atomicAdd(&s_stats[2], n_drop);
     }
+    if (n_miss) atomicAdd(&s_stats[0], n_miss);
+    if (n_sub) atomicAdd(&s_stats[1], n_sub);
+    if (n_drop) atomicAdd(&s_stats[2], n_drop);
     __syncthreads();
     if (p.stats != nullptr && tid < 3 && s_stats[tid]) atomicAdd(&p.stats[tid], s_stats[tid]);
 }
@@ -588,7 +646,7 @@ __global__ void __launch_bounds__(1024) scan_kernel(ScanParams p) {
             for (int t = lane; t < p.n_tiles; t += WAVE) sum += p.tile_stats[t * 4 + wave];
 #pragma unroll
         for (int m = 32; m >= 1; m >>= 1) sum += __shfl_xor(sum, m, WAVE);
-        if (lane == 0) p.stats[wave] = sum;
+        if (lane == 0) { p.stats[wave] = sum; p.stats[3 + wave] = 0; }
     }
 }
 
@@ -663,10 +721,16 @@ int launch_front(const FrontParams &p, int dtype, hipStream_t st) {
 }
 
 int launch_remap(const RemapParams &p, hipStream_t st) {
-    if (p.stats) hipLaunchKernelGGL(zero_ints_kernel, dim3(1), dim3(64), 0, st, p.stats, 3);
+    if (p.stats) hipLaunchKernelGGL(zero_ints_kernel, dim3(1), dim3(64), 0, st, p.stats, 6);
     if (p.T > 0) {
         const size_t lds = (size_t)p.E * p.R * sizeof(int32_t);
-        hipLaunchKernelGGL(remap_kernel, dim3((p.T + 255) / 256), dim3(256), lds, st, p);
+        int blocks = (p.T + 255) / 256;
+        if (p.flags & BM_GATE_DIST) {
+            // every workgroup reads all ids for the request set: bound their number; in place, a single
+            // workgroup reads the set before it overwrites anything
+            blocks = p.ids_out == p.ids_in ? 1 : (blocks > 256 ? 256 : blocks);
+        }
+        hipLaunchKernelGGL(remap_kernel, dim3(blocks), dim3(256), lds, st, p);
     }
     return launch_status(__func__);
 }

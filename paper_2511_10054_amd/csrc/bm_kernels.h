@@ -11,12 +11,13 @@ struct RemapParams {
     uint32_t flags;         // BM_REMAP_UNIQUE and the gate bits
     float tau, gamma;       // TAE and margin thresholds
     int rho;                // replacement budget per token
+    float beta;             // distribution-gate threshold
     const uint64_t *bitmap;
     const int32_t *table;
     const int32_t *ids_in;
     int32_t *ids_out;
     float *w;
-    int32_t *stats;         // 3 ints or null
+    int32_t *stats;         // 6 ints or null
 };
 
 struct ScanParams {
@@ -47,6 +48,7 @@ struct FrontParams {
     uint32_t flags;
     float tau, gamma;       // TAE and margin thresholds (gate bits of flags)
     int rho;                // replacement budget per token
+    float beta;             // distribution-gate threshold (BM_GATE_DIST: only when one tile holds the batch)
     int32_t *ids;           // [T][K] router's choice
     float *w;               // [T][K]
     const uint64_t *bitmap; // null => routing only (no substitution, no histogram)

@@ -6,7 +6,7 @@ import pytest
 
 import oracle
 import workloads
-from helpers import DeviceLayer, HostLayer, err_metric
+from helpers import DeviceLayer, HostLayer, err_metric, safe_threshold, tae_margin
 
 pytestmark = pytest.mark.gpu
 
@@ -23,22 +23,24 @@ def _layers(name):
     return _cache[name]
 
 
-def _check(name, T, n_sample, unique=False):
+def _check(name, T, n_sample, unique=False, **gates):
     spec = workloads.CONFIGS[name]
     base_host, base_dev = _layers(name)
-    print(f"fullsize {name} T={T} unique={unique}", flush=True)
+    print(f"fullsize {name} T={T} unique={unique} {gates}", flush=True)
     host = HostLayer(spec, T, base=base_host)
-    dev = DeviceLayer(host, unique=unique, base=base_dev)
+    dev = DeviceLayer(host, unique=unique, base=base_dev, **gates)
     out = dev.forward()
     # indices on all tokens
     lay = host.lay
     ids_ref, w_ref = oracle.route_topk(host.f32(host.x), host.f32(host.w_router), host.bias, spec.K)
-    ids2_ref, w2_ref, st = oracle.buddy_remap(ids_ref, host.mask, host.table, H=spec.H, unique=unique, w=w_ref)
+    ids2_ref, w2_ref, st = oracle.buddy_remap_gated(ids_ref, host.mask, host.table, w_ref, H=spec.H, unique=unique,
+                                                    **gates)
     off_ref, perm_ref, inv_ref = oracle.permute(ids2_ref, spec.E)
     np.testing.assert_array_equal(out["ids"], ids_ref)
     np.testing.assert_array_equal(out["ids_remapped"], ids2_ref)
     np.testing.assert_allclose(out["w"], w2_ref, rtol=2e-5, atol=1e-7)
-    assert out["stats"].tolist() == [st["n_miss"], st["n_substituted"], st["n_dropped"]]
+    assert out["stats"].tolist() == [st["n_miss"], st["n_substituted"], st["n_dropped"], st["n_requested"],
+                                     st["n_requested_offloaded"], st["bypassed"]]
     np.testing.assert_array_equal(out["offsets"], off_ref)
     np.testing.assert_array_equal(out["perm"], perm_ref)
     np.testing.assert_array_equal(out["inv_perm"], inv_ref)
@@ -49,9 +51,15 @@ def _check(name, T, n_sample, unique=False):
     used = np.unique(ids2_ref[ids2_ref >= 0])
     extra = [int(np.nonzero((ids2_ref == e).any(1))[0][0]) for e in used]
     rows = np.unique(np.concatenate([rows, np.array(extra, dtype=rows.dtype)]))
-    ref = host.oracle_forward(oracle, unique=unique, rows=rows)
-    np.testing.assert_array_equal(ref["ids_remapped"], ids2_ref[rows])
-    err = err_metric(out["y"][rows], ref["y"])
+    if gates:      # the distribution gate sees the whole batch: feed the sampled tokens' final ids and weights
+        f = host.f32
+        y_ref = oracle.experts_combine(f(host.x)[rows], ids2_ref[rows], w2_ref[rows], f(host.wg), f(host.wu),
+                                       f(host.wd), f(host.sg), f(host.su), f(host.sd))
+    else:
+        ref = host.oracle_forward(oracle, unique=unique, rows=rows)
+        np.testing.assert_array_equal(ref["ids_remapped"], ids2_ref[rows])
+        y_ref = ref["y"]
+    err = err_metric(out["y"][rows], y_ref)
     print(f"   sample {len(rows)} tokens, err {err:.3e}, stats {st}", flush=True)
     assert np.isfinite(out["y"]).all()
     assert err <= 2e-2, err
@@ -77,3 +85,15 @@ def test_c4_qwen3():
 def test_c5_deepseek():
     _check("c5_deepseek", 8192, 256)
     _check("c5_deepseek", 8192, 64, unique=True)
+
+
+def test_gated_full_size():
+    # the paper's best setting uses a budget of 3 replacements per token (Section 5.1) behind the TAE gate;
+    # the distribution gate is placed just above the batch's own delta (open) and at it (closed)
+    spec = workloads.CONFIGS["c5_deepseek"]
+    host = HostLayer(spec, 8192, base=_layers("c5_deepseek")[0])
+    _, w = oracle.route_topk(host.f32(host.x), host.f32(host.w_router), host.bias, spec.K)
+    tau = safe_threshold(tae_margin(w)[0], 0.15)                  # percentile calibration of Section 3.1
+    _check("c5_deepseek", 8192, 64, unique=True, tau=tau, rho=3, beta=0.99)
+    _check("c3_mixtral_prefill", 4096, 48, beta=0.5)              # 4 of 8 requested experts offloaded: closed
+    _check("c2_mixtral_decode", 8, 8, unique=True, rho=1, beta=0.9)

@@ -5,7 +5,8 @@ import pytest
 
 import oracle
 import workloads
-from helpers import DeviceLayer, HostLayer, err_metric, to_device
+from helpers import DeviceLayer, HostLayer, err_metric, to_device, tae_margin as _tae_margin, \
+    safe_threshold as _threshold, beta_pair
 
 pytestmark = pytest.mark.gpu
 
@@ -86,12 +87,12 @@ def test_buddy_remap(T, E, K, R, n_res, unique):
         d_ids = to_device(ids)
         d_out = torch.full((T, K), -9, dtype=torch.int32, device="cuda")
         d_w = to_device(w)
-        d_stats = torch.full((3,), -9, dtype=torch.int32, device="cuda")
+        d_stats = torch.full((6,), -9, dtype=torch.int32, device="cuda")
         bm.bm_buddy_remap(desc, to_device(workloads.pack_bitmap(res)), to_device(table), d_ids, d_out, d_w, d_stats)
         torch.cuda.synchronize()
         np.testing.assert_array_equal(d_out.cpu().numpy(), ref)
         np.testing.assert_array_equal(d_w.cpu().numpy(), w_ref.astype(np.float32))
-        assert d_stats.cpu().tolist() == [st["n_miss"], st["n_substituted"], st["n_dropped"]]
+        assert d_stats.cpu().tolist() == [st["n_miss"], st["n_substituted"], st["n_dropped"], 0, 0, 0]
         # in place, no weights, no stats
         bm.bm_buddy_remap(desc, to_device(workloads.pack_bitmap(res)), to_device(table), d_ids, d_ids)
         torch.cuda.synchronize()
@@ -148,7 +149,8 @@ def _check_layer(host, unique, renorm=True, H=None, **gates):
     np.testing.assert_array_equal(out["ids_remapped"], ref["ids_remapped"])
     np.testing.assert_allclose(out["w"], ref["w"], rtol=2e-5, atol=1e-7)
     st = ref["stats"]
-    assert out["stats"].tolist() == [st["n_miss"], st["n_substituted"], st["n_dropped"]]
+    assert out["stats"].tolist() == [st["n_miss"], st["n_substituted"], st["n_dropped"], st["n_requested"],
+                                     st["n_requested_offloaded"], st["bypassed"]]
     off_ref, perm_ref, inv_ref = oracle.permute(ref["ids_remapped"], spec.E)
     np.testing.assert_array_equal(out["offsets"], off_ref)
     np.testing.assert_array_equal(out["perm"], perm_ref)
@@ -211,7 +213,7 @@ def test_all_resident_is_plain_topk_moe():
     host = HostLayer(spec, 150, mask=np.ones(spec.E, bool))
     out, ref, _ = _check_layer(host, unique=True)
     np.testing.assert_array_equal(out["ids"], out["ids_remapped"])
-    assert out["stats"].tolist() == [0, 0, 0]
+    assert out["stats"].tolist() == [0, 0, 0, 0, 0, 0]
 
 
 def test_nothing_resident_leaves_only_shared_experts():
@@ -265,28 +267,6 @@ def test_fp32_output_flag_and_empty_batch():
 # ------------------------------------------------ gates in front of Algorithm 1
 
 
-def _tae_margin(w):
-    """TAE (Eq. 1) and top-two margin of gate weights, numpy fp64 - used only to place thresholds."""
-    p = w / w.sum(1, keepdims=True)
-    K = p.shape[1]
-    tae = -(np.where(p > 0, p * np.log(np.where(p > 0, p, 1.0)), 0.0)).sum(1) / np.log(K)
-    top = -np.sort(-p, axis=1)
-    return tae, top[:, 0] - top[:, 1]
-
-
-def _threshold(values, q):
-    """A threshold near the q-quantile of `values` in the middle of the widest nearby gap, so that the
-    fp32 device value and the fp64 oracle value of every token fall on the same side of it."""
-    v = np.unique(values)
-    if len(v) < 2:
-        return float(v[0]) + 0.25
-    i = int(q * (len(v) - 1))
-    lo, hi = max(0, i - 8), min(len(v) - 1, i + 8)
-    j = lo + int(np.argmax(np.diff(v[lo:hi + 1])))
-    assert v[j + 1] - v[j] > 2e-5, "no safe gap"
-    return float(0.5 * (v[j] + v[j + 1]))
-
-
 @pytest.mark.parametrize("T,E,K,R,n_res", [(1, 8, 2, 3, 4), (1000, 24, 4, 6, 9), (513, 64, 6, 8, 16),
                                            (257, 256, 32, 32, 40)])
 @pytest.mark.parametrize("unique", [False, True])
@@ -301,24 +281,35 @@ def test_buddy_remap_gated(T, E, K, R, n_res, unique):
     tae, margin = _tae_margin(w.astype(np.float64))
     tau, gamma = _threshold(tae, 0.4), _threshold(margin, 0.7)
     base = bm.BM_REMAP_UNIQUE if unique else 0
-    for gates in (dict(tau=tau), dict(gamma=gamma), dict(rho=1), dict(rho=0), dict(tau=tau, gamma=gamma, rho=2)):
+    delta, above = beta_pair(oracle.distribution_delta(ids, res)[0])   # gate closed / one fp32 step on: open
+    for gates in (dict(tau=tau), dict(gamma=gamma), dict(rho=1), dict(rho=0), dict(tau=tau, gamma=gamma, rho=2),
+                  dict(beta=delta), dict(beta=above), dict(beta=above, tau=tau, rho=1), dict(beta=0.0)):
         ref, w_ref, st = oracle.buddy_remap_gated(ids, res, table, w, H=R, unique=unique, **gates)
         flags = base | (bm.BM_GATE_TAE if "tau" in gates else 0) | (bm.BM_GATE_MARGIN if "gamma" in gates else 0) \
-            | (bm.BM_REPLACE_BUDGET if "rho" in gates else 0)
+            | (bm.BM_REPLACE_BUDGET if "rho" in gates else 0) | (bm.BM_GATE_DIST if "beta" in gates else 0)
         desc = bm.LayerDesc(T=T, d=32, E=E, F=0, K=K, n_shared=0, R=R, H=R, dtype=bm.BM_BF16, flags=flags,
                             tae_tau=gates.get("tau", 0.0), margin_gamma=gates.get("gamma", 0.0),
-                            rho=gates.get("rho", 0))
+                            rho=gates.get("rho", 0), dist_beta=gates.get("beta", 0.0))
         d_out = torch.full((T, K), -9, dtype=torch.int32, device="cuda")
         d_w = to_device(w)
-        d_stats = torch.full((3,), -9, dtype=torch.int32, device="cuda")
+        d_stats = torch.full((6,), -9, dtype=torch.int32, device="cuda")
         bm.bm_buddy_remap(desc, to_device(workloads.pack_bitmap(res)), to_device(table), to_device(ids), d_out,
                           d_w, d_stats)
         torch.cuda.synchronize()
         np.testing.assert_array_equal(d_out.cpu().numpy(), ref, err_msg=str(gates))
         np.testing.assert_array_equal(d_w.cpu().numpy(), w_ref.astype(np.float32))
-        assert d_stats.cpu().tolist() == [st["n_miss"], st["n_substituted"], st["n_dropped"]]
+        assert d_stats.cpu().tolist() == [st["n_miss"], st["n_substituted"], st["n_dropped"], st["n_requested"],
+                                          st["n_requested_offloaded"], st["bypassed"]], gates
         if T > 100 and ("tau" in gates or "gamma" in gates):
             assert 0 < st["n_substituted"] and 0 < st["n_dropped"]
+        if "beta" in gates:
+            # in place: the request set must be read before any id is overwritten
+            d_ids = to_device(ids)
+            bm.bm_buddy_remap(desc, to_device(workloads.pack_bitmap(res)), to_device(table), d_ids, d_ids,
+                              to_device(w))
+            torch.cuda.synchronize()
+            np.testing.assert_array_equal(d_ids.cpu().numpy(), ref, err_msg="in place " + str(gates))
+            assert st["bypassed"] == (0 if gates["beta"] == above else 1)
 
 
 def test_gates_need_weights():
@@ -355,3 +346,10 @@ def test_gated_layer_matches_oracle(name, over, T, unique):
     out, ref, _ = _check_layer(host, unique, tau=tau, gamma=gamma, rho=1)
     replaced = (ref["ids_remapped"] != ref["ids"]) & (ref["ids_remapped"] >= 0)
     assert (replaced.sum(1) <= 1).all()
+    # distribution gate (Eq. 2) at the batch's own delta (closed) and one fp32 step above it (open)
+    ids, _ = oracle.route_topk(host.f32(host.x), host.f32(host.w_router), host.bias, spec.K)
+    closed, open_ = beta_pair(oracle.distribution_delta(ids, host.mask)[0])
+    out, ref, _ = _check_layer(host, unique, beta=closed)
+    assert ref["stats"]["bypassed"] == 1 and ref["stats"]["n_substituted"] == 0
+    out, ref, _ = _check_layer(host, unique, beta=open_, tau=tau)
+    assert ref["stats"]["bypassed"] == 0 and ref["stats"]["n_substituted"] > 0

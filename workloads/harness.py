@@ -44,17 +44,18 @@ class HostLayer:
     def f32(self, a):
         return None if a is None else self.lay.as_f32(a)
 
-    def oracle_forward(self, oracle, unique=False, renorm=True, H=None, rows=None, tau=None, gamma=None, rho=None):
+    def oracle_forward(self, oracle, unique=False, renorm=True, H=None, rows=None, tau=None, gamma=None, rho=None, beta=None):
         """Oracle on all tokens or on the token subset `rows` (tokens are independent)."""
         x = self.f32(self.x)
         if rows is not None:
+            assert beta is None, "the distribution gate looks at the whole batch"
             x = x[rows]
         # non-resident experts are never read by the oracle's FFN either; NaN poison is harmless
         return oracle.moe_forward(x, self.f32(self.w_router), self.bias, self.f32(self.wg), self.f32(self.wu),
                                   self.f32(self.wd), self.mask, self.table, self.spec.K,
                                   H=self.spec.H if H is None else H, renorm=renorm, unique=unique,
                                   ws_gate=self.f32(self.sg), ws_up=self.f32(self.su), ws_down=self.f32(self.sd),
-                                  tau=tau, gamma=gamma, rho=rho)
+                                  tau=tau, gamma=gamma, rho=rho, beta=beta)
 
 
 def to_device(a, device="cuda"):
@@ -73,10 +74,10 @@ class DeviceLayer:
     """Uploads a HostLayer and runs the library through the Python binding."""
 
     def __init__(self, host: HostLayer, unique=False, renorm=True, H=None, y_f32=False, base=None, pack=False,
-                 tau=None, gamma=None, rho=None):
+                 tau=None, gamma=None, rho=None, beta=None):
         """base: another DeviceLayer whose uploaded (and packed) weights are reused.
         pack: also build the fragment-major weight copies (bm_pack_weights), once.
-        tau / gamma / rho: TAE gate, margin gate, replacement budget (None = off)."""
+        tau / gamma / rho / beta: TAE gate, margin gate, replacement budget, distribution gate (None = off)."""
         import torch
         import paper_2511_10054_amd as bm
         self.bm = bm
@@ -84,11 +85,11 @@ class DeviceLayer:
         s = host.spec
         flags = (bm.BM_RENORM_TOPK if renorm else 0) | (bm.BM_REMAP_UNIQUE if unique else 0) | (bm.BM_Y_F32 if y_f32 else 0)
         flags |= (bm.BM_GATE_TAE if tau is not None else 0) | (bm.BM_GATE_MARGIN if gamma is not None else 0)
-        flags |= bm.BM_REPLACE_BUDGET if rho is not None else 0
+        flags |= (bm.BM_REPLACE_BUDGET if rho is not None else 0) | (bm.BM_GATE_DIST if beta is not None else 0)
         self.desc = bm.LayerDesc(T=host.T, d=s.d, E=s.E, F=s.F, K=s.K, n_shared=s.n_shared, R=s.R,
                                  H=s.H if H is None else H,
                                  dtype=bm.BM_BF16 if s.dtype == "bf16" else bm.BM_F32, flags=flags,
-                                 tae_tau=tau or 0.0, margin_gamma=gamma or 0.0, rho=rho or 0)
+                                 tae_tau=tau or 0.0, margin_gamma=gamma or 0.0, rho=rho or 0, dist_beta=beta or 0.0)
         self.x = to_device(host.x)
         self.w_router = to_device(host.w_router)
         self.bias = to_device(host.bias)
@@ -125,7 +126,7 @@ class DeviceLayer:
             dbg = dict(ids=torch.full((T, K), -7, **i32), ids_remapped=torch.full((T, K), -7, **i32),
                        w=torch.full((T, K), -7.0, dtype=torch.float32, device="cuda"),
                        offsets=torch.full((E + 1,), -7, **i32), perm=torch.full((T * K,), -7, **i32),
-                       inv_perm=torch.full((T * K,), -7, **i32), stats=torch.full((3,), -7, **i32))
+                       inv_perm=torch.full((T * K,), -7, **i32), stats=torch.full((6,), -7, **i32))
         self.bm.bm_moe_forward(self.desc, self.x, self.weights, self.bitmap, self.table, self.y, self.workspace, dbg)
         torch.cuda.synchronize()
         out = dict(y=self.y.float().cpu().numpy())
