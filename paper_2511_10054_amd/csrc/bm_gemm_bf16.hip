@@ -573,6 +573,212 @@ __global__ void __launch_bounds__(256) grouped_gemm256_dma_bf16_kernel(GemmParam
     }
 }
 
+// ---------------------------------------------------------------------------
+// 256 x 256 tile with k-steps of 64 and direct-to-LDS loads that fetch whole
+// 128-byte lines.  The vector cache moves one 128-byte line per two cycles
+// whether a load uses all of it or half, so the 64-byte row pieces of a k-step
+// of 32 cost twice the cache time of the MFMAs' data and leave the matrix cores
+// waiting on load issue; here one load instruction covers 8 rows x 128 bytes.
+// A k-step of 64 is two parts of 32 KB (the activation rows, the weight rows)
+// and LDS holds five parts as a ring, ordered B(0) A(0) B(1) A(1) B(2) ...:
+//   during k-step kt the slots hold B(kt) A(kt) B(kt+1) A(kt+1) B(kt+2).
+//   One barrier per k-step, before its last 16 MFMAs (every wave has read its
+//   last fragments of B(kt), A(kt) by then, and B(kt+1), A(kt+1) have landed);
+//   after it A(kt+2) goes into B(kt)'s slot under the last 16 MFMAs, and B(kt+3)
+//   into A(kt)'s slot spread under the next k-step's first 48 (bursts of loads
+//   hold up a wave's MFMAs at issue: every instruction is hand-placed and fenced).
+// LDS rows are 128 bytes, piece p of row r at slot p ^ ((r >> 1) & 7) (applied
+// by choosing which global piece a lane fetches): conflict-free fragment reads.
+// Needs Kd divisible by 64.
+// ---------------------------------------------------------------------------
+constexpr int P_PART = 256 * 64;                       // bf16 elements per part
+// vmcnt and lgkmcnt in one s_waitcnt
+#define BM_WAIT_VM_LGKM(vm, lgkm) \
+    __builtin_amdgcn_s_waitcnt(((vm) & 15) | (7 << 4) | ((lgkm) << 8) | (((vm) >> 4) << 14))
+
+template <bool DUAL>
+__global__ void __launch_bounds__(256) grouped_gemm256_k64_bf16_kernel(GemmParams p) {
+    __shared__ __attribute__((aligned(1024))) uint16_t smem[5 * P_PART];         // 160 KB: the whole LDS
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm = wave >> 1, wn = wave & 1;
+    const int r32 = lane & 31, half = lane >> 5;
+
+    const int n_mt = p.n_mtiles[0];
+    const int n_nt = DUAL ? (p.N + 127) / 128 : (p.N + 255) / 256;
+    const int total = n_mt * n_nt;
+    const int per_xcd = (total + 7) >> 3;
+    const int lid = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
+    if ((int)(blockIdx.x >> 3) >= per_xcd || lid >= total) return;
+    int mt, nt;
+    tile_of(lid, n_mt, n_nt, mt, nt);
+
+    const int g = p.mt_group[mt];
+    const int row0 = p.mt_row0[mt];
+    const int row_end = p.offsets[g + 1];
+    const int n0 = nt * (DUAL ? 128 : 256);
+    const int N = p.N, Kd = p.Kd;
+
+    const uint16_t *a = static_cast<const uint16_t *>(p.a);
+    const uint16_t *b0, *b1;
+    if (g < p.E) {
+        b0 = static_cast<const uint16_t *>(p.b0) + (size_t)g * N * Kd;
+        b1 = DUAL ? static_cast<const uint16_t *>(p.b1) + (size_t)g * N * Kd : nullptr;
+    } else {
+        b0 = static_cast<const uint16_t *>(p.sb0) + (size_t)(g - p.E) * N * Kd;
+        b1 = DUAL ? static_cast<const uint16_t *>(p.sb1) + (size_t)(g - p.E) * N * Kd : nullptr;
+    }
+
+    // Load instruction j of this wave fills the 1 KB block (4*j + wave) of a part: 8 tile rows of 128
+    // bytes.  Lane i supplies row 8*block + i/8 and LDS slot i%8 of it, i.e. global piece
+    // (i % 8) ^ ((row >> 1) & 7).
+    const uint16_t *pa[8], *pb[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+        const int r = 8 * (4 * j + wave) + (lane >> 3);          // row inside the 256-row part
+        const int piece = (lane & 7) ^ ((r >> 1) & 7);
+        const int pos = min(row0 + r, row_end - 1);
+        const int src = p.row_map ? p.row_map[pos] : pos;
+        pa[j] = a + (size_t)src * Kd + piece * 8;
+        if (DUAL) {
+            const int f = min(n0 + (r & 127), N - 1);
+            pb[j] = ((r >> 7) ? b1 : b0) + (size_t)f * Kd + piece * 8;
+        } else {
+            const int n = min(n0 + r, N - 1);
+            pb[j] = b0 + (size_t)n * Kd + piece * 8;
+        }
+    }
+
+    // fragment offsets inside a part, per 16-wide k slice s: row (.. + r32), piece 2*s + half
+    int fa_off[4], fb_off[4];
+#pragma unroll
+    for (int s = 0; s < 4; ++s) {
+        const int pc = ((2 * s + half) ^ ((r32 >> 1) & 7)) << 3;
+        fa_off[s] = (wm * 128 + r32) * 64 + pc;
+        fb_off[s] = (DUAL ? (wn * 64 + r32) : (wn * 128 + r32)) * 64 + pc;
+    }
+
+    f32x16 acc[4][4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
+
+    const int KT = Kd / 64;
+    bf16x8 f0a[4], f0b[4], f1a[4], f1b[4];
+
+// load j_ of part (ptrs_) of k-step tile_ into slot_
+#define BM_DMA1(ptrs_, slot_, tile_, j_)                                                           \
+    __builtin_amdgcn_global_load_lds(                                                              \
+        (const BM_GLOBAL void *)(ptrs_[j_] + min((tile_), KT - 1) * 64),                           \
+        (BM_LDS void *)(smem + (slot_) * P_PART + wave * 512 + (j_) * 2048), 16, 0, 0)
+#define BM_LD(ptr_) as_bf16x8(*reinterpret_cast<const u32x4 *>(ptr_))
+#define BM_BOFF(i_) (DUAL ? (((i_) >> 1) * 8192 + ((i_) & 1) * 2048) : (i_) * 2048)
+// fragment read d_ of 8, in the order the MFMAs need them: a0 b0 b1 b2 b3 a1 a2 a3
+#define BM_RD(d_, fa_, fb_, sa_, sb_)                                                              \
+    {                                                                                              \
+        if ((d_) == 0) fa_[0] = BM_LD(sa_);                                                        \
+        else if ((d_) <= 4) fb_[(d_) - 1] = BM_LD((sb_) + BM_BOFF((d_) - 1));                      \
+        else fa_[(d_) - 4] = BM_LD((sa_) + ((d_) - 4) * 2048);                                     \
+    }
+#define BM_MFMA1(m_, fa_, fb_)                                                                     \
+    acc[(m_) >> 2][(m_) & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa_[(m_) >> 2], fb_[(m_) & 3], \
+                                                                        acc[(m_) >> 2][(m_) & 3], 0, 0, 0)
+// one 16-wide k slice: 16 MFMAs on (fa_, fb_); under MFMAs 0-7 the fragments of the next slice are read
+// into (na_, nb_); under MFMAs 9, 12, 15 up to three loads j0_.. of B(kt+2) are issued.  The
+// scheduling fences keep this interleaving as written.
+#define BM_SLICE(fa_, fb_, na_, nb_, s_next, j0_, nj_)                                             \
+    {                                                                                              \
+        const uint16_t *sa_ = smem + sA * P_PART + fa_off[s_next];                                 \
+        const uint16_t *sb_ = smem + sB * P_PART + fb_off[s_next];                                 \
+        _Pragma("unroll") for (int m = 0; m < 16; ++m) {                                           \
+            BM_MFMA1(m, fa_, fb_);                                                                 \
+            if (m < 8) BM_RD(m, na_, nb_, sa_, sb_)                                                \
+            else if (m == 9 && (nj_) > 0) BM_DMA1(pb, sAp, kt + 2, (j0_));                         \
+            else if (m == 12 && (nj_) > 1) BM_DMA1(pb, sAp, kt + 2, (j0_) + 1);                    \
+            else if (m == 15 && (nj_) > 2) BM_DMA1(pb, sAp, kt + 2, ((j0_) + 2) & 7);                  \
+            __builtin_amdgcn_sched_barrier(0);                                                     \
+        }                                                                                          \
+    }
+
+    // prologue: B(0) A(0) B(1) A(1) in flight, B(0) and A(0) landed, first fragments read
+#pragma unroll
+    for (int j = 0; j < 8; ++j) BM_DMA1(pb, 0, 0, j);
+#pragma unroll
+    for (int j = 0; j < 8; ++j) BM_DMA1(pa, 1, 0, j);
+#pragma unroll
+    for (int j = 0; j < 8; ++j) BM_DMA1(pb, 2, 1, j);
+#pragma unroll
+    for (int j = 0; j < 8; ++j) BM_DMA1(pa, 3, 1, j);
+    BM_WAIT_VMCNT(16);
+    BM_BARE_BARRIER();
+    {
+        const uint16_t *sa_ = smem + 1 * P_PART + fa_off[0];
+        const uint16_t *sb_ = smem + 0 * P_PART + fb_off[0];
+#pragma unroll
+        for (int d = 0; d < 8; ++d) BM_RD(d, f0a, f0b, sa_, sb_)
+    }
+
+    int sB = 0, sA = 1, sAp = 4;                       // slots of B(kt), A(kt), A(kt-1)
+    for (int kt = 0; kt < KT; ++kt) {
+        BM_SLICE(f0a, f0b, f1a, f1b, 1, 0, 3);         // B(kt+2) loads 0-2 go into the slot A(kt-1) has left
+        BM_SLICE(f1a, f1b, f0a, f0b, 2, 3, 3);
+        BM_SLICE(f0a, f0b, f1a, f1b, 3, 6, 2);
+        // every fragment of B(kt), A(kt) is in registers; A(kt+1), B(kt+1) have landed (this wave's part:
+        // at most the 8 loads of B(kt+2) are outstanding); after the barrier both hold for every wave
+        BM_WAIT_VM_LGKM(8, 0);
+        BM_BARE_BARRIER();
+        const int sBn = sB >= 3 ? sB - 3 : sB + 2, sAn = sA >= 3 ? sA - 3 : sA + 2;
+        {
+            // last slice: A(kt+2) goes into the slot B(kt) has left, one load under every other MFMA,
+            // the first fragments of k-step kt+1 are read under the others
+            const uint16_t *sa_ = smem + sAn * P_PART + fa_off[0];
+            const uint16_t *sb_ = smem + sBn * P_PART + fb_off[0];
+#pragma unroll
+            for (int m = 0; m < 16; ++m) {
+                BM_MFMA1(m, f1a, f1b);
+                if ((m & 1) == 0) BM_DMA1(pa, sB, kt + 2, m >> 1);
+                else BM_RD(m >> 1, f0a, f0b, sa_, sb_)
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        }
+        sAp = sA;
+        sB = sBn;
+        sA = sAn;
+    }
+    BM_WAIT_VMCNT(0);                                  // no load may land in LDS after this workgroup is gone
+#undef BM_DMA1
+#undef BM_LD
+#undef BM_BOFF
+#undef BM_RD
+#undef BM_MFMA1
+#undef BM_SLICE
+
+    uint16_t *c = static_cast<uint16_t *>(p.c);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            const int row = row0 + wm * 128 + i * 32 + 8 * (v >> 2) + 4 * half + (v & 3);
+            if (row >= row_end) continue;
+            if (DUAL) {
+#pragma unroll
+                for (int jj = 0; jj < 2; ++jj) {
+                    const int f = n0 + wn * 64 + jj * 32 + r32;
+                    if (f < N) stg16(&c[(size_t)row * N + f], f32_to_bf16(silu(acc[i][jj][v]) * acc[i][2 + jj][v]));
+                }
+            } else {
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const int n = n0 + wn * 128 + j * 32 + r32;
+                    if (n < N) stg16(&c[(size_t)row * N + n], f32_to_bf16(acc[i][j][v]));
+                }
+            }
+        }
+    }
+}
+
 static int grid_for(const GemmParams &p, bool dual) {
     const int n_nt = dual ? (p.N + 127) / 128 : (p.N + 255) / 256;
     const int total = p.max_mtiles * n_nt;
@@ -580,24 +786,20 @@ static int grid_for(const GemmParams &p, bool dual) {
 }
 
 int launch_gateup_bf16(const GemmParams &p, hipStream_t st) {
-    if (p.BM == 256)
-        hipLaunchKernelGGL((grouped_gemm256_dma_bf16_kernel<true>), dim3(grid_for(p, true)), dim3(256), 0, st, p);
-    else if (p.BM == 256 && p.Kd % 64 == 0)
-        hipLaunchKernelGGL((grouped_gemm256_bf16_kernel<true>), dim3(grid_for(p, true)), dim3(256), 0, st, p);
+    if (p.BM == 256 && p.Kd % 64 == 0)
+        hipLaunchKernelGGL((grouped_gemm256_k64_bf16_kernel<true>), dim3(grid_for(p, true)), dim3(256), 0, st, p);
     else if (p.BM == 256)
-        hipLaunchKernelGGL((grouped_gemm_bf16_kernel<true, 256>), dim3(grid_for(p, true)), dim3(256), 0, st, p);
+        hipLaunchKernelGGL((grouped_gemm256_dma_bf16_kernel<true>), dim3(grid_for(p, true)), dim3(256), 0, st, p);
     else
         hipLaunchKernelGGL((grouped_gemm_bf16_kernel<true, 128>), dim3(grid_for(p, true)), dim3(256), 0, st, p);
     return launch_status(__func__);
 }
 
 int launch_down_bf16(const GemmParams &p, hipStream_t st) {
-    if (p.BM == 256)
-        hipLaunchKernelGGL((grouped_gemm256_dma_bf16_kernel<false>), dim3(grid_for(p, false)), dim3(256), 0, st, p);
-    else if (p.BM == 256 && p.Kd % 64 == 0)
-        hipLaunchKernelGGL((grouped_gemm256_bf16_kernel<false>), dim3(grid_for(p, false)), dim3(256), 0, st, p);
+    if (p.BM == 256 && p.Kd % 64 == 0)
+        hipLaunchKernelGGL((grouped_gemm256_k64_bf16_kernel<false>), dim3(grid_for(p, false)), dim3(256), 0, st, p);
     else if (p.BM == 256)
-        hipLaunchKernelGGL((grouped_gemm_bf16_kernel<false, 256>), dim3(grid_for(p, false)), dim3(256), 0, st, p);
+        hipLaunchKernelGGL((grouped_gemm256_dma_bf16_kernel<false>), dim3(grid_for(p, false)), dim3(256), 0, st, p);
     else
         hipLaunchKernelGGL((grouped_gemm_bf16_kernel<false, 128>), dim3(grid_for(p, false)), dim3(256), 0, st, p);
     return launch_status(__func__);
