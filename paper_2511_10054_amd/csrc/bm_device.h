@@ -18,17 +18,15 @@ __device__ __forceinline__ float bf16_to_f32(uint16_t b) {
     return __builtin_bit_cast(float, (uint32_t)b << 16);
 }
 
-// round-to-nearest-even, NaN kept quiet
-__device__ __forceinline__ uint16_t f32_to_bf16(float f) {
-    uint32_t u = __builtin_bit_cast(uint32_t, f);
-    if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x40u);
-    u += 0x7fffu + ((u >> 16) & 1u);
-    return (uint16_t)(u >> 16);
+// fp32 -> bf16, round to nearest even (v_cvt_pk_bf16_f32: one instruction for two values, NaN stays NaN)
+typedef float bm_f32x2 __attribute__((ext_vector_type(2)));
+typedef __bf16 bm_bf16x2 __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
+    const bm_f32x2 v = {lo, hi};
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bm_bf16x2));
 }
 
-__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
-    return (uint32_t)f32_to_bf16(lo) | ((uint32_t)f32_to_bf16(hi) << 16);
-}
+__device__ __forceinline__ uint16_t f32_to_bf16(float f) { return (uint16_t)(pack_bf16x2(f, 0.0f) & 0xffffu); }
 
 __device__ __forceinline__ bf16x8 as_bf16x8(u32x4 v) { return __builtin_bit_cast(bf16x8, v); }
 
@@ -43,7 +41,9 @@ __device__ __forceinline__ void stg16(void *p, uint16_t v) { *(BM_GLOBAL uint16_
 __device__ __forceinline__ int ldg_i32(const void *p) { return *(const BM_GLOBAL int *)p; }
 __device__ __forceinline__ float ldg_f32(const void *p) { return *(const BM_GLOBAL float *)p; }
 
-__device__ __forceinline__ float silu(float a) { return a / (1.0f + __expf(-a)); }
+// x * sigmoid(x) with the hardware exponential and reciprocal (both within 1 ulp; the result is rounded
+// to bf16 or feeds an fp32 product)
+__device__ __forceinline__ float silu(float a) { return a * __builtin_amdgcn_rcpf(1.0f + __expf(-a)); }
 
 __device__ __forceinline__ int lane_id() { return (int)(threadIdx.x & (WAVE - 1)); }
 

@@ -603,50 +603,22 @@ __global__ void __launch_bounds__(256) grouped_gemm256_k64_bf16_kernel(GemmParam
     const int wm = wave >> 1, wn = wave & 1;
     const int r32 = lane & 31, half = lane >> 5;
 
+    // Persistent: workgroup b serves the XCD it was dealt to (b % 8) and walks that XCD's share of the
+    // logical tiles with stride (workgroups per XCD), so the workgroups that run together on an XCD work
+    // on consecutive logical tiles (see tile_of) and a workgroup keeps its compute unit: the next tile's
+    // first loads fly while the finished tile is written out, and nothing is relaunched.
     const int n_mt = p.n_mtiles[0];
     const int n_nt = DUAL ? (p.N + 127) / 128 : (p.N + 255) / 256;
     const int total = n_mt * n_nt;
     const int per_xcd = (total + 7) >> 3;
-    const int lid = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
-    if ((int)(blockIdx.x >> 3) >= per_xcd || lid >= total) return;
-    int mt, nt;
-    tile_of(lid, n_mt, n_nt, mt, nt);
+    const int xcd = blockIdx.x & 7, stride = gridDim.x >> 3;
+    int idx = blockIdx.x >> 3;
+    if (idx >= per_xcd || xcd * per_xcd + idx >= total) return;
 
-    const int g = p.mt_group[mt];
-    const int row0 = p.mt_row0[mt];
-    const int row_end = p.offsets[g + 1];
-    const int n0 = nt * (DUAL ? 128 : 256);
     const int N = p.N, Kd = p.Kd;
-
+    const int KT = Kd / 64;
     const uint16_t *a = static_cast<const uint16_t *>(p.a);
-    const uint16_t *b0, *b1;
-    if (g < p.E) {
-        b0 = static_cast<const uint16_t *>(p.b0) + (size_t)g * N * Kd;
-        b1 = DUAL ? static_cast<const uint16_t *>(p.b1) + (size_t)g * N * Kd : nullptr;
-    } else {
-        b0 = static_cast<const uint16_t *>(p.sb0) + (size_t)(g - p.E) * N * Kd;
-        b1 = DUAL ? static_cast<const uint16_t *>(p.sb1) + (size_t)(g - p.E) * N * Kd : nullptr;
-    }
-
-    // Load instruction j of this wave fills the 1 KB block (4*j + wave) of a part: 8 tile rows of 128
-    // bytes.  Lane i supplies row 8*block + i/8 and LDS slot i%8 of it, i.e. global piece
-    // (i % 8) ^ ((row >> 1) & 7).
-    const uint16_t *pa[8], *pb[8];
-#pragma unroll
-    for (int j = 0; j < 8; ++j) {
-        const int r = 8 * (4 * j + wave) + (lane >> 3);          // row inside the 256-row part
-        const int piece = (lane & 7) ^ ((r >> 1) & 7);
-        const int pos = min(row0 + r, row_end - 1);
-        const int src = p.row_map ? p.row_map[pos] : pos;
-        pa[j] = a + (size_t)src * Kd + piece * 8;
-        if (DUAL) {
-            const int f = min(n0 + (r & 127), N - 1);
-            pb[j] = ((r >> 7) ? b1 : b0) + (size_t)f * Kd + piece * 8;
-        } else {
-            const int n = min(n0 + r, N - 1);
-            pb[j] = b0 + (size_t)n * Kd + piece * 8;
-        }
-    }
+    uint16_t *c = static_cast<uint16_t *>(p.c);
 
     // fragment offsets inside a part, per 16-wide k slice s: row (.. + r32), piece 2*s + half
     int fa_off[4], fb_off[4];
@@ -658,21 +630,57 @@ __global__ void __launch_bounds__(256) grouped_gemm256_k64_bf16_kernel(GemmParam
     }
 
     f32x16 acc[4][4];
-#pragma unroll
-    for (int i = 0; i < 4; ++i)
-#pragma unroll
-        for (int j = 0; j < 4; ++j)
-#pragma unroll
-            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
-
-    const int KT = Kd / 64;
     bf16x8 f0a[4], f0b[4], f1a[4], f1b[4];
+    const uint16_t *pa[8], *pb[8];
+    int row0, row_end, n0;                             // of the tile whose loads are being issued
 
+// Pointers of logical tile lid_.  Load instruction j of this wave fills the 1 KB block (4*j + wave) of a
+// part: 8 tile rows of 128 bytes.  Lane i supplies row 8*block + i/8 and LDS slot i%8 of it, i.e.
+// global piece (i % 8) ^ ((row >> 1) & 7).
+#define BM_SETUP(lid_)                                                                             \
+    {                                                                                              \
+        int mt_, nt_;                                                                              \
+        tile_of((lid_), n_mt, n_nt, mt_, nt_);                                                     \
+        const int g_ = p.mt_group[mt_];                                                            \
+        row0 = p.mt_row0[mt_];                                                                     \
+        row_end = p.offsets[g_ + 1];                                                               \
+        n0 = nt_ * (DUAL ? 128 : 256);                                                             \
+        const uint16_t *b0_, *b1_;                                                                 \
+        if (g_ < p.E) {                                                                            \
+            b0_ = static_cast<const uint16_t *>(p.b0) + (size_t)g_ * N * Kd;                       \
+            b1_ = DUAL ? static_cast<const uint16_t *>(p.b1) + (size_t)g_ * N * Kd : nullptr;      \
+        } else {                                                                                   \
+            b0_ = static_cast<const uint16_t *>(p.sb0) + (size_t)(g_ - p.E) * N * Kd;              \
+            b1_ = DUAL ? static_cast<const uint16_t *>(p.sb1) + (size_t)(g_ - p.E) * N * Kd : nullptr; \
+        }                                                                                          \
+        _Pragma("unroll") for (int j = 0; j < 8; ++j) {                                            \
+            const int r_ = 8 * (4 * j + wave) + (lane >> 3);                                       \
+            const int piece_ = (lane & 7) ^ ((r_ >> 1) & 7);                                       \
+            const int pos_ = min(row0 + r_, row_end - 1);                                          \
+            const int src_ = p.row_map ? p.row_map[pos_] : pos_;                                   \
+            pa[j] = a + (size_t)src_ * Kd + piece_ * 8;                                            \
+            if (DUAL) {                                                                            \
+                const int f_ = min(n0 + (r_ & 127), N - 1);                                        \
+                pb[j] = ((r_ >> 7) ? b1_ : b0_) + (size_t)f_ * Kd + piece_ * 8;                    \
+            } else {                                                                               \
+                const int n_ = min(n0 + r_, N - 1);                                                \
+                pb[j] = b0_ + (size_t)n_ * Kd + piece_ * 8;                                        \
+            }                                                                                      \
+        }                                                                                          \
+    }
 // load j_ of part (ptrs_) of k-step tile_ into slot_
 #define BM_DMA1(ptrs_, slot_, tile_, j_)                                                           \
     __builtin_amdgcn_global_load_lds(                                                              \
         (const BM_GLOBAL void *)(ptrs_[j_] + min((tile_), KT - 1) * 64),                           \
         (BM_LDS void *)(smem + (slot_) * P_PART + wave * 512 + (j_) * 2048), 16, 0, 0)
+// B(0) A(0) B(1) A(1) of the tile set up last into slots 0..3
+#define BM_PROLOGUE()                                                                              \
+    {                                                                                              \
+        _Pragma("unroll") for (int j = 0; j < 8; ++j) BM_DMA1(pb, 0, 0, j);                        \
+        _Pragma("unroll") for (int j = 0; j < 8; ++j) BM_DMA1(pa, 1, 0, j);                        \
+        _Pragma("unroll") for (int j = 0; j < 8; ++j) BM_DMA1(pb, 2, 1, j);                        \
+        _Pragma("unroll") for (int j = 0; j < 8; ++j) BM_DMA1(pa, 3, 1, j);                        \
+    }
 #define BM_LD(ptr_) as_bf16x8(*reinterpret_cast<const u32x4 *>(ptr_))
 #define BM_BOFF(i_) (DUAL ? (((i_) >> 1) * 8192 + ((i_) & 1) * 2048) : (i_) * 2048)
 // fragment read d_ of 8, in the order the MFMAs need them: a0 b0 b1 b2 b3 a1 a2 a3
@@ -697,86 +705,138 @@ __global__ void __launch_bounds__(256) grouped_gemm256_k64_bf16_kernel(GemmParam
             if (m < 8) BM_RD(m, na_, nb_, sa_, sb_)                                                \
             else if (m == 9 && (nj_) > 0) BM_DMA1(pb, sAp, kt + 2, (j0_));                         \
             else if (m == 12 && (nj_) > 1) BM_DMA1(pb, sAp, kt + 2, (j0_) + 1);                    \
-            else if (m == 15 && (nj_) > 2) BM_DMA1(pb, sAp, kt + 2, ((j0_) + 2) & 7);                  \
+            else if (m == 15 && (nj_) > 2) BM_DMA1(pb, sAp, kt + 2, ((j0_) + 2) & 7);              \
             __builtin_amdgcn_sched_barrier(0);                                                     \
         }                                                                                          \
     }
 
-    // prologue: B(0) A(0) B(1) A(1) in flight, B(0) and A(0) landed, first fragments read
+    BM_SETUP(xcd * per_xcd + idx);
+    BM_PROLOGUE();
+    for (;;) {
+        const int t_row0 = row0, t_row_end = row_end, t_n0 = n0;    // the tile being multiplied
 #pragma unroll
-    for (int j = 0; j < 8; ++j) BM_DMA1(pb, 0, 0, j);
+        for (int i = 0; i < 4; ++i)
 #pragma unroll
-    for (int j = 0; j < 8; ++j) BM_DMA1(pa, 1, 0, j);
+            for (int j = 0; j < 4; ++j)
 #pragma unroll
-    for (int j = 0; j < 8; ++j) BM_DMA1(pb, 2, 1, j);
-#pragma unroll
-    for (int j = 0; j < 8; ++j) BM_DMA1(pa, 3, 1, j);
-    BM_WAIT_VMCNT(16);
-    BM_BARE_BARRIER();
-    {
-        const uint16_t *sa_ = smem + 1 * P_PART + fa_off[0];
-        const uint16_t *sb_ = smem + 0 * P_PART + fb_off[0];
-#pragma unroll
-        for (int d = 0; d < 8; ++d) BM_RD(d, f0a, f0b, sa_, sb_)
-    }
-
-    int sB = 0, sA = 1, sAp = 4;                       // slots of B(kt), A(kt), A(kt-1)
-    for (int kt = 0; kt < KT; ++kt) {
-        BM_SLICE(f0a, f0b, f1a, f1b, 1, 0, 3);         // B(kt+2) loads 0-2 go into the slot A(kt-1) has left
-        BM_SLICE(f1a, f1b, f0a, f0b, 2, 3, 3);
-        BM_SLICE(f0a, f0b, f1a, f1b, 3, 6, 2);
-        // every fragment of B(kt), A(kt) is in registers; A(kt+1), B(kt+1) have landed (this wave's part:
-        // at most the 8 loads of B(kt+2) are outstanding); after the barrier both hold for every wave
-        BM_WAIT_VM_LGKM(8, 0);
+                for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
+        // B(0) and A(0) have landed: vector memory operations complete in issue order, and whatever was
+        // issued after them (B(1), A(1), then the previous tile's stores), at most the 16 youngest are
+        // still out, which leaves B(0) and A(0) done however many store instructions there were
+        BM_WAIT_VMCNT(16);
         BM_BARE_BARRIER();
-        const int sBn = sB >= 3 ? sB - 3 : sB + 2, sAn = sA >= 3 ? sA - 3 : sA + 2;
         {
-            // last slice: A(kt+2) goes into the slot B(kt) has left, one load under every other MFMA,
-            // the first fragments of k-step kt+1 are read under the others
-            const uint16_t *sa_ = smem + sAn * P_PART + fa_off[0];
-            const uint16_t *sb_ = smem + sBn * P_PART + fb_off[0];
+            const uint16_t *sa_ = smem + 1 * P_PART + fa_off[0];
+            const uint16_t *sb_ = smem + 0 * P_PART + fb_off[0];
 #pragma unroll
-            for (int m = 0; m < 16; ++m) {
-                BM_MFMA1(m, f1a, f1b);
-                if ((m & 1) == 0) BM_DMA1(pa, sB, kt + 2, m >> 1);
-                else BM_RD(m >> 1, f0a, f0b, sa_, sb_)
-                __builtin_amdgcn_sched_barrier(0);
+            for (int d = 0; d < 8; ++d) BM_RD(d, f0a, f0b, sa_, sb_)
+        }
+
+        int sB = 0, sA = 1, sAp = 4;                   // slots of B(kt), A(kt), A(kt-1)
+        for (int kt = 0; kt < KT; ++kt) {
+            BM_SLICE(f0a, f0b, f1a, f1b, 1, 0, 3);     // B(kt+2) loads 0-2 go into the slot A(kt-1) has left
+            BM_SLICE(f1a, f1b, f0a, f0b, 2, 3, 3);
+            BM_SLICE(f0a, f0b, f1a, f1b, 3, 6, 2);
+            // every fragment of B(kt), A(kt) is in registers; A(kt+1), B(kt+1) have landed (this wave's
+            // part: at most the 8 loads of B(kt+2) are outstanding); after the barrier both hold for
+            // every wave
+            BM_WAIT_VM_LGKM(8, 0);
+            BM_BARE_BARRIER();
+            const int sBn = sB >= 3 ? sB - 3 : sB + 2, sAn = sA >= 3 ? sA - 3 : sA + 2;
+            {
+                // last slice: A(kt+2) goes into the slot B(kt) has left, one load under every other
+                // MFMA, the first fragments of k-step kt+1 are read under the others
+                const uint16_t *sa_ = smem + sAn * P_PART + fa_off[0];
+                const uint16_t *sb_ = smem + sBn * P_PART + fb_off[0];
+#pragma unroll
+                for (int m = 0; m < 16; ++m) {
+                    BM_MFMA1(m, f1a, f1b);
+                    if ((m & 1) == 0) BM_DMA1(pa, sB, kt + 2, m >> 1);
+                    else BM_RD(m >> 1, f0a, f0b, sa_, sb_)
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+            }
+            sAp = sA;
+            sB = sBn;
+            sA = sAn;
+        }
+        // The tile is done.  Loads past its last k-step (clamped repeats) may still be landing and other
+        // waves may still be reading fragments: drain both, then start the next tile's loads so that they
+        // fly while this tile is written out.
+        BM_WAIT_VM_LGKM(0, 0);
+        BM_BARE_BARRIER();
+        idx += stride;
+        const bool more = idx < per_xcd && xcd * per_xcd + idx < total;      // uniform over the workgroup
+        if (more) {
+            BM_SETUP(xcd * per_xcd + idx);
+            BM_PROLOGUE();
+        }
+
+        // Write-out through the free fifth slot (8 KB per wave): the accumulators hold one column per lane,
+        // so they are first laid out row-major in LDS as bf16 - neighbouring lanes swap one value so that
+        // every lane writes a packed pair - and read back as 16-byte pieces: one store instruction then
+        // writes whole 128-byte lines (8 x fewer instructions than 2-byte stores straight from the
+        // accumulators).  A wave uses only its own region and LDS operations of a wave stay in order.
+        {
+            constexpr int OC = DUAL ? 2 : 4;            // 32-column output blocks per wave
+            constexpr int CR = DUAL ? 32 : 16;          // rows per chunk
+            constexpr int SD = DUAL ? 32 : 80;          // LDS row stride in dwords (padded: conflict-free)
+            constexpr int PR = OC * 4;                  // 16-byte pieces per output row
+            uint32_t *stage = reinterpret_cast<uint32_t *>(smem + 4 * P_PART) + wave * 2048;
+            const bool odd = lane & 1;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+#pragma unroll
+                for (int ch = 0; ch < 32 / CR; ++ch) {
+#pragma unroll
+                    for (int j = 0; j < OC; ++j) {
+#pragma unroll
+                        for (int vv = 0; vv < CR / 2; vv += 2) {
+                            const int v = ch * (CR / 2) + vv;          // even; rows of v and v+1 are adjacent
+                            float x0, x1;
+                            if (DUAL) {
+                                x0 = silu(acc[i][j][v]) * acc[i][2 + j][v];
+                                x1 = silu(acc[i][j][v + 1]) * acc[i][2 + j][v + 1];
+                            } else {
+                                x0 = acc[i][j][v];
+                                x1 = acc[i][j][v + 1];
+                            }
+                            // even lane keeps row v and gets the right-hand neighbour's value of that row;
+                            // odd lane keeps row v+1 and gets the left-hand neighbour's
+                            const float send = odd ? x0 : x1;
+                            const float recv = __builtin_bit_cast(
+                                float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, send), 0xB1, 0xF, 0xF, true));
+                            const uint32_t pk = odd ? pack_bf16x2(recv, x1) : pack_bf16x2(x0, recv);
+                            const int lrow = 8 * ((v >> 2) - ch * (CR / 8)) + 4 * half + (v & 3) + (odd ? 1 : 0);
+                            stage[lrow * SD + j * 16 + (r32 >> 1)] = pk;
+                        }
+                    }
+#pragma unroll
+                    for (int t = 0; t < 4; ++t) {
+                        const int q = lane + 64 * t;
+                        const int lrow = q / PR, pc = q % PR;
+                        const u32x4 val = *reinterpret_cast<const u32x4 *>(stage + lrow * SD + pc * 4);
+                        const int row = t_row0 + wm * 128 + i * 32 + ch * CR + lrow;
+                        const int col = t_n0 + wn * (OC * 32) + pc * 8;
+#ifdef BM_EXP_FEWSTORES
+                        if (row < t_row_end && col < N && (val.x == 0x12345678u || i == 0)) stg128(&c[(size_t)row * N + col], val);
+#else
+                        if (row < t_row_end && col < N) stg128(&c[(size_t)row * N + col], val);
+#endif
+                    }
+                }
             }
         }
-        sAp = sA;
-        sB = sBn;
-        sA = sAn;
+        if (!more) break;
     }
-    BM_WAIT_VMCNT(0);                                  // no load may land in LDS after this workgroup is gone
+#undef BM_SETUP
+#undef BM_PROLOGUE
 #undef BM_DMA1
 #undef BM_LD
 #undef BM_BOFF
 #undef BM_RD
 #undef BM_MFMA1
 #undef BM_SLICE
-
-    uint16_t *c = static_cast<uint16_t *>(p.c);
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-#pragma unroll
-        for (int v = 0; v < 16; ++v) {
-            const int row = row0 + wm * 128 + i * 32 + 8 * (v >> 2) + 4 * half + (v & 3);
-            if (row >= row_end) continue;
-            if (DUAL) {
-#pragma unroll
-                for (int jj = 0; jj < 2; ++jj) {
-                    const int f = n0 + wn * 64 + jj * 32 + r32;
-                    if (f < N) stg16(&c[(size_t)row * N + f], f32_to_bf16(silu(acc[i][jj][v]) * acc[i][2 + jj][v]));
-                }
-            } else {
-#pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    const int n = n0 + wn * 128 + j * 32 + r32;
-                    if (n < N) stg16(&c[(size_t)row * N + n], f32_to_bf16(acc[i][j][v]));
-                }
-            }
-        }
-    }
 }
 
 static int grid_for(const GemmParams &p, bool dual) {
@@ -785,9 +845,16 @@ static int grid_for(const GemmParams &p, bool dual) {
     return ((total + 7) / 8) * 8;
 }
 
+// One workgroup per compute unit (a workgroup takes a whole unit's LDS), fewer when there are fewer tiles;
+// always a multiple of 8 so that every XCD gets the same number.
+static int persistent_grid(const GemmParams &p, bool dual) {
+    const int g = grid_for(p, dual);
+    return g < 256 ? g : 256;
+}
+
 int launch_gateup_bf16(const GemmParams &p, hipStream_t st) {
     if (p.BM == 256 && p.Kd % 64 == 0)
-        hipLaunchKernelGGL((grouped_gemm256_k64_bf16_kernel<true>), dim3(grid_for(p, true)), dim3(256), 0, st, p);
+        hipLaunchKernelGGL((grouped_gemm256_k64_bf16_kernel<true>), dim3(persistent_grid(p, true)), dim3(256), 0, st, p);
     else if (p.BM == 256)
         hipLaunchKernelGGL((grouped_gemm256_dma_bf16_kernel<true>), dim3(grid_for(p, true)), dim3(256), 0, st, p);
     else
@@ -797,7 +864,7 @@ int launch_gateup_bf16(const GemmParams &p, hipStream_t st) {
 
 int launch_down_bf16(const GemmParams &p, hipStream_t st) {
     if (p.BM == 256 && p.Kd % 64 == 0)
-        hipLaunchKernelGGL((grouped_gemm256_k64_bf16_kernel<false>), dim3(grid_for(p, false)), dim3(256), 0, st, p);
+        hipLaunchKernelGGL((grouped_gemm256_k64_bf16_kernel<false>), dim3(persistent_grid(p, false)), dim3(256), 0, st, p);
     else if (p.BM == 256)
         hipLaunchKernelGGL((grouped_gemm256_dma_bf16_kernel<false>), dim3(grid_for(p, false)), dim3(256), 0, st, p);
     else
