@@ -372,13 +372,13 @@ int bm_moe_forward(const bm_layer_desc *desc, const void *x, const bm_weights *w
 
     // 4. gate/up projection + SwiGLU, 5. down projection
     GemmParams gp{};
-    gp.a = x; gp.row_map = cp.row_token;
+    gp.a = x; gp.row_map = cp.row_token; gp.a_rows = T;
     gp.b0 = wt->w_gate; gp.b1 = wt->w_up; gp.sb0 = wt->ws_gate; gp.sb1 = wt->ws_up;
     gp.c = at<void>(ws, L.h);
     gp.N = desc->F; gp.Kd = desc->d; gp.E = E; gp.n_groups = G; gp.max_mtiles = L.mtiles_max; gp.BM = sp.BM;
     gp.mt_group = sp.mt_group; gp.mt_row0 = sp.mt_row0; gp.n_mtiles = sp.n_mtiles; gp.offsets = sp.offsets;
     GemmParams dp = gp;
-    dp.a = gp.c; dp.row_map = nullptr;
+    dp.a = gp.c; dp.row_map = nullptr; dp.a_rows = L.rows_max;
     dp.b0 = wt->w_down; dp.b1 = nullptr; dp.sb0 = wt->ws_down; dp.sb1 = nullptr;
     dp.c = at<void>(ws, L.o);
     dp.N = desc->d; dp.Kd = desc->F;

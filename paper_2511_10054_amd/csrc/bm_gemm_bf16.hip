@@ -599,7 +599,10 @@ constexpr int P_PART = 256 * 64;                       // bf16 elements per part
 template <bool DUAL>
 __global__ void __launch_bounds__(256) grouped_gemm256_k64_bf16_kernel(GemmParams p) {
     __shared__ __attribute__((aligned(1024))) uint16_t smem[5 * P_PART];         // 160 KB: the whole LDS
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    // the wave index as a scalar: everything derived from it (LDS targets of the loads, tile halves) then
+    // stays in scalar registers and costs no vector instructions in the main loop
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wm = wave >> 1, wn = wave & 1;
     const int r32 = lane & 31, half = lane >> 5;
 
@@ -631,7 +634,10 @@ __global__ void __launch_bounds__(256) grouped_gemm256_k64_bf16_kernel(GemmParam
 
     f32x16 acc[4][4];
     bf16x8 f0a[4], f0b[4], f1a[4], f1b[4];
-    const uint16_t *pa[8], *pb[8];
+    // Load addresses are (uniform base + k offset) + a 32-bit byte offset per lane, so that the k advance
+    // is scalar arithmetic and a load needs no vector address computation.
+    uint32_t oa[8], ob[8];
+    const uint16_t *base_b0, *base_b1;
     int row0, row_end, n0;                             // of the tile whose loads are being issued
 
 // Pointers of logical tile lid_.  Load instruction j of this wave fills the 1 KB block (4*j + wave) of a
@@ -645,41 +651,38 @@ __global__ void __launch_bounds__(256) grouped_gemm256_k64_bf16_kernel(GemmParam
         row0 = p.mt_row0[mt_];                                                                     \
         row_end = p.offsets[g_ + 1];                                                               \
         n0 = nt_ * (DUAL ? 128 : 256);                                                             \
-        const uint16_t *b0_, *b1_;                                                                 \
         if (g_ < p.E) {                                                                            \
-            b0_ = static_cast<const uint16_t *>(p.b0) + (size_t)g_ * N * Kd;                       \
-            b1_ = DUAL ? static_cast<const uint16_t *>(p.b1) + (size_t)g_ * N * Kd : nullptr;      \
+            base_b0 = static_cast<const uint16_t *>(p.b0) + (size_t)g_ * N * Kd;                   \
+            base_b1 = DUAL ? static_cast<const uint16_t *>(p.b1) + (size_t)g_ * N * Kd : base_b0;  \
         } else {                                                                                   \
-            b0_ = static_cast<const uint16_t *>(p.sb0) + (size_t)(g_ - p.E) * N * Kd;              \
-            b1_ = DUAL ? static_cast<const uint16_t *>(p.sb1) + (size_t)(g_ - p.E) * N * Kd : nullptr; \
+            base_b0 = static_cast<const uint16_t *>(p.sb0) + (size_t)(g_ - p.E) * N * Kd;          \
+            base_b1 = DUAL ? static_cast<const uint16_t *>(p.sb1) + (size_t)(g_ - p.E) * N * Kd : base_b0; \
         }                                                                                          \
         _Pragma("unroll") for (int j = 0; j < 8; ++j) {                                            \
             const int r_ = 8 * (4 * j + wave) + (lane >> 3);                                       \
             const int piece_ = (lane & 7) ^ ((r_ >> 1) & 7);                                       \
             const int pos_ = min(row0 + r_, row_end - 1);                                          \
             const int src_ = p.row_map ? p.row_map[pos_] : pos_;                                   \
-            pa[j] = a + (size_t)src_ * Kd + piece_ * 8;                                            \
-            if (DUAL) {                                                                            \
-                const int f_ = min(n0 + (r_ & 127), N - 1);                                        \
-                pb[j] = ((r_ >> 7) ? b1_ : b0_) + (size_t)f_ * Kd + piece_ * 8;                    \
-            } else {                                                                               \
-                const int n_ = min(n0 + r_, N - 1);                                                \
-                pb[j] = b0_ + (size_t)n_ * Kd + piece_ * 8;                                        \
-            }                                                                                      \
+            oa[j] = ((uint32_t)src_ * (uint32_t)Kd + piece_ * 8) * 2u;                             \
+            /* DUAL: rows 0-127 of the part are W_gate rows (loads 0-3), rows 128-255 W_up rows (4-7) */ \
+            const int n_ = DUAL ? min(n0 + (r_ & 127), N - 1) : min(n0 + r_, N - 1);               \
+            ob[j] = ((uint32_t)n_ * (uint32_t)Kd + piece_ * 8) * 2u;                               \
         }                                                                                          \
     }
-// load j_ of part (ptrs_) of k-step tile_ into slot_
-#define BM_DMA1(ptrs_, slot_, tile_, j_)                                                           \
+// load j_ of the activation part (A) / weight part (B) of k-step tile_ into slot_
+#define BM_DMA_AT(base_, off_, slot_, tile_, j_)                                                   \
     __builtin_amdgcn_global_load_lds(                                                              \
-        (const BM_GLOBAL void *)(ptrs_[j_] + min((tile_), KT - 1) * 64),                           \
+        (const BM_GLOBAL void *)(reinterpret_cast<const char *>((base_) + min((tile_), KT - 1) * 64) + (off_)), \
         (BM_LDS void *)(smem + (slot_) * P_PART + wave * 512 + (j_) * 2048), 16, 0, 0)
+#define BM_DMA_A(slot_, tile_, j_) BM_DMA_AT(a, oa[j_], slot_, tile_, j_)
+#define BM_DMA_B(slot_, tile_, j_) BM_DMA_AT(((j_) < 4 ? base_b0 : base_b1), ob[j_], slot_, tile_, j_)
 // B(0) A(0) B(1) A(1) of the tile set up last into slots 0..3
 #define BM_PROLOGUE()                                                                              \
     {                                                                                              \
-        _Pragma("unroll") for (int j = 0; j < 8; ++j) BM_DMA1(pb, 0, 0, j);                        \
-        _Pragma("unroll") for (int j = 0; j < 8; ++j) BM_DMA1(pa, 1, 0, j);                        \
-        _Pragma("unroll") for (int j = 0; j < 8; ++j) BM_DMA1(pb, 2, 1, j);                        \
-        _Pragma("unroll") for (int j = 0; j < 8; ++j) BM_DMA1(pa, 3, 1, j);                        \
+        _Pragma("unroll") for (int j = 0; j < 8; ++j) BM_DMA_B(0, 0, j);                           \
+        _Pragma("unroll") for (int j = 0; j < 8; ++j) BM_DMA_A(1, 0, j);                           \
+        _Pragma("unroll") for (int j = 0; j < 8; ++j) BM_DMA_B(2, 1, j);                           \
+        _Pragma("unroll") for (int j = 0; j < 8; ++j) BM_DMA_A(3, 1, j);                           \
     }
 #define BM_LD(ptr_) as_bf16x8(*reinterpret_cast<const u32x4 *>(ptr_))
 #define BM_BOFF(i_) (DUAL ? (((i_) >> 1) * 8192 + ((i_) & 1) * 2048) : (i_) * 2048)
@@ -703,9 +706,9 @@ __global__ void __launch_bounds__(256) grouped_gemm256_k64_bf16_kernel(GemmParam
         _Pragma("unroll") for (int m = 0; m < 16; ++m) {                                           \
             BM_MFMA1(m, fa_, fb_);                                                                 \
             if (m < 8) BM_RD(m, na_, nb_, sa_, sb_)                                                \
-            else if (m == 9 && (nj_) > 0) BM_DMA1(pb, sAp, kt + 2, (j0_));                         \
-            else if (m == 12 && (nj_) > 1) BM_DMA1(pb, sAp, kt + 2, (j0_) + 1);                    \
-            else if (m == 15 && (nj_) > 2) BM_DMA1(pb, sAp, kt + 2, ((j0_) + 2) & 7);              \
+            else if (m == 9 && (nj_) > 0) BM_DMA_B(sAp, kt + 2, (j0_));                          \
+            else if (m == 12 && (nj_) > 1) BM_DMA_B(sAp, kt + 2, (j0_) + 1);                     \
+            else if (m == 15 && (nj_) > 2) BM_DMA_B(sAp, kt + 2, ((j0_) + 2) & 7);               \
             __builtin_amdgcn_sched_barrier(0);                                                     \
         }                                                                                          \
     }
@@ -751,7 +754,7 @@ __global__ void __launch_bounds__(256) grouped_gemm256_k64_bf16_kernel(GemmParam
 #pragma unroll
                 for (int m = 0; m < 16; ++m) {
                     BM_MFMA1(m, f1a, f1b);
-                    if ((m & 1) == 0) BM_DMA1(pa, sB, kt + 2, m >> 1);
+                    if ((m & 1) == 0) BM_DMA_A(sB, kt + 2, m >> 1);
                     else BM_RD(m >> 1, f0a, f0b, sa_, sb_)
                     __builtin_amdgcn_sched_barrier(0);
                 }
@@ -831,7 +834,9 @@ __global__ void __launch_bounds__(256) grouped_gemm256_k64_bf16_kernel(GemmParam
     }
 #undef BM_SETUP
 #undef BM_PROLOGUE
-#undef BM_DMA1
+#undef BM_DMA_AT
+#undef BM_DMA_A
+#undef BM_DMA_B
 #undef BM_LD
 #undef BM_BOFF
 #undef BM_RD
@@ -852,8 +857,15 @@ static int persistent_grid(const GemmParams &p, bool dual) {
     return g < 256 ? g : 256;
 }
 
+// the k-step-64 kernel addresses rows by 32-bit byte offsets from a uniform base
+static bool k64_ok(const GemmParams &p) {
+    const unsigned long long lim = 1ull << 32;
+    return p.BM == 256 && p.Kd % 64 == 0 && (unsigned long long)p.a_rows * p.Kd * 2 < lim &&
+           (unsigned long long)p.N * p.Kd * 2 < lim;
+}
+
 int launch_gateup_bf16(const GemmParams &p, hipStream_t st) {
-    if (p.BM == 256 && p.Kd % 64 == 0)
+    if (k64_ok(p))
         hipLaunchKernelGGL((grouped_gemm256_k64_bf16_kernel<true>), dim3(persistent_grid(p, true)), dim3(256), 0, st, p);
     else if (p.BM == 256)
         hipLaunchKernelGGL((grouped_gemm256_dma_bf16_kernel<true>), dim3(grid_for(p, true)), dim3(256), 0, st, p);
@@ -863,7 +875,7 @@ int launch_gateup_bf16(const GemmParams &p, hipStream_t st) {
 }
 
 int launch_down_bf16(const GemmParams &p, hipStream_t st) {
-    if (p.BM == 256 && p.Kd % 64 == 0)
+    if (k64_ok(p))
         hipLaunchKernelGGL((grouped_gemm256_k64_bf16_kernel<false>), dim3(persistent_grid(p, false)), dim3(256), 0, st, p);
     else if (p.BM == 256)
         hipLaunchKernelGGL((grouped_gemm256_dma_bf16_kernel<false>), dim3(grid_for(p, false)), dim3(256), 0, st, p);

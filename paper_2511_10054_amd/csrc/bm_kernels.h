@@ -66,6 +66,7 @@ struct FrontParams {
 struct GemmParams {
     const void *a;                // activations: [T][Kd] gathered via row_map, or [rows][Kd]
     const int32_t *row_map;       // row -> row of a (null: identity)
+    long long a_rows;             // rows of a (bound for 32-bit byte offsets)
     const void *b0, *b1;          // routed weights ([E][N][Kd]); b1 = second matrix (up) or null
     const void *sb0, *sb1;        // shared-expert weights ([n_shared][N][Kd])
     void *c;                      // [rows][N]
