@@ -156,6 +156,30 @@ def buddy_remap_gated(ids, resident_mask, table, w=None, H: Optional[int] = None
     return out, w2, _stats_dict(stats)
 
 
+def coactivation(ids, E: int, A=None, M=None):
+    """Section 3.2 counts of one batch of routed ids, added to A [E] / M [E][E] (int64; created if None)."""
+    ids = np.ascontiguousarray(ids, dtype=np.int32)
+    T, K = ids.shape
+    A = np.zeros(E, np.int64) if A is None else A
+    M = np.zeros((E, E), np.int64) if M is None else M
+    assert A.dtype == np.int64 and M.dtype == np.int64 and M.flags.c_contiguous
+    assert lib().bm_oracle_coactivation(T, K, E, _p(ids, _I32), _p(A, _I64), _p(M, _I64)) == 0
+    return A, M
+
+
+def build_buddy_lists(M, alpha: float, k_max: int):
+    """Eq. 4-6: (table [E][k_max] padded with -1, lengths [E], q of each entry [E][k_max])."""
+    M = np.ascontiguousarray(M, dtype=np.int64)
+    E = M.shape[0]
+    table = np.empty((E, k_max), np.int32)
+    length = np.empty(E, np.int32)
+    q = np.empty((E, k_max), np.float64)
+    f = lib().bm_oracle_build_buddy_lists
+    f.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_void_p, _D, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p]
+    assert f(E, k_max, M.ctypes.data, float(alpha), table.ctypes.data, length.ctypes.data, q.ctypes.data) == 0
+    return table, length, q
+
+
 def permute(ids, E: int):
     ids = np.ascontiguousarray(ids, dtype=np.int32)
     T, K = ids.shape

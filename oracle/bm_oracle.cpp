@@ -264,6 +264,77 @@ int bm_oracle_buddy_remap_gated(int T, int K, int E, int R, int H, int unique, i
     return 0;
 }
 
+// Section 3.2, "Empirical Evidence from Profiling": over the routed tokens,
+//   A[i]    = number of tokens with i in S(x)
+//   M[i][j] = number of tokens with i and j both in S(x), i != j (M[i][i] = 0)
+// The counts of this batch are ADDED to A [E] and M [E][E] (int64), so a corpus
+// can be fed batch by batch.  Ids outside [0,E) are ignored; an expert that a
+// token lists twice counts once for that token.
+int bm_oracle_coactivation(int T, int K, int E, const int32_t* ids, int64_t* A, int64_t* M) {
+    for (int t = 0; t < T; ++t) {
+        std::vector<char> in_s(E, 0);
+        for (int k = 0; k < K; ++k) {
+            int32_t e = ids[(size_t)t * K + k];
+            if (e >= 0 && e < E) in_s[e] = 1;
+        }
+        for (int i = 0; i < E; ++i) {
+            if (!in_s[i]) continue;
+            A[i] += 1;
+            for (int j = 0; j < E; ++j)
+                if (j != i && in_s[j]) M[(size_t)i * E + j] += 1;
+        }
+    }
+    return 0;
+}
+
+// Section 3.2 Eq. 4 and Section 3.3 Eq. 5-6: buddy lists from the co-activation
+// counts.  Per pivot i:
+//   q[j|i] = M[i][j] / sum_{j' != i} M[i][j'],  q[i|i] = 0           (Eq. 4)
+//   pi_i   = peers by descending q (equal q: lower expert index first)
+//   t_i    = min { t : sum_{r<=t} q[pi_i(r)|i] >= alpha }            (Eq. 5)
+//   B(i)   = { pi_i(1..t_i) }, cut to at most k_max entries          (Eq. 6)
+// A pivot with no co-activation at all (row sum 0) gets an empty list; any
+// other pivot gets at least one entry.  Peers with q = 0 are never listed.
+// table [E][k_max] is filled best first and padded with -1; len [E] (nullable)
+// receives the list lengths; q_out [E][k_max] (nullable) the q of each entry.
+// Not modelled (the paper calls them optional stabilisers): probability-
+// weighted counts, Laplace smoothing, warm-up down-weighting.
+int bm_oracle_build_buddy_lists(int E, int k_max, const int64_t* M, double alpha, int32_t* table,
+                                int32_t* len, double* q_out) {
+    for (int i = 0; i < E; ++i) {
+        double total = 0.0;
+        for (int j = 0; j < E; ++j) if (j != i) total += (double)M[(size_t)i * E + j];
+        std::vector<double> q(E, 0.0);
+        if (total > 0.0)
+            for (int j = 0; j < E; ++j) if (j != i) q[j] = (double)M[(size_t)i * E + j] / total;
+        std::vector<int> order;
+        for (int j = 0; j < E; ++j) if (j != i && q[j] > 0.0) order.push_back(j);
+        // insertion sort: descending q, equal q keep ascending index (stable)
+        for (size_t a = 1; a < order.size(); ++a) {
+            int x = order[a];
+            size_t b = a;
+            while (b > 0 && q[order[b - 1]] < q[x]) { order[b] = order[b - 1]; --b; }
+            order[b] = x;
+        }
+        // Eq. 5 with both sides multiplied by the row sum: the prefix sum of q is a ratio of counts, and
+        // "count >= alpha * total" has a single rounding (the device evaluates the same fp64 expression)
+        int t_i = 0;
+        int64_t cum = 0;
+        for (size_t r = 0; r < order.size(); ++r) {
+            cum += M[(size_t)i * E + order[r]];
+            t_i = (int)r + 1;
+            if ((double)cum >= alpha * total) break;
+        }
+        if (t_i > k_max) t_i = k_max;
+        for (int r = 0; r < k_max; ++r) {
+            table[(size_t)i * k_max + r] = r < t_i ? order[r] : -1;
+            if (q_out) q_out[(size_t)i * k_max + r] = r < t_i ? q[order[r]] : 0.0;
+        }
+        if (len) len[i] = t_i;
+    }
+    return 0;
+}
+
 // Grouping of the surviving assignments by expert (Section 2.2: each token's
 // selected experts run and their outputs are aggregated; the grouping itself
 // is the execution order of this build): a stable counting sort of the flat
