@@ -172,6 +172,33 @@ int bm_buddy_remap(const bm_layer_desc *desc, const uint64_t *residency_bitmap,
                    const int32_t *buddy_table, const int32_t *ids_in, int32_t *ids_out,
                    float *w, bm_remap_stats *stats, void *stream);
 
+/* Profiling statistics (Section 3.2, "Empirical Evidence from Profiling"): for
+ * the batch of routed ids [T][K] (device int32),
+ *   activations[i]      += number of tokens with i in S(x)
+ *   coactivations[i][j] += number of tokens with i and j both in S(x), i != j
+ * activations [E] and coactivations [E][E] are device int64 running totals that
+ * the caller zeroes before the first batch; the diagonal is never written.  Ids
+ * outside [0,E) are ignored and an expert listed twice by a token counts once.
+ * Exact (integer atomics); batches may be fed in any order.  Uses T, E, K. */
+int bm_coactivation_accumulate(const bm_layer_desc *desc, const int32_t *ids, int64_t *activations,
+                               int64_t *coactivations, void *stream);
+
+/* Buddy lists from the co-activation counts (Section 3.2 Eq. 4, Section 3.3
+ * Eq. 5-6).  Per pivot i: q[j|i] = coactivations[i][j] / (sum of row i without
+ * the diagonal); peers sorted by descending q, equal q to the lower index; the
+ * list is the shortest prefix whose q sums to at least alpha, at most R entries,
+ * at least one when the row sum is positive, none when it is zero; peers with
+ * q = 0 are never listed.  The threshold test is made on the counts,
+ * prefix count >= (double)alpha * (double)row sum, in fp64.
+ * buddy_table [E][R] int32 (device, written; best first, padded with -1) has the
+ * layout bm_buddy_remap and bm_moe_forward read.  list_len [E] int32 and
+ * q [E][R] fp32 (the q of each listed entry, 0 in the padding) are optional
+ * device outputs.  0 < alpha <= 1.  Uses E, R of desc.  Not modelled: the
+ * optional stabilisers of Section 3.3 (probability-weighted counts, Laplace
+ * smoothing, warm-up down-weighting). */
+int bm_build_buddy_table(const bm_layer_desc *desc, const int64_t *coactivations, float alpha,
+                         int32_t *buddy_table, int32_t *list_len, float *q, void *stream);
+
 /* Grouping of the surviving assignments by expert, the execution order of the
  * expert FFNs (Section 2.2: the selected experts run, their outputs are
  * aggregated): a stable counting sort of the flat indices a = t*K + k with

@@ -63,12 +63,14 @@ def load_library() -> ctypes.CDLL:
         lib.bm_pack_weights.argtypes = [ctypes.POINTER(LayerDesc), ctypes.POINTER(Weights), vp, vp]
         lib.bm_pack_weights.restype = i32
         lib.bm_route_topk.argtypes = [ctypes.POINTER(LayerDesc), vp, vp, vp, vp, vp, vp]
+        lib.bm_coactivation_accumulate.argtypes = [ctypes.POINTER(LayerDesc), vp, vp, vp, vp]
+        lib.bm_build_buddy_table.argtypes = [ctypes.POINTER(LayerDesc), vp, ctypes.c_float, vp, vp, vp, vp]
         lib.bm_buddy_remap.argtypes = [ctypes.POINTER(LayerDesc), vp, vp, vp, vp, vp, vp, vp]
         lib.bm_permute_by_expert.argtypes = [ctypes.POINTER(LayerDesc), vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
         lib.bm_moe_forward.argtypes = [ctypes.POINTER(LayerDesc), vp, ctypes.POINTER(Weights), vp, vp, vp, vp,
                                        ctypes.c_size_t, ctypes.POINTER(DebugOut), vp]
         for f in (lib.bm_validate_tables, lib.bm_route_topk, lib.bm_buddy_remap, lib.bm_permute_by_expert,
-                  lib.bm_moe_forward):
+                  lib.bm_moe_forward, lib.bm_coactivation_accumulate, lib.bm_build_buddy_table):
             f.restype = i32
         _lib = lib
     return _lib
@@ -117,6 +119,21 @@ def bm_buddy_remap(desc: LayerDesc, bitmap, table, ids_in, ids_out, w=None, stat
     _check(load_library().bm_buddy_remap(ctypes.byref(desc), _ptr(bitmap), _ptr(table), _ptr(ids_in),
                                          _ptr(ids_out), _ptr(w), _ptr(stats),
                                          _stream() if stream is None else stream), "bm_buddy_remap")
+
+
+def bm_coactivation_accumulate(desc: LayerDesc, ids, activations, coactivations, stream: Optional[int] = None):
+    """Adds the batch's counts to activations [E] / coactivations [E][E] (device int64)."""
+    _check(load_library().bm_coactivation_accumulate(ctypes.byref(desc), _ptr(ids), _ptr(activations),
+                                                     _ptr(coactivations),
+                                                     _stream() if stream is None else stream),
+           "bm_coactivation_accumulate")
+
+
+def bm_build_buddy_table(desc: LayerDesc, coactivations, alpha: float, table, list_len=None, q=None,
+                         stream: Optional[int] = None):
+    _check(load_library().bm_build_buddy_table(ctypes.byref(desc), _ptr(coactivations), ctypes.c_float(alpha),
+                                               _ptr(table), _ptr(list_len), _ptr(q),
+                                               _stream() if stream is None else stream), "bm_build_buddy_table")
 
 
 def bm_permute_by_expert(desc: LayerDesc, ids_remapped, offsets, perm, inv_perm, workspace,

@@ -9,7 +9,7 @@ from concurrent.futures import ThreadPoolExecutor
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libbuddymoe.so")
-SOURCES = ["bm_api.hip", "bm_front.hip", "bm_gemm_bf16.hip", "bm_skinny_bf16.hip", "bm_pack.hip", "bm_ffn_misc.hip"]
+SOURCES = ["bm_api.hip", "bm_front.hip", "bm_gemm_bf16.hip", "bm_skinny_bf16.hip", "bm_pack.hip", "bm_ffn_misc.hip", "bm_profile.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-fPIC", "-std=c++17", "-Wall", "-Wno-unused-function",

@@ -213,6 +213,30 @@ int bm_validate_tables(const bm_layer_desc *desc, const uint64_t *bitmap_host, c
     return BM_OK;
 }
 
+int bm_coactivation_accumulate(const bm_layer_desc *desc, const int32_t *ids, int64_t *activations,
+                               int64_t *coactivations, void *stream) {
+    if (!desc) return BM_ERR_NULL;
+    if (desc->T < 0 || desc->E <= 0 || desc->K <= 0 || desc->E > BM_MAX_E || desc->K > BM_MAX_K) return BM_ERR_SHAPE;
+    if (desc->T == 0) return BM_OK;
+    if (!ids || !activations || !coactivations) return BM_ERR_NULL;
+    (void)hipGetLastError();
+    return launch_coactivation(ids, desc->T, desc->K, desc->E, reinterpret_cast<long long *>(activations),
+                               reinterpret_cast<long long *>(coactivations), static_cast<hipStream_t>(stream))
+               ? BM_ERR_HIP : BM_OK;
+}
+
+int bm_build_buddy_table(const bm_layer_desc *desc, const int64_t *coactivations, float alpha, int32_t *buddy_table,
+                         int32_t *list_len, float *q, void *stream) {
+    if (!desc) return BM_ERR_NULL;
+    if (desc->E <= 0 || desc->E > BM_MAX_E || desc->R <= 0 || desc->R > BM_MAX_R) return BM_ERR_SHAPE;
+    if (!(alpha > 0.0f && alpha <= 1.0f)) return BM_ERR_SHAPE;
+    if (!coactivations || !buddy_table) return BM_ERR_NULL;
+    (void)hipGetLastError();
+    return launch_buddy_build(reinterpret_cast<const long long *>(coactivations), desc->E, desc->R, alpha, buddy_table,
+                              list_len, q, static_cast<hipStream_t>(stream))
+               ? BM_ERR_HIP : BM_OK;
+}
+
 int bm_route_topk(const bm_layer_desc *desc, const void *x, const void *w_router, const float *bias,
                   int32_t *ids, float *w, void *stream) {
     int rc = check_desc(desc, false);

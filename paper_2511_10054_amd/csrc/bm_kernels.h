@@ -134,4 +134,9 @@ int launch_combine(const CombineParams &p, bool o_bf16, hipStream_t st);
 int launch_pack(const void *src0, const void *src1, void *dst, int n, int N, int Kd, const uint64_t *bitmap,
                 hipStream_t st);
 
+// profiling statistics and buddy lists (bm_profile.hip)
+int launch_coactivation(const int32_t *ids, int T, int K, int E, long long *A, long long *M, hipStream_t st);
+int launch_buddy_build(const long long *M, int E, int R, float alpha, int32_t *table, int32_t *list_len, float *q,
+                       hipStream_t st);
+
 }  // namespace bm

@@ -23,7 +23,8 @@ def test_library_exports_every_declared_symbol():
     header = open(os.path.join(ROOT, "include", "buddymoe.h")).read()
     names = set(re.findall(r"\b(bm_[a-z_]+)\s*\(", header))
     assert {"bm_route_topk", "bm_buddy_remap", "bm_permute_by_expert", "bm_moe_forward",
-            "bm_workspace_bytes", "bm_validate_tables", "bm_strerror"} <= names
+            "bm_workspace_bytes", "bm_validate_tables", "bm_strerror", "bm_coactivation_accumulate",
+            "bm_build_buddy_table"} <= names
     lib = bm.load_library()
     for n in names:
         assert hasattr(lib, n), n
@@ -120,6 +121,13 @@ def test_host_side_argument_errors_launch_nothing():
                               None, None) == -2
     assert lib.bm_buddy_remap(ctypes.byref(_desc(flags=bm.BM_GATE_MARGIN, margin_gamma=float("nan"))), one, one,
                               one, one, one, None, None) == -2
+    assert lib.bm_coactivation_accumulate(ctypes.byref(d), one, None, one, None) == -1
+    assert lib.bm_coactivation_accumulate(ctypes.byref(_desc(E=300)), one, one, one, None) == -2
+    lib.bm_build_buddy_table.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_float] + [ctypes.c_void_p] * 4
+    assert lib.bm_build_buddy_table(ctypes.byref(d), one, 0.0, one, None, None, None) == -2      # alpha in (0, 1]
+    assert lib.bm_build_buddy_table(ctypes.byref(d), one, 1.5, one, None, None, None) == -2
+    assert lib.bm_build_buddy_table(ctypes.byref(d), None, 0.5, one, None, None, None) == -1
+    assert lib.bm_build_buddy_table(ctypes.byref(_desc(R=0, H=0)), one, 0.5, one, None, None, None) == -2
     assert lib.bm_permute_by_expert(ctypes.byref(d), one, one, one, one, None, 1 << 20, None) == -4
     assert lib.bm_permute_by_expert(ctypes.byref(d), one, one, one, one, one, 16, None) == -4
     assert lib.bm_permute_by_expert(ctypes.byref(d), one, one, one, one, ctypes.c_void_p(264), 1 << 20, None) == -4
