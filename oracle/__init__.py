@@ -180,6 +180,41 @@ def build_buddy_lists(M, alpha: float, k_max: int):
     return table, length, q
 
 
+def softmax_all(z) -> np.ndarray:
+    z = np.ascontiguousarray(z, dtype=np.float64)
+    p = np.empty_like(z)
+    assert lib().bm_oracle_softmax(z.shape[0], z.shape[1], _p(z, _D), _p(p, _D)) == 0
+    return p
+
+
+def buddy_remap_psi(ids, resident_mask, table, q, zhat, eta: float, w=None, H: Optional[int] = None,
+                    unique: bool = False, tau=None, gamma=None, rho=None, beta=None):
+    """Eq. 3 (kappa = 0): the acceptable buddy of largest q * (1 + eta * zhat) instead of the first one.
+    Returns (ids_remapped, w_after_drops, stats dict, per-token decision margin)."""
+    ids = np.ascontiguousarray(ids, dtype=np.int32)
+    T, K = ids.shape
+    res = np.ascontiguousarray(np.asarray(resident_mask, dtype=bool).astype(np.uint8))
+    E = len(res)
+    table = np.ascontiguousarray(table, dtype=np.int32)
+    R = table.shape[1]
+    H = R if H is None else H
+    q = np.ascontiguousarray(q, dtype=np.float64)
+    zhat = np.ascontiguousarray(zhat, dtype=np.float64)
+    assert q.shape == (E, R) and zhat.shape == (T, E)
+    out = np.empty_like(ids)
+    w2 = None if w is None else np.array(w, dtype=np.float64, order="C", copy=True)
+    stats = np.zeros(6, dtype=np.int64)
+    margin = np.empty(T, dtype=np.float64)
+    f = lib().bm_oracle_buddy_remap_psi
+    f.argtypes = [ctypes.c_int] * 6 + _GATE_ARGS + [ctypes.c_int, _D] + [ctypes.c_void_p] * 9
+    rc = f(T, K, E, R, H, int(unique), *_gate_values(tau, gamma, rho, beta), 1, float(eta), q.ctypes.data,
+           zhat.ctypes.data, res.ctypes.data, table.ctypes.data, ids.ctypes.data, out.ctypes.data,
+           None if w2 is None else w2.ctypes.data, stats.ctypes.data, margin.ctypes.data)
+    if rc:
+        raise ValueError("bad arguments")
+    return out, w2, _stats_dict(stats), margin
+
+
 def permute(ids, E: int):
     ids = np.ascontiguousarray(ids, dtype=np.int32)
     T, K = ids.shape
@@ -219,7 +254,8 @@ def experts_combine(x, ids, w, w_gate, w_up, w_down, ws_gate=None, ws_up=None, w
 
 def moe_forward(x, w_router, bias, w_gate, w_up, w_down, resident_mask, table, K: int,
                 H: Optional[int] = None, renorm: bool = True, unique: bool = False,
-                ws_gate=None, ws_up=None, ws_down=None, tau=None, gamma=None, rho=None, beta=None):
+                ws_gate=None, ws_up=None, ws_down=None, tau=None, gamma=None, rho=None, beta=None,
+                eta=None, q=None):
     """Whole layer. Returns dict(y, ids, ids_remapped, w, stats).  tau / gamma / rho: the TAE gate,
     margin gate, replacement budget and distribution gate (beta) in front of Algorithm 1 (None = off)."""
     x, w_router, bias = _f32(x), _f32(w_router), _f32(bias)
@@ -237,6 +273,19 @@ def moe_forward(x, w_router, bias, w_gate, w_up, w_down, resident_mask, table, K
     ids2 = np.empty((T, K), dtype=np.int32)
     w = np.empty((T, K), dtype=np.float64)
     stats = np.zeros(6, dtype=np.int64)
+    if eta is not None:
+        # token-aware buddy priority (Eq. 3): q [E][R] of the table entries, zhat = softmax over all experts
+        q = np.ascontiguousarray(q, dtype=np.float64)
+        margin = np.empty(T, dtype=np.float64)
+        f = lib().bm_oracle_moe_forward_psi
+        f.argtypes = [ctypes.c_int] * 10 + _GATE_ARGS + [_D] + [ctypes.c_void_p] * 18
+        vp = lambda a: None if a is None else a.ctypes.data
+        rc = f(T, d, E, F, K, n_shared, R, H, int(renorm), int(unique), *_gate_values(tau, gamma, rho, beta),
+               float(eta), vp(q), vp(x), vp(w_router), vp(bias), vp(w_gate), vp(w_up), vp(w_down), vp(ws_gate),
+               vp(ws_up), vp(ws_down), vp(res), vp(table), vp(y), vp(ids), vp(ids2), vp(w), vp(stats), vp(margin))
+        if rc:
+            raise ValueError("bad shape")
+        return dict(y=y, ids=ids, ids_remapped=ids2, w=w, stats=_stats_dict(stats), margin=margin)
     if tau is None and gamma is None and rho is None and beta is None:
         rc = lib().bm_oracle_moe_forward(T, d, E, F, K, n_shared, R, H, int(renorm), int(unique),
                                          _p(x, _F), _p(w_router, _F), _p(bias, _F),

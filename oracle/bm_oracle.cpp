@@ -196,11 +196,24 @@ double bm_oracle_distribution_delta(int T, int K, int E, const uint8_t* resident
 // required with use_tae / use_margin (read for the gates before any drop, then
 // updated).  stats[6] = {misses, substituted, dropped, |R(B)|, offloaded among
 // R(B), bypassed 0/1}; the last three are 0 without use_dist.
-int bm_oracle_buddy_remap_gated(int T, int K, int E, int R, int H, int unique, int use_tae, double tau,
-                                int use_margin, double gamma, int use_budget, int rho, int use_dist,
-                                double beta, const uint8_t* resident, const int32_t* table,
-                                const int32_t* ids_in, int32_t* ids_out, double* w, int64_t* stats) {
-    if (H > R || H < 0 || ((use_tae || use_margin) && !w)) return -1;
+//
+// Token-aware buddy priority (Section 3.1, Eq. 3, with kappa = 0): with use_psi the
+// substitute is not the first acceptable entry of the row but the acceptable entry
+// (same acceptance test, same first H entries) of largest
+//   Psi(j|i,x) = q[j|i] * (1 + eta * zhat_j(x)),
+// equal Psi going to the earlier entry.  q [E][R] holds q[j|i] of every table entry;
+// zhat [T][E] is the normalised router logit of every expert for every token
+// (reading: the softmax probability p_j(x) over all experts).  eta = 0 reproduces
+// the table order whenever the rows are sorted by q.  margin_out [T] (nullable):
+// per token the smallest relative gap (best - second) / best over its decisions
+// that had at least two acceptable entries (1e300 if none) - how close the token
+// came to a different choice.
+int bm_oracle_buddy_remap_psi(int T, int K, int E, int R, int H, int unique, int use_tae, double tau,
+                              int use_margin, double gamma, int use_budget, int rho, int use_dist,
+                              double beta, int use_psi, double eta, const double* q, const double* zhat,
+                              const uint8_t* resident, const int32_t* table, const int32_t* ids_in,
+                              int32_t* ids_out, double* w, int64_t* stats, double* margin_out) {
+    if (H > R || H < 0 || ((use_tae || use_margin) && !w) || (use_psi && (!q || !zhat))) return -1;
     int64_t n_miss = 0, n_sub = 0, n_drop = 0, dist[2] = {0, 0};
     bool bypass = false;
     if (use_dist) bypass = bm_oracle_distribution_delta(T, K, E, resident, ids_in, dist) >= beta && dist[0] > 0;
@@ -221,6 +234,7 @@ int bm_oracle_buddy_remap_gated(int T, int K, int E, int R, int H, int unique, i
             if (use_margin && (p1 - p2) >= gamma) allowed = false;
         }
         int replaced = 0;
+        double tok_margin = 1e300;
 
         std::vector<char> in_u(E, 0);
         for (int k = 0; k < K; ++k) {
@@ -239,10 +253,19 @@ int bm_oracle_buddy_remap_gated(int T, int K, int E, int R, int H, int unique, i
             ++n_miss;
             int32_t chosen = -1;
             if (allowed && !(use_budget && replaced >= rho)) {
+                double best = 0.0, second = -1.0;
                 for (int r = 0; r < H; ++r) {
                     int32_t b = table[(size_t)e * R + r];
                     if (b < 0 || b >= E) continue;
-                    if (resident[b] && !(unique && in_u[b])) { chosen = b; break; }
+                    if (!(resident[b] && !(unique && in_u[b]))) continue;
+                    if (!use_psi) { chosen = b; break; }
+                    const double psi = q[(size_t)e * R + r] * (1.0 + eta * zhat[(size_t)t * E + b]);
+                    if (chosen < 0 || psi > best) { second = chosen < 0 ? -1.0 : best; best = psi; chosen = b; }
+                    else if (psi > second) second = psi;
+                }
+                if (use_psi && chosen >= 0 && second >= 0.0 && best > 0.0) {
+                    const double m = (best - second) / best;
+                    if (m < tok_margin) tok_margin = m;
                 }
             }
             if (chosen >= 0) {
@@ -256,12 +279,22 @@ int bm_oracle_buddy_remap_gated(int T, int K, int E, int R, int H, int unique, i
                 ++n_drop;
             }
         }
+        if (margin_out) margin_out[t] = tok_margin;
     }
     if (stats) {
         stats[0] = n_miss; stats[1] = n_sub; stats[2] = n_drop;
         stats[3] = dist[0]; stats[4] = dist[1]; stats[5] = bypass ? 1 : 0;
     }
     return 0;
+}
+
+int bm_oracle_buddy_remap_gated(int T, int K, int E, int R, int H, int unique, int use_tae, double tau,
+                                int use_margin, double gamma, int use_budget, int rho, int use_dist,
+                                double beta, const uint8_t* resident, const int32_t* table,
+                                const int32_t* ids_in, int32_t* ids_out, double* w, int64_t* stats) {
+    return bm_oracle_buddy_remap_psi(T, K, E, R, H, unique, use_tae, tau, use_margin, gamma, use_budget, rho,
+                                     use_dist, beta, 0, 0.0, nullptr, nullptr, resident, table, ids_in, ids_out,
+                                     w, stats, nullptr);
 }
 
 // Section 3.2, "Empirical Evidence from Profiling": over the routed tokens,
@@ -459,6 +492,47 @@ int bm_oracle_moe_forward_gated(int T, int d, int E, int F, int K, int n_shared,
     if (rc) return rc;
     rc = bm_oracle_buddy_remap_gated(T, K, E, R, H, unique, use_tae, tau, use_margin, gamma, use_budget, rho,
                                      use_dist, beta, resident, table, ids.data(), ids2.data(), w.data(), stats);
+    if (rc) return rc;
+    rc = bm_oracle_experts_combine(T, d, E, F, K, n_shared, x, ids2.data(), w.data(), w_gate, w_up, w_down,
+                                   ws_gate, ws_up, ws_down, y);
+    if (rc) return rc;
+    if (ids_out) std::memcpy(ids_out, ids.data(), sizeof(int32_t) * ids.size());
+    if (ids_remapped_out) std::memcpy(ids_remapped_out, ids2.data(), sizeof(int32_t) * ids2.size());
+    if (w_out) std::memcpy(w_out, w.data(), sizeof(double) * w.size());
+    return 0;
+}
+
+// Softmax probabilities of all experts, p [T][E], from logits z [T][E] (Section 3, "Notation").
+int bm_oracle_softmax(int T, int E, const double* z, double* p) {
+    for (int t = 0; t < T; ++t) {
+        const double* zt = z + (size_t)t * E;
+        double zmax = zt[0], sum = 0.0;
+        for (int e = 1; e < E; ++e) if (zt[e] > zmax) zmax = zt[e];
+        for (int e = 0; e < E; ++e) sum += std::exp(zt[e] - zmax);
+        for (int e = 0; e < E; ++e) p[(size_t)t * E + e] = std::exp(zt[e] - zmax) / sum;
+    }
+    return 0;
+}
+
+// The whole layer with token-aware buddy priority (and optionally the gates); zhat = softmax(z).
+int bm_oracle_moe_forward_psi(int T, int d, int E, int F, int K, int n_shared, int R, int H, int renorm,
+                              int unique, int use_tae, double tau, int use_margin, double gamma,
+                              int use_budget, int rho, int use_dist, double beta, double eta, const double* q,
+                              const float* x, const float* w_router, const float* bias, const float* w_gate,
+                              const float* w_up, const float* w_down, const float* ws_gate, const float* ws_up,
+                              const float* ws_down, const uint8_t* resident, const int32_t* table, double* y,
+                              int32_t* ids_out, int32_t* ids_remapped_out, double* w_out, int64_t* stats,
+                              double* margin_out) {
+    std::vector<double> z((size_t)T * E), w((size_t)T * K), p((size_t)T * E);
+    std::vector<int32_t> ids((size_t)T * K), ids2((size_t)T * K);
+    int rc = bm_oracle_router_logits(T, d, E, x, w_router, bias, z.data());
+    if (rc) return rc;
+    rc = bm_oracle_topk_gates(T, E, K, renorm, z.data(), ids.data(), w.data());
+    if (rc) return rc;
+    bm_oracle_softmax(T, E, z.data(), p.data());
+    rc = bm_oracle_buddy_remap_psi(T, K, E, R, H, unique, use_tae, tau, use_margin, gamma, use_budget, rho,
+                                   use_dist, beta, 1, eta, q, p.data(), resident, table, ids.data(), ids2.data(),
+                                   w.data(), stats, margin_out);
     if (rc) return rc;
     rc = bm_oracle_experts_combine(T, d, E, F, K, n_shared, x, ids2.data(), w.data(), w_gate, w_up, w_down,
                                    ws_gate, ws_up, ws_down, y);
