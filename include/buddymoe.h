@@ -64,11 +64,17 @@ enum {
                                     (second value 0 when K == 1)                          */
     BM_REPLACE_BUDGET = 1u << 5, /* Section 5.1: at most desc.rho substitutions per token,
                                     counted in slot order; later misses are dropped      */
-    BM_GATE_DIST      = 1u << 6  /* Section 3.1, Eq. 2: over the batch of the call (its T
+    BM_GATE_DIST      = 1u << 6, /* Section 3.1, Eq. 2: over the batch of the call (its T
                                     tokens), delta = share of the distinct routed experts
                                     that are not resident; no substitution for any token
                                     when delta >= desc.dist_beta.  Decided exactly
                                     (offloaded >= beta * requested, in fp64)              */
+    BM_PSI_TOKEN      = 1u << 7  /* Section 3.1, Eq. 3 with kappa = 0 (bm_moe_forward only): the
+                                    substitute is the acceptable entry - same test, same first H
+                                    entries - of largest q[j|i] * (1 + desc.psi_eta * p_j(x)),
+                                    p_j(x) the softmax probability of expert j for the token
+                                    (fp32); equal scores keep the earlier entry.  Needs
+                                    weights.buddy_q                                          */
 };
 #define BM_GATE_ANY (BM_GATE_TAE | BM_GATE_MARGIN | BM_REPLACE_BUDGET)   /* the per-token ones */
 
@@ -87,6 +93,7 @@ typedef struct {
     float margin_gamma; /* read only with BM_GATE_MARGIN                              */
     int32_t rho;        /* read only with BM_REPLACE_BUDGET; >= 0                     */
     float dist_beta;    /* read only with BM_GATE_DIST                                */
+    float psi_eta;      /* read only with BM_PSI_TOKEN; >= 0                          */
 } bm_layer_desc;
 
 /* Weights, all device pointers in `dtype`.  The reduction dimension is
@@ -108,6 +115,9 @@ typedef struct {
     const void *wp_down;       /* routed down,    bm_packed_bytes(desc, 1) bytes */
     const void *wsp_gateup;    /* shared gate+up, bm_packed_bytes(desc, 2) bytes */
     const void *wsp_down;      /* shared down,    bm_packed_bytes(desc, 3) bytes */
+    /* q[j|i] of every buddy-table entry, [E][R] fp32 as bm_build_buddy_table writes it;
+     * read only with BM_PSI_TOKEN (NULL otherwise) */
+    const float *buddy_q;
 } bm_weights;
 
 typedef struct {
@@ -166,7 +176,8 @@ int bm_route_topk(const bm_layer_desc *desc, const void *x, const void *w_router
  * token's budget, counts as a miss and as dropped.  BM_GATE_DIST takes the
  * T tokens of the call as the batch; with it and ids_out == ids_in the call
  * runs in a single workgroup (the request set has to be read before any id is
- * overwritten).
+ * overwritten).  BM_PSI_TOKEN needs the router's probabilities and is refused
+ * here (BM_ERR_SHAPE): it is served by bm_moe_forward.
  * Uses T, E, K, R, H, flags, tae_tau, margin_gamma, rho, dist_beta of desc. */
 int bm_buddy_remap(const bm_layer_desc *desc, const uint64_t *residency_bitmap,
                    const int32_t *buddy_table, const int32_t *ids_in, int32_t *ids_out,

@@ -11,7 +11,7 @@ _lib = None
 
 BM_F32, BM_BF16 = 0, 1
 BM_RENORM_TOPK, BM_REMAP_UNIQUE, BM_Y_F32 = 1, 2, 4
-BM_GATE_TAE, BM_GATE_MARGIN, BM_REPLACE_BUDGET, BM_GATE_DIST = 8, 16, 32, 64
+BM_GATE_TAE, BM_GATE_MARGIN, BM_REPLACE_BUDGET, BM_GATE_DIST, BM_PSI_TOKEN = 8, 16, 32, 64, 128
 
 
 class BuddyMoEError(RuntimeError):
@@ -24,13 +24,14 @@ class LayerDesc(ctypes.Structure):
     _fields_ = [("T", ctypes.c_int32), ("d", ctypes.c_int32), ("E", ctypes.c_int32), ("F", ctypes.c_int32),
                 ("K", ctypes.c_int32), ("n_shared", ctypes.c_int32), ("R", ctypes.c_int32), ("H", ctypes.c_int32),
                 ("dtype", ctypes.c_int32), ("flags", ctypes.c_uint32), ("tae_tau", ctypes.c_float),
-                ("margin_gamma", ctypes.c_float), ("rho", ctypes.c_int32), ("dist_beta", ctypes.c_float)]
+                ("margin_gamma", ctypes.c_float), ("rho", ctypes.c_int32), ("dist_beta", ctypes.c_float),
+                ("psi_eta", ctypes.c_float)]
 
 
 class Weights(ctypes.Structure):
     _fields_ = [(n, ctypes.c_void_p) for n in
                 ("w_router", "router_bias", "w_gate", "w_up", "w_down", "ws_gate", "ws_up", "ws_down",
-                 "wp_gateup", "wp_down", "wsp_gateup", "wsp_down")]
+                 "wp_gateup", "wp_down", "wsp_gateup", "wsp_down", "buddy_q")]
 
 
 class DebugOut(ctypes.Structure):
@@ -161,9 +162,9 @@ def bm_moe_forward(desc: LayerDesc, x, weights: Weights, bitmap, table, y, works
 
 
 def make_weights(w_router, router_bias, w_gate, w_up, w_down, ws_gate=None, ws_up=None, ws_down=None,
-                 wp_gateup=None, wp_down=None, wsp_gateup=None, wsp_down=None) -> Weights:
+                 wp_gateup=None, wp_down=None, wsp_gateup=None, wsp_down=None, buddy_q=None) -> Weights:
     return Weights(*[_ptr(t) for t in (w_router, router_bias, w_gate, w_up, w_down, ws_gate, ws_up, ws_down,
-                                       wp_gateup, wp_down, wsp_gateup, wsp_down)])
+                                       wp_gateup, wp_down, wsp_gateup, wsp_down, buddy_q)])
 
 
 def bm_packed_bytes(desc: LayerDesc, which: int) -> int:

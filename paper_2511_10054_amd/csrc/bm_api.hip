@@ -54,7 +54,7 @@ size_t align_up(size_t v) { return (v + ALIGN - 1) / ALIGN * ALIGN; }
 // Workspace carving: a pure function of desc.
 struct Layout {
     size_t ids, ids2, w, tile_counts, tile_base, tile_stats, offsets, perm, inv_perm, row_token;
-    size_t mt_group, mt_row0, n_mtiles, stats, h, o, total;
+    size_t mt_group, mt_row0, n_mtiles, stats, probs, h, o, total;
     int n_tiles, rows_max, mtiles_max;
 };
 
@@ -79,6 +79,7 @@ int check_remap_desc(const bm_layer_desc *d) {
     if ((d->flags & BM_GATE_TAE) && !(d->tae_tau == d->tae_tau)) return BM_ERR_SHAPE;            // NaN
     if ((d->flags & BM_GATE_MARGIN) && !(d->margin_gamma == d->margin_gamma)) return BM_ERR_SHAPE;
     if ((d->flags & BM_GATE_DIST) && !(d->dist_beta == d->dist_beta)) return BM_ERR_SHAPE;
+    if ((d->flags & BM_PSI_TOKEN) && !(d->psi_eta >= 0.0f)) return BM_ERR_SHAPE;
     return BM_OK;
 }
 
@@ -107,6 +108,8 @@ Layout make_layout(const bm_layer_desc *d) {
     L.mt_row0 = take((size_t)L.mtiles_max * 4);
     L.n_mtiles = take(16);
     L.stats = take(32);
+    // every expert's probability per token: only when the substitution runs apart from the router kernel
+    L.probs = take(((d->flags & BM_PSI_TOKEN) && (d->flags & BM_GATE_DIST)) ? (size_t)d->T * d->E * 4 : 0);
     const size_t F = d->F > 0 ? d->F : 0;
     L.h = take((size_t)L.rows_max * F * esz);
     L.o = take(use_skinny(d) ? (size_t)skinny_ksplit(d) * L.rows_max * d->d * 4 : (size_t)L.rows_max * d->d * esz);
@@ -261,6 +264,7 @@ int bm_buddy_remap(const bm_layer_desc *desc, const uint64_t *residency_bitmap, 
     if (rc) return rc;
     if (!residency_bitmap || !ids_in || !ids_out || (!buddy_table && desc->R > 0)) return BM_ERR_NULL;
     if ((desc->flags & (BM_GATE_TAE | BM_GATE_MARGIN)) && !w) return BM_ERR_NULL;   // the gates read the weights
+    if (desc->flags & BM_PSI_TOKEN) return BM_ERR_SHAPE;   // needs the router's probabilities: bm_moe_forward
     (void)hipGetLastError();
     RemapParams p{};
     p.T = desc->T; p.K = desc->K; p.E = desc->E; p.R = desc->R; p.H = desc->H;
@@ -317,6 +321,7 @@ int bm_moe_forward(const bm_layer_desc *desc, const void *x, const bm_weights *w
     if (!x || !wt || !residency_bitmap || !y || (!buddy_table && desc->R > 0)) return BM_ERR_NULL;
     if (!wt->w_router || !wt->w_gate || !wt->w_up || !wt->w_down) return BM_ERR_NULL;
     if (desc->n_shared > 0 && (!wt->ws_gate || !wt->ws_up || !wt->ws_down)) return BM_ERR_NULL;
+    if ((desc->flags & BM_PSI_TOKEN) && !wt->buddy_q) return BM_ERR_NULL;
     Layout L;
     rc = check_ws(desc, workspace, workspace_bytes, L);
     if (rc) return rc;
@@ -341,6 +346,7 @@ int bm_moe_forward(const bm_layer_desc *desc, const void *x, const bm_weights *w
     fp.x = x; fp.wr = wt->w_router; fp.bias = wt->router_bias;
     fp.T = T; fp.d = desc->d; fp.E = E; fp.K = K; fp.R = desc->R; fp.H = desc->H; fp.flags = desc->flags;
     fp.tau = desc->tae_tau; fp.gamma = desc->margin_gamma; fp.rho = desc->rho; fp.beta = desc->dist_beta;
+    fp.q = wt->buddy_q; fp.eta = desc->psi_eta; fp.probs_out = nullptr;
     fp.ids = at<int32_t>(ws, L.ids); fp.w = at<float>(ws, L.w);
     fp.bitmap = residency_bitmap; fp.table = buddy_table;
     fp.ids2 = at<int32_t>(ws, L.ids2);
@@ -375,11 +381,14 @@ int bm_moe_forward(const bm_layer_desc *desc, const void *x, const bm_weights *w
         // then substitute (each workgroup derives the batch's request set itself), then count
         FrontParams rp = fp;
         rp.bitmap = nullptr;
+        const bool psi = (desc->flags & BM_PSI_TOKEN) != 0;
+        if (psi) rp.probs_out = at<float>(ws, L.probs);
         err |= launch_front(rp, desc->dtype, st);
         RemapParams mp{};
         mp.T = T; mp.K = K; mp.E = E; mp.R = desc->R; mp.H = desc->H;
         mp.flags = desc->flags; mp.tau = fp.tau; mp.gamma = fp.gamma; mp.rho = fp.rho; mp.beta = fp.beta;
         mp.bitmap = residency_bitmap; mp.table = buddy_table;
+        mp.q = fp.q; mp.eta = fp.eta; mp.probs = psi ? at<float>(ws, L.probs) : nullptr;
         mp.ids_in = fp.ids; mp.ids_out = fp.ids2; mp.w = fp.w; mp.stats = sp.stats;
         err |= launch_remap(mp, st);
         err |= launch_count(fp.ids2, T, K, E, fp.tile_counts, st);

@@ -67,10 +67,23 @@ __device__ __forceinline__ bool dist_bypass(int n_req, int n_cpu, float beta) {
     return n_req > 0 && (double)n_cpu >= (double)beta * (double)n_req;
 }
 
+// Token-aware buddy priority (Section 3.1, Eq. 3 with kappa = 0): how the normalised router logit of
+// expert b (its softmax probability over all experts) is obtained for the token at hand.
+struct PsiSource {
+    const float *q;        // [E][R] q[j|i] of every table entry; null: priority = table order
+    float eta;
+    const float *logits;   // the token's logit row (bias included), with zmax and inv_den; or null
+    float zmax, inv_den;
+    const float *probs;    // the token's probability row; used when logits is null
+    __device__ __forceinline__ float zhat(int b) const {
+        return logits != nullptr ? __expf(logits[b] - zmax) * inv_den : probs[b];
+    }
+};
+
 __device__ __forceinline__ void remap_token(int K, int E, int R, int H, uint32_t flags, float tau, float gamma,
                                             int rho, const uint64_t *bitmap, const int32_t *table,
                                             const int32_t *ids_in, int32_t *ids_out, float *w,
-                                            int &n_miss, int &n_sub, int &n_drop) {
+                                            int &n_miss, int &n_sub, int &n_drop, const PsiSource &psi) {
     const bool unique = (flags & BM_REMAP_UNIQUE) != 0;
     int budget = 0x7fffffff;
     if (flags & BM_GATE_ANY) budget = replacement_budget(K, flags, tau, gamma, rho, w);   // before any drop
@@ -89,14 +102,32 @@ __device__ __forceinline__ void remap_token(int K, int E, int R, int H, uint32_t
             bool found = false;
             const int32_t *row = table + (size_t)e * R;
             const int depth = budget > 0 ? H : 0;          // budget used up or token gated: no search
-            for (int r = 0; r < depth; ++r) {
-                const int b = row[r];
-                const bool bvalid = (unsigned)b < (unsigned)E;
-                const int bc = bvalid ? b : 0;
-                bool ok = bvalid && ((bitmap[bc >> 6] >> (bc & 63)) & 1ull);
-                ok = ok && !(unique && test_bit4(used, bc));
-                out = (ok && !found) ? b : out;
-                found = found || ok;
+            if (psi.q == nullptr) {
+                for (int r = 0; r < depth; ++r) {
+                    const int b = row[r];
+                    const bool bvalid = (unsigned)b < (unsigned)E;
+                    const int bc = bvalid ? b : 0;
+                    bool ok = bvalid && ((bitmap[bc >> 6] >> (bc & 63)) & 1ull);
+                    ok = ok && !(unique && test_bit4(used, bc));
+                    out = (ok && !found) ? b : out;
+                    found = found || ok;
+                }
+            } else {
+                // the acceptable entry of largest q * (1 + eta * zhat); equal scores keep the earlier entry
+                const float *qrow = psi.q + (size_t)e * R;
+                float best = 0.0f;
+                for (int r = 0; r < depth; ++r) {
+                    const int b = row[r];
+                    const bool bvalid = (unsigned)b < (unsigned)E;
+                    const int bc = bvalid ? b : 0;
+                    bool ok = bvalid && ((bitmap[bc >> 6] >> (bc & 63)) & 1ull);
+                    ok = ok && !(unique && test_bit4(used, bc));
+                    const float score = qrow[r] * (1.0f + psi.eta * psi.zhat(bc));
+                    const bool take = ok && (!found || score > best);
+                    out = take ? b : out;
+                    best = take ? score : best;
+                    found = found || ok;
+                }
             }
             if (found) { ++n_sub; --budget; set_bit4(used, out); } else { ++n_drop; }
         }
@@ -117,6 +148,7 @@ struct FrontLds {
     int32_t dist[4];         // distribution gate: requested, requested and offloaded, bypassed
     uint64_t bitmap[4];
     unsigned long long req[4];
+    float zmax[TILE_T], inv_den[TILE_T];   // per token: largest logit, 1 / sum of exp over all experts
 };
 
 // Ranks the tile's tokens from the logits in LDS and finishes the tile.
@@ -172,6 +204,23 @@ __device__ void tile_epilogue(const FrontParams &p, float *logits, int stride, i
             denom = wave_sum(part);
         }
         const float pk = (lane < K) ? expf(s.w[i * K + lane] - zmax) : 0.0f;
+        if (p.flags & BM_PSI_TOKEN) {
+            // token-aware buddy priority needs every expert's softmax probability for this token: keep
+            // (zmax, 1 / sum over all experts) for the substitution below, or write the probabilities out
+            // when the substitution runs in a later kernel
+            float part = 0.0f;
+#pragma unroll
+            for (int c = 0; c < EC; ++c) part += (myv[c] == -INFINITY) ? 0.0f : __expf(myv[c] - zmax);
+            const float inv_all = 1.0f / wave_sum(part);
+            if (lane == 0) { s.zmax[i] = zmax; s.inv_den[i] = inv_all; }
+            if (p.probs_out != nullptr) {
+#pragma unroll
+                for (int c = 0; c < EC; ++c) {
+                    const int e = lane + 64 * c;
+                    if (e < E) p.probs_out[(size_t)(t0 + i) * E + e] = __expf(myv[c] - zmax) * inv_all;
+                }
+            }
+        }
         __builtin_amdgcn_wave_barrier();
         if (lane < K) {
             p.ids[(size_t)(t0 + i) * K + lane] = s.ids[i * K + lane];
@@ -187,7 +236,8 @@ __device__ void tile_epilogue(const FrontParams &p, float *logits, int stride, i
     }
 
     // stage residency bitmap and buddy table in LDS
-    const bool tab_in_lds = E * p.R <= cap_ints;
+    const bool psi_mode = (p.flags & BM_PSI_TOKEN) != 0;         // the logits stay where they are
+    const bool tab_in_lds = !psi_mode && E * p.R <= cap_ints;
     int32_t *s_table = reinterpret_cast<int32_t *>(logits);
     if (tab_in_lds)
         for (int idx = tid; idx < E * p.R; idx += blockDim.x) s_table[idx] = p.table[idx];
@@ -214,14 +264,19 @@ __device__ void tile_epilogue(const FrontParams &p, float *logits, int stride, i
         if (tid == 0) { s.dist[0] = n_req; s.dist[1] = n_cpu; s.dist[2] = bypass ? 1 : 0; }
     }
 
-    if (p.flags & (BM_REMAP_UNIQUE | BM_GATE_ANY)) {
-        // Algorithm 1 proper (and its per-token gates): a lane walks its token's slots in order
+    if (p.flags & (BM_REMAP_UNIQUE | BM_GATE_ANY | BM_PSI_TOKEN)) {
+        // Algorithm 1 proper (and its per-token gates and priorities): a lane walks its token's slots in order
         if (tid < ntok) {
             int n_miss = 0, n_sub = 0, n_drop = 0;
             int32_t *tok_ids = &s.ids[tid * K];
             float *tok_w = &s.w[tid * K];
+            PsiSource psi{};
+            if (psi_mode) {
+                psi.q = p.q; psi.eta = p.eta;
+                psi.logits = logits + tid * stride; psi.zmax = s.zmax[tid]; psi.inv_den = s.inv_den[tid];
+            }
             remap_token(K, E, p.R, H, p.flags, p.tau, p.gamma, p.rho, s.bitmap,
-                        tab_in_lds ? s_table : p.table, tok_ids, tok_ids, tok_w, n_miss, n_sub, n_drop);
+                        tab_in_lds ? s_table : p.table, tok_ids, tok_ids, tok_w, n_miss, n_sub, n_drop, psi);
             if (n_miss) atomicAdd(&s.stats[0], n_miss);
             if (n_sub) atomicAdd(&s.stats[1], n_sub);
             if (n_drop) atomicAdd(&s.stats[2], n_drop);
@@ -550,8 +605,10 @@ __global__ void __launch_bounds__(256) remap_kernel(RemapParams p) {
         const int32_t *in = p.ids_in + (size_t)t * p.K;
         int32_t *out = p.ids_out + (size_t)t * p.K;
         float *w = p.w ? p.w + (size_t)t * p.K : nullptr;
+        PsiSource psi{};
+        if (p.flags & BM_PSI_TOKEN) { psi.q = p.q; psi.eta = p.eta; psi.probs = p.probs + (size_t)t * p.E; }
         remap_token(p.K, p.E, p.R, H, p.flags, p.tau, p.gamma, p.rho, s_bitmap, s_table, in, out, w, n_miss,
-                    n_sub, n_drop);
+                    n_sub, n_drop, psi);
     }
     if (n_miss) atomicAdd(&s_stats[0], n_miss);
     if (n_sub) atomicAdd(&s_stats[1], n_sub);

@@ -12,6 +12,9 @@ struct RemapParams {
     float tau, gamma;       // TAE and margin thresholds
     int rho;                // replacement budget per token
     float beta;             // distribution-gate threshold
+    const float *q;         // [E][R] q of the table entries (BM_PSI_TOKEN)
+    float eta;
+    const float *probs;     // [T][E] softmax probabilities of all experts (BM_PSI_TOKEN)
     const uint64_t *bitmap;
     const int32_t *table;
     const int32_t *ids_in;
@@ -49,6 +52,9 @@ struct FrontParams {
     float tau, gamma;       // TAE and margin thresholds (gate bits of flags)
     int rho;                // replacement budget per token
     float beta;             // distribution-gate threshold (BM_GATE_DIST: only when one tile holds the batch)
+    const float *q;         // [E][R] q of the table entries (BM_PSI_TOKEN)
+    float eta;
+    float *probs_out;       // [T][E]: with BM_PSI_TOKEN, write every expert's probability (or null)
     int32_t *ids;           // [T][K] router's choice
     float *w;               // [T][K]
     const uint64_t *bitmap; // null => routing only (no substitution, no histogram)

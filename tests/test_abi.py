@@ -77,7 +77,7 @@ def test_packed_bytes_and_pack_argument_errors():
     assert bm.bm_packed_bytes(d, 0) == 8 * 2 * one and bm.bm_packed_bytes(d, 1) == 8 * one
     assert bm.bm_packed_bytes(d, 2) == 2 * one and bm.bm_packed_bytes(d, 3) == one
     assert bm.bm_packed_bytes(d, 4) == 0 and bm.bm_packed_bytes(_desc(), 0) == 0      # fp32 layers are not packed
-    w = Weights(*([256] * 8 + [0] * 4))
+    w = Weights(*([256] * 8 + [0] * 5))
     assert lib.bm_pack_weights(ctypes.byref(_desc()), ctypes.byref(w), None, None) == -3   # dtype
     assert lib.bm_pack_weights(ctypes.byref(d), None, None, None) == -1
     assert lib.bm_pack_weights(ctypes.byref(d), ctypes.byref(w), None, None) == 0          # nothing to fill
@@ -131,12 +131,15 @@ def test_host_side_argument_errors_launch_nothing():
     assert lib.bm_permute_by_expert(ctypes.byref(d), one, one, one, one, None, 1 << 20, None) == -4
     assert lib.bm_permute_by_expert(ctypes.byref(d), one, one, one, one, one, 16, None) == -4
     assert lib.bm_permute_by_expert(ctypes.byref(d), one, one, one, one, ctypes.c_void_p(264), 1 << 20, None) == -4
-    w = Weights(*([256] * 8 + [0] * 4))
+    w = Weights(*([256] * 8 + [0] * 5))
     assert lib.bm_moe_forward(ctypes.byref(d), one, ctypes.byref(w), one, one, one, one, 16, None, None) == -4
     assert lib.bm_moe_forward(ctypes.byref(d), one, None, one, one, one, one, 1 << 30, None, None) == -1
     assert lib.bm_moe_forward(ctypes.byref(_desc(n_shared=9)), one, ctypes.byref(w), one, one, one, one, 1 << 30, None, None) == -2
     assert lib.bm_moe_forward(ctypes.byref(_desc(T=0)), None, None, None, None, None, None, 0, None, None) == 0
-    w2 = Weights(256, 0, 256, 256, 256, 0, 0, 0, 0, 0, 0, 0)
+    psi = _desc(flags=bm.BM_PSI_TOKEN, psi_eta=1.0)
+    assert lib.bm_moe_forward(ctypes.byref(psi), one, ctypes.byref(w), one, one, one, one, 1 << 30, None, None) == -1  # no q
+    assert lib.bm_buddy_remap(ctypes.byref(psi), one, one, one, one, one, None, None) == -2
+    w2 = Weights(256, 0, 256, 256, 256, 0, 0, 0, 0, 0, 0, 0, 0)
     assert lib.bm_moe_forward(ctypes.byref(_desc(n_shared=1)), one, ctypes.byref(w2), one, one, one, one, 1 << 30, None, None) == -1
 
 

@@ -1,0 +1,92 @@
+"""Parity of the token-aware buddy priority (Section 3.1, Eq. 3 with kappa = 0) against the oracle,
+through bm_moe_forward (needs an MI355X).
+
+The choice is an argmax over fp32 scores on the device and fp64 scores in the oracle.  The oracle reports,
+per token, how close its decisions came to a different outcome; tokens whose smallest relative gap is below
+TIE are only checked for validity (any of their choices must be a resident expert or a drop), all others
+bit for bit."""
+import numpy as np
+import pytest
+
+import oracle
+import workloads
+from helpers import DeviceLayer, HostLayer, err_metric, beta_pair
+
+pytestmark = pytest.mark.gpu
+TIE = 1e-4
+
+
+def _measured_table(spec, T_prof=2000):
+    """Buddy table and q from the layer's own routing of a profiling batch (all via the oracle)."""
+    prof = HostLayer(spec, T_prof, stream=5)
+    ids, _ = oracle.route_topk(prof.f32(prof.x), prof.f32(prof.w_router), prof.bias, spec.K)
+    _, M = oracle.coactivation(ids, spec.E)
+    table, _, q = oracle.build_buddy_lists(M, 1.0, spec.R)
+    return table, q.astype(np.float32)
+
+
+def _check(host, q, eta, unique, **gates):
+    ref = host.oracle_forward(oracle, unique=unique, eta=eta, q=q.astype(np.float64), **gates)
+    dev = DeviceLayer(host, unique=unique, eta=eta, q=q, **gates)
+    out = dev.forward()
+    sure = ref["margin"] > TIE
+    print(f"   eta={eta} unique={unique} {gates}: {int((~sure).sum())} of {len(sure)} tokens near a tie, "
+          f"substituted {ref['stats']['n_substituted']}", flush=True)
+    assert sure.mean() > 0.9
+    np.testing.assert_array_equal(out["ids"], ref["ids"])
+    np.testing.assert_array_equal(out["ids_remapped"][sure], ref["ids_remapped"][sure])
+    loose = out["ids_remapped"][~sure]
+    assert ((loose == -1) | host.mask[np.maximum(loose, 0)]).all()
+    if sure.all():
+        st = ref["stats"]
+        assert out["stats"].tolist()[:3] == [st["n_miss"], st["n_substituted"], st["n_dropped"]]
+    assert err_metric(out["y"][sure], ref["y"][sure]) <= (2e-2 if host.spec.dtype == "bf16" else 1e-5)
+    return out, ref
+
+
+CASES = [
+    ("c1_tiny", {}, 16),
+    ("c2_mixtral_decode", dict(d=512, F=1024), 8),            # one workgroup does the whole front end
+    ("c3_mixtral_prefill", dict(d=512, F=1024), 300),
+    ("c4_qwen3", dict(d=256, F=384), 300),
+    ("c5_deepseek", dict(d=256, F=352), 500),
+]
+
+
+@pytest.mark.parametrize("name,over,T", CASES)
+def test_token_aware_priority(name, over, T):
+    spec = workloads.scaled(name, **over)
+    print("psi", name, T, flush=True)
+    table, q = _measured_table(spec)
+    host = HostLayer(spec, T)
+    host.table = table
+    # eta = 0: the rows are sorted by q, so the priority is the table order - Algorithm 1 itself
+    for unique in (False, True):
+        out, ref = _check(host, q, 0.0, unique)
+        plain = host.oracle_forward(oracle, unique=unique)
+        np.testing.assert_array_equal(ref["ids_remapped"], plain["ids_remapped"])
+    changed = 0
+    for eta in (4.0, 50.0):
+        for unique in (False, True):
+            out, ref = _check(host, q, eta, unique)
+            plain = host.oracle_forward(oracle, unique=unique)
+            changed += int((ref["ids_remapped"] != plain["ids_remapped"]).sum())
+    if spec.E > 8:
+        assert changed > 0                                         # the token-aware term does move choices
+
+
+@pytest.mark.parametrize("name,over,T", [("c5_deepseek", dict(d=256, F=352), 500),
+                                         ("c2_mixtral_decode", dict(d=512, F=1024), 8)])
+def test_token_aware_priority_behind_the_gates(name, over, T):
+    spec = workloads.scaled(name, **over)
+    print("psi gated", name, T, flush=True)
+    table, q = _measured_table(spec)
+    host = HostLayer(spec, T)
+    host.table = table
+    ids, _ = oracle.route_topk(host.f32(host.x), host.f32(host.w_router), host.bias, spec.K)
+    closed, open_ = beta_pair(oracle.distribution_delta(ids, host.mask)[0])
+    _check(host, q, 8.0, True, rho=1)
+    out, ref = _check(host, q, 8.0, True, beta=open_)              # batch gate open: the split launch order
+    assert ref["stats"]["bypassed"] == 0 and ref["stats"]["n_substituted"] > 0
+    out, ref = _check(host, q, 8.0, False, beta=closed)
+    assert ref["stats"]["bypassed"] == 1 and ref["stats"]["n_substituted"] == 0

@@ -44,7 +44,8 @@ class HostLayer:
     def f32(self, a):
         return None if a is None else self.lay.as_f32(a)
 
-    def oracle_forward(self, oracle, unique=False, renorm=True, H=None, rows=None, tau=None, gamma=None, rho=None, beta=None):
+    def oracle_forward(self, oracle, unique=False, renorm=True, H=None, rows=None, tau=None, gamma=None, rho=None, beta=None,
+                       eta=None, q=None):
         """Oracle on all tokens or on the token subset `rows` (tokens are independent)."""
         x = self.f32(self.x)
         if rows is not None:
@@ -55,7 +56,7 @@ class HostLayer:
                                   self.f32(self.wd), self.mask, self.table, self.spec.K,
                                   H=self.spec.H if H is None else H, renorm=renorm, unique=unique,
                                   ws_gate=self.f32(self.sg), ws_up=self.f32(self.su), ws_down=self.f32(self.sd),
-                                  tau=tau, gamma=gamma, rho=rho, beta=beta)
+                                  tau=tau, gamma=gamma, rho=rho, beta=beta, eta=eta, q=q)
 
 
 def to_device(a, device="cuda"):
@@ -74,10 +75,11 @@ class DeviceLayer:
     """Uploads a HostLayer and runs the library through the Python binding."""
 
     def __init__(self, host: HostLayer, unique=False, renorm=True, H=None, y_f32=False, base=None, pack=False,
-                 tau=None, gamma=None, rho=None, beta=None):
+                 tau=None, gamma=None, rho=None, beta=None, eta=None, q=None):
         """base: another DeviceLayer whose uploaded (and packed) weights are reused.
         pack: also build the fragment-major weight copies (bm_pack_weights), once.
-        tau / gamma / rho / beta: TAE gate, margin gate, replacement budget, distribution gate (None = off)."""
+        tau / gamma / rho / beta: TAE gate, margin gate, replacement budget, distribution gate (None = off).
+        eta, q: token-aware buddy priority with q [E][R] (numpy fp32) of the table entries."""
         import torch
         import paper_2511_10054_amd as bm
         self.bm = bm
@@ -86,10 +88,11 @@ class DeviceLayer:
         flags = (bm.BM_RENORM_TOPK if renorm else 0) | (bm.BM_REMAP_UNIQUE if unique else 0) | (bm.BM_Y_F32 if y_f32 else 0)
         flags |= (bm.BM_GATE_TAE if tau is not None else 0) | (bm.BM_GATE_MARGIN if gamma is not None else 0)
         flags |= (bm.BM_REPLACE_BUDGET if rho is not None else 0) | (bm.BM_GATE_DIST if beta is not None else 0)
+        flags |= bm.BM_PSI_TOKEN if eta is not None else 0
         self.desc = bm.LayerDesc(T=host.T, d=s.d, E=s.E, F=s.F, K=s.K, n_shared=s.n_shared, R=s.R,
                                  H=s.H if H is None else H,
                                  dtype=bm.BM_BF16 if s.dtype == "bf16" else bm.BM_F32, flags=flags,
-                                 tae_tau=tau or 0.0, margin_gamma=gamma or 0.0, rho=rho or 0, dist_beta=beta or 0.0)
+                                 tae_tau=tau or 0.0, margin_gamma=gamma or 0.0, rho=rho or 0, dist_beta=beta or 0.0, psi_eta=eta or 0.0)
         self.x = to_device(host.x)
         self.w_router = to_device(host.w_router)
         self.bias = to_device(host.bias)
@@ -108,7 +111,9 @@ class DeviceLayer:
             self.packed = [torch.empty(max(bm.bm_packed_bytes(self.desc, i), 16), dtype=torch.uint8, device="cuda")
                            if (i < 2 or s.n_shared) else None for i in range(4)]
         pk = self.packed or [None] * 4
-        self.weights = make_weights(self.w_router, self.bias, self.wg, self.wu, self.wd, self.sg, self.su, self.sd, *pk)
+        self.q = to_device(np.ascontiguousarray(q, dtype=np.float32)) if q is not None else None
+        self.weights = make_weights(self.w_router, self.bias, self.wg, self.wu, self.wd, self.sg, self.su, self.sd, *pk,
+                                    buddy_q=self.q)
         if self.packed is not None and not (base is not None and base.packed is not None):
             bm.bm_pack_weights(self.desc, self.weights, self.bitmap)      # only resident experts are read
             torch.cuda.synchronize()
