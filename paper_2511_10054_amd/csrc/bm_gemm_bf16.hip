@@ -844,6 +844,248 @@ __global__ void __launch_bounds__(256) grouped_gemm256_k64_bf16_kernel(GemmParam
 #undef BM_SLICE
 }
 
+// The same kernel on v_mfma_f32_16x16x32_bf16: per flop the 16 x 16 form draws less power than the
+// 32 x 32 one, and these kernels run against the chip's power limit, so the clock it leaves is higher.
+template <bool DUAL>
+__global__ void __launch_bounds__(256) grouped_gemm256_k64w_bf16_kernel(GemmParams p) {
+    __shared__ __attribute__((aligned(1024))) uint16_t smem[5 * P_PART];         // 160 KB: the whole LDS
+    const int tid = threadIdx.x, lane = tid & 63;
+    // the wave index as a scalar: everything derived from it (LDS targets of the loads, tile halves) then
+    // stays in scalar registers and costs no vector instructions in the main loop
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wm = wave >> 1, wn = wave & 1;
+    const int r16 = lane & 15, quad = lane >> 4;           // MFMA 16x16x32: row (or column) and k eighth
+
+    // Persistent: workgroup b serves the XCD it was dealt to (b % 8) and walks that XCD's share of the
+    // logical tiles with stride (workgroups per XCD), so the workgroups that run together on an XCD work
+    // on consecutive logical tiles (see tile_of) and a workgroup keeps its compute unit: the next tile's
+    // first loads fly while the finished tile is written out, and nothing is relaunched.
+    const int n_mt = p.n_mtiles[0];
+    const int n_nt = DUAL ? (p.N + 127) / 128 : (p.N + 255) / 256;
+    const int total = n_mt * n_nt;
+    const int per_xcd = (total + 7) >> 3;
+    const int xcd = blockIdx.x & 7, stride = gridDim.x >> 3;
+    int idx = blockIdx.x >> 3;
+    if (idx >= per_xcd || xcd * per_xcd + idx >= total) return;
+
+    const int N = p.N, Kd = p.Kd;
+    const int KT = Kd / 64;
+    const uint16_t *a = static_cast<const uint16_t *>(p.a);
+    uint16_t *c = static_cast<uint16_t *>(p.c);
+
+    // fragment offsets inside a part, per 32-wide k slice s: row (.. + r16), piece 4*s + quad
+    int fa_off[2], fb_off[2];
+#pragma unroll
+    for (int s = 0; s < 2; ++s) {
+        const int pc = ((4 * s + quad) ^ ((r16 >> 1) & 7)) << 3;
+        fa_off[s] = (wm * 128 + r16) * 64 + pc;
+        fb_off[s] = (DUAL ? (wn * 64 + r16) : (wn * 128 + r16)) * 64 + pc;
+    }
+
+    f32x4 acc[8][8];                                   // 16 x 16 tiles: rows i*16.., columns j*16..
+    bf16x8 f0a[8], f0b[8], f1a[8], f1b[8];
+    // Load addresses are (uniform base + k offset) + a 32-bit byte offset per lane, so that the k advance
+    // is scalar arithmetic and a load needs no vector address computation.
+    uint32_t oa[8], ob[8];
+    const uint16_t *base_b0, *base_b1;
+    int row0, row_end, n0;                             // of the tile whose loads are being issued
+
+// Pointers of logical tile lid_.  Load instruction j of this wave fills the 1 KB block (4*j + wave) of a
+// part: 8 tile rows of 128 bytes.  Lane i supplies row 8*block + i/8 and LDS slot i%8 of it, i.e.
+// global piece (i % 8) ^ ((row >> 1) & 7).
+#define BM_SETUP(lid_)                                                                             \
+    {                                                                                              \
+        int mt_, nt_;                                                                              \
+        tile_of((lid_), n_mt, n_nt, mt_, nt_);                                                     \
+        const int g_ = p.mt_group[mt_];                                                            \
+        row0 = p.mt_row0[mt_];                                                                     \
+        row_end = p.offsets[g_ + 1];                                                               \
+        n0 = nt_ * (DUAL ? 128 : 256);                                                             \
+        if (g_ < p.E) {                                                                            \
+            base_b0 = static_cast<const uint16_t *>(p.b0) + (size_t)g_ * N * Kd;                   \
+            base_b1 = DUAL ? static_cast<const uint16_t *>(p.b1) + (size_t)g_ * N * Kd : base_b0;  \
+        } else {                                                                                   \
+            base_b0 = static_cast<const uint16_t *>(p.sb0) + (size_t)(g_ - p.E) * N * Kd;          \
+            base_b1 = DUAL ? static_cast<const uint16_t *>(p.sb1) + (size_t)(g_ - p.E) * N * Kd : base_b0; \
+        }                                                                                          \
+        _Pragma("unroll") for (int j = 0; j < 8; ++j) {                                            \
+            const int r_ = 8 * (4 * j + wave) + (lane >> 3);                                       \
+            const int piece_ = (lane & 7) ^ ((r_ >> 1) & 7);                                       \
+            const int pos_ = min(row0 + r_, row_end - 1);                                          \
+            const int src_ = p.row_map ? p.row_map[pos_] : pos_;                                   \
+            oa[j] = ((uint32_t)src_ * (uint32_t)Kd + piece_ * 8) * 2u;                             \
+            /* DUAL: rows 0-127 of the part are W_gate rows (loads 0-3), rows 128-255 W_up rows (4-7) */ \
+            const int n_ = DUAL ? min(n0 + (r_ & 127), N - 1) : min(n0 + r_, N - 1);               \
+            ob[j] = ((uint32_t)n_ * (uint32_t)Kd + piece_ * 8) * 2u;                               \
+        }                                                                                          \
+    }
+// load j_ of the activation part (A) / weight part (B) of k-step tile_ into slot_
+#define BM_DMA_AT(base_, off_, slot_, tile_, j_)                                                   \
+    __builtin_amdgcn_global_load_lds(                                                              \
+        (const BM_GLOBAL void *)(reinterpret_cast<const char *>((base_) + min((tile_), KT - 1) * 64) + (off_)), \
+        (BM_LDS void *)(smem + (slot_) * P_PART + wave * 512 + (j_) * 2048), 16, 0, 0)
+#define BM_DMA_A(slot_, tile_, j_) BM_DMA_AT(a, oa[j_], slot_, tile_, j_)
+#define BM_DMA_B(slot_, tile_, j_) BM_DMA_AT(((j_) < 4 ? base_b0 : base_b1), ob[j_], slot_, tile_, j_)
+// B(0) A(0) B(1) A(1) of the tile set up last into slots 0..3
+#define BM_PROLOGUE()                                                                              \
+    {                                                                                              \
+        _Pragma("unroll") for (int j = 0; j < 8; ++j) BM_DMA_B(0, 0, j);                           \
+        _Pragma("unroll") for (int j = 0; j < 8; ++j) BM_DMA_A(1, 0, j);                           \
+        _Pragma("unroll") for (int j = 0; j < 8; ++j) BM_DMA_B(2, 1, j);                           \
+        _Pragma("unroll") for (int j = 0; j < 8; ++j) BM_DMA_A(3, 1, j);                           \
+    }
+#define BM_LD(ptr_) as_bf16x8(*reinterpret_cast<const u32x4 *>(ptr_))
+// weight fragment j of 8: 16 weight rows; DUAL: fragments 0-3 are W_gate rows, 4-7 the same rows of W_up
+#define BM_BOFF(j_) (DUAL ? (((j_) >> 2) * 8192 + ((j_) & 3) * 1024) : (j_) * 1024)
+// fragment read d_ of 16, in the order the MFMAs need them: a0 b0..b7 a1..a7
+#define BM_RD(d_, fa_, fb_, sa_, sb_)                                                              \
+    {                                                                                              \
+        if ((d_) == 0) fa_[0] = BM_LD(sa_);                                                        \
+        else if ((d_) <= 8) fb_[(d_) - 1] = BM_LD((sb_) + BM_BOFF((d_) - 1));                      \
+        else fa_[(d_) - 8] = BM_LD((sa_) + ((d_) - 8) * 1024);                                     \
+    }
+#define BM_MFMA1(m_, fa_, fb_)                                                                     \
+    acc[(m_) >> 3][(m_) & 7] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fa_[(m_) >> 3], fb_[(m_) & 7], \
+                                                                        acc[(m_) >> 3][(m_) & 7], 0, 0, 0)
+
+    BM_SETUP(xcd * per_xcd + idx);
+    BM_PROLOGUE();
+    for (;;) {
+        const int t_row0 = row0, t_row_end = row_end, t_n0 = n0;    // the tile being multiplied
+#pragma unroll
+        for (int i = 0; i < 8; ++i)
+#pragma unroll
+            for (int j = 0; j < 8; ++j)
+#pragma unroll
+                for (int v = 0; v < 4; ++v) acc[i][j][v] = 0.0f;
+        // B(0) and A(0) have landed: vector memory operations complete in issue order, and whatever was
+        // issued after them (B(1), A(1), then the previous tile's stores), at most the 16 youngest are
+        // still out, which leaves B(0) and A(0) done however many store instructions there were
+        BM_WAIT_VMCNT(16);
+        BM_BARE_BARRIER();
+        {
+            const uint16_t *sa_ = smem + 1 * P_PART + fa_off[0];
+            const uint16_t *sb_ = smem + 0 * P_PART + fb_off[0];
+#pragma unroll
+            for (int d = 0; d < 16; ++d) BM_RD(d, f0a, f0b, sa_, sb_)
+        }
+
+        int sB = 0, sA = 1, sAp = 4;                   // slots of B(kt), A(kt), A(kt-1)
+        for (int kt = 0; kt < KT; ++kt) {
+            {
+                // first k slice of 32: 64 MFMAs; the second slice's fragments are read under MFMAs 0-31 (one
+                // read per two MFMAs), the 8 loads of B(kt+2) go into the slot A(kt-1) has left under MFMAs
+                // 33, 37, ..., 61
+                const uint16_t *sa_ = smem + sA * P_PART + fa_off[1];
+                const uint16_t *sb_ = smem + sB * P_PART + fb_off[1];
+#pragma unroll
+                for (int m = 0; m < 64; ++m) {
+                    BM_MFMA1(m, f0a, f0b);
+                    if (m < 32 && (m & 1) == 0) BM_RD(m >> 1, f1a, f1b, sa_, sb_)
+                    else if (m > 32 && (m & 3) == 1) BM_DMA_B(sAp, kt + 2, (m - 33) >> 2);
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+            }
+            // every fragment of B(kt), A(kt) is in registers; A(kt+1), B(kt+1) have landed (this wave's
+            // part: at most the 8 loads of B(kt+2) are outstanding); after the barrier both hold for
+            // every wave
+            BM_WAIT_VM_LGKM(8, 0);
+            BM_BARE_BARRIER();
+            const int sBn = sB >= 3 ? sB - 3 : sB + 2, sAn = sA >= 3 ? sA - 3 : sA + 2;
+            {
+                // second slice: A(kt+2) goes into the slot B(kt) has left, one load under every fourth MFMA
+                // of the first half; the first fragments of k-step kt+1 are read under the second half
+                const uint16_t *sa_ = smem + sAn * P_PART + fa_off[0];
+                const uint16_t *sb_ = smem + sBn * P_PART + fb_off[0];
+#pragma unroll
+                for (int m = 0; m < 64; ++m) {
+                    BM_MFMA1(m, f1a, f1b);
+                    if (m < 32 && (m & 3) == 0) BM_DMA_A(sB, kt + 2, m >> 2);
+                    else if (m >= 32 && (m & 1) == 0) BM_RD((m - 32) >> 1, f0a, f0b, sa_, sb_)
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+            }
+            sAp = sA;
+            sB = sBn;
+            sA = sAn;
+        }
+        // The tile is done.  Loads past its last k-step (clamped repeats) may still be landing and other
+        // waves may still be reading fragments: drain both, then start the next tile's loads so that they
+        // fly while this tile is written out.
+        BM_WAIT_VM_LGKM(0, 0);
+        BM_BARE_BARRIER();
+        idx += stride;
+        const bool more = idx < per_xcd && xcd * per_xcd + idx < total;      // uniform over the workgroup
+        if (more) {
+            BM_SETUP(xcd * per_xcd + idx);
+            BM_PROLOGUE();
+        }
+
+        // Write-out through the free fifth slot (8 KB per wave): an accumulator tile holds, per lane, four
+        // rows of one column; 16 rows at a time are laid out row-major in LDS as bf16 - neighbouring lanes
+        // swap one value so that every lane writes a packed pair - and read back as 16-byte pieces, so a
+        // store instruction writes whole 128-byte lines.  A wave uses only its own region and LDS
+        // operations of a wave stay in order.
+        {
+            constexpr int OC = DUAL ? 4 : 8;            // 16-column output blocks per wave
+            constexpr int SD = DUAL ? 36 : 72;          // LDS row stride in dwords (padded against conflicts)
+            constexpr int PR = OC * 2;                  // 16-byte pieces per output row
+            uint32_t *stage = reinterpret_cast<uint32_t *>(smem + 4 * P_PART) + wave * 2048;
+            const bool odd = lane & 1;
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+#pragma unroll
+                for (int j = 0; j < OC; ++j) {
+#pragma unroll
+                    for (int v = 0; v < 4; v += 2) {
+                        float x0, x1;
+                        if (DUAL) {
+                            x0 = silu(acc[i][j][v]) * acc[i][4 + j][v];
+                            x1 = silu(acc[i][j][v + 1]) * acc[i][4 + j][v + 1];
+                        } else {
+                            x0 = acc[i][j][v];
+                            x1 = acc[i][j][v + 1];
+                        }
+                        // even lane keeps row v and gets the right-hand neighbour's value of that row;
+                        // odd lane keeps row v+1 and gets the left-hand neighbour's
+                        const float send = odd ? x0 : x1;
+                        const float recv = __builtin_bit_cast(
+                            float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, send), 0xB1, 0xF, 0xF, true));
+                        const uint32_t pk = odd ? pack_bf16x2(recv, x1) : pack_bf16x2(x0, recv);
+                        const int lrow = 4 * quad + v + (odd ? 1 : 0);
+                        stage[lrow * SD + j * 8 + (r16 >> 1)] = pk;
+                    }
+                }
+#pragma unroll
+                for (int t = 0; t < PR / 4; ++t) {
+                    const int q = lane + 64 * t;
+                    const int lrow = q / PR, pc = q % PR;
+                    const u32x4 val = *reinterpret_cast<const u32x4 *>(stage + lrow * SD + pc * 4);
+                    const int row = t_row0 + wm * 128 + i * 16 + lrow;
+                    const int col = t_n0 + wn * (OC * 16) + pc * 8;
+                    if (row < t_row_end && col < N) stg128(&c[(size_t)row * N + col], val);
+                }
+            }
+        }
+        if (!more) break;
+    }
+#undef BM_SETUP
+#undef BM_PROLOGUE
+#undef BM_DMA_AT
+#undef BM_DMA_A
+#undef BM_DMA_B
+#undef BM_LD
+#undef BM_BOFF
+#undef BM_RD
+#undef BM_MFMA1
+}
+
+// The 16 x 16 x 32 form is used for the gate/up projection.  For the down projection the compiler's
+// register assignment of that form moves accumulator tiles between registers inside the main loop
+// (measured 70 % slower), so it stays on the 32 x 32 x 16 form.
+#define BM_K64_GATEUP grouped_gemm256_k64w_bf16_kernel<true>
+#define BM_K64_DOWN grouped_gemm256_k64_bf16_kernel<false>
+
 static int grid_for(const GemmParams &p, bool dual) {
     const int n_nt = dual ? (p.N + 127) / 128 : (p.N + 255) / 256;
     const int total = p.max_mtiles * n_nt;
@@ -866,7 +1108,7 @@ static bool k64_ok(const GemmParams &p) {
 
 int launch_gateup_bf16(const GemmParams &p, hipStream_t st) {
     if (k64_ok(p))
-        hipLaunchKernelGGL((grouped_gemm256_k64_bf16_kernel<true>), dim3(persistent_grid(p, true)), dim3(256), 0, st, p);
+        hipLaunchKernelGGL((BM_K64_GATEUP), dim3(persistent_grid(p, true)), dim3(256), 0, st, p);
     else if (p.BM == 256)
         hipLaunchKernelGGL((grouped_gemm256_dma_bf16_kernel<true>), dim3(grid_for(p, true)), dim3(256), 0, st, p);
     else
@@ -876,7 +1118,7 @@ int launch_gateup_bf16(const GemmParams &p, hipStream_t st) {
 
 int launch_down_bf16(const GemmParams &p, hipStream_t st) {
     if (k64_ok(p))
-        hipLaunchKernelGGL((grouped_gemm256_k64_bf16_kernel<false>), dim3(persistent_grid(p, false)), dim3(256), 0, st, p);
+        hipLaunchKernelGGL((BM_K64_DOWN), dim3(persistent_grid(p, false)), dim3(256), 0, st, p);
     else if (p.BM == 256)
         hipLaunchKernelGGL((grouped_gemm256_dma_bf16_kernel<false>), dim3(grid_for(p, false)), dim3(256), 0, st, p);
     else
