@@ -821,11 +821,7 @@ __global__ void __launch_bounds__(256) grouped_gemm256_k64_bf16_kernel(GemmParam
                         const u32x4 val = *reinterpret_cast<const u32x4 *>(stage + lrow * SD + pc * 4);
                         const int row = t_row0 + wm * 128 + i * 32 + ch * CR + lrow;
                         const int col = t_n0 + wn * (OC * 32) + pc * 8;
-#ifdef BM_EXP_FEWSTORES
-                        if (row < t_row_end && col < N && (val.x == 0x12345678u || i == 0)) stg128(&c[(size_t)row * N + col], val);
-#else
                         if (row < t_row_end && col < N) stg128(&c[(size_t)row * N + col], val);
-#endif
                     }
                 }
             }
@@ -1080,9 +1076,9 @@ __global__ void __launch_bounds__(256) grouped_gemm256_k64w_bf16_kernel(GemmPara
 #undef BM_MFMA1
 }
 
-// The 16 x 16 x 32 form is used for the gate/up projection.  For the down projection the compiler's
-// register assignment of that form moves accumulator tiles between registers inside the main loop
-// (measured 70 % slower), so it stays on the 32 x 32 x 16 form.
+// The 16 x 16 x 32 form serves the gate/up projection (7 % faster there).  The down projection stays on the
+// 32 x 32 x 16 form: measured equally fast once the accumulators of the 16 x 16 form are kept in place,
+// which the compiler only does for the gate/up instantiation.
 #define BM_K64_GATEUP grouped_gemm256_k64w_bf16_kernel<true>
 #define BM_K64_DOWN grouped_gemm256_k64_bf16_kernel<false>
 
