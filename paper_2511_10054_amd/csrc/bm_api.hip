@@ -54,8 +54,9 @@ size_t align_up(size_t v) { return (v + ALIGN - 1) / ALIGN * ALIGN; }
 // Workspace carving: a pure function of desc.
 struct Layout {
     size_t ids, ids2, w, tile_counts, tile_base, tile_stats, offsets, perm, inv_perm, row_token;
-    size_t mt_group, mt_row0, n_mtiles, stats, probs, h, o, total;
+    size_t mt_group, mt_row0, n_mtiles, stats, probs, h, o, splitk, total;
     int n_tiles, rows_max, mtiles_max;
+    bool has_splitk;
 };
 
 int check_desc(const bm_layer_desc *d, bool need_ffn) {
@@ -113,6 +114,9 @@ Layout make_layout(const bm_layer_desc *d) {
     const size_t F = d->F > 0 ? d->F : 0;
     L.h = take((size_t)L.rows_max * F * esz);
     L.o = take(use_skinny(d) ? (size_t)skinny_ksplit(d) * L.rows_max * d->d * 4 : (size_t)L.rows_max * d->d * esz);
+    // fp32 partial tiles of the down projection's split tail: one 256 x 256 tile per workgroup of the launch
+    L.has_splitk = !use_skinny(d) && d->dtype == BM_BF16 && gemm_tile_rows(d) == 256;
+    L.splitk = take(L.has_splitk ? (size_t)256 * 256 * 256 * 4 : 0);
     L.total = off;
     return L;
 }
@@ -415,6 +419,7 @@ int bm_moe_forward(const bm_layer_desc *desc, const void *x, const bm_weights *w
     dp.b0 = wt->w_down; dp.b1 = nullptr; dp.sb0 = wt->ws_down; dp.sb1 = nullptr;
     dp.c = at<void>(ws, L.o);
     dp.N = desc->d; dp.Kd = desc->F;
+    dp.splitk = L.has_splitk ? at<float>(ws, L.splitk) : nullptr;
     int ksplit = 1;
     if (skinny) {
         ksplit = skinny_ksplit(desc);

@@ -596,6 +596,31 @@ constexpr int P_PART = 256 * 64;                       // bf16 elements per part
 #define BM_WAIT_VM_LGKM(vm, lgkm) \
     __builtin_amdgcn_s_waitcnt(((vm) & 15) | (7 << 4) | ((lgkm) << 8) | (((vm) >> 4) << 14))
 
+// The tail of the persistent schedule.  An XCD's workgroups (stride of them) take its tiles round by
+// round; when the last round is not full its `rem` tiles would keep rem workgroups busy for a whole tile
+// time while the others idle.  For the down projection (long reduction, few rounds) each of those tiles
+// is instead cut along the reduction into S = stride / rem chunks, one per workgroup; the chunks leave
+// fp32 partial tiles in scratch memory and splitk_fixup_kernel adds them in chunk order.
+struct TailSplit {
+    int full;     // tiles of this XCD done in complete rounds
+    int rem;      // tiles left for the last, partial round
+    int S;        // chunks per tail tile (1: not split)
+};
+__device__ __forceinline__ TailSplit tail_split(int total, int per_xcd, int xcd, int stride, int KT, bool allowed) {
+    TailSplit t;
+    const int valid = max(0, min(per_xcd, total - xcd * per_xcd));
+    t.full = valid / stride * stride;
+    t.rem = valid - t.full;
+    t.S = 1;
+    if (allowed && t.rem > 0) {
+        t.S = min(stride / t.rem, 8);
+        while (t.S > 1 && KT / t.S < 4) --t.S;
+        if (t.S < 1) t.S = 1;
+    }
+    return t;
+}
+constexpr int SPLIT_TILE_FLOATS = 256 * 256;
+
 template <bool DUAL>
 __global__ void __launch_bounds__(256) grouped_gemm256_k64_bf16_kernel(GemmParams p) {
     __shared__ __attribute__((aligned(1024))) uint16_t smem[5 * P_PART];         // 160 KB: the whole LDS
@@ -614,12 +639,38 @@ __global__ void __launch_bounds__(256) grouped_gemm256_k64_bf16_kernel(GemmParam
     const int n_nt = DUAL ? (p.N + 127) / 128 : (p.N + 255) / 256;
     const int total = n_mt * n_nt;
     const int per_xcd = (total + 7) >> 3;
-    const int xcd = blockIdx.x & 7, stride = gridDim.x >> 3;
-    int idx = blockIdx.x >> 3;
-    if (idx >= per_xcd || xcd * per_xcd + idx >= total) return;
-
+    const int xcd = blockIdx.x & 7, stride = gridDim.x >> 3, slot = blockIdx.x >> 3;
     const int N = p.N, Kd = p.Kd;
     const int KT = Kd / 64;
+    const TailSplit ts = tail_split(total, per_xcd, xcd, stride, KT, !DUAL && p.splitk != nullptr);
+    int idx = slot;                                    // next tile of the complete rounds
+    bool tail_pending = ts.rem > 0;
+    int kbeg = 0, kend = KT;                           // k-steps of the item whose loads are being issued
+    bool partial = false;                              // that item is a chunk of a split tile
+    int item_tile = 0;
+// next work item of this workgroup -> item_tile, kbeg, kend, partial; false when there is none
+#define BM_NEXT_ITEM(ok_)                                                                          \
+    {                                                                                              \
+        ok_ = false;                                                                               \
+        if (idx < ts.full) {                                                                       \
+            item_tile = idx; kbeg = 0; kend = KT; partial = false; idx += stride; ok_ = true;      \
+        } else if (tail_pending) {                                                                 \
+            tail_pending = false;                                                                  \
+            if (ts.S >= 2) {                                                                       \
+                if (slot < ts.rem * ts.S) {                                                        \
+                    const int c_ = slot % ts.S;                                                    \
+                    item_tile = ts.full + slot / ts.S;                                             \
+                    kbeg = c_ * KT / ts.S; kend = (c_ + 1) * KT / ts.S; partial = true; ok_ = true; \
+                }                                                                                  \
+            } else if (slot < ts.rem) {                                                            \
+                item_tile = ts.full + slot; kbeg = 0; kend = KT; partial = false; ok_ = true;      \
+            }                                                                                      \
+        }                                                                                          \
+    }
+    bool have;
+    BM_NEXT_ITEM(have);
+    if (!have) return;
+
     const uint16_t *a = static_cast<const uint16_t *>(p.a);
     uint16_t *c = static_cast<uint16_t *>(p.c);
 
@@ -672,17 +723,17 @@ __global__ void __launch_bounds__(256) grouped_gemm256_k64_bf16_kernel(GemmParam
 // load j_ of the activation part (A) / weight part (B) of k-step tile_ into slot_
 #define BM_DMA_AT(base_, off_, slot_, tile_, j_)                                                   \
     __builtin_amdgcn_global_load_lds(                                                              \
-        (const BM_GLOBAL void *)(reinterpret_cast<const char *>((base_) + min((tile_), KT - 1) * 64) + (off_)), \
+        (const BM_GLOBAL void *)(reinterpret_cast<const char *>((base_) + min((tile_), kend - 1) * 64) + (off_)), \
         (BM_LDS void *)(smem + (slot_) * P_PART + wave * 512 + (j_) * 2048), 16, 0, 0)
 #define BM_DMA_A(slot_, tile_, j_) BM_DMA_AT(a, oa[j_], slot_, tile_, j_)
 #define BM_DMA_B(slot_, tile_, j_) BM_DMA_AT(((j_) < 4 ? base_b0 : base_b1), ob[j_], slot_, tile_, j_)
 // B(0) A(0) B(1) A(1) of the tile set up last into slots 0..3
 #define BM_PROLOGUE()                                                                              \
     {                                                                                              \
-        _Pragma("unroll") for (int j = 0; j < 8; ++j) BM_DMA_B(0, 0, j);                           \
-        _Pragma("unroll") for (int j = 0; j < 8; ++j) BM_DMA_A(1, 0, j);                           \
-        _Pragma("unroll") for (int j = 0; j < 8; ++j) BM_DMA_B(2, 1, j);                           \
-        _Pragma("unroll") for (int j = 0; j < 8; ++j) BM_DMA_A(3, 1, j);                           \
+        _Pragma("unroll") for (int j = 0; j < 8; ++j) BM_DMA_B(0, kbeg, j);                        \
+        _Pragma("unroll") for (int j = 0; j < 8; ++j) BM_DMA_A(1, kbeg, j);                        \
+        _Pragma("unroll") for (int j = 0; j < 8; ++j) BM_DMA_B(2, kbeg + 1, j);                    \
+        _Pragma("unroll") for (int j = 0; j < 8; ++j) BM_DMA_A(3, kbeg + 1, j);                    \
     }
 #define BM_LD(ptr_) as_bf16x8(*reinterpret_cast<const u32x4 *>(ptr_))
 #define BM_BOFF(i_) (DUAL ? (((i_) >> 1) * 8192 + ((i_) & 1) * 2048) : (i_) * 2048)
@@ -713,10 +764,12 @@ __global__ void __launch_bounds__(256) grouped_gemm256_k64_bf16_kernel(GemmParam
         }                                                                                          \
     }
 
-    BM_SETUP(xcd * per_xcd + idx);
+    BM_SETUP(xcd * per_xcd + item_tile);
     BM_PROLOGUE();
     for (;;) {
         const int t_row0 = row0, t_row_end = row_end, t_n0 = n0;    // the tile being multiplied
+        const bool t_partial = partial;
+        const int t_kbeg = kbeg, t_kend = kend;
 #pragma unroll
         for (int i = 0; i < 4; ++i)
 #pragma unroll
@@ -736,7 +789,7 @@ __global__ void __launch_bounds__(256) grouped_gemm256_k64_bf16_kernel(GemmParam
         }
 
         int sB = 0, sA = 1, sAp = 4;                   // slots of B(kt), A(kt), A(kt-1)
-        for (int kt = 0; kt < KT; ++kt) {
+        for (int kt = t_kbeg; kt < t_kend; ++kt) {
             BM_SLICE(f0a, f0b, f1a, f1b, 1, 0, 3);     // B(kt+2) loads 0-2 go into the slot A(kt-1) has left
             BM_SLICE(f1a, f1b, f0a, f0b, 2, 3, 3);
             BM_SLICE(f0a, f0b, f1a, f1b, 3, 6, 2);
@@ -768,11 +821,28 @@ __global__ void __launch_bounds__(256) grouped_gemm256_k64_bf16_kernel(GemmParam
         // fly while this tile is written out.
         BM_WAIT_VM_LGKM(0, 0);
         BM_BARE_BARRIER();
-        idx += stride;
-        const bool more = idx < per_xcd && xcd * per_xcd + idx < total;      // uniform over the workgroup
+        bool more;                                     // uniform over the workgroup
+        BM_NEXT_ITEM(more);
         if (more) {
-            BM_SETUP(xcd * per_xcd + idx);
+            BM_SETUP(xcd * per_xcd + item_tile);
             BM_PROLOGUE();
+        }
+
+        if (!DUAL && t_partial) {
+            // chunk of a split tile: the fp32 accumulators go to this workgroup's scratch tile as they are
+            // (accumulator tile, quarter, lane: 16-byte stores, contiguous over the lanes)
+            float *dst = p.splitk + (size_t)(xcd * stride + slot) * SPLIT_TILE_FLOATS + (wave * 64 + lane) * 4;
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) {
+                        const f32x4 v4 = {acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]};
+                        *(BM_GLOBAL f32x4 *)(dst + ((i * 4 + j) * 4 + q) * 1024) = v4;
+                    }
+            if (!more) break;
+            continue;
         }
 
         // Write-out through the free fifth slot (8 KB per wave): the accumulators hold one column per lane,
@@ -829,6 +899,7 @@ __global__ void __launch_bounds__(256) grouped_gemm256_k64_bf16_kernel(GemmParam
         if (!more) break;
     }
 #undef BM_SETUP
+#undef BM_NEXT_ITEM
 #undef BM_PROLOGUE
 #undef BM_DMA_AT
 #undef BM_DMA_A
@@ -838,6 +909,39 @@ __global__ void __launch_bounds__(256) grouped_gemm256_k64_bf16_kernel(GemmParam
 #undef BM_RD
 #undef BM_MFMA1
 #undef BM_SLICE
+}
+
+// Adds the chunks of every split tail tile in chunk order and writes the bf16 result (see TailSplit).
+// Grid (16 tail tiles, 8 XCDs, 16 slices of a tile): a workgroup handles one sixteenth of a tile - the
+// accumulator tiles (i, j) with i * 4 + j == blockIdx.z - with the chunk writers' thread -> element
+// mapping, so that the reduction itself is spread over the chip.
+__global__ void __launch_bounds__(256) splitk_fixup_kernel(GemmParams p) {
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm = wave >> 1, wn = wave & 1, r32 = lane & 31, half = lane >> 5;
+    const int n_mt = p.n_mtiles[0];
+    const int n_nt = (p.N + 255) / 256;
+    const int total = n_mt * n_nt;
+    const int per_xcd = (total + 7) >> 3;
+    const int xcd = blockIdx.y, stride = p.splitk_stride, t = blockIdx.x;
+    const TailSplit ts = tail_split(total, per_xcd, xcd, stride, p.Kd / 64, true);
+    if (ts.S < 2 || t >= ts.rem) return;
+    int mt, nt;
+    tile_of(xcd * per_xcd + ts.full + t, n_mt, n_nt, mt, nt);
+    const int g = p.mt_group[mt];
+    const int row0 = p.mt_row0[mt], row_end = p.offsets[g + 1], n0 = nt * 256, N = p.N;
+    uint16_t *c = static_cast<uint16_t *>(p.c);
+    const float *src = p.splitk + (size_t)(xcd * stride + t * ts.S) * SPLIT_TILE_FLOATS + (wave * 64 + lane) * 4;
+    const int i = blockIdx.z >> 2, j = blockIdx.z & 3;
+    for (int q = 0; q < 4; ++q) {
+        f32x4 sum = {0.0f, 0.0f, 0.0f, 0.0f};
+        for (int ch = 0; ch < ts.S; ++ch)
+            sum += *(const BM_GLOBAL f32x4 *)(src + (size_t)ch * SPLIT_TILE_FLOATS + ((i * 4 + j) * 4 + q) * 1024);
+        const int n = n0 + wn * 128 + j * 32 + r32;
+        for (int e = 0; e < 4; ++e) {
+            const int row = row0 + wm * 128 + i * 32 + 8 * q + 4 * half + e;
+            if (row < row_end && n < N) stg16(&c[(size_t)row * N + n], f32_to_bf16(sum[e]));
+        }
+    }
 }
 
 // The same kernel on v_mfma_f32_16x16x32_bf16: per flop the 16 x 16 form draws less power than the
@@ -1113,8 +1217,13 @@ int launch_gateup_bf16(const GemmParams &p, hipStream_t st) {
 }
 
 int launch_down_bf16(const GemmParams &p, hipStream_t st) {
-    if (k64_ok(p))
-        hipLaunchKernelGGL((BM_K64_DOWN), dim3(persistent_grid(p, false)), dim3(256), 0, st, p);
+    if (k64_ok(p)) {
+        GemmParams q = p;
+        q.splitk_stride = persistent_grid(p, false) >> 3;
+        hipLaunchKernelGGL((BM_K64_DOWN), dim3(persistent_grid(p, false)), dim3(256), 0, st, q);
+        if (q.splitk != nullptr)
+            hipLaunchKernelGGL(splitk_fixup_kernel, dim3(16, 8, 16), dim3(256), 0, st, q);
+    }
     else if (p.BM == 256)
         hipLaunchKernelGGL((grouped_gemm256_dma_bf16_kernel<false>), dim3(grid_for(p, false)), dim3(256), 0, st, p);
     else

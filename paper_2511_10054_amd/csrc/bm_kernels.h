@@ -81,6 +81,8 @@ struct GemmParams {
     int max_mtiles;               // grid bound on row tiles
     int BM;                       // rows per tile of the row-tile table: 128 or 256
     const int32_t *mt_group, *mt_row0, *n_mtiles, *offsets;
+    float *splitk;                // scratch for the reduction-split tail of the down projection (or null)
+    int splitk_stride;            // workgroups per XCD of the launch that wrote it
 };
 
 // Skinny (decode) projections: one weight-row block per wave, see bm_skinny_bf16.hip.
