@@ -612,16 +612,20 @@ __device__ __forceinline__ TailSplit tail_split(int total, int per_xcd, int xcd,
     t.full = valid / stride * stride;
     t.rem = valid - t.full;
     t.S = 1;
-    if (allowed && t.rem > 0) {
+    // worth it only for long reductions: a chunk costs a 256 KB partial tile written and read back, which
+    // a tile of fewer than 64 k-steps does not take long enough to repay
+    if (allowed && t.rem > 0 && KT >= 64) {
         t.S = min(stride / t.rem, 8);
-        while (t.S > 1 && KT / t.S < 4) --t.S;
+        while (t.S > 1 && KT / t.S < 16) --t.S;
         if (t.S < 1) t.S = 1;
     }
     return t;
 }
 constexpr int SPLIT_TILE_FLOATS = 256 * 256;
 
-template <bool DUAL>
+// SPLIT: compile the reduction-split tail in (kept out of the other instantiations: its write-out of raw
+// accumulators costs registers that short tiles cannot afford to spill around)
+template <bool DUAL, bool SPLIT>
 __global__ void __launch_bounds__(256) grouped_gemm256_k64_bf16_kernel(GemmParams p) {
     __shared__ __attribute__((aligned(1024))) uint16_t smem[5 * P_PART];         // 160 KB: the whole LDS
     const int tid = threadIdx.x, lane = tid & 63;
@@ -642,7 +646,7 @@ __global__ void __launch_bounds__(256) grouped_gemm256_k64_bf16_kernel(GemmParam
     const int xcd = blockIdx.x & 7, stride = gridDim.x >> 3, slot = blockIdx.x >> 3;
     const int N = p.N, Kd = p.Kd;
     const int KT = Kd / 64;
-    const TailSplit ts = tail_split(total, per_xcd, xcd, stride, KT, !DUAL && p.splitk != nullptr);
+    const TailSplit ts = tail_split(total, per_xcd, xcd, stride, KT, SPLIT && p.splitk != nullptr);
     int idx = slot;                                    // next tile of the complete rounds
     bool tail_pending = ts.rem > 0;
     int kbeg = 0, kend = KT;                           // k-steps of the item whose loads are being issued
@@ -828,7 +832,7 @@ __global__ void __launch_bounds__(256) grouped_gemm256_k64_bf16_kernel(GemmParam
             BM_PROLOGUE();
         }
 
-        if (!DUAL && t_partial) {
+        if (SPLIT && t_partial) {
             // chunk of a split tile: the fp32 accumulators go to this workgroup's scratch tile as they are
             // (accumulator tile, quarter, lane: 16-byte stores, contiguous over the lanes)
             float *dst = p.splitk + (size_t)(xcd * stride + slot) * SPLIT_TILE_FLOATS + (wave * 64 + lane) * 4;
@@ -1184,7 +1188,8 @@ __global__ void __launch_bounds__(256) grouped_gemm256_k64w_bf16_kernel(GemmPara
 // 32 x 32 x 16 form: measured equally fast once the accumulators of the 16 x 16 form are kept in place,
 // which the compiler only does for the gate/up instantiation.
 #define BM_K64_GATEUP grouped_gemm256_k64w_bf16_kernel<true>
-#define BM_K64_DOWN grouped_gemm256_k64_bf16_kernel<false>
+#define BM_K64_DOWN grouped_gemm256_k64_bf16_kernel<false, false>
+#define BM_K64_DOWN_SPLIT grouped_gemm256_k64_bf16_kernel<false, true>
 
 static int grid_for(const GemmParams &p, bool dual) {
     const int n_nt = dual ? (p.N + 127) / 128 : (p.N + 255) / 256;
@@ -1218,11 +1223,15 @@ int launch_gateup_bf16(const GemmParams &p, hipStream_t st) {
 
 int launch_down_bf16(const GemmParams &p, hipStream_t st) {
     if (k64_ok(p)) {
-        GemmParams q = p;
-        q.splitk_stride = persistent_grid(p, false) >> 3;
-        hipLaunchKernelGGL((BM_K64_DOWN), dim3(persistent_grid(p, false)), dim3(256), 0, st, q);
-        if (q.splitk != nullptr)
+        // the reduction-split tail (see TailSplit) pays only for long reductions
+        if (p.splitk != nullptr && p.Kd / 64 >= 64) {
+            GemmParams q = p;
+            q.splitk_stride = persistent_grid(p, false) >> 3;
+            hipLaunchKernelGGL((BM_K64_DOWN_SPLIT), dim3(persistent_grid(p, false)), dim3(256), 0, st, q);
             hipLaunchKernelGGL(splitk_fixup_kernel, dim3(16, 8, 16), dim3(256), 0, st, q);
+        } else {
+            hipLaunchKernelGGL((BM_K64_DOWN), dim3(persistent_grid(p, false)), dim3(256), 0, st, p);
+        }
     }
     else if (p.BM == 256)
         hipLaunchKernelGGL((grouped_gemm256_dma_bf16_kernel<false>), dim3(grid_for(p, false)), dim3(256), 0, st, p);
