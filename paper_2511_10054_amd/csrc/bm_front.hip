@@ -322,7 +322,10 @@ __device__ void tile_epilogue(const FrontParams &p, float *logits, int stride, i
         p.ids2[(size_t)t0 * K + idx] = s.ids[idx];
         p.w[(size_t)t0 * K + idx] = s.w[idx];
     }
-    for (int e = tid; e < E; e += blockDim.x) p.tile_counts[(size_t)tile * E + e] = s.counts[e];
+    // histograms are stored expert-major ([E][tiles]): the single workgroup that scans them reads and writes
+    // whole lines, the strided side is spread over the many workgroups here
+    const int n_tiles_all = (p.T + TILE_T - 1) / TILE_T;
+    for (int e = tid; e < E; e += blockDim.x) p.tile_counts[(size_t)e * n_tiles_all + tile] = s.counts[e];
     if (tid < 3) p.tile_stats[tile * 4 + tid] = s.stats[tid];
 }
 
@@ -635,7 +638,8 @@ __global__ void __launch_bounds__(256) count_kernel(const int32_t *ids, int T, i
         if ((unsigned)e < (unsigned)E) atomicAdd(&counts[e], 1);
     }
     __syncthreads();
-    for (int e = tid; e < E; e += blockDim.x) tile_counts[(size_t)tile * E + e] = counts[e];
+    const int n_tiles_all = (T + TILE_T - 1) / TILE_T;
+    for (int e = tid; e < E; e += blockDim.x) tile_counts[(size_t)e * n_tiles_all + tile] = counts[e];
 }
 
 // ---------------------------------------------------------------------------
@@ -655,10 +659,10 @@ __global__ void __launch_bounds__(1024) scan_kernel(ScanParams p) {
         int run = 0;
         for (int tb = 0; tb < p.n_tiles; tb += WAVE) {
             const int t = tb + lane;
-            const int c = (t < p.n_tiles) ? p.tile_counts[(size_t)t * p.E + e] : 0;
+            const int c = (t < p.n_tiles) ? p.tile_counts[(size_t)e * p.n_tiles + t] : 0;
             int tot;
             const int ex = wave_excl_scan(c, tot);
-            if (t < p.n_tiles) p.tile_base[(size_t)t * p.E + e] = run + ex;
+            if (t < p.n_tiles) p.tile_base[(size_t)e * p.n_tiles + t] = run + ex;
             run += tot;
         }
         if (lane == 0) total[e] = run;
@@ -714,6 +718,7 @@ __global__ void __launch_bounds__(1024) scan_kernel(ScanParams p) {
 __global__ void __launch_bounds__(256) scatter_kernel(ScatterParams p) {
     __shared__ int32_t s_ids[TILE_T * BM_MAX_K];
     const int tid = threadIdx.x, tile = blockIdx.x, t0 = tile * TILE_T;
+    const int n_tiles_all = (p.T + TILE_T - 1) / TILE_T;
     const int K = p.K, E = p.E;
     const int ntok = min(TILE_T, p.T - t0);
     const int n = ntok * K;
@@ -730,7 +735,7 @@ __global__ void __launch_bounds__(256) scatter_kernel(ScatterParams p) {
         if (e >= 0) {
             int rank = 0;
             for (int j = 0; j < idx; ++j) rank += (s_ids[j] == e) ? 1 : 0;
-            pos = p.offsets[e] + p.tile_base[(size_t)tile * E + e] + rank;
+            pos = p.offsets[e] + p.tile_base[(size_t)e * n_tiles_all + tile] + rank;
             p.perm[pos] = a;
             if (p.row_token) p.row_token[pos] = a / K;
         }

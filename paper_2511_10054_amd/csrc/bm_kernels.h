@@ -25,8 +25,8 @@ struct RemapParams {
 
 struct ScanParams {
     int T, E, n_shared, n_tiles, BM;
-    const int32_t *tile_counts;   // [n_tiles][E]
-    int32_t *tile_base;           // [n_tiles][E]
+    const int32_t *tile_counts;   // [E][n_tiles]
+    int32_t *tile_base;           // [E][n_tiles]
     const int32_t *tile_stats;    // [n_tiles][4] or null
     int32_t *offsets;             // [E + n_shared + 1]
     int32_t *mt_group, *mt_row0;  // row-tile table
@@ -38,7 +38,7 @@ struct ScatterParams {
     int T, K, E, n_shared;
     const int32_t *ids;           // [T][K] after substitution
     const int32_t *offsets;       // [E + n_shared + 1]
-    const int32_t *tile_base;     // [n_tiles][E]
+    const int32_t *tile_base;     // [E][n_tiles]
     int32_t *perm, *inv_perm;     // [T*K]
     int32_t *row_token;           // [rows] or null
 };
@@ -60,7 +60,7 @@ struct FrontParams {
     const uint64_t *bitmap; // null => routing only (no substitution, no histogram)
     const int32_t *table;   // [E][R]
     int32_t *ids2;          // [T][K] after substitution
-    int32_t *tile_counts;   // [n_tiles][E]
+    int32_t *tile_counts;   // [E][n_tiles]
     int32_t *tile_stats;    // [n_tiles][4]
     int fused;              // one workgroup walks all tiles and also does the scan and the scatter
     ScanParams scan;        // used when fused
