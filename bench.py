@@ -31,10 +31,10 @@ PEAK_BF16_TFLOPS = 2500.0    # MI355X dense bf16 MFMA
 # WRITE_SIZE runs summarised under profiles/ (counter x copy-kernel calibration); default shapes,
 # first-resident mode only.  Re-measure after changing that kernel.
 TRAFFIC_BYTES = {
-    "c2_mixtral_decode_T64": 1335.1e6,
-    "c3_mixtral_prefill_T4096": 3828.0e6,
-    "c4_qwen3_T2048": 646.2e6,
-    "c5_deepseek_T8192": 1723.1e6,
+    "c2_mixtral_decode_T64": 1182.5e6,
+    "c3_mixtral_prefill_T4096": 4425.0e6,
+    "c4_qwen3_T2048": 603.5e6,
+    "c5_deepseek_T8192": 1967.1e6,
 }
 
 WORKLOADS = {
