@@ -2,22 +2,23 @@
 //
 // Rows are the surviving assignments, grouped by expert; a row-tile table
 // built on the device says which group each tile of BM rows belongs to.  One
-// workgroup computes BM rows x 256 weight rows with v_mfma_f32_32x32x16_bf16
-// and fp32 accumulators:
+// workgroup computes BM rows x 256 weight rows with fp32 accumulators:
 //   DUAL  : the 256 weight rows are 128 rows of W_gate and the same 128 rows
 //           of W_up; the epilogue writes h = silu(g) * u as bf16.
 //   !DUAL : 256 rows of W_down; the epilogue writes the product as bf16.
-// Four waves (2 x 2) per workgroup, two shapes: BM = 256 (wave tile 128 x 128,
-// all 256 accumulator registers) for large groups - per flop it needs a third
-// less LDS and L2 traffic than the smaller tile, and LDS bandwidth is what
-// bounds these kernels first - and BM = 128 (wave tile 64 x 128) when groups
-// are small and a 256-row tile would be mostly padding.
 // Both operands have the reduction dimension contiguous, so a lane's MFMA
-// operand (8 consecutive k) is one 16-byte piece of a row.  Tiles of BK = 64
-// are staged through LDS, double-buffered, with the next tile's global loads in
-// flight while the current one is multiplied.  LDS rows are 128 bytes; the 64
-// banks span two rows, so piece p of row r is stored at slot p ^ ((r >> 1) & 7):
-// the 16 lanes of one ds_read_b128 pass (16 rows, same p) then hit 16 distinct
+// operand (8 consecutive k) is one 16-byte piece of a row.
+//
+// Kernels, in the order the launchers prefer them:
+//   grouped_gemm256_k64w / k64   BM = 256, persistent, k-steps of 64 with whole-line direct-to-LDS
+//                                loads (gate/up on the 16x16x32 MFMA, down on the 32x32x16 one, the
+//                                latter with a reduction-split tail for long reductions)
+//   grouped_gemm256_dma          BM = 256, k-steps of 32 (reduction not a multiple of 64, or offsets
+//                                beyond 32 bits)
+//   grouped_gemm_bf16_kernel     BM = 128, 8 waves, register-staged double buffer, for groups too small
+//                                for 256-row tiles
+// LDS rows of 128 bytes: the 64 banks span two rows, so piece p of row r is stored at slot
+// p ^ ((r >> 1) & 7); the 16 lanes of one ds_read_b128 pass (16 rows, same p) then hit 16 distinct
 // 16-byte slots (measured: zero bank-conflict cycles).
 #include "bm_kernels.h"
 
@@ -199,206 +200,22 @@ __global__ void __launch_bounds__(256) grouped_gemm_bf16_kernel(GemmParams p) {
     }
 }
 
-// ---------------------------------------------------------------------------
-// Large-group kernel: 256 rows x 256 weight rows per workgroup, 4 waves (2 x 2),
-// wave tile 128 x 128 (all 256 accumulator registers), one wave per SIMD.  With a
-// single wave per SIMD nothing hides a stall, so the loop is software-pipelined
-// by hand and the instruction mix is pinned with sched_group_barrier:
-//   * BK = 32 tiles in a 3-stage LDS ring; iteration kt multiplies stage kt%3,
-//     writes tile kt+2 (loaded one iteration earlier into registers) to stage
-//     (kt+2)%3 and issues the global loads of tile kt+3; one barrier per
-//     iteration.  Stage (kt+1)%3 is complete before iteration kt starts, so the
-//     first fragments of the next tile are read under the last MFMAs of this one.
-//   * every LDS read, LDS write and global load is issued between two MFMAs.
-// LDS rows are 64 bytes here (4 pieces); the 64 banks span 4 rows, so piece p of
-// row r sits at slot p ^ ((r >> 2) & 3).
-// ---------------------------------------------------------------------------
+// 256-row tiles with k-steps of 32: LDS rows are 64 bytes (4 pieces); the 64 banks span 4 rows, so piece p
+// of row r sits at slot p ^ ((r >> 2) & 3).
 constexpr int L_BK = 32, L_BM = 256, L_STAGE = (L_BM + G_BN) * L_BK;   // bf16 elements per stage
 
 __device__ __forceinline__ int lds_slot32(int row, int piece) { return row * L_BK + ((piece ^ ((row >> 2) & 3)) << 3); }
 
-template <bool DUAL>
-__global__ void __launch_bounds__(256) grouped_gemm256_bf16_kernel(GemmParams p) {
-    __shared__ __attribute__((aligned(16))) uint16_t smem[3 * L_STAGE];          // 96 KB
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int wm = wave >> 1, wn = wave & 1;
-    const int r32 = lane & 31, half = lane >> 5;
-
-    const int n_mt = p.n_mtiles[0];
-    const int n_nt = DUAL ? (p.N + 127) / 128 : (p.N + 255) / 256;
-    const int total = n_mt * n_nt;
-    const int per_xcd = (total + 7) >> 3;
-    const int lid = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
-    if ((int)(blockIdx.x >> 3) >= per_xcd || lid >= total) return;
-    int mt, nt;
-    tile_of(lid, n_mt, n_nt, mt, nt);
-
-    const int g = p.mt_group[mt];
-    const int row0 = p.mt_row0[mt];
-    const int row_end = p.offsets[g + 1];
-    const int n0 = nt * (DUAL ? 128 : 256);
-    const int N = p.N, Kd = p.Kd;
-
-    const uint16_t *a = static_cast<const uint16_t *>(p.a);
-    const uint16_t *b0, *b1;
-    if (g < p.E) {
-        b0 = static_cast<const uint16_t *>(p.b0) + (size_t)g * N * Kd;
-        b1 = DUAL ? static_cast<const uint16_t *>(p.b1) + (size_t)g * N * Kd : nullptr;
-    } else {
-        b0 = static_cast<const uint16_t *>(p.sb0) + (size_t)(g - p.E) * N * Kd;
-        b1 = DUAL ? static_cast<const uint16_t *>(p.sb1) + (size_t)(g - p.E) * N * Kd : nullptr;
-    }
-
-    // global sources: thread covers rows lrow + 64*i, one 16-byte piece (4 per 64-byte tile row)
-    const int lrow = tid >> 2, chunk = tid & 3;
-    const uint16_t *pa[4];
-    const uint16_t *pb[4];
-    int s_off[8];                                      // LDS destinations inside a stage (A rows, then B rows)
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        const int r = lrow + 64 * i;
-        const int pos = min(row0 + r, row_end - 1);
-        const int src = p.row_map ? p.row_map[pos] : pos;
-        pa[i] = a + (size_t)src * Kd + chunk * 8;
-        s_off[i] = lds_slot32(r, chunk);
-        if (DUAL) {
-            const int f = min(n0 + (r & 127), N - 1);
-            pb[i] = ((r >> 7) ? b1 : b0) + (size_t)f * Kd + chunk * 8;
-        } else {
-            const int n = min(n0 + r, N - 1);
-            pb[i] = b0 + (size_t)n * Kd + chunk * 8;
-        }
-        s_off[4 + i] = L_BM * L_BK + lds_slot32(r, chunk);
-    }
-
-    // fragment sources inside a stage: 4 row blocks of A, 4 of B, for k-step 0 and 1
-    int fa_off[2][4], fb_off[2][4];
-#pragma unroll
-    for (int kk = 0; kk < 2; ++kk)
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const int ar = wm * 128 + i * 32 + r32;
-            const int br = DUAL ? ((i >> 1) * 128 + wn * 64 + (i & 1) * 32 + r32) : (wn * 128 + i * 32 + r32);
-            fa_off[kk][i] = lds_slot32(ar, kk * 2 + half);
-            fb_off[kk][i] = L_BM * L_BK + lds_slot32(br, kk * 2 + half);
-        }
-
-    f32x16 acc[4][4];
-#pragma unroll
-    for (int i = 0; i < 4; ++i)
-#pragma unroll
-        for (int j = 0; j < 4; ++j)
-#pragma unroll
-            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
-
-    const int KT = Kd / L_BK;
-    u32x4 rg[2][8];                                    // two register sets of one tile each
-    bf16x8 f0a[4], f0b[4], f1a[4], f1b[4];
-
-#define BM_GLOAD(set_, tile_)                                                              \
-    {                                                                                      \
-        const int k0_ = min((tile_), KT - 1) * L_BK;                                       \
-        _Pragma("unroll") for (int i = 0; i < 4; ++i) rg[set_][i] = ldg128(pa[i] + k0_);   \
-        _Pragma("unroll") for (int i = 0; i < 4; ++i) rg[set_][4 + i] = ldg128(pb[i] + k0_); \
-    }
-#define BM_SSTORE(set_, stage_)                                                            \
-    {                                                                                      \
-        uint16_t *st_ = smem + (stage_) * L_STAGE;                                         \
-        _Pragma("unroll") for (int i = 0; i < 8; ++i)                                      \
-            *reinterpret_cast<u32x4 *>(st_ + s_off[i]) = rg[set_][i];                      \
-    }
-#define BM_FREAD(fa_, fb_, stage_, kk_)                                                    \
-    {                                                                                      \
-        const uint16_t *st_ = smem + (stage_) * L_STAGE;                                   \
-        _Pragma("unroll") for (int i = 0; i < 4; ++i)                                      \
-            fa_[i] = as_bf16x8(*reinterpret_cast<const u32x4 *>(st_ + fa_off[kk_][i]));    \
-        _Pragma("unroll") for (int i = 0; i < 4; ++i)                                      \
-            fb_[i] = as_bf16x8(*reinterpret_cast<const u32x4 *>(st_ + fb_off[kk_][i]));    \
-    }
-#define BM_MFMA16(fa_, fb_)                                                                \
-    _Pragma("unroll") for (int i = 0; i < 4; ++i)                                          \
-        _Pragma("unroll") for (int j = 0; j < 4; ++j)                                      \
-            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa_[i], fb_[j], acc[i][j], 0, 0, 0);
-
-    // prologue: tiles 0 and 1 in stages 0 and 1, tile 2 in register set 0, first fragments loaded
-    BM_GLOAD(0, 0);
-    BM_GLOAD(1, 1);
-    BM_SSTORE(0, 0);
-    BM_SSTORE(1, 1);
-    BM_GLOAD(0, 2);
-    __syncthreads();
-    BM_FREAD(f0a, f0b, 0, 0);
-
-    int st_cur = 0, st_nxt = 1, st_wr = 2;
-    for (int kt = 0; kt < KT; kt += 2) {
-        // two iterations per trip so that the register-set index is a compile-time constant
-#pragma unroll
-        for (int h = 0; h < 2; ++h) {
-            BM_FREAD(f1a, f1b, st_cur, 1);             // k-step 1 of this tile, under the first MFMAs
-            BM_GLOAD(1 - h, kt + h + 3);               // tile kt+3 -> the register set written out last iteration
-            BM_MFMA16(f0a, f0b);
-            BM_FREAD(f0a, f0b, st_nxt, 0);             // first fragments of the next tile
-            BM_SSTORE(h, st_wr);                       // tile kt+2 (loaded one iteration ago)
-            BM_MFMA16(f1a, f1b);
-            // instruction mix: one LDS read / global load / LDS write between consecutive MFMAs
-            _Pragma("unroll") for (int q = 0; q < 8; ++q) {
-                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   // MFMA
-                __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);   // DS read  (f1)
-            }
-            _Pragma("unroll") for (int q = 0; q < 8; ++q) {
-                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-                __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);   // VMEM read
-            }
-            _Pragma("unroll") for (int q = 0; q < 8; ++q) {
-                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-                __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);   // DS read  (next f0)
-            }
-            _Pragma("unroll") for (int q = 0; q < 8; ++q) {
-                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-                __builtin_amdgcn_sched_group_barrier(0x200, 1, 0);   // DS write
-            }
-            __syncthreads();
-            const int t = st_cur; st_cur = st_nxt; st_nxt = st_wr; st_wr = t;
-        }
-    }
-#undef BM_GLOAD
-#undef BM_SSTORE
-#undef BM_FREAD
-#undef BM_MFMA16
-
-    uint16_t *c = static_cast<uint16_t *>(p.c);
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-#pragma unroll
-        for (int v = 0; v < 16; ++v) {
-            const int row = row0 + wm * 128 + i * 32 + 8 * (v >> 2) + 4 * half + (v & 3);
-            if (row >= row_end) continue;
-            if (DUAL) {
-#pragma unroll
-                for (int jj = 0; jj < 2; ++jj) {
-                    const int f = n0 + wn * 64 + jj * 32 + r32;
-                    if (f < N) stg16(&c[(size_t)row * N + f], f32_to_bf16(silu(acc[i][jj][v]) * acc[i][2 + jj][v]));
-                }
-            } else {
-#pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    const int n = n0 + wn * 128 + j * 32 + r32;
-                    if (n < N) stg16(&c[(size_t)row * N + n], f32_to_bf16(acc[i][j][v]));
-                }
-            }
-        }
-    }
-}
-
 // ---------------------------------------------------------------------------
-// Same tile and wave layout, but the tiles go from global memory straight into
+// Fallback for reductions that are a multiple of 32 but not of 64.  256 rows x 256 weight rows per
+// workgroup, 4 waves (2 x 2) with wave tiles of 128 x 128; the tiles go from global memory straight into
 // LDS (global_load_lds_dwordx4: each lane's 16 bytes land at M0 + 16 * lane, so
 // one instruction fills 16 tile rows of 64 bytes; the swizzle is applied by
 // choosing which piece a lane fetches).  No staging registers, no LDS-write
 // instructions, and a 5-stage ring over the whole 160 KB of LDS: the loads of
-// tile kt+4 are issued in iteration kt and first needed three iterations later
-// (three tiles, 96 KB, in flight per compute unit: the kernel is bound by the
-// latency of its L2 traffic, about 57 GB/s per compute unit at 1 PFLOP/s).
+// tile kt+4 are issued in iteration kt and first needed three iterations later.
+// Its 64-byte row pieces use half of every cache line they fetch, which is what
+// the k-step-64 kernels below avoid.
 //   iteration kt:  wait until tile kt+1 has landed (at most the 16 loads of tiles
 //   kt+2, kt+3 outstanding) -> barrier (every wave's part of tile kt+1 is in LDS
 //   and every wave is done with stage (kt-1)%5) -> issue tile kt+4 into stage
