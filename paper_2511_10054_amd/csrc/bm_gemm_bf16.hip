@@ -15,7 +15,7 @@
 //                                latter with a reduction-split tail for long reductions)
 //   grouped_gemm256_dma          BM = 256, k-steps of 32 (reduction not a multiple of 64, or offsets
 //                                beyond 32 bits)
-//   grouped_gemm_bf16_kernel     BM = 128, 8 waves, register-staged double buffer, for groups too small
+//   grouped_gemm_bf16_kernel     BM = 128, 4 waves, register-staged double buffer, for groups too small
 //                                for 256-row tiles
 // LDS rows of 128 bytes: the 64 banks span two rows, so piece p of row r is stored at slot
 // p ^ ((r >> 1) & 7); the 16 lanes of one ds_read_b128 pass (16 rows, same p) then hit 16 distinct
