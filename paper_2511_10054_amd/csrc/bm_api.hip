@@ -39,9 +39,16 @@ bool use_skinny(const bm_layer_desc *d) {
 int skinny_ksplit(const bm_layer_desc *d) {
     // small groups: the persistent kernel splits the reduction inside one workgroup, no slices
     if ((long long)d->T * d->K <= 32 && (bm::skinny_p_ok(d->F, 14) || bm::skinny_p_ok(d->F, 8))) return 1;
-    if ((long long)d->T * d->K > 32)
+    if ((long long)d->T * d->K > 32) {
+        // LDS-staged kernel: the fewest slices that still give every compute unit two workgroups (64 weight
+        // rows each) - longer weight streams per workgroup and fewer fp32 partial outputs beat a finer
+        // split (measured on the Mixtral-shaped layer: 2 slices 107 us, 4: 114, 7: 120, 14: 129)
+        const long long groups = d->E + d->n_shared < (long long)d->T * d->K ? d->E + d->n_shared : (long long)d->T * d->K;
+        for (int s = 2; s <= SKINNY_KSPLIT; ++s)
+            if (bm::skinny_lds_ok(d->F, s) && d->F / (512 * s) >= 2 && (d->d / 64) * groups * s >= 512) return s;
         for (int s = SKINNY_KSPLIT; s > 1; --s)
             if (bm::skinny_lds_ok(d->F, s) && d->F / (512 * s) >= 2) return s;
+    }
     for (int s = SKINNY_KSPLIT; s >= 1; --s)
         if (bm::skinny_q_ok(d->F, s)) return s;
     const int ksteps = d->F / 32;
