@@ -895,15 +895,16 @@ __global__ void __launch_bounds__(256) grouped_gemm256_k64w_bf16_kernel(GemmPara
         for (int kt = 0; kt < KT; ++kt) {
             {
                 // first k slice of 32: 64 MFMAs; the second slice's fragments are read under MFMAs 0-31 (one
-                // read per two MFMAs), the 8 loads of B(kt+2) go into the slot A(kt-1) has left under MFMAs
-                // 33, 37, ..., 61
+                // read per two MFMAs), the 8 loads of B(kt+2) go into the slot A(kt-1) has left, one under
+                // every eighth MFMA (spread evenly: bunched loads hold up the MFMAs behind them at issue;
+                // measured 5 % on the whole kernel)
                 const uint16_t *sa_ = smem + sA * P_PART + fa_off[1];
                 const uint16_t *sb_ = smem + sB * P_PART + fb_off[1];
 #pragma unroll
                 for (int m = 0; m < 64; ++m) {
                     BM_MFMA1(m, f0a, f0b);
                     if (m < 32 && (m & 1) == 0) BM_RD(m >> 1, f1a, f1b, sa_, sb_)
-                    else if (m > 32 && (m & 3) == 1) BM_DMA_B(sAp, kt + 2, (m - 33) >> 2);
+                    if ((m & 7) == 5) BM_DMA_B(sAp, kt + 2, m >> 3);
                     __builtin_amdgcn_sched_barrier(0);
                 }
             }
@@ -914,15 +915,15 @@ __global__ void __launch_bounds__(256) grouped_gemm256_k64w_bf16_kernel(GemmPara
             BM_BARE_BARRIER();
             const int sBn = sB >= 3 ? sB - 3 : sB + 2, sAn = sA >= 3 ? sA - 3 : sA + 2;
             {
-                // second slice: A(kt+2) goes into the slot B(kt) has left, one load under every fourth MFMA
-                // of the first half; the first fragments of k-step kt+1 are read under the second half
+                // second slice: A(kt+2) goes into the slot B(kt) has left, one load under every eighth MFMA;
+                // the first fragments of k-step kt+1 are read under the second half
                 const uint16_t *sa_ = smem + sAn * P_PART + fa_off[0];
                 const uint16_t *sb_ = smem + sBn * P_PART + fb_off[0];
 #pragma unroll
                 for (int m = 0; m < 64; ++m) {
                     BM_MFMA1(m, f1a, f1b);
-                    if (m < 32 && (m & 3) == 0) BM_DMA_A(sB, kt + 2, m >> 2);
-                    else if (m >= 32 && (m & 1) == 0) BM_RD((m - 32) >> 1, f0a, f0b, sa_, sb_)
+                    if ((m & 7) == 1) BM_DMA_A(sB, kt + 2, m >> 3);
+                    if (m >= 32 && (m & 1) == 0) BM_RD((m - 32) >> 1, f0a, f0b, sa_, sb_)
                     __builtin_amdgcn_sched_barrier(0);
                 }
             }
