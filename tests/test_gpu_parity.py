@@ -360,3 +360,43 @@ def test_gated_layer_matches_oracle(name, over, T, unique):
     assert ref["stats"]["bypassed"] == 1 and ref["stats"]["n_substituted"] == 0
     out, ref, _ = _check_layer(host, unique, beta=open_, tau=tau)
     assert ref["stats"]["bypassed"] == 0 and ref["stats"]["n_substituted"] > 0
+
+
+# ------------------------------------------------------------------ HIP graph
+
+
+@pytest.mark.parametrize("name,over,T", [("c2_mixtral_decode", dict(d=512, F=1024), 8),
+                                         ("c2_mixtral_decode", dict(d=1024, F=2048), 64),
+                                         ("c5_deepseek", dict(d=256, F=352), 500)])
+def test_forward_replays_from_a_hip_graph(name, over, T):
+    """The whole layer is a fixed sequence of kernel launches on the caller's stream (no allocation, no
+    synchronisation, no memset): captured once, replayed with new inputs in the same buffers, with eager
+    work in between, every replay must equal the eager result for those inputs."""
+    torch = _torch()
+    spec = workloads.scaled(name, **over)
+    _say("graph", name, T)
+    hosts = [HostLayer(spec, T, stream=s) for s in (0, 1, 2)]
+    dev = DeviceLayer(hosts[0], unique=True, rho=1)
+    eager = []
+    for h in hosts:                                             # eager results for the three inputs
+        dev.x.copy_(to_device(h.x))
+        eager.append(dev.forward(debug=False)["y"].copy())
+    assert not np.array_equal(eager[0], eager[1])
+    dev.x.copy_(to_device(hosts[0].x))
+    side = torch.cuda.Stream()                                  # default priority
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        dev.bm.bm_moe_forward(dev.desc, dev.x, dev.weights, dev.bitmap, dev.table, dev.y, dev.workspace, None)  # warm-up
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        dev.bm.bm_moe_forward(dev.desc, dev.x, dev.weights, dev.bitmap, dev.table, dev.y, dev.workspace, None)
+    for rep in range(2):
+        for i in (2, 0, 1):
+            dev.x.copy_(to_device(hosts[i].x))
+            dev.y.zero_()                                       # eager work between the replays
+            torch.cuda.synchronize()
+            graph.replay()
+            torch.cuda.synchronize()
+            np.testing.assert_array_equal(dev.y.float().cpu().numpy(), eager[i], err_msg=f"replay {rep} input {i}")
