@@ -2,7 +2,9 @@
 //
 // Rows are the surviving assignments, grouped by expert; a row-tile table
 // built on the device says which group each tile of BM rows belongs to.  One
-// workgroup computes BM rows x 256 weight rows with fp32 accumulators:
+// workgroup computes BM rows x 256 weight rows with fp32 accumulators (v_mfma_f32_16x16x32_bf16 in the
+// main kernel - per flop it draws less power than the 32 x 32 x 16 form, and these kernels run against
+// the chip's power limit - v_mfma_f32_32x32x16_bf16 in the fallbacks):
 //   DUAL  : the 256 weight rows are 128 rows of W_gate and the same 128 rows
 //           of W_up; the epilogue writes h = silu(g) * u as bf16.
 //   !DUAL : 256 rows of W_down; the epilogue writes the product as bf16.
@@ -10,9 +12,9 @@
 // operand (8 consecutive k) is one 16-byte piece of a row.
 //
 // Kernels, in the order the launchers prefer them:
-//   grouped_gemm256_k64w / k64   BM = 256, persistent, k-steps of 64 with whole-line direct-to-LDS
-//                                loads (gate/up on the 16x16x32 MFMA, down on the 32x32x16 one, the
-//                                latter with a reduction-split tail for long reductions)
+//   grouped_gemm256_k64w         BM = 256, persistent, k-steps of 64 with whole-line direct-to-LDS
+//                                loads, v_mfma_f32_16x16x32_bf16; the down projection with a
+//                                reduction-split tail for long reductions
 //   grouped_gemm256_dma          BM = 256, k-steps of 32 (reduction not a multiple of 64, or offsets
 //                                beyond 32 bits)
 //   grouped_gemm_bf16_kernel     BM = 128, 4 waves, register-staged double buffer, for groups too small
@@ -443,14 +445,14 @@ constexpr int SPLIT_TILE_FLOATS = 256 * 256;
 // SPLIT: compile the reduction-split tail in (kept out of the other instantiations: its write-out of raw
 // accumulators costs registers that short tiles cannot afford to spill around)
 template <bool DUAL, bool SPLIT>
-__global__ void __launch_bounds__(256) grouped_gemm256_k64_bf16_kernel(GemmParams p) {
+__global__ void __launch_bounds__(256) grouped_gemm256_k64w_bf16_kernel(GemmParams p) {
     __shared__ __attribute__((aligned(1024))) uint16_t smem[5 * P_PART];         // 160 KB: the whole LDS
     const int tid = threadIdx.x, lane = tid & 63;
     // the wave index as a scalar: everything derived from it (LDS targets of the loads, tile halves) then
     // stays in scalar registers and costs no vector instructions in the main loop
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wm = wave >> 1, wn = wave & 1;
-    const int r32 = lane & 31, half = lane >> 5;
+    const int r16 = lane & 15, quad = lane >> 4;           // MFMA 16x16x32: row (or column) and k eighth
 
     // Persistent: workgroup b serves the XCD it was dealt to (b % 8) and walks that XCD's share of the
     // logical tiles with stride (workgroups per XCD), so the workgroups that run together on an XCD work
@@ -491,306 +493,6 @@ __global__ void __launch_bounds__(256) grouped_gemm256_k64_bf16_kernel(GemmParam
     bool have;
     BM_NEXT_ITEM(have);
     if (!have) return;
-
-    const uint16_t *a = static_cast<const uint16_t *>(p.a);
-    uint16_t *c = static_cast<uint16_t *>(p.c);
-
-    // fragment offsets inside a part, per 16-wide k slice s: row (.. + r32), piece 2*s + half
-    int fa_off[4], fb_off[4];
-#pragma unroll
-    for (int s = 0; s < 4; ++s) {
-        const int pc = ((2 * s + half) ^ ((r32 >> 1) & 7)) << 3;
-        fa_off[s] = (wm * 128 + r32) * 64 + pc;
-        fb_off[s] = (DUAL ? (wn * 64 + r32) : (wn * 128 + r32)) * 64 + pc;
-    }
-
-    f32x16 acc[4][4];
-    bf16x8 f0a[4], f0b[4], f1a[4], f1b[4];
-    // Load addresses are (uniform base + k offset) + a 32-bit byte offset per lane, so that the k advance
-    // is scalar arithmetic and a load needs no vector address computation.
-    uint32_t oa[8], ob[8];
-    const uint16_t *base_b0, *base_b1;
-    int row0, row_end, n0;                             // of the tile whose loads are being issued
-
-// Pointers of logical tile lid_.  Load instruction j of this wave fills the 1 KB block (4*j + wave) of a
-// part: 8 tile rows of 128 bytes.  Lane i supplies row 8*block + i/8 and LDS slot i%8 of it, i.e.
-// global piece (i % 8) ^ ((row >> 1) & 7).
-#define BM_SETUP(lid_)                                                                             \
-    {                                                                                              \
-        int mt_, nt_;                                                                              \
-        tile_of((lid_), n_mt, n_nt, mt_, nt_);                                                     \
-        const int g_ = p.mt_group[mt_];                                                            \
-        row0 = p.mt_row0[mt_];                                                                     \
-        row_end = p.offsets[g_ + 1];                                                               \
-        n0 = nt_ * (DUAL ? 128 : 256);                                                             \
-        if (g_ < p.E) {                                                                            \
-            base_b0 = static_cast<const uint16_t *>(p.b0) + (size_t)g_ * N * Kd;                   \
-            base_b1 = DUAL ? static_cast<const uint16_t *>(p.b1) + (size_t)g_ * N * Kd : base_b0;  \
-        } else {                                                                                   \
-            base_b0 = static_cast<const uint16_t *>(p.sb0) + (size_t)(g_ - p.E) * N * Kd;          \
-            base_b1 = DUAL ? static_cast<const uint16_t *>(p.sb1) + (size_t)(g_ - p.E) * N * Kd : base_b0; \
-        }                                                                                          \
-        _Pragma("unroll") for (int j = 0; j < 8; ++j) {                                            \
-            const int r_ = 8 * (4 * j + wave) + (lane >> 3);                                       \
-            const int piece_ = (lane & 7) ^ ((r_ >> 1) & 7);                                       \
-            const int pos_ = min(row0 + r_, row_end - 1);                                          \
-            const int src_ = p.row_map ? p.row_map[pos_] : pos_;                                   \
-            oa[j] = ((uint32_t)src_ * (uint32_t)Kd + piece_ * 8) * 2u;                             \
-            /* DUAL: rows 0-127 of the part are W_gate rows (loads 0-3), rows 128-255 W_up rows (4-7) */ \
-            const int n_ = DUAL ? min(n0 + (r_ & 127), N - 1) : min(n0 + r_, N - 1);               \
-            ob[j] = ((uint32_t)n_ * (uint32_t)Kd + piece_ * 8) * 2u;                               \
-        }                                                                                          \
-    }
-// load j_ of the activation part (A) / weight part (B) of k-step tile_ into slot_
-#define BM_DMA_AT(base_, off_, slot_, tile_, j_)                                                   \
-    __builtin_amdgcn_global_load_lds(                                                              \
-        (const BM_GLOBAL void *)(reinterpret_cast<const char *>((base_) + min((tile_), kend - 1) * 64) + (off_)), \
-        (BM_LDS void *)(smem + (slot_) * P_PART + wave * 512 + (j_) * 2048), 16, 0, 0)
-#define BM_DMA_A(slot_, tile_, j_) BM_DMA_AT(a, oa[j_], slot_, tile_, j_)
-#define BM_DMA_B(slot_, tile_, j_) BM_DMA_AT(((j_) < 4 ? base_b0 : base_b1), ob[j_], slot_, tile_, j_)
-// B(0) A(0) B(1) A(1) of the tile set up last into slots 0..3
-#define BM_PROLOGUE()                                                                              \
-    {                                                                                              \
-        _Pragma("unroll") for (int j = 0; j < 8; ++j) BM_DMA_B(0, kbeg, j);                        \
-        _Pragma("unroll") for (int j = 0; j < 8; ++j) BM_DMA_A(1, kbeg, j);                        \
-        _Pragma("unroll") for (int j = 0; j < 8; ++j) BM_DMA_B(2, kbeg + 1, j);                    \
-        _Pragma("unroll") for (int j = 0; j < 8; ++j) BM_DMA_A(3, kbeg + 1, j);                    \
-    }
-#define BM_LD(ptr_) as_bf16x8(*reinterpret_cast<const u32x4 *>(ptr_))
-#define BM_BOFF(i_) (DUAL ? (((i_) >> 1) * 8192 + ((i_) & 1) * 2048) : (i_) * 2048)
-// fragment read d_ of 8, in the order the MFMAs need them: a0 b0 b1 b2 b3 a1 a2 a3
-#define BM_RD(d_, fa_, fb_, sa_, sb_)                                                              \
-    {                                                                                              \
-        if ((d_) == 0) fa_[0] = BM_LD(sa_);                                                        \
-        else if ((d_) <= 4) fb_[(d_) - 1] = BM_LD((sb_) + BM_BOFF((d_) - 1));                      \
-        else fa_[(d_) - 4] = BM_LD((sa_) + ((d_) - 4) * 2048);                                     \
-    }
-#define BM_MFMA1(m_, fa_, fb_)                                                                     \
-    acc[(m_) >> 2][(m_) & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa_[(m_) >> 2], fb_[(m_) & 3], \
-                                                                        acc[(m_) >> 2][(m_) & 3], 0, 0, 0)
-// one 16-wide k slice: 16 MFMAs on (fa_, fb_); under MFMAs 0-7 the fragments of the next slice are read
-// into (na_, nb_); under MFMAs 9, 12, 15 up to three loads j0_.. of B(kt+2) are issued.  The
-// scheduling fences keep this interleaving as written.
-#define BM_SLICE(fa_, fb_, na_, nb_, s_next, j0_, nj_)                                             \
-    {                                                                                              \
-        const uint16_t *sa_ = smem + sA * P_PART + fa_off[s_next];                                 \
-        const uint16_t *sb_ = smem + sB * P_PART + fb_off[s_next];                                 \
-        _Pragma("unroll") for (int m = 0; m < 16; ++m) {                                           \
-            BM_MFMA1(m, fa_, fb_);                                                                 \
-            if (m < 8) BM_RD(m, na_, nb_, sa_, sb_)                                                \
-            else if (m == 9 && (nj_) > 0) BM_DMA_B(sAp, kt + 2, (j0_));                          \
-            else if (m == 12 && (nj_) > 1) BM_DMA_B(sAp, kt + 2, (j0_) + 1);                     \
-            else if (m == 15 && (nj_) > 2) BM_DMA_B(sAp, kt + 2, ((j0_) + 2) & 7);               \
-            __builtin_amdgcn_sched_barrier(0);                                                     \
-        }                                                                                          \
-    }
-
-    BM_SETUP(xcd * per_xcd + item_tile);
-    BM_PROLOGUE();
-    for (;;) {
-        const int t_row0 = row0, t_row_end = row_end, t_n0 = n0;    // the tile being multiplied
-        const bool t_partial = partial;
-        const int t_kbeg = kbeg, t_kend = kend;
-#pragma unroll
-        for (int i = 0; i < 4; ++i)
-#pragma unroll
-            for (int j = 0; j < 4; ++j)
-#pragma unroll
-                for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
-        // B(0) and A(0) have landed: vector memory operations complete in issue order, and whatever was
-        // issued after them (B(1), A(1), then the previous tile's stores), at most the 16 youngest are
-        // still out, which leaves B(0) and A(0) done however many store instructions there were
-        BM_WAIT_VMCNT(16);
-        BM_BARE_BARRIER();
-        {
-            const uint16_t *sa_ = smem + 1 * P_PART + fa_off[0];
-            const uint16_t *sb_ = smem + 0 * P_PART + fb_off[0];
-#pragma unroll
-            for (int d = 0; d < 8; ++d) BM_RD(d, f0a, f0b, sa_, sb_)
-        }
-
-        int sB = 0, sA = 1, sAp = 4;                   // slots of B(kt), A(kt), A(kt-1)
-        for (int kt = t_kbeg; kt < t_kend; ++kt) {
-            BM_SLICE(f0a, f0b, f1a, f1b, 1, 0, 3);     // B(kt+2) loads 0-2 go into the slot A(kt-1) has left
-            BM_SLICE(f1a, f1b, f0a, f0b, 2, 3, 3);
-            BM_SLICE(f0a, f0b, f1a, f1b, 3, 6, 2);
-            // every fragment of B(kt), A(kt) is in registers; A(kt+1), B(kt+1) have landed (this wave's
-            // part: at most the 8 loads of B(kt+2) are outstanding); after the barrier both hold for
-            // every wave
-            BM_WAIT_VM_LGKM(8, 0);
-            BM_BARE_BARRIER();
-            const int sBn = sB >= 3 ? sB - 3 : sB + 2, sAn = sA >= 3 ? sA - 3 : sA + 2;
-            {
-                // last slice: A(kt+2) goes into the slot B(kt) has left, one load under every other
-                // MFMA, the first fragments of k-step kt+1 are read under the others
-                const uint16_t *sa_ = smem + sAn * P_PART + fa_off[0];
-                const uint16_t *sb_ = smem + sBn * P_PART + fb_off[0];
-#pragma unroll
-                for (int m = 0; m < 16; ++m) {
-                    BM_MFMA1(m, f1a, f1b);
-                    if ((m & 1) == 0) BM_DMA_A(sB, kt + 2, m >> 1);
-                    else BM_RD(m >> 1, f0a, f0b, sa_, sb_)
-                    __builtin_amdgcn_sched_barrier(0);
-                }
-            }
-            sAp = sA;
-            sB = sBn;
-            sA = sAn;
-        }
-        // The tile is done.  Loads past its last k-step (clamped repeats) may still be landing and other
-        // waves may still be reading fragments: drain both, then start the next tile's loads so that they
-        // fly while this tile is written out.
-        BM_WAIT_VM_LGKM(0, 0);
-        BM_BARE_BARRIER();
-        bool more;                                     // uniform over the workgroup
-        BM_NEXT_ITEM(more);
-        if (more) {
-            BM_SETUP(xcd * per_xcd + item_tile);
-            BM_PROLOGUE();
-        }
-
-        if (SPLIT && t_partial) {
-            // chunk of a split tile: the fp32 accumulators go to this workgroup's scratch tile as they are
-            // (accumulator tile, quarter, lane: 16-byte stores, contiguous over the lanes)
-            float *dst = p.splitk + (size_t)(xcd * stride + slot) * SPLIT_TILE_FLOATS + (wave * 64 + lane) * 4;
-#pragma unroll
-            for (int i = 0; i < 4; ++i)
-#pragma unroll
-                for (int j = 0; j < 4; ++j)
-#pragma unroll
-                    for (int q = 0; q < 4; ++q) {
-                        const f32x4 v4 = {acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]};
-                        *(BM_GLOBAL f32x4 *)(dst + ((i * 4 + j) * 4 + q) * 1024) = v4;
-                    }
-            if (!more) break;
-            continue;
-        }
-
-        // Write-out through the free fifth slot (8 KB per wave): the accumulators hold one column per lane,
-        // so they are first laid out row-major in LDS as bf16 - neighbouring lanes swap one value so that
-        // every lane writes a packed pair - and read back as 16-byte pieces: one store instruction then
-        // writes whole 128-byte lines (8 x fewer instructions than 2-byte stores straight from the
-        // accumulators).  A wave uses only its own region and LDS operations of a wave stay in order.
-        {
-            constexpr int OC = DUAL ? 2 : 4;            // 32-column output blocks per wave
-            constexpr int CR = DUAL ? 32 : 16;          // rows per chunk
-            constexpr int SD = DUAL ? 32 : 80;          // LDS row stride in dwords (padded: conflict-free)
-            constexpr int PR = OC * 4;                  // 16-byte pieces per output row
-            uint32_t *stage = reinterpret_cast<uint32_t *>(smem + 4 * P_PART) + wave * 2048;
-            const bool odd = lane & 1;
-#pragma unroll
-            for (int i = 0; i < 4; ++i) {
-#pragma unroll
-                for (int ch = 0; ch < 32 / CR; ++ch) {
-#pragma unroll
-                    for (int j = 0; j < OC; ++j) {
-#pragma unroll
-                        for (int vv = 0; vv < CR / 2; vv += 2) {
-                            const int v = ch * (CR / 2) + vv;          // even; rows of v and v+1 are adjacent
-                            float x0, x1;
-                            if (DUAL) {
-                                x0 = silu(acc[i][j][v]) * acc[i][2 + j][v];
-                                x1 = silu(acc[i][j][v + 1]) * acc[i][2 + j][v + 1];
-                            } else {
-                                x0 = acc[i][j][v];
-                                x1 = acc[i][j][v + 1];
-                            }
-                            // even lane keeps row v and gets the right-hand neighbour's value of that row;
-                            // odd lane keeps row v+1 and gets the left-hand neighbour's
-                            const float send = odd ? x0 : x1;
-                            const float recv = __builtin_bit_cast(
-                                float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, send), 0xB1, 0xF, 0xF, true));
-                            const uint32_t pk = odd ? pack_bf16x2(recv, x1) : pack_bf16x2(x0, recv);
-                            const int lrow = 8 * ((v >> 2) - ch * (CR / 8)) + 4 * half + (v & 3) + (odd ? 1 : 0);
-                            stage[lrow * SD + j * 16 + (r32 >> 1)] = pk;
-                        }
-                    }
-#pragma unroll
-                    for (int t = 0; t < 4; ++t) {
-                        const int q = lane + 64 * t;
-                        const int lrow = q / PR, pc = q % PR;
-                        const u32x4 val = *reinterpret_cast<const u32x4 *>(stage + lrow * SD + pc * 4);
-                        const int row = t_row0 + wm * 128 + i * 32 + ch * CR + lrow;
-                        const int col = t_n0 + wn * (OC * 32) + pc * 8;
-                        if (row < t_row_end && col < N) stg128(&c[(size_t)row * N + col], val);
-                    }
-                }
-            }
-        }
-        if (!more) break;
-    }
-#undef BM_SETUP
-#undef BM_NEXT_ITEM
-#undef BM_PROLOGUE
-#undef BM_DMA_AT
-#undef BM_DMA_A
-#undef BM_DMA_B
-#undef BM_LD
-#undef BM_BOFF
-#undef BM_RD
-#undef BM_MFMA1
-#undef BM_SLICE
-}
-
-// Adds the chunks of every split tail tile in chunk order and writes the bf16 result (see TailSplit).
-// Grid (16 tail tiles, 8 XCDs, 16 slices of a tile): a workgroup handles one sixteenth of a tile - the
-// accumulator tiles (i, j) with i * 4 + j == blockIdx.z - with the chunk writers' thread -> element
-// mapping, so that the reduction itself is spread over the chip.
-__global__ void __launch_bounds__(256) splitk_fixup_kernel(GemmParams p) {
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int wm = wave >> 1, wn = wave & 1, r32 = lane & 31, half = lane >> 5;
-    const int n_mt = p.n_mtiles[0];
-    const int n_nt = (p.N + 255) / 256;
-    const int total = n_mt * n_nt;
-    const int per_xcd = (total + 7) >> 3;
-    const int xcd = blockIdx.y, stride = p.splitk_stride, t = blockIdx.x;
-    const TailSplit ts = tail_split(total, per_xcd, xcd, stride, p.Kd / 64, true);
-    if (ts.S < 2 || t >= ts.rem) return;
-    int mt, nt;
-    tile_of(xcd * per_xcd + ts.full + t, n_mt, n_nt, mt, nt);
-    const int g = p.mt_group[mt];
-    const int row0 = p.mt_row0[mt], row_end = p.offsets[g + 1], n0 = nt * 256, N = p.N;
-    uint16_t *c = static_cast<uint16_t *>(p.c);
-    const float *src = p.splitk + (size_t)(xcd * stride + t * ts.S) * SPLIT_TILE_FLOATS + (wave * 64 + lane) * 4;
-    const int i = blockIdx.z >> 2, j = blockIdx.z & 3;
-    for (int q = 0; q < 4; ++q) {
-        f32x4 sum = {0.0f, 0.0f, 0.0f, 0.0f};
-        for (int ch = 0; ch < ts.S; ++ch)
-            sum += *(const BM_GLOBAL f32x4 *)(src + (size_t)ch * SPLIT_TILE_FLOATS + ((i * 4 + j) * 4 + q) * 1024);
-        const int n = n0 + wn * 128 + j * 32 + r32;
-        for (int e = 0; e < 4; ++e) {
-            const int row = row0 + wm * 128 + i * 32 + 8 * q + 4 * half + e;
-            if (row < row_end && n < N) stg16(&c[(size_t)row * N + n], f32_to_bf16(sum[e]));
-        }
-    }
-}
-
-// The same kernel on v_mfma_f32_16x16x32_bf16: per flop the 16 x 16 form draws less power than the
-// 32 x 32 one, and these kernels run against the chip's power limit, so the clock it leaves is higher.
-template <bool DUAL>
-__global__ void __launch_bounds__(256) grouped_gemm256_k64w_bf16_kernel(GemmParams p) {
-    __shared__ __attribute__((aligned(1024))) uint16_t smem[5 * P_PART];         // 160 KB: the whole LDS
-    const int tid = threadIdx.x, lane = tid & 63;
-    // the wave index as a scalar: everything derived from it (LDS targets of the loads, tile halves) then
-    // stays in scalar registers and costs no vector instructions in the main loop
-    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int wm = wave >> 1, wn = wave & 1;
-    const int r16 = lane & 15, quad = lane >> 4;           // MFMA 16x16x32: row (or column) and k eighth
-
-    // Persistent: workgroup b serves the XCD it was dealt to (b % 8) and walks that XCD's share of the
-    // logical tiles with stride (workgroups per XCD), so the workgroups that run together on an XCD work
-    // on consecutive logical tiles (see tile_of) and a workgroup keeps its compute unit: the next tile's
-    // first loads fly while the finished tile is written out, and nothing is relaunched.
-    const int n_mt = p.n_mtiles[0];
-    const int n_nt = DUAL ? (p.N + 127) / 128 : (p.N + 255) / 256;
-    const int total = n_mt * n_nt;
-    const int per_xcd = (total + 7) >> 3;
-    const int xcd = blockIdx.x & 7, stride = gridDim.x >> 3;
-    int idx = blockIdx.x >> 3;
-    if (idx >= per_xcd || xcd * per_xcd + idx >= total) return;
-
-    const int N = p.N, Kd = p.Kd;
-    const int KT = Kd / 64;
     const uint16_t *a = static_cast<const uint16_t *>(p.a);
     uint16_t *c = static_cast<uint16_t *>(p.c);
 
@@ -843,17 +545,17 @@ __global__ void __launch_bounds__(256) grouped_gemm256_k64w_bf16_kernel(GemmPara
 // load j_ of the activation part (A) / weight part (B) of k-step tile_ into slot_
 #define BM_DMA_AT(base_, off_, slot_, tile_, j_)                                                   \
     __builtin_amdgcn_global_load_lds(                                                              \
-        (const BM_GLOBAL void *)(reinterpret_cast<const char *>((base_) + min((tile_), KT - 1) * 64) + (off_)), \
+        (const BM_GLOBAL void *)(reinterpret_cast<const char *>((base_) + min((tile_), kend - 1) * 64) + (off_)), \
         (BM_LDS void *)(smem + (slot_) * P_PART + wave * 512 + (j_) * 2048), 16, 0, 0)
 #define BM_DMA_A(slot_, tile_, j_) BM_DMA_AT(a, oa[j_], slot_, tile_, j_)
 #define BM_DMA_B(slot_, tile_, j_) BM_DMA_AT(((j_) < 4 ? base_b0 : base_b1), ob[j_], slot_, tile_, j_)
 // B(0) A(0) B(1) A(1) of the tile set up last into slots 0..3
 #define BM_PROLOGUE()                                                                              \
     {                                                                                              \
-        _Pragma("unroll") for (int j = 0; j < 8; ++j) BM_DMA_B(0, 0, j);                           \
-        _Pragma("unroll") for (int j = 0; j < 8; ++j) BM_DMA_A(1, 0, j);                           \
-        _Pragma("unroll") for (int j = 0; j < 8; ++j) BM_DMA_B(2, 1, j);                           \
-        _Pragma("unroll") for (int j = 0; j < 8; ++j) BM_DMA_A(3, 1, j);                           \
+        _Pragma("unroll") for (int j = 0; j < 8; ++j) BM_DMA_B(0, kbeg, j);                        \
+        _Pragma("unroll") for (int j = 0; j < 8; ++j) BM_DMA_A(1, kbeg, j);                        \
+        _Pragma("unroll") for (int j = 0; j < 8; ++j) BM_DMA_B(2, kbeg + 1, j);                    \
+        _Pragma("unroll") for (int j = 0; j < 8; ++j) BM_DMA_A(3, kbeg + 1, j);                    \
     }
 #define BM_LD(ptr_) as_bf16x8(*reinterpret_cast<const u32x4 *>(ptr_))
 // weight fragment j of 8: 16 weight rows; DUAL: fragments 0-3 are W_gate rows, 4-7 the same rows of W_up
@@ -865,14 +567,27 @@ __global__ void __launch_bounds__(256) grouped_gemm256_k64w_bf16_kernel(GemmPara
         else if ((d_) <= 8) fb_[(d_) - 1] = BM_LD((sb_) + BM_BOFF((d_) - 1));                      \
         else fa_[(d_) - 8] = BM_LD((sa_) + ((d_) - 8) * 1024);                                     \
     }
+// For the down projection the MFMA is written as an assembly statement with the accumulator tied to an
+// AGPR tile as input and output: with the builtin the register allocator lets accumulator tiles change
+// registers across the loop and fills the loop with copies (measured 70 % slower).  No accumulator is
+// touched again within 63 MFMAs, and a barrier and the tile bookkeeping lie between the loop and the
+// first read of an accumulator, so the wait states the compiler cannot see here are always met.
 #define BM_MFMA1(m_, fa_, fb_)                                                                     \
-    acc[(m_) >> 3][(m_) & 7] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fa_[(m_) >> 3], fb_[(m_) & 7], \
-                                                                        acc[(m_) >> 3][(m_) & 7], 0, 0, 0)
+    {                                                                                              \
+        if (DUAL)                                                                                  \
+            acc[(m_) >> 3][(m_) & 7] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(                    \
+                fa_[(m_) >> 3], fb_[(m_) & 7], acc[(m_) >> 3][(m_) & 7], 0, 0, 0);                 \
+        else                                                                                       \
+            asm("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0"                                          \
+                : "+a"(acc[(m_) >> 3][(m_) & 7]) : "v"(fa_[(m_) >> 3]), "v"(fb_[(m_) & 7]));       \
+    }
 
-    BM_SETUP(xcd * per_xcd + idx);
+    BM_SETUP(xcd * per_xcd + item_tile);
     BM_PROLOGUE();
     for (;;) {
         const int t_row0 = row0, t_row_end = row_end, t_n0 = n0;    // the tile being multiplied
+        const bool t_partial = partial;
+        const int t_kbeg = kbeg, t_kend = kend;
 #pragma unroll
         for (int i = 0; i < 8; ++i)
 #pragma unroll
@@ -892,7 +607,7 @@ __global__ void __launch_bounds__(256) grouped_gemm256_k64w_bf16_kernel(GemmPara
         }
 
         int sB = 0, sA = 1, sAp = 4;                   // slots of B(kt), A(kt), A(kt-1)
-        for (int kt = 0; kt < KT; ++kt) {
+        for (int kt = t_kbeg; kt < t_kend; ++kt) {
             {
                 // first k slice of 32: 64 MFMAs; the second slice's fragments are read under MFMAs 0-31 (one
                 // read per two MFMAs), the 8 loads of B(kt+2) go into the slot A(kt-1) has left, one under
@@ -936,11 +651,23 @@ __global__ void __launch_bounds__(256) grouped_gemm256_k64w_bf16_kernel(GemmPara
         // fly while this tile is written out.
         BM_WAIT_VM_LGKM(0, 0);
         BM_BARE_BARRIER();
-        idx += stride;
-        const bool more = idx < per_xcd && xcd * per_xcd + idx < total;      // uniform over the workgroup
+        bool more;                                     // uniform over the workgroup
+        BM_NEXT_ITEM(more);
         if (more) {
-            BM_SETUP(xcd * per_xcd + idx);
+            BM_SETUP(xcd * per_xcd + item_tile);
             BM_PROLOGUE();
+        }
+
+        if (SPLIT && t_partial) {
+            // chunk of a split tile: the fp32 accumulators go to this workgroup's scratch tile as they are
+            // (accumulator tile, lane: 16-byte stores, contiguous over the lanes)
+            float *dst = p.splitk + (size_t)(xcd * stride + slot) * SPLIT_TILE_FLOATS + wave * (64 * 256) + lane * 4;
+#pragma unroll
+            for (int i = 0; i < 8; ++i)
+#pragma unroll
+                for (int j = 0; j < 8; ++j) *(BM_GLOBAL f32x4 *)(dst + (i * 8 + j) * 256) = acc[i][j];
+            if (!more) break;
+            continue;
         }
 
         // Write-out through the free fifth slot (8 KB per wave): an accumulator tile holds, per lane, four
@@ -992,6 +719,7 @@ __global__ void __launch_bounds__(256) grouped_gemm256_k64w_bf16_kernel(GemmPara
         if (!more) break;
     }
 #undef BM_SETUP
+#undef BM_NEXT_ITEM
 #undef BM_PROLOGUE
 #undef BM_DMA_AT
 #undef BM_DMA_A
@@ -1002,12 +730,42 @@ __global__ void __launch_bounds__(256) grouped_gemm256_k64w_bf16_kernel(GemmPara
 #undef BM_MFMA1
 }
 
-// The 16 x 16 x 32 form serves the gate/up projection (7 % faster there).  The down projection stays on the
-// 32 x 32 x 16 form: measured equally fast once the accumulators of the 16 x 16 form are kept in place,
-// which the compiler only does for the gate/up instantiation.
-#define BM_K64_GATEUP grouped_gemm256_k64w_bf16_kernel<true>
-#define BM_K64_DOWN grouped_gemm256_k64_bf16_kernel<false, false>
-#define BM_K64_DOWN_SPLIT grouped_gemm256_k64_bf16_kernel<false, true>
+// Adds the chunks of every split tail tile in chunk order and writes the bf16 result (see TailSplit).
+// Grid (16 tail tiles, 8 XCDs, 16 slices of a tile): a workgroup handles one sixteenth of a tile - the
+// accumulator tiles (i, j) with i * 8 + j in [4 * blockIdx.z, 4 * blockIdx.z + 4) - with the chunk
+// writers' thread -> element mapping, so that the reduction itself is spread over the chip.
+__global__ void __launch_bounds__(256) splitk_fixup_kernel(GemmParams p) {
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm = wave >> 1, wn = wave & 1, r16 = lane & 15, quad = lane >> 4;
+    const int n_mt = p.n_mtiles[0];
+    const int n_nt = (p.N + 255) / 256;
+    const int total = n_mt * n_nt;
+    const int per_xcd = (total + 7) >> 3;
+    const int xcd = blockIdx.y, stride = p.splitk_stride, t = blockIdx.x;
+    const TailSplit ts = tail_split(total, per_xcd, xcd, stride, p.Kd / 64, true);
+    if (ts.S < 2 || t >= ts.rem) return;
+    int mt, nt;
+    tile_of(xcd * per_xcd + ts.full + t, n_mt, n_nt, mt, nt);
+    const int g = p.mt_group[mt];
+    const int row0 = p.mt_row0[mt], row_end = p.offsets[g + 1], n0 = nt * 256, N = p.N;
+    uint16_t *c = static_cast<uint16_t *>(p.c);
+    const float *src = p.splitk + (size_t)(xcd * stride + t * ts.S) * SPLIT_TILE_FLOATS + wave * (64 * 256) + lane * 4;
+    for (int q = 0; q < 4; ++q) {
+        const int ij = blockIdx.z * 4 + q, i = ij >> 3, j = ij & 7;
+        f32x4 sum = {0.0f, 0.0f, 0.0f, 0.0f};
+        for (int ch = 0; ch < ts.S; ++ch)
+            sum += *(const BM_GLOBAL f32x4 *)(src + (size_t)ch * SPLIT_TILE_FLOATS + ij * 256);
+        const int n = n0 + wn * 128 + j * 16 + r16;
+        for (int e = 0; e < 4; ++e) {
+            const int row = row0 + wm * 128 + i * 16 + 4 * quad + e;
+            if (row < row_end && n < N) stg16(&c[(size_t)row * N + n], f32_to_bf16(sum[e]));
+        }
+    }
+}
+
+#define BM_K64_GATEUP grouped_gemm256_k64w_bf16_kernel<true, false>
+#define BM_K64_DOWN grouped_gemm256_k64w_bf16_kernel<false, false>
+#define BM_K64_DOWN_SPLIT grouped_gemm256_k64w_bf16_kernel<false, true>
 
 static int grid_for(const GemmParams &p, bool dual) {
     const int n_nt = dual ? (p.N + 127) / 128 : (p.N + 255) / 256;
