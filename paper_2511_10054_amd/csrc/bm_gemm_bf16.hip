@@ -631,14 +631,15 @@ __global__ void __launch_bounds__(256) grouped_gemm256_k64w_bf16_kernel(GemmPara
             const int sBn = sB >= 3 ? sB - 3 : sB + 2, sAn = sA >= 3 ? sA - 3 : sA + 2;
             {
                 // second slice: A(kt+2) goes into the slot B(kt) has left, one load under every eighth MFMA;
-                // the first fragments of k-step kt+1 are read under the second half
+                // the first fragments of k-step kt+1 are read under the first half, so that none of
+                // them is still in flight when the next k-step starts
                 const uint16_t *sa_ = smem + sAn * P_PART + fa_off[0];
                 const uint16_t *sb_ = smem + sBn * P_PART + fb_off[0];
 #pragma unroll
                 for (int m = 0; m < 64; ++m) {
                     BM_MFMA1(m, f1a, f1b);
                     if ((m & 7) == 1) BM_DMA_A(sB, kt + 2, m >> 3);
-                    if (m >= 32 && (m & 1) == 0) BM_RD((m - 32) >> 1, f0a, f0b, sa_, sb_)
+                    if (m < 32 && (m & 1) == 0) BM_RD(m >> 1, f0a, f0b, sa_, sb_)
                     __builtin_amdgcn_sched_barrier(0);
                 }
             }
