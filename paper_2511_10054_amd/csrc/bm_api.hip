@@ -42,7 +42,7 @@ int skinny_ksplit(const bm_layer_desc *d) {
     if ((long long)d->T * d->K > 32) {
         // LDS-staged kernel: the fewest slices that still give every compute unit two workgroups (64 weight
         // rows each) - longer weight streams per workgroup and fewer fp32 partial outputs beat a finer
-        // split (measured on the Mixtral-shaped layer: 2 slices 107 us, 4: 114, 7: 120, 14: 129)
+        // split (measured on the Mixtral-shaped layer at 64 tokens: 2 slices 99 us, 4: 111, 7: 115; unsplit 147)
         const long long groups = d->E + d->n_shared < (long long)d->T * d->K ? d->E + d->n_shared : (long long)d->T * d->K;
         for (int s = 2; s <= SKINNY_KSPLIT; ++s)
             if (bm::skinny_lds_ok(d->F, s) && d->F / (512 * s) >= 2 && (d->d / 64) * groups * s >= 512) return s;
