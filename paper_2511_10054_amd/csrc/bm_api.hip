@@ -301,7 +301,9 @@ int bm_permute_by_expert(const bm_layer_desc *desc, const int32_t *ids_remapped,
     if (rc) return rc;
     hipStream_t st = static_cast<hipStream_t>(stream);
     (void)hipGetLastError();
-    int err = launch_count(ids_remapped, d2.T, d2.K, d2.E, at<int32_t>(workspace, L.tile_counts), st);
+    int err = 0;
+    if (!grouping_small((long long)d2.T * d2.K))       // the small-batch kernel counts for itself
+        err = launch_count(ids_remapped, d2.T, d2.K, d2.E, at<int32_t>(workspace, L.tile_counts), st);
     ScanParams sp{};
     sp.T = d2.T; sp.E = d2.E; sp.n_shared = 0; sp.n_tiles = L.n_tiles; sp.BM = 128;
     sp.tile_counts = at<int32_t>(workspace, L.tile_counts);
@@ -312,12 +314,11 @@ int bm_permute_by_expert(const bm_layer_desc *desc, const int32_t *ids_remapped,
     sp.mt_row0 = at<int32_t>(workspace, L.mt_row0);
     sp.n_mtiles = at<int32_t>(workspace, L.n_mtiles);
     sp.stats = nullptr;
-    err |= launch_scan(sp, st);
     ScatterParams cp{};
     cp.T = d2.T; cp.K = d2.K; cp.E = d2.E; cp.n_shared = 0;
     cp.ids = ids_remapped; cp.offsets = offsets; cp.tile_base = sp.tile_base;
     cp.perm = perm; cp.inv_perm = inv_perm; cp.row_token = nullptr;
-    err |= launch_scatter(cp, st);
+    err |= launch_grouping(sp, cp, st);
     return err ? BM_ERR_HIP : BM_OK;
 }
 
@@ -402,15 +403,13 @@ int bm_moe_forward(const bm_layer_desc *desc, const void *x, const bm_weights *w
         mp.q = fp.q; mp.eta = fp.eta; mp.probs = psi ? at<float>(ws, L.probs) : nullptr;
         mp.ids_in = fp.ids; mp.ids_out = fp.ids2; mp.w = fp.w; mp.stats = sp.stats;
         err |= launch_remap(mp, st);
-        err |= launch_count(fp.ids2, T, K, E, fp.tile_counts, st);
+        if (!grouping_small((long long)T * K)) err |= launch_count(fp.ids2, T, K, E, fp.tile_counts, st);
         ScanParams sq = sp;
         sq.tile_stats = nullptr; sq.stats = nullptr;      // written by the substitution kernel
-        err |= launch_scan(sq, st);
-        err |= launch_scatter(cp, st);
+        err |= launch_grouping(sq, cp, st);
     } else {
         err |= launch_front(fp, desc->dtype, st);
-        err |= launch_scan(sp, st);
-        err |= launch_scatter(cp, st);
+        err |= launch_grouping(sp, cp, st);
     }
     mark(1);
 

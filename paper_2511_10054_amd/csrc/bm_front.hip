@@ -335,7 +335,7 @@ __device__ void tile_epilogue(const FrontParams &p, float *logits, int stride, i
 // statistics and the stable placement, from the per-tile histograms and
 // substituted ids kept in LDS.  Saves the scan and scatter launches.
 // ---------------------------------------------------------------------------
-constexpr int FUSED_TILES = 2;
+constexpr int FUSED_TILES = 1;
 
 struct FusedLds {
     int32_t ids[FUSED_TILES][TILE_T * BM_MAX_K];   // substituted ids of every tile
@@ -357,6 +357,32 @@ __device__ __forceinline__ int wave_excl_scan(int v, int &total) {
     }
     total = __shfl(incl, 63, WAVE);
     return incl - v;
+}
+
+// Stable placement of A assignments whose substituted ids sit in LDS (-1 = dropped): the position of
+// assignment a is start[e] plus the number of earlier assignments with the same expert e.  One wave
+// per expert walks the assignments 64 at a time; the rank inside a step is a ballot and a popcount.
+__device__ void place_assignments(const int32_t *ids, int A, int E, int K, const int32_t *start,
+                                  const ScatterParams &c) {
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, nw = blockDim.x >> 6;
+    for (int e = wave; e < E; e += nw) {
+        int run = start[e];
+        if (start[e + 1] == run) continue;             // nothing routed to this expert
+        for (int base = 0; base < A; base += WAVE) {
+            const int a = base + lane;
+            const bool mine = a < A && ids[a] == e;
+            const unsigned long long m = __ballot(mine);
+            if (mine) {
+                const int pos = run + __popcll(m & ((1ull << lane) - 1ull));
+                c.perm[pos] = a;
+                if (c.row_token) c.row_token[pos] = a / K;
+                c.inv_perm[a] = pos;
+            }
+            run += __popcll(m);
+        }
+    }
+    for (int a = tid; a < A; a += blockDim.x)
+        if (ids[a] < 0) c.inv_perm[a] = -1;
 }
 
 __device__ void fused_tail(const FrontParams &p, FusedLds &fs, int n_tiles) {
@@ -403,26 +429,9 @@ __device__ void fused_tail(const FrontParams &p, FusedLds &fs, int n_tiles) {
         p.scan.stats[tid] = sum;
         p.scan.stats[3 + tid] = (p.flags & BM_GATE_DIST) ? fs.dist[tid] : 0;
     }
-    // stable placement
+    // stable placement (the batch is one tile)
     const int live = fs.start[E];
-    for (int tile = 0; tile < n_tiles; ++tile) {
-        const int t0 = tile * TILE_T, ntok = min(TILE_T, p.T - t0), n = ntok * K;
-        for (int idx = tid; idx < n; idx += blockDim.x) {
-            const int e = fs.ids[tile][idx];
-            const int a = t0 * K + idx;
-            int pos = -1;
-            if (e >= 0) {
-                int rank = 0;
-                for (int j = 0; j < idx; ++j) rank += (fs.ids[tile][j] == e) ? 1 : 0;
-                int base = fs.start[e];
-                for (int t = 0; t < tile; ++t) base += fs.counts[t][e];
-                pos = base + rank;
-                p.scat.perm[pos] = a;
-                if (p.scat.row_token) p.scat.row_token[pos] = a / K;
-            }
-            p.scat.inv_perm[a] = pos;
-        }
-    }
+    place_assignments(fs.ids[0], p.T * K, E, K, fs.start, p.scat);
     for (int pos = live + tid; pos < p.T * K; pos += blockDim.x) p.scat.perm[pos] = -1;
     if (p.scat.row_token)
         for (int sidx = 0; sidx < n_shared; ++sidx)
@@ -755,6 +764,84 @@ __global__ void __launch_bounds__(256) scatter_kernel(ScatterParams p) {
 }
 
 // ---------------------------------------------------------------------------
+// Scan and scatter in one workgroup for small batches (at most SMALL_A
+// assignments): the substituted ids are staged in LDS, every expert's count
+// and the stable positions come from ballots over them (place_assignments).
+// Writes what scan_kernel and scatter_kernel write, except the per-tile bases.
+// ---------------------------------------------------------------------------
+constexpr int SMALL_A = 1024;
+
+__global__ void __launch_bounds__(1024) group_small_kernel(ScanParams p, ScatterParams c) {
+    __shared__ int32_t ids[SMALL_A];
+    __shared__ int32_t total[BM_MAX_E + 8];
+    __shared__ int32_t start[BM_MAX_E + 9];
+    __shared__ int32_t tstart[BM_MAX_E + 9];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, nw = blockDim.x >> 6;
+    const int E = p.E, G = p.E + p.n_shared, K = c.K, A = c.T * c.K;
+    for (int a = tid; a < A; a += blockDim.x) {
+        const int e = c.ids[a];
+        ids[a] = ((unsigned)e < (unsigned)E) ? e : -1;
+    }
+    __syncthreads();
+    for (int e = wave; e < E; e += nw) {
+        int cnt = 0;
+        for (int base = 0; base < A; base += WAVE) {
+            const int a = base + lane;
+            cnt += __popcll(__ballot(a < A && ids[a] == e));
+        }
+        if (lane == 0) total[e] = cnt;
+    }
+    for (int g = E + tid; g < G; g += blockDim.x) total[g] = p.T;
+    __syncthreads();
+    if (wave == 0) {                               // exclusive scans over the groups, a few consecutive groups per lane
+        constexpr int PER = (BM_MAX_E + 8 + 63) / 64;
+        int cnt[PER], nt[PER], sum_c = 0, sum_t = 0;
+#pragma unroll
+        for (int i = 0; i < PER; ++i) {
+            const int g = lane * PER + i;
+            const int n = g < G ? total[g] : 0;
+            cnt[i] = n;
+            nt[i] = (n + p.BM - 1) / p.BM;
+            sum_c += n;
+            sum_t += nt[i];
+        }
+        int tot_c, tot_t;
+        int run_c = wave_excl_scan(sum_c, tot_c), run_t = wave_excl_scan(sum_t, tot_t);
+#pragma unroll
+        for (int i = 0; i < PER; ++i) {
+            const int g = lane * PER + i;
+            if (g <= G) { start[g] = run_c; tstart[g] = run_t; }
+            run_c += cnt[i];
+            run_t += nt[i];
+        }
+        if (lane == 0) { p.n_mtiles[0] = tot_t; p.n_mtiles[1] = tot_c; }
+    }
+    __syncthreads();
+    for (int g = tid; g <= G; g += blockDim.x) p.offsets[g] = start[g];
+    for (int g = tid; g < G; g += blockDim.x) {
+        const int nt = tstart[g + 1] - tstart[g];
+        for (int i = 0; i < nt; ++i) {
+            p.mt_group[tstart[g] + i] = g;
+            p.mt_row0[tstart[g] + i] = start[g] + i * p.BM;
+        }
+    }
+    if (p.stats != nullptr && wave < 3) {          // one wave per counter, lanes over the tiles
+        int sum = 0;
+        if (p.tile_stats != nullptr)
+            for (int t = lane; t < p.n_tiles; t += WAVE) sum += p.tile_stats[t * 4 + wave];
+#pragma unroll
+        for (int m = 32; m >= 1; m >>= 1) sum += __shfl_xor(sum, m, WAVE);
+        if (lane == 0) { p.stats[wave] = sum; p.stats[3 + wave] = 0; }
+    }
+    place_assignments(ids, A, E, K, start, c);
+    const int live = start[E];
+    for (int pos = live + tid; pos < A; pos += blockDim.x) c.perm[pos] = -1;
+    if (c.row_token)
+        for (int sidx = 0; sidx < p.n_shared; ++sidx)
+            for (int t = tid; t < p.T; t += blockDim.x) c.row_token[start[E + sidx] + t] = t;
+}
+
+// ---------------------------------------------------------------------------
 // Host-side launchers
 // ---------------------------------------------------------------------------
 template <int NB, int NW, int U>
@@ -806,6 +893,18 @@ int launch_count(const int32_t *ids, int T, int K, int E, int32_t *tile_counts, 
 int launch_scan(const ScanParams &p, hipStream_t st) {
     hipLaunchKernelGGL(scan_kernel, dim3(1), dim3(1024), 0, st, p);
     return launch_status(__func__);
+}
+
+bool grouping_small(long long assignments) { return assignments <= SMALL_A; }
+
+// scan + scatter: one kernel for small batches
+int launch_grouping(const ScanParams &sp, const ScatterParams &cp, hipStream_t st) {
+    if (grouping_small((long long)cp.T * cp.K)) {
+        if (cp.T > 0) hipLaunchKernelGGL(group_small_kernel, dim3(1), dim3(1024), 0, st, sp, cp);
+        return launch_status(__func__);
+    }
+    const int rc = launch_scan(sp, st);
+    return rc | launch_scatter(cp, st);
 }
 
 int launch_scatter(const ScatterParams &p, hipStream_t st) {
