@@ -313,15 +313,33 @@ __device__ __forceinline__ void skinny_lds_pass(const SkinnyParams &p, const uin
     constexpr int XW = CH / 4;                          // k-steps of a chunk each wave stages
     BM_OPAQUE_PTR(w0);
     BM_OPAQUE_PTR(w1);
+    static_assert(XW == 2, "a wave stages one 128-byte line of every activation row per chunk");
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, lr = lane & 15, lk = lane >> 4;
     const uint16_t *a = static_cast<const uint16_t *>(p.a);
-    const uint16_t *xa[NBT];
+    // Staging loads are issued in whole lines: instruction j of row block tb reads rows 8j..8j+7, lane l
+    // row 8j + l / 8 and 16-byte piece l % 8 of the line, i.e. k-step (l % 8) / 4 and quarter l % 4 of
+    // that k-step.  (With the operand layout itself, 16 rows x 64 bytes per instruction, these loads
+    // cost the vector memory path as much time as the weight stream they accompany.)
+    const int q8 = lane >> 3, p8 = lane & 7;
+    const uint16_t *xa[NBT][2];
 #pragma unroll
-    for (int tb = 0; tb < NBT; ++tb) {
-        const int pos = min(row_begin + tb * 16 + lr, row_end - 1);
-        const int src = p.row_map ? ldg_i32(p.row_map + pos) : pos;
-        xa[tb] = a + (size_t)src * p.Kd + lk * 8 + (XW * wave) * 32;
+    for (int tb = 0; tb < NBT; ++tb)
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+            const int pos = min(row_begin + tb * 16 + 8 * j + q8, row_end - 1);
+            const int src = p.row_map ? ldg_i32(p.row_map + pos) : pos;
+            xa[tb][j] = a + (size_t)src * p.Kd + (XW * wave) * 32 + p8 * 8;
+        }
+    // Place of (row r, quarter c) inside a 1 KB operand fragment in LDS: rows 64 bytes apart, the
+    // quarters of a row rotated by the row's index / 4, so that neither the staging stores (8 rows x
+    // 4 quarters) nor the operand reads (16 rows, one quarter) meet in a bank.
+    int wslot[2];
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+        const int r = 8 * j + q8;
+        wslot[j] = (p8 >> 2) * NBT * 64 + r * 4 + ((p8 & 3) ^ ((r >> 2) & 3));
     }
+    const int rslot = lr * 4 + (lk ^ ((lr >> 2) & 3));
     f32x4 acc0[NBT], acc1[NBT];
 #pragma unroll
     for (int tb = 0; tb < NBT; ++tb) {
@@ -332,12 +350,12 @@ __device__ __forceinline__ void skinny_lds_pass(const SkinnyParams &p, const uin
     const int nch = (k_end - k_begin) / (CH * 32);
 
 #define BM_LOAD_X(k_)                                                                      \
-    _Pragma("unroll") for (int i = 0; i < XW; ++i)                                         \
-        _Pragma("unroll") for (int tb = 0; tb < NBT; ++tb) xr[i * NBT + tb] = ldg128(xa[tb] + (k_) + i * 32);
+    _Pragma("unroll") for (int j = 0; j < 2; ++j)                                          \
+        _Pragma("unroll") for (int tb = 0; tb < NBT; ++tb) xr[j * NBT + tb] = ldg128(xa[tb][j] + (k_));
 #define BM_STORE_X(buf_)                                                                   \
-    _Pragma("unroll") for (int i = 0; i < XW; ++i)                                         \
+    _Pragma("unroll") for (int j = 0; j < 2; ++j)                                          \
         _Pragma("unroll") for (int tb = 0; tb < NBT; ++tb)                                 \
-            xs[(((buf_) * CH + XW * wave + i) * NBT + tb) * 64 + lane] = xr[i * NBT + tb];
+            xs[(((buf_) * CH + XW * wave) * NBT + tb) * 64 + wslot[j]] = xr[j * NBT + tb];
 
     BM_LOAD_X(k_begin);
 #pragma unroll
@@ -355,7 +373,7 @@ __device__ __forceinline__ void skinny_lds_pass(const SkinnyParams &p, const uin
         const int kn_ = k_begin + ((c_) + 1) * (CH * 32);                                            \
         if (REFILL_) { BM_LOAD_X(kn_); }                                                             \
         {                                                                                            \
-            const u32x4 *xc = xs + (size_t)((c_) & 1) * CH * NBT * 64 + lane;                        \
+            const u32x4 *xc = xs + (size_t)((c_) & 1) * CH * NBT * 64 + rslot;                       \
             _Pragma("unroll") for (int u = 0; u < CH; ++u) {                                         \
                 bf16x8 xb[NBT];                                                                      \
                 _Pragma("unroll") for (int tb = 0; tb < NBT; ++tb)                                   \
