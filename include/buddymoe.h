@@ -218,7 +218,8 @@ int bm_build_buddy_table(const bm_layer_desc *desc, const int64_t *coactivations
  *   perm [T*K]: perm[pos] = a for pos < live count, -1 after
  *   inv_perm [T*K]: position of assignment a, -1 if dropped
  * All device int32.  workspace: device scratch of at least
- * bm_workspace_bytes(desc) bytes, 256-byte aligned.  Uses T, E, K of desc. */
+ * bm_workspace_bytes(desc) bytes, 256-byte aligned.  Uses T, E, K of desc.
+ * T = 0 writes offsets (all zero) only; the other arrays may then be NULL. */
 int bm_permute_by_expert(const bm_layer_desc *desc, const int32_t *ids_remapped,
                          int32_t *offsets, int32_t *perm, int32_t *inv_perm,
                          void *workspace, size_t workspace_bytes, void *stream);

@@ -293,7 +293,7 @@ int bm_permute_by_expert(const bm_layer_desc *desc, const int32_t *ids_remapped,
     if (!desc) return BM_ERR_NULL;
     if (desc->T < 0 || desc->E <= 0 || desc->K <= 0 || desc->E > BM_MAX_E || desc->K > BM_MAX_K) return BM_ERR_SHAPE;
     if ((long long)desc->T * desc->K > (1ll << 30)) return BM_ERR_SHAPE;
-    if (!ids_remapped || !offsets || !perm || !inv_perm) return BM_ERR_NULL;
+    if (!offsets || (desc->T > 0 && (!ids_remapped || !perm || !inv_perm))) return BM_ERR_NULL;   // empty batch: offsets only
     bm_layer_desc d2 = *desc;
     d2.n_shared = 0;
     Layout L;

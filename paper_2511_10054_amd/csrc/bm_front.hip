@@ -900,7 +900,7 @@ bool grouping_small(long long assignments) { return assignments <= SMALL_A; }
 // scan + scatter: one kernel for small batches
 int launch_grouping(const ScanParams &sp, const ScatterParams &cp, hipStream_t st) {
     if (grouping_small((long long)cp.T * cp.K)) {
-        if (cp.T > 0) hipLaunchKernelGGL(group_small_kernel, dim3(1), dim3(1024), 0, st, sp, cp);
+        hipLaunchKernelGGL(group_small_kernel, dim3(1), dim3(1024), 0, st, sp, cp);   // also for an empty batch: offsets
         return launch_status(__func__);
     }
     const int rc = launch_scan(sp, st);

@@ -102,7 +102,8 @@ def test_buddy_remap(T, E, K, R, n_res, unique):
 # ------------------------------------------------------------- permutation
 
 
-@pytest.mark.parametrize("T,K,E", [(1, 2, 8), (57, 3, 11), (1000, 6, 64), (4096, 8, 128), (33, 32, 256)])
+@pytest.mark.parametrize("T,K,E", [(0, 2, 8), (1, 2, 8), (57, 3, 11), (32, 32, 256), (128, 8, 200), (129, 8, 64),
+                                   (1000, 6, 64), (4096, 8, 128), (33, 32, 256)])
 def test_permute_by_expert(T, K, E):
     torch = _torch()
     import paper_2511_10054_amd as bm
