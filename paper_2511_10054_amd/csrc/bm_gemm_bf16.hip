@@ -751,11 +751,22 @@ __global__ void __launch_bounds__(256) splitk_fixup_kernel(GemmParams p) {
     const int row0 = p.mt_row0[mt], row_end = p.offsets[g + 1], n0 = nt * 256, N = p.N;
     uint16_t *c = static_cast<uint16_t *>(p.c);
     const float *src = p.splitk + (size_t)(xcd * stride + t * ts.S) * SPLIT_TILE_FLOATS + wave * (64 * 256) + lane * 4;
+    // all loads of the workgroup's share go out before the first sum (S <= 8 chunks, tail_split): one
+    // round trip to memory instead of one per chunk
+    f32x4 part[4][8];
+#pragma unroll
+    for (int q = 0; q < 4; ++q)
+#pragma unroll
+        for (int ch = 0; ch < 8; ++ch)
+            if (ch < ts.S)
+                part[q][ch] = *(const BM_GLOBAL f32x4 *)(src + (size_t)ch * SPLIT_TILE_FLOATS + (blockIdx.z * 4 + q) * 256);
+#pragma unroll
     for (int q = 0; q < 4; ++q) {
         const int ij = blockIdx.z * 4 + q, i = ij >> 3, j = ij & 7;
         f32x4 sum = {0.0f, 0.0f, 0.0f, 0.0f};
-        for (int ch = 0; ch < ts.S; ++ch)
-            sum += *(const BM_GLOBAL f32x4 *)(src + (size_t)ch * SPLIT_TILE_FLOATS + ij * 256);
+#pragma unroll
+        for (int ch = 0; ch < 8; ++ch)
+            if (ch < ts.S) sum += part[q][ch];
         const int n = n0 + wn * 128 + j * 16 + r16;
         for (int e = 0; e < 4; ++e) {
             const int row = row0 + wm * 128 + i * 16 + 4 * quad + e;
