@@ -55,17 +55,37 @@ __device__ __forceinline__ float wave_sum(float v) {
     return v;
 }
 
-// (value, index) argmax over the wave: larger value wins, equal values go to
-// the lower index
-__device__ __forceinline__ void wave_argmax(float &v, int &i) {
-#pragma unroll
-    for (int m = 32; m >= 1; m >>= 1) {
-        float ov = __shfl_xor(v, m, WAVE);
-        int oi = __shfl_xor(i, m, WAVE);
-        bool take = (ov > v) || (ov == v && oi < i);
-        v = take ? ov : v;
-        i = take ? oi : i;
+// Largest 32-bit key over the wave, returned to every lane as a wave-uniform value.  Within a row of
+// 16 lanes: four DPP exchanges (lane ^ 1, lane ^ 2, mirror inside a half row, mirror inside the row);
+// the four row results are then read with v_readlane and compared on the scalar side.
+__device__ __forceinline__ uint32_t wave_max_u32(uint32_t v) {
+#define BM_DPP_MAX(ctrl_)                                                                             \
+    {                                                                                                 \
+        const uint32_t o_ = (uint32_t)__builtin_amdgcn_update_dpp((int)v, (int)v, ctrl_, 0xF, 0xF, false); \
+        v = o_ > v ? o_ : v;                                                                          \
     }
+    BM_DPP_MAX(0xB1)     // quad_perm [1, 0, 3, 2]
+    BM_DPP_MAX(0x4E)     // quad_perm [2, 3, 0, 1]
+    BM_DPP_MAX(0x141)    // row_half_mirror
+    BM_DPP_MAX(0x140)    // row_mirror
+#undef BM_DPP_MAX
+    uint32_t best = 0;
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+        const uint32_t o = (uint32_t)__builtin_amdgcn_readlane((int)v, 16 * r);
+        best = o > best ? o : best;
+    }
+    return best;
+}
+
+// Order-preserving map of finite floats (and infinities) to unsigned integers, and back.  -0 is mapped
+// like +0, so keys of equal floats are equal.
+__device__ __forceinline__ uint32_t float_to_ordered(float f) {
+    const uint32_t u = __builtin_bit_cast(uint32_t, f == 0.0f ? 0.0f : f);
+    return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+}
+__device__ __forceinline__ float ordered_to_float(uint32_t k) {
+    return __builtin_bit_cast(float, (k & 0x80000000u) ? (k & 0x7fffffffu) : ~k);
 }
 
 }  // namespace bm

@@ -163,10 +163,10 @@ __device__ void tile_epilogue(const FrontParams &p, float *logits, int stride, i
     const int E = p.E, K = p.K;
     const int ec = (E + 63) >> 6;
 
-    // Ranking by counting: lane l owns experts l, l+64, ...; the rank of an expert is the number of
-    // experts that beat it (larger logit, or equal logit and lower index), found with E broadcast
-    // reads of the logit row - no cross-lane traffic.  Experts of rank < K are the selection,
-    // slot = rank.
+    // Lane l owns experts l, l+64, ...  Few experts - ranking by counting: the rank of an expert is the
+    // number of experts that beat it (larger logit, or equal logit and lower index), found with E
+    // broadcast reads of the logit row, no cross-lane traffic; experts of rank < K are the selection,
+    // slot = rank.  Many experts - K rounds of a wave-wide maximum (see below).  Same order either way.
     for (int i = wave; i < ntok; i += nw) {
         const float *zr = logits + i * stride;
         float myv[EC];
@@ -177,19 +177,48 @@ __device__ void tile_epilogue(const FrontParams &p, float *logits, int stride, i
             myv[c] = (e < E) ? zr[e] : -INFINITY;
             rank[c] = 0;
         }
+        if (E <= 16) {
 #pragma unroll 16
-        for (int j = 0; j < E; ++j) {                  // branch-free body, unrolled: the LDS reads go out in batches
-            const float zj = zr[j];
+            for (int j = 0; j < E; ++j) {              // branch-free body, unrolled: the LDS reads go out in batches
+                const float zj = zr[j];
 #pragma unroll
-            for (int c = 0; c < EC; ++c)
-                rank[c] += (int)(zj > myv[c]) | ((int)(zj == myv[c]) & (int)(j < lane + 64 * c));
-        }
+                for (int c = 0; c < EC; ++c)
+                    rank[c] += (int)(zj > myv[c]) | ((int)(zj == myv[c]) & (int)(j < lane + 64 * c));
+            }
 #pragma unroll
-        for (int c = 0; c < EC; ++c) {
-            const int e = lane + 64 * c;
-            if (e < E && rank[c] < K) {
-                s.ids[i * K + rank[c]] = e;
-                s.w[i * K + rank[c]] = myv[c];            // the logit for now; replaced by the gate weight below
+            for (int c = 0; c < EC; ++c) {
+                const int e = lane + 64 * c;
+                if (e < E && rank[c] < K) {
+                    s.ids[i * K + rank[c]] = e;
+                    s.w[i * K + rank[c]] = myv[c];        // the logit for now; replaced by the gate weight below
+                }
+            }
+        } else {
+            // Many experts: K rounds of "largest remaining" instead (counting costs E reads per lane).
+            // A round takes the wave-wide maximum of the order-preserving integer image of the logits,
+            // then the lowest expert index that holds it (ballots, lowest set lane of the lowest c);
+            // that expert's owner takes it out of the race (0 is below the image of every float).
+            uint32_t key[EC];
+#pragma unroll
+            for (int c = 0; c < EC; ++c) key[c] = (lane + 64 * c < E) ? float_to_ordered(myv[c]) : 0u;
+            for (int r = 0; r < K; ++r) {
+                uint32_t mine = key[0];
+#pragma unroll
+                for (int c = 1; c < EC; ++c) mine = key[c] > mine ? key[c] : mine;
+                const uint32_t best = wave_max_u32(mine);
+                int e_win = -1;
+#pragma unroll
+                for (int c = EC - 1; c >= 0; --c) {
+                    const unsigned long long m = __ballot(key[c] == best);
+                    if (m != 0ull) e_win = 64 * c + (int)__builtin_ctzll(m);
+                }
+#pragma unroll
+                for (int c = 0; c < EC; ++c)
+                    if (lane + 64 * c == e_win) key[c] = 0u;
+                if (lane == 0) {
+                    s.ids[i * K + r] = e_win;
+                    s.w[i * K + r] = ordered_to_float(best);
+                }
             }
         }
         __builtin_amdgcn_wave_barrier();
