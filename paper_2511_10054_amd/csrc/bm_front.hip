@@ -692,18 +692,38 @@ __global__ void __launch_bounds__(1024) scan_kernel(ScanParams p) {
     __shared__ int32_t tstart[BM_MAX_E + 9];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, nw = blockDim.x >> 6;
     const int G = p.E + p.n_shared;
-    // per expert: exclusive scan of its counts over the tiles, 64 tiles per wave step
-    for (int e = wave; e < p.E; e += nw) {
-        int run = 0;
-        for (int tb = 0; tb < p.n_tiles; tb += WAVE) {
-            const int t = tb + lane;
-            const int c = (t < p.n_tiles) ? p.tile_counts[(size_t)e * p.n_tiles + t] : 0;
-            int tot;
-            const int ex = wave_excl_scan(c, tot);
-            if (t < p.n_tiles) p.tile_base[(size_t)e * p.n_tiles + t] = run + ex;
-            run += tot;
+    // per expert: exclusive scan of its counts over the tiles, 64 tiles per wave step.  A wave takes EB
+    // experts at a time and issues the loads of SB steps of each together: every load is a round trip
+    // to memory, the scans between them are short.
+    constexpr int SB = 4, EB = 4;
+    for (int e0 = wave; e0 < p.E; e0 += nw * EB) {          // experts e0, e0 + nw, ..: few experts spread over the waves
+        int run[EB];
+#pragma unroll
+        for (int j = 0; j < EB; ++j) run[j] = 0;
+        for (int tb = 0; tb < p.n_tiles; tb += SB * WAVE) {
+            int c[EB][SB];
+#pragma unroll
+            for (int j = 0; j < EB; ++j)
+#pragma unroll
+                for (int i = 0; i < SB; ++i) {
+                    const int t = tb + i * WAVE + lane;
+                    c[j][i] = (e0 + j * nw < p.E && t < p.n_tiles) ? p.tile_counts[(size_t)(e0 + j * nw) * p.n_tiles + t] : 0;
+                }
+#pragma unroll
+            for (int j = 0; j < EB; ++j)
+#pragma unroll
+                for (int i = 0; i < SB; ++i) {
+                    if (tb + i * WAVE >= p.n_tiles || e0 + j * nw >= p.E) continue;   // uniform over the wave
+                    const int t = tb + i * WAVE + lane;
+                    int tot;
+                    const int ex = wave_excl_scan(c[j][i], tot);
+                    if (e0 + j * nw < p.E && t < p.n_tiles) p.tile_base[(size_t)(e0 + j * nw) * p.n_tiles + t] = run[j] + ex;
+                    run[j] += tot;
+                }
         }
-        if (lane == 0) total[e] = run;
+#pragma unroll
+        for (int j = 0; j < EB; ++j)
+            if (lane == 0 && e0 + j * nw < p.E) total[e0 + j * nw] = run[j];
     }
     for (int g = p.E + tid; g < G; g += blockDim.x) total[g] = p.T;
     __syncthreads();
