@@ -58,6 +58,31 @@ def test_route_topk(name, over, T, renorm):
     np.testing.assert_allclose(w.cpu().numpy(), w_ref, rtol=2e-5, atol=1e-7)
 
 
+@pytest.mark.parametrize("E,K", [(8, 3), (16, 5), (24, 6), (64, 8), (130, 8), (256, 32)])
+def test_route_topk_breaks_ties_towards_the_lowest_index(E, K):
+    """Equal logits (hidden state 0, a bias with repeated values, +0 and -0 among them): the
+    selection is the oracle's, ties to the lowest expert index, on both top-k code paths."""
+    torch = _torch()
+    import paper_2511_10054_amd as bm
+    _say("route ties", E, K)
+    T, d = 37, 64
+    g = np.random.default_rng(E * 100 + K)
+    levels = np.array([0.0, -0.0, 0.5, -1.25, 2.0, 0.5], dtype=np.float32)
+    bias = levels[g.integers(0, len(levels), size=E)].astype(np.float32)
+    x = np.zeros((T, d), dtype=np.float32)
+    wr = g.standard_normal((E, d)).astype(np.float32)
+    ids_ref, w_ref = oracle.route_topk(x, wr, bias, K, True)
+    assert (ids_ref[0] == ids_ref[-1]).all()
+    desc = bm.LayerDesc(T=T, d=d, E=E, F=0, K=K, n_shared=0, R=0, H=0, dtype=bm.BM_BF16, flags=bm.BM_RENORM_TOPK)
+    ids = torch.full((T, K), -9, dtype=torch.int32, device="cuda")
+    w = torch.full((T, K), -9.0, dtype=torch.float32, device="cuda")
+    bm.bm_route_topk(desc, to_device(workloads.f32_to_bf16_bits(x)), to_device(workloads.f32_to_bf16_bits(wr)),
+                     to_device(bias), ids, w)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(ids.cpu().numpy(), ids_ref)
+    np.testing.assert_allclose(w.cpu().numpy(), w_ref, rtol=2e-5, atol=1e-7)
+
+
 # ------------------------------------------------------------------- remap
 
 
