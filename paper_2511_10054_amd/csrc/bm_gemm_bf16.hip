@@ -584,30 +584,38 @@ __global__ void __launch_bounds__(256) grouped_gemm256_k64w_bf16_kernel(GemmPara
 
     BM_SETUP(xcd * per_xcd + item_tile);
     BM_PROLOGUE();
+    // The ring runs on across tiles: during the last two k-steps of a tile the loads already fetch the
+    // first two k-steps of the workgroup's next item (instead of repeats of the last k-step), so a new
+    // tile starts with its operands in LDS and nothing is drained in between.
+    int sB = 0, sA = 1, sAp = 4;                       // slots of B(kt), A(kt), and of A(kt-1) (free)
+    // first tile: B(0) and A(0) have landed - vector memory operations complete in issue order and only
+    // the 16 loads of B(1), A(1) are younger
+    BM_WAIT_VMCNT(16);
     for (;;) {
         const int t_row0 = row0, t_row_end = row_end, t_n0 = n0;    // the tile being multiplied
         const bool t_partial = partial;
         const int t_kbeg = kbeg, t_kend = kend;
+        bool more = false;                             // the loads have moved on to a next item (uniform)
 #pragma unroll
         for (int i = 0; i < 8; ++i)
 #pragma unroll
             for (int j = 0; j < 8; ++j)
 #pragma unroll
                 for (int v = 0; v < 4; ++v) acc[i][j][v] = 0.0f;
-        // B(0) and A(0) have landed: vector memory operations complete in issue order, and whatever was
-        // issued after them (B(1), A(1), then the previous tile's stores), at most the 16 youngest are
-        // still out, which leaves B(0) and A(0) done however many store instructions there were
-        BM_WAIT_VMCNT(16);
+        // Every wave's part of B(0), A(0) is in LDS (first tile: the wait above; later tiles: they were
+        // waited for in the middle of the previous tile's last k-step), and every wave is done with
+        // the write-out staging in the slot the first loads of this tile will fill.
         BM_BARE_BARRIER();
         {
-            const uint16_t *sa_ = smem + 1 * P_PART + fa_off[0];
-            const uint16_t *sb_ = smem + 0 * P_PART + fb_off[0];
+            const uint16_t *sa_ = smem + sA * P_PART + fa_off[0];
+            const uint16_t *sb_ = smem + sB * P_PART + fb_off[0];
 #pragma unroll
             for (int d = 0; d < 16; ++d) BM_RD(d, f0a, f0b, sa_, sb_)
         }
 
-        int sB = 0, sA = 1, sAp = 4;                   // slots of B(kt), A(kt), A(kt-1)
         for (int kt = t_kbeg; kt < t_kend; ++kt) {
+            // k-step the loads of this trip fetch: two ahead, in the next item once this one is through
+            const int kl = more ? kbeg + (kt + 2 - t_kend) : kt + 2;
             {
                 // first k slice of 32: 64 MFMAs; the second slice's fragments are read under MFMAs 0-31 (one
                 // read per two MFMAs), the 8 loads of B(kt+2) go into the slot A(kt-1) has left, one under
@@ -619,26 +627,28 @@ __global__ void __launch_bounds__(256) grouped_gemm256_k64w_bf16_kernel(GemmPara
                 for (int m = 0; m < 64; ++m) {
                     BM_MFMA1(m, f0a, f0b);
                     if (m < 32 && (m & 1) == 0) BM_RD(m >> 1, f1a, f1b, sa_, sb_)
-                    if ((m & 7) == 5) BM_DMA_B(sAp, kt + 2, m >> 3);
+                    if ((m & 7) == 5) BM_DMA_B(sAp, kl, m >> 3);
                     __builtin_amdgcn_sched_barrier(0);
                 }
             }
             // every fragment of B(kt), A(kt) is in registers; A(kt+1), B(kt+1) have landed (this wave's
-            // part: at most the 8 loads of B(kt+2) are outstanding); after the barrier both hold for
-            // every wave
+            // part: at most the 8 loads of B(kt+2) are outstanding - whatever was issued before them,
+            // the previous tile's stores included, is complete); after the barrier both hold for every wave
             BM_WAIT_VM_LGKM(8, 0);
             BM_BARE_BARRIER();
             const int sBn = sB >= 3 ? sB - 3 : sB + 2, sAn = sA >= 3 ? sA - 3 : sA + 2;
             {
                 // second slice: A(kt+2) goes into the slot B(kt) has left, one load under every eighth MFMA;
                 // the first fragments of k-step kt+1 are read under the first half, so that none of
-                // them is still in flight when the next k-step starts
+                // them is still in flight when the next k-step starts (after the last k-step of a tile
+                // they are the next tile's and are read again at its start: no register stays live
+                // across the write-out)
                 const uint16_t *sa_ = smem + sAn * P_PART + fa_off[0];
                 const uint16_t *sb_ = smem + sBn * P_PART + fb_off[0];
 #pragma unroll
                 for (int m = 0; m < 64; ++m) {
                     BM_MFMA1(m, f1a, f1b);
-                    if ((m & 7) == 1) BM_DMA_A(sB, kt + 2, m >> 3);
+                    if ((m & 7) == 1) BM_DMA_A(sB, kl, m >> 3);
                     if (m < 32 && (m & 1) == 0) BM_RD(m >> 1, f0a, f0b, sa_, sb_)
                     __builtin_amdgcn_sched_barrier(0);
                 }
@@ -646,18 +656,14 @@ __global__ void __launch_bounds__(256) grouped_gemm256_k64w_bf16_kernel(GemmPara
             sAp = sA;
             sB = sBn;
             sA = sAn;
+            if (kt == t_kend - 3) {
+                // the loads of this item are all issued: from here on they fetch the next one
+                BM_NEXT_ITEM(more);
+                if (more) BM_SETUP(xcd * per_xcd + item_tile);
+            }
         }
-        // The tile is done.  Loads past its last k-step (clamped repeats) may still be landing and other
-        // waves may still be reading fragments: drain both, then start the next tile's loads so that they
-        // fly while this tile is written out.
-        BM_WAIT_VM_LGKM(0, 0);
-        BM_BARE_BARRIER();
-        bool more;                                     // uniform over the workgroup
-        BM_NEXT_ITEM(more);
-        if (more) {
-            BM_SETUP(xcd * per_xcd + item_tile);
-            BM_PROLOGUE();
-        }
+        // The tile is done.  The slot A(last k-step) sat in is free for every wave since the barrier in
+        // the middle of that k-step; it stages the write-out while the next tile's loads land elsewhere.
 
         if (SPLIT && t_partial) {
             // chunk of a split tile: the fp32 accumulators go to this workgroup's scratch tile as they are
@@ -671,7 +677,7 @@ __global__ void __launch_bounds__(256) grouped_gemm256_k64w_bf16_kernel(GemmPara
             continue;
         }
 
-        // Write-out through the free fifth slot (8 KB per wave): an accumulator tile holds, per lane, four
+        // Write-out through the free slot (8 KB per wave): an accumulator tile holds, per lane, four
         // rows of one column; 16 rows at a time are laid out row-major in LDS as bf16 - neighbouring lanes
         // swap one value so that every lane writes a packed pair - and read back as 16-byte pieces, so a
         // store instruction writes whole 128-byte lines.  A wave uses only its own region and LDS
@@ -680,7 +686,7 @@ __global__ void __launch_bounds__(256) grouped_gemm256_k64w_bf16_kernel(GemmPara
             constexpr int OC = DUAL ? 4 : 8;            // 16-column output blocks per wave
             constexpr int SD = DUAL ? 36 : 72;          // LDS row stride in dwords (padded against conflicts)
             constexpr int PR = OC * 2;                  // 16-byte pieces per output row
-            uint32_t *stage = reinterpret_cast<uint32_t *>(smem + 4 * P_PART) + wave * 2048;
+            uint32_t *stage = reinterpret_cast<uint32_t *>(smem + sAp * P_PART) + wave * 2048;
             const bool odd = lane & 1;
 #pragma unroll
             for (int i = 0; i < 8; ++i) {
@@ -719,6 +725,9 @@ __global__ void __launch_bounds__(256) grouped_gemm256_k64w_bf16_kernel(GemmPara
         }
         if (!more) break;
     }
+    // the last tile's loads ran past its end (repeats of its last k-step): nothing may still be landing in
+    // LDS when the workgroup ends
+    BM_WAIT_VM_LGKM(0, 0);
 #undef BM_SETUP
 #undef BM_NEXT_ITEM
 #undef BM_PROLOGUE
@@ -795,7 +804,8 @@ static int persistent_grid(const GemmParams &p, bool dual) {
 // the k-step-64 kernel addresses rows by 32-bit byte offsets from a uniform base
 static bool k64_ok(const GemmParams &p) {
     const unsigned long long lim = 1ull << 32;
-    return p.BM == 256 && p.Kd % 64 == 0 && (unsigned long long)p.a_rows * p.Kd * 2 < lim &&
+    // (and hands the loads over to the next tile three k-steps before a tile ends)
+    return p.BM == 256 && p.Kd % 64 == 0 && p.Kd >= 256 && (unsigned long long)p.a_rows * p.Kd * 2 < lim &&
            (unsigned long long)p.N * p.Kd * 2 < lim;
 }
 
