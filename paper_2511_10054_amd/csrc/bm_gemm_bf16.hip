@@ -668,11 +668,17 @@ __global__ void __launch_bounds__(256) grouped_gemm256_k64w_bf16_kernel(GemmPara
         if (SPLIT && t_partial) {
             // chunk of a split tile: the fp32 accumulators go to this workgroup's scratch tile as they are
             // (accumulator tile, lane: 16-byte stores, contiguous over the lanes)
+            // (the address advances store by store behind an optimisation barrier: 64 addresses computed
+            // up front cost registers, and the spills land in the main loop)
             float *dst = p.splitk + (size_t)(xcd * stride + slot) * SPLIT_TILE_FLOATS + wave * (64 * 256) + lane * 4;
 #pragma unroll
             for (int i = 0; i < 8; ++i)
 #pragma unroll
-                for (int j = 0; j < 8; ++j) *(BM_GLOBAL f32x4 *)(dst + (i * 8 + j) * 256) = acc[i][j];
+                for (int j = 0; j < 8; ++j) {
+                    *(BM_GLOBAL f32x4 *)dst = acc[i][j];
+                    dst += 256;
+                    asm volatile("" : "+v"(dst));
+                }
             if (!more) break;
             continue;
         }
