@@ -31,10 +31,10 @@ PEAK_BF16_TFLOPS = 2500.0    # MI355X dense bf16 MFMA
 # WRITE_SIZE runs summarised under profiles/ (counter x copy-kernel calibration); default shapes,
 # first-resident mode only.  Re-measure after changing that kernel.
 TRAFFIC_BYTES = {
-    "c2_mixtral_decode_T64": 1182.5e6,
-    "c3_mixtral_prefill_T4096": 4536.3e6,
-    "c4_qwen3_T2048": 601.8e6,
-    "c5_deepseek_T8192": 1828.4e6,
+    "c2_mixtral_decode_T64": 1182.4e6,
+    "c3_mixtral_prefill_T4096": 4004.3e6,
+    "c4_qwen3_T2048": 590.6e6,
+    "c5_deepseek_T8192": 1737.0e6,
 }
 
 WORKLOADS = {
