@@ -468,21 +468,25 @@ __device__ void fused_tail(const FrontParams &p, FusedLds &fs, int n_tiles) {
 }
 
 // ---------------------------------------------------------------------------
-// bf16 front kernel: router product on MFMA 32x32x16 (tokens x experts),
+// bf16 front kernel: router product on MFMA 16x16x32 (tokens x experts),
 // operands read from global memory directly in the instruction's layout:
-// lane l supplies row/column (l % 32) and the 8 consecutive k values starting
-// at 8 * (l / 32), i.e. one 16-byte load per operand per k-step.  The waves
-// split the hidden dimension in batches of U k-steps; the loads of a batch are
-// all issued before its MFMAs.  The partial logit tiles of the waves are
-// written to LDS side by side and added in wave order (reproducible sum), or,
-// when NW tiles do not fit, added into one tile wave after wave.
-// NB = number of 32-expert column blocks, NW = waves per workgroup.
+// lane l supplies row/column (l % 16) and the 8 consecutive k values starting
+// at 8 * (l / 16), i.e. one 16-byte load per operand per k-step, 64 contiguous
+// bytes per row.  (The vector memory path moves one 128-byte line per two
+// cycles whatever part of it is used, and with many experts these loads bound
+// the kernel; the 32x32x16 form reads 32 bytes per row and instruction.)  The
+// waves split the hidden dimension in batches of U k-steps; the loads of a
+// batch are all issued before its MFMAs.  The partial logit tiles of the waves
+// are written to LDS side by side and added in wave order (reproducible sum),
+// or, when NW tiles do not fit, added into one tile wave after wave.
+// NB = number of 16-expert column blocks, NW = waves per workgroup.
 // FUSED: one workgroup walks all (<= FUSED_TILES) tiles and finishes the
 // grouping itself.
 // ---------------------------------------------------------------------------
 template <int NB, int NW, int U, bool FUSED>
 __global__ void __launch_bounds__(NW * 64) front_bf16_kernel(FrontParams p) {
-    constexpr int STRIDE = NB * 32 + 1;
+    static_assert(TILE_T == 32, "two 16-token row blocks per tile");
+    constexpr int STRIDE = NB * 16 + 1;
     constexpr int TILE = TILE_T * STRIDE;
     constexpr int NS_FIT = (68 * 1024) / (TILE * 4);
     constexpr int NS = NS_FIT >= NW ? NW : (NS_FIT < 1 ? 1 : NS_FIT);   // partial tiles kept side by side
@@ -491,7 +495,7 @@ __global__ void __launch_bounds__(NW * 64) front_bf16_kernel(FrontParams p) {
     __shared__ FusedLds fs_store[FUSED ? 1 : 0 + 1];
     FusedLds &fs = fs_store[0];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int r32 = lane & 31, half = lane >> 5;
+    const int r16 = lane & 15, kq = lane >> 4;
     const uint16_t *x = static_cast<const uint16_t *>(p.x);
     const uint16_t *wr = static_cast<const uint16_t *>(p.wr);
     const int n_tiles = (p.T + TILE_T - 1) / TILE_T;
@@ -499,68 +503,79 @@ __global__ void __launch_bounds__(NW * 64) front_bf16_kernel(FrontParams p) {
 
     const uint16_t *wb[NB];
 #pragma unroll
-    for (int nb = 0; nb < NB; ++nb) wb[nb] = wr + (size_t)min(nb * 32 + r32, p.E - 1) * p.d + half * 8;
-    const int ksteps = p.d >> 4;
+    for (int nb = 0; nb < NB; ++nb) wb[nb] = wr + (size_t)min(nb * 16 + r16, p.E - 1) * p.d + kq * 8;
+    const int ksteps = p.d >> 5;
     const int nbatch = ksteps / U;
 
     for (int tile = tile_begin; tile < tile_end; ++tile) {
         const int t0 = tile * TILE_T;
-        const int trow = min(t0 + r32, p.T - 1);
-        const uint16_t *xa = x + (size_t)trow * p.d + half * 8;
-        f32x16 acc[NB];
+        const bool two = p.T - t0 > 16;                // the tile's second 16-token block holds tokens (uniform)
+        const uint16_t *xa[2];
 #pragma unroll
-        for (int nb = 0; nb < NB; ++nb)
+        for (int tb = 0; tb < 2; ++tb) xa[tb] = x + (size_t)min(t0 + tb * 16 + r16, p.T - 1) * p.d + kq * 8;
+        f32x4 acc[2][NB];
 #pragma unroll
-            for (int v = 0; v < 16; ++v) acc[nb][v] = 0.0f;
+        for (int tb = 0; tb < 2; ++tb)
+#pragma unroll
+            for (int nb = 0; nb < NB; ++nb) acc[tb][nb] = f32x4{0.f, 0.f, 0.f, 0.f};
 
         for (int bt = wave; bt < nbatch; bt += NW) {
-            const int k0 = bt * U * 16;
-            u32x4 ra[U], rb[NB][U];
+            const int k0 = bt * U * 32;
+            u32x4 ra[2][U], rb[NB][U];
 #pragma unroll
             for (int u = 0; u < U; ++u) {
-                ra[u] = ldg128(xa + k0 + u * 16);
+                ra[0][u] = ldg128(xa[0] + k0 + u * 32);
+                if (two) ra[1][u] = ldg128(xa[1] + k0 + u * 32);
 #pragma unroll
-                for (int nb = 0; nb < NB; ++nb) rb[nb][u] = ldg128(wb[nb] + k0 + u * 16);
+                for (int nb = 0; nb < NB; ++nb) rb[nb][u] = ldg128(wb[nb] + k0 + u * 32);
             }
             __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
             for (int u = 0; u < U; ++u)
 #pragma unroll
-                for (int nb = 0; nb < NB; ++nb)
-                    acc[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(ra[u]), as_bf16x8(rb[nb][u]), acc[nb], 0, 0, 0);
+                for (int nb = 0; nb < NB; ++nb) {
+                    acc[0][nb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(ra[0][u]), as_bf16x8(rb[nb][u]), acc[0][nb], 0, 0, 0);
+                    if (two)
+                        acc[1][nb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(ra[1][u]), as_bf16x8(rb[nb][u]), acc[1][nb], 0, 0, 0);
+                }
         }
         for (int ks = nbatch * U + wave; ks < ksteps; ks += NW) {       // k-steps past the last full batch
-            const bf16x8 a = as_bf16x8(ldg128(xa + ks * 16));
+            const bf16x8 a0 = as_bf16x8(ldg128(xa[0] + ks * 32)), a1 = as_bf16x8(ldg128(xa[1] + ks * 32));
 #pragma unroll
-            for (int nb = 0; nb < NB; ++nb)
-                acc[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, as_bf16x8(ldg128(wb[nb] + ks * 16)), acc[nb], 0, 0, 0);
+            for (int nb = 0; nb < NB; ++nb) {
+                const bf16x8 b = as_bf16x8(ldg128(wb[nb] + ks * 32));
+                acc[0][nb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a0, b, acc[0][nb], 0, 0, 0);
+                acc[1][nb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a1, b, acc[1][nb], 0, 0, 0);
+            }
         }
 
-        // D[i][j]: lane holds column j = l % 32 and rows i = 8*(v/4) + 4*(l/32) + v%4.
+        // D[i][j] of a 16x16 block: lane holds column j = l % 16 and rows i = 4 * (l / 16) + v.
         // NS partial tiles sit side by side in LDS; wave w adds into slot w % NS in round w / NS,
         // then the slots are added in slot order: one fixed association, reproducible.
         for (int r = 0; r < (NW + NS - 1) / NS; ++r) {
             if (wave / NS == r) {
                 float *mine = part + (wave % NS) * TILE;
 #pragma unroll
-                for (int nb = 0; nb < NB; ++nb)
+                for (int tb = 0; tb < 2; ++tb)
 #pragma unroll
-                    for (int v = 0; v < 16; ++v) {
-                        float *q = &mine[(8 * (v >> 2) + 4 * half + (v & 3)) * STRIDE + nb * 32 + r32];
-                        *q = (r == 0 ? 0.0f : *q) + acc[nb][v];
-                    }
+                    for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+                        for (int v = 0; v < 4; ++v) {
+                            float *q = &mine[(tb * 16 + 4 * kq + v) * STRIDE + nb * 16 + r16];
+                            *q = (r == 0 ? 0.0f : *q) + acc[tb][nb][v];
+                        }
             }
             __syncthreads();
         }
-        for (int idx = tid; idx < TILE_T * NB * 32; idx += NW * 64) {
-            const int i = idx / (NB * 32), e = idx - i * (NB * 32);
+        for (int idx = tid; idx < TILE_T * NB * 16; idx += NW * 64) {
+            const int i = idx / (NB * 16), e = idx - i * (NB * 16);
             float sum = (p.bias != nullptr && e < p.E) ? p.bias[e] : 0.0f;
 #pragma unroll
             for (int w = 0; w < NS; ++w) sum += part[w * TILE + i * STRIDE + e];
             part[i * STRIDE + e] = sum;                // slot 0 becomes the logit tile (own element only)
         }
         __syncthreads();
-        tile_epilogue<(NB + 1) / 2>(p, part, STRIDE, TILE, s, tile);
+        tile_epilogue<(NB + 3) / 4>(p, part, STRIDE, TILE, s, tile);
         if (FUSED) {
             __syncthreads();
             const int n = min(TILE_T, p.T - t0) * p.K;
@@ -908,12 +923,14 @@ int launch_front(const FrontParams &p, int dtype, hipStream_t st) {
     if (dtype == BM_F32) {
         hipLaunchKernelGGL(front_f32_kernel, dim3(n_tiles), dim3(256), 0, st, p);
     } else {
-        const int nb = (p.E + 31) / 32;
-        // a tile is latency-bound: 16 waves split the product and rank two tokens each
-        if (nb <= 1) launch_front_bf16<1, 16, 8>(p, n_tiles, st);
+        const int nb = (p.E + 15) / 16;
+        // a tile is latency-bound: 16 waves split the product and rank two tokens each; U keeps a batch
+        // of loads ((2 + NB) * U registers quadruples) inside the 128 registers a wave of 16 has
+        if (nb <= 1) launch_front_bf16<1, 16, 4>(p, n_tiles, st);
         else if (nb <= 2) launch_front_bf16<2, 16, 4>(p, n_tiles, st);
         else if (nb <= 4) launch_front_bf16<4, 16, 2>(p, n_tiles, st);
-        else launch_front_bf16<8, 8, 2>(p, n_tiles, st);
+        else if (nb <= 8) launch_front_bf16<8, 8, 2>(p, n_tiles, st);
+        else launch_front_bf16<16, 8, 1>(p, n_tiles, st);
     }
     return launch_status(__func__);
 }
