@@ -97,6 +97,7 @@ Layout make_layout(const bm_layer_desc *d) {
     const int n_shared = d->n_shared > 0 ? d->n_shared : 0;
     const int G = d->E + n_shared;
     L.n_tiles = (d->T + TILE_T - 1) / TILE_T;
+    const int tiles16 = (d->T + 15) / 16;          // the front kernel's tiles of small batches (per-tile arrays)
     L.rows_max = (int)(A + (size_t)n_shared * d->T);
     L.mtiles_max = L.rows_max / 128 + G;         // bound for the smaller of the two row-tile heights
     const size_t esz = d->dtype == BM_BF16 ? 2 : 4;
@@ -105,9 +106,9 @@ Layout make_layout(const bm_layer_desc *d) {
     L.ids = take(A * 4);
     L.ids2 = take(A * 4);
     L.w = take(A * 4);
-    L.tile_counts = take((size_t)L.n_tiles * d->E * 4);
+    L.tile_counts = take((size_t)tiles16 * d->E * 4);
     L.tile_base = take((size_t)L.n_tiles * d->E * 4);
-    L.tile_stats = take((size_t)L.n_tiles * 16);
+    L.tile_stats = take((size_t)tiles16 * 16);
     L.offsets = take((size_t)(G + 1) * 4);
     L.perm = take(A * 4);
     L.inv_perm = take(A * 4);
@@ -264,6 +265,7 @@ int bm_route_topk(const bm_layer_desc *desc, const void *x, const void *w_router
     p.flags = desc->flags;
     p.ids = ids; p.w = w;
     p.bitmap = nullptr;
+    p.tile_tokens = front_tile_tokens(desc->T, desc->K, desc->dtype, false);
     return launch_front(p, desc->dtype, static_cast<hipStream_t>(stream)) ? BM_ERR_HIP : BM_OK;
 }
 
@@ -364,11 +366,14 @@ int bm_moe_forward(const bm_layer_desc *desc, const void *x, const bm_weights *w
     fp.ids2 = at<int32_t>(ws, L.ids2);
     fp.tile_counts = at<int32_t>(ws, L.tile_counts);
     fp.tile_stats = at<int32_t>(ws, L.tile_stats);
+    const bool fuse = front_can_fuse(T, desc->dtype, desc->flags);
+    fp.tile_tokens = front_tile_tokens(T, K, desc->dtype, fuse);
 
     // 2. offsets, tile bases, row-tile table, statistics
     ScanParams sp{};
     const bool skinny = use_skinny(desc);
-    sp.T = T; sp.E = E; sp.n_shared = desc->n_shared; sp.n_tiles = L.n_tiles;
+    sp.T = T; sp.E = E; sp.n_shared = desc->n_shared;
+    sp.n_tiles = (T + fp.tile_tokens - 1) / fp.tile_tokens;   // tiles of the front kernel (per-tile statistics)
     sp.BM = skinny ? (1 << 20) : gemm_tile_rows(desc);   // skinny: one table entry per live group
     sp.tile_counts = fp.tile_counts; sp.tile_base = at<int32_t>(ws, L.tile_base);
     sp.tile_stats = fp.tile_stats;
@@ -383,7 +388,7 @@ int bm_moe_forward(const bm_layer_desc *desc, const void *x, const bm_weights *w
     cp.ids = fp.ids2; cp.offsets = sp.offsets; cp.tile_base = sp.tile_base;
     cp.perm = at<int32_t>(ws, L.perm); cp.inv_perm = at<int32_t>(ws, L.inv_perm);
     cp.row_token = at<int32_t>(ws, L.row_token);
-    if (front_can_fuse(T, desc->dtype)) {      // decode-sized batch: one kernel does steps 1-3
+    if (fuse) {                                // decode-sized batch: one kernel does steps 1-3
         fp.fused = 1;
         fp.scan = sp;
         fp.scat = cp;

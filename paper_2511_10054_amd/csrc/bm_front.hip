@@ -2,7 +2,8 @@
 // substitution (Section 4, Algorithm 1) and the stable grouping of the
 // surviving assignments by expert.
 //
-// Tokens are processed in tiles of TILE_T = 32.  One workgroup owns one tile:
+// Tokens are processed in tiles of TILE_T = 32 (16 for small bf16 batches, see
+// front_tile_tokens).  One workgroup owns one tile:
 // its waves split the hidden dimension for the router product (MFMA for bf16,
 // fp32 FMA for fp32), the partial logits meet in LDS, then each wave ranks
 // whole tokens (one expert per lane), 32 lanes walk Algorithm 1 for the 32
@@ -10,7 +11,9 @@
 // one-workgroup scan turns the histograms into group offsets, per-tile bases
 // and the row-tile table of the grouped GEMMs; a scatter kernel then places
 // every assignment (rank inside the tile by counting earlier equal keys, so
-// the order is the stable one and no atomics decide a position).
+// the order is the stable one and no atomics decide a position).  Small batches
+// get offsets and placement from one workgroup instead (group_small_kernel), or
+// from the front kernel itself (FUSED).
 #include "bm_kernels.h"
 
 namespace bm {
@@ -158,8 +161,8 @@ template <int EC>   // EC = ceil(E / 64) experts per lane (compile-time bound)
 __device__ void tile_epilogue(const FrontParams &p, float *logits, int stride, int cap_ints,
                               FrontLds &s, int tile) {
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, nw = blockDim.x >> 6;
-    const int t0 = tile * TILE_T;
-    const int ntok = min(TILE_T, p.T - t0);
+    const int t0 = tile * p.tile_tokens;
+    const int ntok = min(p.tile_tokens, p.T - t0);
     const int E = p.E, K = p.K;
     const int ec = (E + 63) >> 6;
 
@@ -353,7 +356,7 @@ __device__ void tile_epilogue(const FrontParams &p, float *logits, int stride, i
     }
     // histograms are stored expert-major ([E][tiles]): the single workgroup that scans them reads and writes
     // whole lines, the strided side is spread over the many workgroups here
-    const int n_tiles_all = (p.T + TILE_T - 1) / TILE_T;
+    const int n_tiles_all = (p.T + p.tile_tokens - 1) / p.tile_tokens;
     for (int e = tid; e < E; e += blockDim.x) p.tile_counts[(size_t)e * n_tiles_all + tile] = s.counts[e];
     if (tid < 3) p.tile_stats[tile * 4 + tid] = s.stats[tid];
 }
@@ -498,7 +501,7 @@ __global__ void __launch_bounds__(NW * 64) front_bf16_kernel(FrontParams p) {
     const int r16 = lane & 15, kq = lane >> 4;
     const uint16_t *x = static_cast<const uint16_t *>(p.x);
     const uint16_t *wr = static_cast<const uint16_t *>(p.wr);
-    const int n_tiles = (p.T + TILE_T - 1) / TILE_T;
+    const int n_tiles = (p.T + p.tile_tokens - 1) / p.tile_tokens;
     const int tile_begin = FUSED ? 0 : blockIdx.x, tile_end = FUSED ? n_tiles : blockIdx.x + 1;
 
     const uint16_t *wb[NB];
@@ -508,8 +511,8 @@ __global__ void __launch_bounds__(NW * 64) front_bf16_kernel(FrontParams p) {
     const int nbatch = ksteps / U;
 
     for (int tile = tile_begin; tile < tile_end; ++tile) {
-        const int t0 = tile * TILE_T;
-        const bool two = p.T - t0 > 16;                // the tile's second 16-token block holds tokens (uniform)
+        const int t0 = tile * p.tile_tokens;
+        const bool two = min(p.tile_tokens, p.T - t0) > 16;   // the tile's second 16-token block holds tokens (uniform)
         const uint16_t *xa[2];
 #pragma unroll
         for (int tb = 0; tb < 2; ++tb) xa[tb] = x + (size_t)min(t0 + tb * 16 + r16, p.T - 1) * p.d + kq * 8;
@@ -578,7 +581,7 @@ __global__ void __launch_bounds__(NW * 64) front_bf16_kernel(FrontParams p) {
         tile_epilogue<(NB + 3) / 4>(p, part, STRIDE, TILE, s, tile);
         if (FUSED) {
             __syncthreads();
-            const int n = min(TILE_T, p.T - t0) * p.K;
+            const int n = min(p.tile_tokens, p.T - t0) * p.K;
             for (int idx = tid; idx < n; idx += NW * 64) fs.ids[tile][idx] = s.ids[idx];
             for (int e = tid; e < p.E; e += NW * 64) fs.counts[tile][e] = s.counts[e];
             if (tid < 3) { fs.stats[tile][tid] = s.stats[tid]; fs.dist[tid] = s.dist[tid]; }
@@ -914,11 +917,23 @@ static void launch_front_bf16(const FrontParams &p, int n_tiles, hipStream_t st)
     else hipLaunchKernelGGL((front_bf16_kernel<NB, NW, U, false>), dim3(n_tiles), dim3(NW * 64), 0, st, p);
 }
 
-// measured: with two tiles the sequential walk (52 us at T=64) loses to the three-kernel path (31 us)
-bool front_can_fuse(int T, int dtype) { return dtype == BM_BF16 && T > 0 && T <= TILE_T; }
+// One workgroup for the whole front end: up to 16 tokens (one 16-token row block; from 17 tokens on two
+// workgroups of 16 tokens plus the grouping kernel are faster), or up to one tile when the distribution
+// gate is on (its in-tile form needs the whole batch in one workgroup and saves two launches).
+bool front_can_fuse(int T, int dtype, uint32_t flags) {
+    return dtype == BM_BF16 && T > 0 && T <= ((flags & BM_GATE_DIST) ? TILE_T : 16);
+}
+
+// Tokens per workgroup of the bf16 front kernel.  A tile's router product is bound by the number of
+// cache lines its loads touch, so small batches are cut into 16-token tiles on twice the compute units
+// (measured at 64 tokens: 12 us instead of 18).  Large batches keep 32: the per-tile histograms the scan
+// and scatter kernels work on are defined on tiles of TILE_T.
+int front_tile_tokens(int T, int K, int dtype, bool fused) {
+    return (dtype == BM_BF16 && !fused && grouping_small((long long)T * K)) ? 16 : TILE_T;
+}
 
 int launch_front(const FrontParams &p, int dtype, hipStream_t st) {
-    const int n_tiles = (p.T + TILE_T - 1) / TILE_T;
+    const int n_tiles = (p.T + p.tile_tokens - 1) / p.tile_tokens;
     if (n_tiles == 0) return 0;
     if (dtype == BM_F32) {
         hipLaunchKernelGGL(front_f32_kernel, dim3(n_tiles), dim3(256), 0, st, p);

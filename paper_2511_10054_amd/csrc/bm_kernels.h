@@ -63,6 +63,7 @@ struct FrontParams {
     int32_t *tile_counts;   // [E][n_tiles]
     int32_t *tile_stats;    // [n_tiles][4]
     int fused;              // one workgroup walks all tiles and also does the scan and the scatter
+    int tile_tokens;        // tokens per workgroup: TILE_T, or 16 for small batches (bf16 kernel, see front_tile_tokens)
     ScanParams scan;        // used when fused
     ScatterParams scat;     // used when fused
 };
@@ -115,7 +116,8 @@ struct CombineParams {
 // the kernel and the HIP error) otherwise
 int launch_status(const char *what);
 
-bool front_can_fuse(int T, int dtype);   // the batch is small enough for the one-workgroup front end
+bool front_can_fuse(int T, int dtype, uint32_t flags);   // the batch is small enough for the one-workgroup front end
+int front_tile_tokens(int T, int K, int dtype, bool fused);   // tokens per workgroup of the front kernel
 int launch_front(const FrontParams &p, int dtype, hipStream_t st);
 int launch_remap(const RemapParams &p, hipStream_t st);
 int launch_count(const int32_t *ids, int T, int K, int E, int32_t *tile_counts, hipStream_t st);
