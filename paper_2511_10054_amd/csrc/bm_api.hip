@@ -107,7 +107,7 @@ Layout make_layout(const bm_layer_desc *d) {
     L.ids2 = take(A * 4);
     L.w = take(A * 4);
     L.tile_counts = take((size_t)tiles16 * d->E * 4);
-    L.tile_base = take((size_t)L.n_tiles * d->E * 4);
+    L.tile_base = take((size_t)tiles16 * d->E * 4);
     L.tile_stats = take((size_t)tiles16 * 16);
     L.offsets = take((size_t)(G + 1) * 4);
     L.perm = take(A * 4);
@@ -265,7 +265,7 @@ int bm_route_topk(const bm_layer_desc *desc, const void *x, const void *w_router
     p.flags = desc->flags;
     p.ids = ids; p.w = w;
     p.bitmap = nullptr;
-    p.tile_tokens = front_tile_tokens(desc->T, desc->K, desc->dtype, false);
+    p.tile_tokens = front_tile_tokens(desc->T, desc->dtype, false);
     return launch_front(p, desc->dtype, static_cast<hipStream_t>(stream)) ? BM_ERR_HIP : BM_OK;
 }
 
@@ -305,7 +305,7 @@ int bm_permute_by_expert(const bm_layer_desc *desc, const int32_t *ids_remapped,
     (void)hipGetLastError();
     int err = 0;
     if (!grouping_small((long long)d2.T * d2.K))       // the small-batch kernel counts for itself
-        err = launch_count(ids_remapped, d2.T, d2.K, d2.E, at<int32_t>(workspace, L.tile_counts), st);
+        err = launch_count(ids_remapped, d2.T, d2.K, d2.E, TILE_T, at<int32_t>(workspace, L.tile_counts), st);
     ScanParams sp{};
     sp.T = d2.T; sp.E = d2.E; sp.n_shared = 0; sp.n_tiles = L.n_tiles; sp.BM = 128;
     sp.tile_counts = at<int32_t>(workspace, L.tile_counts);
@@ -317,7 +317,7 @@ int bm_permute_by_expert(const bm_layer_desc *desc, const int32_t *ids_remapped,
     sp.n_mtiles = at<int32_t>(workspace, L.n_mtiles);
     sp.stats = nullptr;
     ScatterParams cp{};
-    cp.T = d2.T; cp.K = d2.K; cp.E = d2.E; cp.n_shared = 0;
+    cp.T = d2.T; cp.K = d2.K; cp.E = d2.E; cp.n_shared = 0; cp.tile_tokens = TILE_T;
     cp.ids = ids_remapped; cp.offsets = offsets; cp.tile_base = sp.tile_base;
     cp.perm = perm; cp.inv_perm = inv_perm; cp.row_token = nullptr;
     err |= launch_grouping(sp, cp, st);
@@ -367,7 +367,7 @@ int bm_moe_forward(const bm_layer_desc *desc, const void *x, const bm_weights *w
     fp.tile_counts = at<int32_t>(ws, L.tile_counts);
     fp.tile_stats = at<int32_t>(ws, L.tile_stats);
     const bool fuse = front_can_fuse(T, desc->dtype, desc->flags);
-    fp.tile_tokens = front_tile_tokens(T, K, desc->dtype, fuse);
+    fp.tile_tokens = front_tile_tokens(T, desc->dtype, fuse);
 
     // 2. offsets, tile bases, row-tile table, statistics
     ScanParams sp{};
@@ -384,7 +384,7 @@ int bm_moe_forward(const bm_layer_desc *desc, const void *x, const bm_weights *w
 
     // 3. stable placement
     ScatterParams cp{};
-    cp.T = T; cp.K = K; cp.E = E; cp.n_shared = desc->n_shared;
+    cp.T = T; cp.K = K; cp.E = E; cp.n_shared = desc->n_shared; cp.tile_tokens = fp.tile_tokens;
     cp.ids = fp.ids2; cp.offsets = sp.offsets; cp.tile_base = sp.tile_base;
     cp.perm = at<int32_t>(ws, L.perm); cp.inv_perm = at<int32_t>(ws, L.inv_perm);
     cp.row_token = at<int32_t>(ws, L.row_token);
@@ -408,7 +408,7 @@ int bm_moe_forward(const bm_layer_desc *desc, const void *x, const bm_weights *w
         mp.q = fp.q; mp.eta = fp.eta; mp.probs = psi ? at<float>(ws, L.probs) : nullptr;
         mp.ids_in = fp.ids; mp.ids_out = fp.ids2; mp.w = fp.w; mp.stats = sp.stats;
         err |= launch_remap(mp, st);
-        if (!grouping_small((long long)T * K)) err |= launch_count(fp.ids2, T, K, E, fp.tile_counts, st);
+        if (!grouping_small((long long)T * K)) err |= launch_count(fp.ids2, T, K, E, fp.tile_tokens, fp.tile_counts, st);
         ScanParams sq = sp;
         sq.tile_stats = nullptr; sq.stats = nullptr;      // written by the substitution kernel
         err |= launch_grouping(sq, cp, st);

@@ -682,11 +682,11 @@ __global__ void zero_ints_kernel(int32_t *p, int n) {
 }
 
 // Per-tile histogram of given ids (stand-alone grouping entry point).
-__global__ void __launch_bounds__(256) count_kernel(const int32_t *ids, int T, int K, int E,
+__global__ void __launch_bounds__(256) count_kernel(const int32_t *ids, int T, int K, int E, int tile_tokens,
                                                     int32_t *tile_counts) {
     __shared__ int32_t counts[BM_MAX_E];
-    const int tid = threadIdx.x, tile = blockIdx.x, t0 = tile * TILE_T;
-    const int n = min(TILE_T, T - t0) * K;
+    const int tid = threadIdx.x, tile = blockIdx.x, t0 = tile * tile_tokens;
+    const int n = min(tile_tokens, T - t0) * K;
     for (int e = tid; e < E; e += blockDim.x) counts[e] = 0;
     __syncthreads();
     for (int idx = tid; idx < n; idx += blockDim.x) {
@@ -694,7 +694,7 @@ __global__ void __launch_bounds__(256) count_kernel(const int32_t *ids, int T, i
         if ((unsigned)e < (unsigned)E) atomicAdd(&counts[e], 1);
     }
     __syncthreads();
-    const int n_tiles_all = (T + TILE_T - 1) / TILE_T;
+    const int n_tiles_all = (T + tile_tokens - 1) / tile_tokens;
     for (int e = tid; e < E; e += blockDim.x) tile_counts[(size_t)e * n_tiles_all + tile] = counts[e];
 }
 
@@ -793,10 +793,10 @@ __global__ void __launch_bounds__(1024) scan_kernel(ScanParams p) {
 // ---------------------------------------------------------------------------
 __global__ void __launch_bounds__(256) scatter_kernel(ScatterParams p) {
     __shared__ int32_t s_ids[TILE_T * BM_MAX_K];
-    const int tid = threadIdx.x, tile = blockIdx.x, t0 = tile * TILE_T;
-    const int n_tiles_all = (p.T + TILE_T - 1) / TILE_T;
+    const int tid = threadIdx.x, tile = blockIdx.x, t0 = tile * p.tile_tokens;
+    const int n_tiles_all = (p.T + p.tile_tokens - 1) / p.tile_tokens;
     const int K = p.K, E = p.E;
-    const int ntok = min(TILE_T, p.T - t0);
+    const int ntok = min(p.tile_tokens, p.T - t0);
     const int n = ntok * K;
     for (int idx = tid; idx < n; idx += blockDim.x) {
         const int e = p.ids[(size_t)t0 * K + idx];
@@ -818,7 +818,7 @@ __global__ void __launch_bounds__(256) scatter_kernel(ScatterParams p) {
         p.inv_perm[a] = pos;
     }
     // positions past the live count hold -1
-    for (int idx = tid; idx < TILE_T * K; idx += blockDim.x) {
+    for (int idx = tid; idx < p.tile_tokens * K; idx += blockDim.x) {
         const int pos = t0 * K + idx;
         if (pos >= live && pos < p.T * K) p.perm[pos] = -1;
     }
@@ -924,12 +924,12 @@ bool front_can_fuse(int T, int dtype, uint32_t flags) {
     return dtype == BM_BF16 && T > 0 && T <= ((flags & BM_GATE_DIST) ? TILE_T : 16);
 }
 
-// Tokens per workgroup of the bf16 front kernel.  A tile's router product is bound by the number of
-// cache lines its loads touch, so small batches are cut into 16-token tiles on twice the compute units
-// (measured at 64 tokens: 12 us instead of 18).  Large batches keep 32: the per-tile histograms the scan
-// and scatter kernels work on are defined on tiles of TILE_T.
-int front_tile_tokens(int T, int K, int dtype, bool fused) {
-    return (dtype == BM_BF16 && !fused && grouping_small((long long)T * K)) ? 16 : TILE_T;
+// Tokens per workgroup of the bf16 front kernel (and per tile of the histograms that the scan and scatter
+// kernels work on).  A tile's router product is bound by the number of cache lines its loads touch, so
+// as long as 32-token tiles would not give every compute unit a workgroup, the batch is cut into 16-token
+// tiles on twice the units (measured at 64 tokens: front kernel 12 us instead of 18).
+int front_tile_tokens(int T, int dtype, bool fused) {
+    return (dtype == BM_BF16 && !fused && (T + TILE_T - 1) / TILE_T < 256) ? 16 : TILE_T;
 }
 
 int launch_front(const FrontParams &p, int dtype, hipStream_t st) {
@@ -965,9 +965,9 @@ int launch_remap(const RemapParams &p, hipStream_t st) {
     return launch_status(__func__);
 }
 
-int launch_count(const int32_t *ids, int T, int K, int E, int32_t *tile_counts, hipStream_t st) {
-    const int n_tiles = (T + TILE_T - 1) / TILE_T;
-    if (n_tiles) hipLaunchKernelGGL(count_kernel, dim3(n_tiles), dim3(256), 0, st, ids, T, K, E, tile_counts);
+int launch_count(const int32_t *ids, int T, int K, int E, int tile_tokens, int32_t *tile_counts, hipStream_t st) {
+    const int n_tiles = (T + tile_tokens - 1) / tile_tokens;
+    if (n_tiles) hipLaunchKernelGGL(count_kernel, dim3(n_tiles), dim3(256), 0, st, ids, T, K, E, tile_tokens, tile_counts);
     return launch_status(__func__);
 }
 
@@ -989,7 +989,7 @@ int launch_grouping(const ScanParams &sp, const ScatterParams &cp, hipStream_t s
 }
 
 int launch_scatter(const ScatterParams &p, hipStream_t st) {
-    const int n_tiles = (p.T + TILE_T - 1) / TILE_T;
+    const int n_tiles = (p.T + p.tile_tokens - 1) / p.tile_tokens;
     if (n_tiles) hipLaunchKernelGGL(scatter_kernel, dim3(n_tiles), dim3(256), 0, st, p);
     return launch_status(__func__);
 }

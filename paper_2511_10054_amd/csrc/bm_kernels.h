@@ -36,6 +36,7 @@ struct ScanParams {
 
 struct ScatterParams {
     int T, K, E, n_shared;
+    int tile_tokens;              // tokens per tile of the histograms (the front kernel's or count kernel's tiles)
     const int32_t *ids;           // [T][K] after substitution
     const int32_t *offsets;       // [E + n_shared + 1]
     const int32_t *tile_base;     // [E][n_tiles]
@@ -117,10 +118,10 @@ struct CombineParams {
 int launch_status(const char *what);
 
 bool front_can_fuse(int T, int dtype, uint32_t flags);   // the batch is small enough for the one-workgroup front end
-int front_tile_tokens(int T, int K, int dtype, bool fused);   // tokens per workgroup of the front kernel
+int front_tile_tokens(int T, int dtype, bool fused);   // tokens per workgroup of the front kernel
 int launch_front(const FrontParams &p, int dtype, hipStream_t st);
 int launch_remap(const RemapParams &p, hipStream_t st);
-int launch_count(const int32_t *ids, int T, int K, int E, int32_t *tile_counts, hipStream_t st);
+int launch_count(const int32_t *ids, int T, int K, int E, int tile_tokens, int32_t *tile_counts, hipStream_t st);
 int launch_scan(const ScanParams &p, hipStream_t st);
 int launch_scatter(const ScatterParams &p, hipStream_t st);
 int launch_grouping(const ScanParams &sp, const ScatterParams &cp, hipStream_t st);   // scan + scatter (one kernel for small batches)
