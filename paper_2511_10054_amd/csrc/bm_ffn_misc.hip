@@ -90,18 +90,35 @@ __global__ void __launch_bounds__(256) combine_kernel(CombineParams p) {
         float acc[8];
 #pragma unroll
         for (int i = 0; i < 8; ++i) acc[i] = 0.0f;
-        for (int k = 0; k < nsrc; ++k) {
+        if (O_BF16) {
+            // rows are fetched four at a time before they are added (in slot order): one 16-byte load in
+            // flight per thread does not keep the memory system busy; a dropped slot reads row 0 with weight 0
+            for (int k0 = 0; k0 < nsrc; k0 += 4) {
+                u32x4 v[4];
+                float wk[4];
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    const int k = k0 + u;
+                    const int pos = k < nsrc ? s_pos[k] : -1;
+                    wk[u] = pos >= 0 ? s_w[k] : 0.0f;
+                    v[u] = ldg128(static_cast<const uint16_t *>(p.o) + (size_t)max(pos, 0) * p.d + j0);
+                }
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    if (k0 + u >= nsrc || s_pos[k0 + u] < 0) continue;
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) {
+                        acc[2 * i] = fmaf(wk[u], bf16_to_f32((uint16_t)(v[u][i] & 0xffffu)), acc[2 * i]);
+                        acc[2 * i + 1] = fmaf(wk[u], bf16_to_f32((uint16_t)(v[u][i] >> 16)), acc[2 * i + 1]);
+                    }
+                }
+            }
+        }
+        for (int k = 0; !O_BF16 && k < nsrc; ++k) {
             const int pos = s_pos[k];
             if (pos < 0) continue;
             const float wk = s_w[k];
-            if (O_BF16) {
-                const u32x4 v = ldg128(static_cast<const uint16_t *>(p.o) + (size_t)pos * p.d + j0);
-#pragma unroll
-                for (int i = 0; i < 4; ++i) {
-                    acc[2 * i] = fmaf(wk, bf16_to_f32((uint16_t)(v[i] & 0xffffu)), acc[2 * i]);
-                    acc[2 * i + 1] = fmaf(wk, bf16_to_f32((uint16_t)(v[i] >> 16)), acc[2 * i + 1]);
-                }
-            } else {
+            {
                 // partial sums of the split reduction are added in slice order first
                 float o[8];
 #pragma unroll
