@@ -158,6 +158,7 @@ LAYER_CASES = [
     ("c1_tiny", dict(d=72, F=100, E=11, K=3, n_resident=5), 45),
     ("c2_mixtral_decode", dict(d=512, F=1024), 1),
     ("c2_mixtral_decode", dict(d=512, F=1024), 8),
+    ("c2_mixtral_decode", dict(d=512, F=1024), 17),       # a full and a one-token 16-token tile
     ("c2_mixtral_decode", dict(d=512, F=1024), 64),
     ("c3_mixtral_prefill", dict(d=512, F=1024), 700),
     ("c3_mixtral_prefill", dict(d=1024, F=416), 333),     # F not a multiple of the column tile
@@ -362,6 +363,7 @@ def test_gates_need_weights():
 GATED_LAYER_CASES = [
     ("c1_tiny", {}, 16, False),
     ("c2_mixtral_decode", dict(d=512, F=1024), 8, False),       # fused one-workgroup front end
+    ("c2_mixtral_decode", dict(d=512, F=1024), 24, True),       # two 16-token tiles; one 32-token tile with the distribution gate
     ("c2_mixtral_decode", dict(d=512, F=1024), 64, True),
     ("c3_mixtral_prefill", dict(d=512, F=1024), 700, False),
     ("c4_qwen3", dict(d=256, F=384), 300, True),
