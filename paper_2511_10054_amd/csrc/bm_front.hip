@@ -494,6 +494,7 @@ __global__ void __launch_bounds__(NW * 64) front_bf16_kernel(FrontParams p) {
     constexpr int NS_FIT = (68 * 1024) / (TILE * 4);
     constexpr int NS = NS_FIT >= NW ? NW : (NS_FIT < 1 ? 1 : NS_FIT);   // partial tiles kept side by side
     __shared__ float part[NS * TILE];
+    __shared__ u32x4 stage[NB == 1 && !FUSED ? NW * 256 : 1];   // 4 KB per wave (see the staged product below)
     __shared__ FrontLds s;
     __shared__ FusedLds fs_store[FUSED ? 1 : 0 + 1];
     FusedLds &fs = fs_store[0];
@@ -522,7 +523,54 @@ __global__ void __launch_bounds__(NW * 64) front_bf16_kernel(FrontParams p) {
 #pragma unroll
             for (int nb = 0; nb < NB; ++nb) acc[tb][nb] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-        for (int bt = wave; bt < nbatch; bt += NW) {
+        // Tiles of at most 16 tokens and 16 experts: the operands are fetched as whole 128-byte lines (8
+        // rows per instruction, half as many lines touched as with 64 bytes per row) and turned into the
+        // MFMA operand order through a wave-private LDS area: stored 8 rows x 128 bytes per register,
+        // read back 16 rows x 16 bytes per fragment, the 16-byte pieces of a row rotated by the row index
+        // against bank conflicts.  No barrier: only the writing wave reads the area, and a wave's LDS
+        // operations stay in order.
+        // (not in the fused kernel, which has no registers to spare: it serves batches of a few tokens,
+        // whose direct loads touch few lines anyway)
+        const bool staged = NB == 1 && U == 4 && !FUSED && !two;
+        if (staged) {
+            u32x4 *area = stage + (NB == 1 && !FUSED ? wave : 0) * 256;   // [operand][row 0..15][piece 0..7]
+            const int lrow = lane >> 3, lpiece = lane & 7;
+            const uint16_t *xs_[2], *ws_[2];
+            int wslot[2];
+#pragma unroll
+            for (int j = 0; j < 2; ++j) {
+                const int r = 8 * j + lrow;
+                xs_[j] = x + (size_t)min(t0 + r, p.T - 1) * p.d + lpiece * 8;
+                ws_[j] = wr + (size_t)min(r, p.E - 1) * p.d + lpiece * 8;
+                wslot[j] = r * 8 + (lpiece ^ (r & 7));
+            }
+            for (int bt = wave; bt < nbatch; bt += NW) {
+                const int k0 = bt * 128;
+                u32x4 rx[2][2], rw[2][2];                           // [line of the 256-byte span][row group]
+#pragma unroll
+                for (int h = 0; h < 2; ++h)
+#pragma unroll
+                    for (int j = 0; j < 2; ++j) {
+                        rx[h][j] = ldg128(xs_[j] + k0 + h * 64);
+                        rw[h][j] = ldg128(ws_[j] + k0 + h * 64);
+                    }
+#pragma unroll
+                for (int h = 0; h < 2; ++h) {
+#pragma unroll
+                    for (int j = 0; j < 2; ++j) {
+                        area[wslot[j]] = rx[h][j];
+                        area[128 + wslot[j]] = rw[h][j];
+                    }
+#pragma unroll
+                    for (int ks = 0; ks < 2; ++ks) {
+                        const int slot = r16 * 8 + ((ks * 4 + kq) ^ (r16 & 7));
+                        const bf16x8 a = as_bf16x8(area[slot]), b = as_bf16x8(area[128 + slot]);
+                        acc[0][0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, acc[0][0], 0, 0, 0);
+                    }
+                }
+            }
+        }
+        for (int bt = wave; !staged && bt < nbatch; bt += NW) {
             const int k0 = bt * U * 32;
             u32x4 ra[2][U], rb[NB][U];
 #pragma unroll
@@ -917,11 +965,11 @@ static void launch_front_bf16(const FrontParams &p, int n_tiles, hipStream_t st)
     else hipLaunchKernelGGL((front_bf16_kernel<NB, NW, U, false>), dim3(n_tiles), dim3(NW * 64), 0, st, p);
 }
 
-// One workgroup for the whole front end: up to 16 tokens (one 16-token row block; from 17 tokens on two
-// workgroups of 16 tokens plus the grouping kernel are faster), or up to one tile when the distribution
+// One workgroup for the whole front end: up to 8 tokens (from there on workgroups of 16 tokens plus the
+// grouping kernel are faster: 15.6 against 17.7 us at 16 tokens), or up to one tile when the distribution
 // gate is on (its in-tile form needs the whole batch in one workgroup and saves two launches).
 bool front_can_fuse(int T, int dtype, uint32_t flags) {
-    return dtype == BM_BF16 && T > 0 && T <= ((flags & BM_GATE_DIST) ? TILE_T : 16);
+    return dtype == BM_BF16 && T > 0 && T <= ((flags & BM_GATE_DIST) ? TILE_T : 8);
 }
 
 // Tokens per workgroup of the bf16 front kernel (and per tile of the histograms that the scan and scatter
