@@ -965,11 +965,12 @@ static void launch_front_bf16(const FrontParams &p, int n_tiles, hipStream_t st)
     else hipLaunchKernelGGL((front_bf16_kernel<NB, NW, U, false>), dim3(n_tiles), dim3(NW * 64), 0, st, p);
 }
 
-// One workgroup for the whole front end: up to 8 tokens (from there on workgroups of 16 tokens plus the
-// grouping kernel are faster: 15.6 against 17.7 us at 16 tokens), or up to one tile when the distribution
-// gate is on (its in-tile form needs the whole batch in one workgroup and saves two launches).
+// One workgroup for the whole front end (router to placement): only with the distribution gate and a
+// batch of at most one tile - the gate's in-tile form needs the whole batch in one workgroup and saves two
+// launches.  Otherwise workgroups of 16 tokens plus the grouping kernel are faster at every batch size
+// (front end at 1 / 8 / 16 tokens: 13.8 / 13.6 / 14.2 us against 15.0 / 16.0 / 17.7 us).
 bool front_can_fuse(int T, int dtype, uint32_t flags) {
-    return dtype == BM_BF16 && T > 0 && T <= ((flags & BM_GATE_DIST) ? TILE_T : 8);
+    return dtype == BM_BF16 && (flags & BM_GATE_DIST) && T > 0 && T <= TILE_T;
 }
 
 // Tokens per workgroup of the bf16 front kernel (and per tile of the histograms that the scan and scatter
