@@ -375,6 +375,7 @@ int bm_moe_forward(const bm_layer_desc *desc, const void *x, const bm_weights *w
     sp.T = T; sp.E = E; sp.n_shared = desc->n_shared;
     sp.n_tiles = (T + fp.tile_tokens - 1) / fp.tile_tokens;   // tiles of the front kernel (per-tile statistics)
     sp.BM = skinny ? (1 << 20) : gemm_tile_rows(desc);   // skinny: one table entry per live group
+    sp.largest_first = skinny ? 1 : 0;
     sp.tile_counts = fp.tile_counts; sp.tile_base = at<int32_t>(ws, L.tile_base);
     sp.tile_stats = fp.tile_stats;
     sp.offsets = at<int32_t>(ws, L.offsets);

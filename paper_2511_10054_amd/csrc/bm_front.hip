@@ -933,11 +933,24 @@ __global__ void __launch_bounds__(1024) group_small_kernel(ScanParams p, Scatter
     }
     __syncthreads();
     for (int g = tid; g <= G; g += blockDim.x) p.offsets[g] = start[g];
-    for (int g = tid; g < G; g += blockDim.x) {
-        const int nt = tstart[g + 1] - tstart[g];
-        for (int i = 0; i < nt; ++i) {
-            p.mt_group[tstart[g] + i] = g;
-            p.mt_row0[tstart[g] + i] = start[g] + i * p.BM;
+    if (p.largest_first) {
+        // decode projections: a group is one work-item column of the grid, and groups with more rows take
+        // longer per item; handing the big ones out first leaves the short items for the end of the launch
+        for (int g = tid; g < G; g += blockDim.x) {
+            const int n = total[g];
+            if (n == 0) continue;
+            int rank = 0;
+            for (int h = 0; h < G; ++h) rank += (total[h] > n || (total[h] == n && h < g)) ? 1 : 0;
+            p.mt_group[rank] = g;
+            p.mt_row0[rank] = start[g];
+        }
+    } else {
+        for (int g = tid; g < G; g += blockDim.x) {
+            const int nt = tstart[g + 1] - tstart[g];
+            for (int i = 0; i < nt; ++i) {
+                p.mt_group[tstart[g] + i] = g;
+                p.mt_row0[tstart[g] + i] = start[g] + i * p.BM;
+            }
         }
     }
     if (p.stats != nullptr && wave < 3) {          // one wave per counter, lanes over the tiles

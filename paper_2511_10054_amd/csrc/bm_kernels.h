@@ -25,6 +25,7 @@ struct RemapParams {
 
 struct ScanParams {
     int T, E, n_shared, n_tiles, BM;
+    int largest_first;            // small-batch kernel, one row tile per group: list the groups by falling row count
     const int32_t *tile_counts;   // [E][n_tiles]
     int32_t *tile_base;           // [E][n_tiles]
     const int32_t *tile_stats;    // [n_tiles][4] or null
