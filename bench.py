@@ -111,6 +111,7 @@ def run_workload(name, T, steps, warmup, with_events=True, unique=False, base=No
     # they stay out of the pass above.
     stage_ms = None
     ms_per_step_ev = None
+    step_pct = None
     if events is not None:
         torch.cuda.synchronize()
         t0 = time.perf_counter()
@@ -119,10 +120,13 @@ def run_workload(name, T, steps, warmup, with_events=True, unique=False, base=No
         torch.cuda.synchronize()
         ms_per_step_ev = (time.perf_counter() - t0) * 1e3 / steps
         acc = np.zeros(4)
+        per_step = []
         for evs in events:
             for j in range(4):
                 acc[j] += hipev.elapsed_ms(evs[j], evs[j + 1])
+            per_step.append(hipev.elapsed_ms(evs[0], evs[4]))
         stage_ms = acc / steps
+        step_pct = [float(np.percentile(per_step, q)) for q in (10, 50, 90)]
         for evs in events:
             hipev.destroy(evs)
 
@@ -133,7 +137,7 @@ def run_workload(name, T, steps, warmup, with_events=True, unique=False, base=No
     rows = a_live + spec.n_shared * T
     groups = n_touched + spec.n_shared
     return dict(spec=spec, host=host, dev=dev, T=T, ms_per_step=ms_per_step, stage_ms=stage_ms,
-                ms_per_step_ev=ms_per_step_ev,
+                ms_per_step_ev=ms_per_step_ev, step_pct=step_pct,
                 a_live=a_live, n_touched=n_touched, rows=rows, groups=groups,
                 stats=stats.cpu().tolist(), gen_s=t_gen)
 
@@ -200,8 +204,8 @@ def cpu_baseline(r, budget_tokens):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=50)
-    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--steps", type=int, default=100)
+    ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", default="c2", choices=sorted(WORKLOADS))
     ap.add_argument("--tokens", type=int, default=None)
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -265,6 +269,7 @@ def main():
         "stages_us": {k: round(float(v) * 1e3, 2) for k, v in
                       zip(("front_and_grouping", "gate_up", "down", "combine"), r["stage_ms"])},
         "ms_per_step_with_stage_events": round(r["ms_per_step_ev"], 5),
+        "step_ms_p10_p50_p90_with_stage_events": [round(v, 5) for v in r["step_pct"]],
     }
     also = args.also_tokens
     if also is None and args.workload == "c2" and not args.tokens:
