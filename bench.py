@@ -183,6 +183,24 @@ def roofline_layer(r):
                 frac=round(ach / PEAK_BF16_TFLOPS, 4), algorithmic_flops=int(flops))
 
 
+def read_stream_gbs():
+    """Achievable HBM read rate: the library's plain streaming-read kernel over 2 GiB, timed with events."""
+    import torch
+    import paper_2511_10054_amd as bm
+    buf = torch.empty(1 << 31, dtype=torch.uint8, device="cuda").random_(0, 255)
+    sink = torch.zeros(1, dtype=torch.int32, device="cuda")
+    for _ in range(3):
+        bm.bm_stream_read(buf, sink)
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+    n = 10
+    ev[0].record()
+    for _ in range(n):
+        bm.bm_stream_read(buf, sink)
+    ev[1].record()
+    torch.cuda.synchronize()
+    return buf.numel() * n / (ev[0].elapsed_time(ev[1]) * 1e-3) / 1e9
+
+
 def cpu_baseline(r, budget_tokens):
     """The oracle as it stands, timed on the host cores on the first n tokens of the workload."""
     import oracle
@@ -286,6 +304,13 @@ def main():
                                      "layer_frac": roofline_layer(r2)["frac"],
                                      "stages_us": {k: round(float(v) * 1e3, 2) for k, v in
                                                    zip(("front_and_grouping", "gate_up", "down", "combine"), r2["stage_ms"])}}
+    rs = read_stream_gbs()
+    out["hbm_read_stream"] = {"achieved": round(rs, 1), "unit": "GB/s", "bytes": 1 << 31,
+                              "note": "bm_stream_read, the practical ceiling of an HBM-bound kernel on this device"}
+    if out["layer_roofline"]["bound"] == "hbm":
+        out["layer_roofline"]["frac_of_read_stream"] = round(out["layer_roofline"]["achieved"] / rs, 4)
+    if roof["bound"] == "hbm":
+        roof["frac_of_read_stream"] = round(roof["achieved"] / rs, 4)
     if not args.no_cpu_baseline:
         base, err = cpu_baseline(r, 64 if args.workload == "c2" else 256)
         out["cpu_baseline"] = base

@@ -10,5 +10,5 @@ from .binding import (  # noqa: F401
     LayerDesc, Weights, BuddyMoEError,
     bm_route_topk, bm_buddy_remap, bm_permute_by_expert, bm_moe_forward,
     bm_workspace_bytes, bm_validate_tables, bm_strerror, library_path, load_library,
-    bm_packed_bytes, bm_pack_weights, bm_coactivation_accumulate, bm_build_buddy_table,
+    bm_packed_bytes, bm_pack_weights, bm_coactivation_accumulate, bm_build_buddy_table, bm_stream_read,
 )

@@ -70,6 +70,8 @@ def load_library() -> ctypes.CDLL:
         lib.bm_permute_by_expert.argtypes = [ctypes.POINTER(LayerDesc), vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
         lib.bm_moe_forward.argtypes = [ctypes.POINTER(LayerDesc), vp, ctypes.POINTER(Weights), vp, vp, vp, vp,
                                        ctypes.c_size_t, ctypes.POINTER(DebugOut), vp]
+        lib.bm_stream_read.argtypes = [vp, ctypes.c_size_t, vp, vp]
+        lib.bm_stream_read.restype = i32
         for f in (lib.bm_validate_tables, lib.bm_route_topk, lib.bm_buddy_remap, lib.bm_permute_by_expert,
                   lib.bm_moe_forward, lib.bm_coactivation_accumulate, lib.bm_build_buddy_table):
             f.restype = i32
@@ -165,6 +167,12 @@ def make_weights(w_router, router_bias, w_gate, w_up, w_down, ws_gate=None, ws_u
                  wp_gateup=None, wp_down=None, wsp_gateup=None, wsp_down=None, buddy_q=None) -> Weights:
     return Weights(*[_ptr(t) for t in (w_router, router_bias, w_gate, w_up, w_down, ws_gate, ws_up, ws_down,
                                        wp_gateup, wp_down, wsp_gateup, wsp_down, buddy_q)])
+
+
+def bm_stream_read(src, sink, stream: Optional[int] = None):
+    """Measurement aid: one streaming read of the whole tensor `src` (see include/buddymoe.h)."""
+    _check(load_library().bm_stream_read(_ptr(src), src.numel() * src.element_size(), _ptr(sink),
+                                         _stream() if stream is None else stream), "bm_stream_read")
 
 
 def bm_packed_bytes(desc: LayerDesc, which: int) -> int:

@@ -152,6 +152,13 @@ void copy_ints(const void *src, void *dst, size_t n, hipStream_t st) {
 
 extern "C" {
 
+int bm_stream_read(const void *src, size_t bytes, uint32_t *sink, void *stream) {
+    if (!sink || (bytes && !src)) return BM_ERR_NULL;
+    if (bytes % 16) return BM_ERR_SHAPE;
+    (void)hipGetLastError();
+    return launch_stream_read(src, bytes, sink, static_cast<hipStream_t>(stream)) ? BM_ERR_HIP : BM_OK;
+}
+
 const char *bm_strerror(int status) {
     switch (status) {
         case BM_OK: return "ok";

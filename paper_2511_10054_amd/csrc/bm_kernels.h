@@ -143,6 +143,7 @@ int launch_skinny_gateup_bf16(const SkinnyParams &p, hipStream_t st);
 int launch_skinny_down_bf16(const SkinnyParams &p, hipStream_t st);
 
 int launch_combine(const CombineParams &p, bool o_bf16, hipStream_t st);
+int launch_stream_read(const void *src, size_t bytes, uint32_t *sink, hipStream_t st);
 
 // fragment-major repacking of n matrices [N][Kd] (two interleaved when src1 is given)
 int launch_pack(const void *src0, const void *src1, void *dst, int n, int N, int Kd, const uint64_t *bitmap,

@@ -313,7 +313,8 @@ __device__ __forceinline__ void skinny_lds_pass(const SkinnyParams &p, const uin
     constexpr int XW = CH / 4;                          // k-steps of a chunk each wave stages
     BM_OPAQUE_PTR(w0);
     BM_OPAQUE_PTR(w1);
-    static_assert(XW == 2, "a wave stages one 128-byte line of every activation row per chunk");
+    static_assert(XW % 2 == 0, "a wave stages whole 128-byte lines (two k-steps) of every activation row");
+    constexpr int XL = XW / 2;                          // lines per row and chunk a wave stages
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, lr = lane & 15, lk = lane >> 4;
     const uint16_t *a = static_cast<const uint16_t *>(p.a);
     // Staging loads are issued in whole lines: instruction j of row block tb reads rows 8j..8j+7, lane l
@@ -346,16 +347,19 @@ __device__ __forceinline__ void skinny_lds_pass(const SkinnyParams &p, const uin
         acc0[tb] = f32x4{0.f, 0.f, 0.f, 0.f};
         acc1[tb] = f32x4{0.f, 0.f, 0.f, 0.f};
     }
-    u32x4 s0[CH], s1[CH], xr[XW * NBT];
+    u32x4 s0[CH], s1[CH], xr[XL * 2 * NBT];
     const int nch = (k_end - k_begin) / (CH * 32);
 
 #define BM_LOAD_X(k_)                                                                      \
-    _Pragma("unroll") for (int j = 0; j < 2; ++j)                                          \
-        _Pragma("unroll") for (int tb = 0; tb < NBT; ++tb) xr[j * NBT + tb] = ldg128(xa[tb][j] + (k_));
+    _Pragma("unroll") for (int li = 0; li < XL; ++li)                                      \
+        _Pragma("unroll") for (int j = 0; j < 2; ++j)                                      \
+            _Pragma("unroll") for (int tb = 0; tb < NBT; ++tb)                             \
+                xr[(li * 2 + j) * NBT + tb] = ldg128(xa[tb][j] + (k_) + li * 64);
 #define BM_STORE_X(buf_)                                                                   \
-    _Pragma("unroll") for (int j = 0; j < 2; ++j)                                          \
-        _Pragma("unroll") for (int tb = 0; tb < NBT; ++tb)                                 \
-            xs[(((buf_) * CH + XW * wave) * NBT + tb) * 64 + wslot[j]] = xr[j * NBT + tb];
+    _Pragma("unroll") for (int li = 0; li < XL; ++li)                                      \
+        _Pragma("unroll") for (int j = 0; j < 2; ++j)                                      \
+            _Pragma("unroll") for (int tb = 0; tb < NBT; ++tb)                             \
+                xs[(((buf_) * CH + XW * wave + 2 * li) * NBT + tb) * 64 + wslot[j]] = xr[(li * 2 + j) * NBT + tb];
 
     BM_LOAD_X(k_begin);
 #pragma unroll

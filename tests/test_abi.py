@@ -153,3 +153,12 @@ def test_product_package_does_not_import_the_oracle():
             if f.endswith((".py", ".hip", ".h", ".cpp")):
                 text = open(os.path.join(root, f)).read()
                 assert "oracle" not in text.lower() or f == "README.md", f
+
+
+def test_stream_read_rejects_bad_arguments_on_the_host():
+    lib = bm.load_library()
+    lib.bm_stream_read.argtypes = [ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p, ctypes.c_void_p]
+    one = ctypes.c_void_p(16)
+    assert lib.bm_stream_read(None, 1024, one, None) == -1
+    assert lib.bm_stream_read(one, 1024, None, None) == -1
+    assert lib.bm_stream_read(one, 1000, one, None) == -2          # not a multiple of 16 bytes

@@ -431,3 +431,21 @@ def test_forward_replays_from_a_hip_graph(name, over, T):
             graph.replay()
             torch.cuda.synchronize()
             np.testing.assert_array_equal(dev.y.float().cpu().numpy(), eager[i], err_msg=f"replay {rep} input {i}")
+
+
+# ------------------------------------------------------------- measurement aid
+
+
+def test_stream_read_runs_and_leaves_memory_alone():
+    """bm_stream_read only reads: the buffer and the sink are unchanged (sizes with and without a tail
+    that is not a multiple of the grid's stride, and the empty buffer)."""
+    torch = _torch()
+    import paper_2511_10054_amd as bm
+    _say("stream read")
+    sink = torch.full((1,), 12345, dtype=torch.int32, device="cuda")
+    for n in (0, 16, 16 * 1000 * 1000 + 48, 1 << 26):
+        buf = torch.arange(n // 4, dtype=torch.int32, device="cuda")
+        ref = buf.clone()
+        bm.bm_stream_read(buf, sink)
+        torch.cuda.synchronize()
+        assert torch.equal(buf, ref) and int(sink.item()) == 12345
