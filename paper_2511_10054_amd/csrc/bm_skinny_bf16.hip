@@ -304,18 +304,39 @@ constexpr int KUNIT = 512;
 // PACKED: the weights come from bm_pack_weights' fragment-major copy, where the 1 KB operand
 // fragment of every (16-row block, k-step) is contiguous (gate and up fragments interleaved), so a
 // wave's stream is one contiguous run; otherwise from the public row-major layout.
+// Public layout (!PACKED): w0 / w1 point at weight row n0, and the rows are fetched as whole 128-byte lines
+// - ring slots 2v and 2v + 1 hold rows 0-7 and 8-15 of line v (two k-steps) of the chunk, lane l row l / 8,
+// 16-byte piece l % 8 - and turned into the two k-steps' operand fragments through `wst`, 2 KB of LDS per
+// wave and matrix (pieces of a row rotated by the row index against bank conflicts; only the writing wave
+// reads it, and a wave's LDS operations stay in order).  Loading the fragments directly, 16 rows x 64
+// bytes per instruction, touches twice the cache lines, which bounds the kernel: 252 us against 191 us for
+// the gate/up projection of the Mixtral-shaped layer at 64 tokens.
 template <bool DUAL, int NBT, bool PACKED>
 __device__ __forceinline__ void skinny_lds_pass(const SkinnyParams &p, const uint16_t *w0, const uint16_t *w1,
-                                                u32x4 *xs, int row_begin, int row_end, int k_begin,
+                                                u32x4 *xs, u32x4 *wst, int row_begin, int row_end, int k_begin,
                                                 int k_end, int n0, int kslice, bool active) {
     constexpr int CH = SkinnyChunk<NBT>::CH;
-    constexpr int KSTEP = PACKED ? 512 * (DUAL ? 2 : 1) : 32;   // weight elements between consecutive k-steps
+    constexpr int KSTEP = 512 * (DUAL ? 2 : 1);         // packed copy: weight elements between consecutive k-steps
     constexpr int XW = CH / 4;                          // k-steps of a chunk each wave stages
     BM_OPAQUE_PTR(w0);
     BM_OPAQUE_PTR(w1);
     static_assert(XW % 2 == 0, "a wave stages whole 128-byte lines (two k-steps) of every activation row");
     constexpr int XL = XW / 2;                          // lines per row and chunk a wave stages
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, lr = lane & 15, lk = lane >> 4;
+    // public layout: this lane's place in the line loads (row 8j + l / 8, piece l % 8) and in the LDS area
+    const uint16_t *wl0[2], *wl1[2];
+    int wwr[2];
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+        const int r = 8 * j + (lane >> 3);
+        wl0[j] = PACKED ? w0 : w0 + (size_t)r * p.Kd + (lane & 7) * 8;
+        wl1[j] = (PACKED || !DUAL) ? w1 : w1 + (size_t)r * p.Kd + (lane & 7) * 8;
+        wwr[j] = r * 8 + ((lane & 7) ^ (r & 7));
+    }
+    // ring slot u of the chunk that starts at reduction index kb_
+#define BM_LOADW(wp_, wl_, u_, kb_)                                                        \
+    (PACKED ? ldg128_stream((wp_) + ((kb_) >> 5) * KSTEP + (u_) * KSTEP)                   \
+            : ldg128_stream((wl_)[(u_) & 1] + (kb_) + ((u_) >> 1) * 64))
     const uint16_t *a = static_cast<const uint16_t *>(p.a);
     // Staging loads are issued in whole lines: instruction j of row block tb reads rows 8j..8j+7, lane l
     // row 8j + l / 8 and 16-byte piece l % 8 of the line, i.e. k-step (l % 8) / 4 and quarter l % 4 of
@@ -364,8 +385,8 @@ __device__ __forceinline__ void skinny_lds_pass(const SkinnyParams &p, const uin
     BM_LOAD_X(k_begin);
 #pragma unroll
     for (int u = 0; u < CH; ++u) {
-        s0[u] = ldg128_stream(w0 + (k_begin >> 5) * KSTEP + u * KSTEP);
-        if (DUAL) s1[u] = ldg128_stream(w1 + (k_begin >> 5) * KSTEP + u * KSTEP);
+        s0[u] = BM_LOADW(w0, wl0, u, k_begin);
+        if (DUAL) s1[u] = BM_LOADW(w1, wl1, u, k_begin);
     }
     BM_STORE_X(0);
     __syncthreads();
@@ -379,19 +400,33 @@ __device__ __forceinline__ void skinny_lds_pass(const SkinnyParams &p, const uin
         {                                                                                            \
             const u32x4 *xc = xs + (size_t)((c_) & 1) * CH * NBT * 64 + rslot;                       \
             _Pragma("unroll") for (int u = 0; u < CH; ++u) {                                         \
-                bf16x8 xb[NBT];                                                                      \
+                bf16x8 xb[NBT], wa, wb;                                                              \
+                if (!PACKED && (u & 1) == 0) {      /* a line's two row groups -> LDS */            \
+                    _Pragma("unroll") for (int j = 0; j < 2; ++j) {                                  \
+                        wst[wwr[j]] = s0[u + j];                                                     \
+                        if (DUAL) wst[128 + wwr[j]] = s1[u + j];                                     \
+                    }                                                                                \
+                }                                                                                    \
+                if (PACKED) {                                                                        \
+                    wa = as_bf16x8(s0[u]);                                                           \
+                    wb = as_bf16x8(s1[DUAL ? u : 0]);                                                \
+                } else {                                                                             \
+                    const int rs_ = lr * 8 + ((((u) & 1) * 4 + lk) ^ (lr & 7));                      \
+                    wa = as_bf16x8(wst[rs_]);                                                        \
+                    wb = as_bf16x8(wst[(DUAL ? 128 : 0) + rs_]);                                     \
+                }                                                                                    \
                 _Pragma("unroll") for (int tb = 0; tb < NBT; ++tb)                                   \
                     xb[tb] = as_bf16x8(xc[(u * NBT + tb) * 64]);                                     \
                 _Pragma("unroll") for (int tb = 0; tb < NBT; ++tb) {                                 \
-                    acc0[tb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(s0[u]), xb[tb],     \
-                                                                       acc0[tb], 0, 0, 0);           \
+                    acc0[tb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wa, xb[tb], acc0[tb], 0, 0, 0); \
                     if (DUAL)                                                                        \
-                        acc1[tb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(s1[u]), xb[tb], \
-                                                                           acc1[tb], 0, 0, 0);       \
+                        acc1[tb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wb, xb[tb], acc1[tb], 0, 0, 0); \
                 }                                                                                    \
-                if (REFILL_) {                                                                       \
-                    s0[u] = ldg128_stream(w0 + (kn_ >> 5) * KSTEP + u * KSTEP);                      \
-                    if (DUAL) s1[u] = ldg128_stream(w1 + (kn_ >> 5) * KSTEP + u * KSTEP);            \
+                if (REFILL_ && (PACKED || (u & 1) == 1)) {     /* public layout: both slots of the line */ \
+                    _Pragma("unroll") for (int v = PACKED ? u : u - 1; v <= u; ++v) {                \
+                        s0[v] = BM_LOADW(w0, wl0, v, kn_);                                           \
+                        if (DUAL) s1[v] = BM_LOADW(w1, wl1, v, kn_);                                 \
+                    }                                                                                \
                 }                                                                                    \
                 __builtin_amdgcn_sched_barrier(0);                                                   \
             }                                                                                        \
@@ -405,6 +440,7 @@ __device__ __forceinline__ void skinny_lds_pass(const SkinnyParams &p, const uin
 #undef BM_CHUNK
 #undef BM_LOAD_X
 #undef BM_STORE_X
+#undef BM_LOADW
     if (!active) return;
 #pragma unroll
     for (int tb = 0; tb < NBT; ++tb) {
@@ -425,7 +461,7 @@ __device__ __forceinline__ void skinny_lds_pass(const SkinnyParams &p, const uin
 
 // One item of the kernel below: 64 weight rows (a 16-row block per wave) of group g over reduction slice kslice.
 template <bool DUAL, int MAXNBT, bool PACKED>
-__device__ __forceinline__ void skinny_lds_item(const SkinnyParams &p, u32x4 *xs, int g, int blk, int kslice) {
+__device__ __forceinline__ void skinny_lds_item(const SkinnyParams &p, u32x4 *xs, u32x4 *wstage, int g, int blk, int kslice) {
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, lr = lane & 15, lk = lane >> 4;
     const int n0w = (blk * 4 + wave) * 16;
     const bool active = n0w < p.N;                    // a wave past the last weight row recomputes block 0 and stores nothing
@@ -442,17 +478,18 @@ __device__ __forceinline__ void skinny_lds_item(const SkinnyParams &p, u32x4 *xs
         w0 = base + ((size_t)gl * (p.N >> 4) + (n0 >> 4)) * (size_t)(p.Kd >> 5) * (512 * NM) + lane * 8;
         if (DUAL) w1 = w0 + 512;
     } else {
-        const size_t gofs = (size_t)gl * p.N * p.Kd;
-        w0 = static_cast<const uint16_t *>(g < p.E ? p.b0 : p.sb0) + gofs + (size_t)(n0 + lr) * p.Kd + lk * 8;
-        if (DUAL) w1 = static_cast<const uint16_t *>(g < p.E ? p.b1 : p.sb1) + gofs + (size_t)(n0 + lr) * p.Kd + lk * 8;
+        const size_t gofs = (size_t)gl * p.N * p.Kd;        // row n0 of the block; the pass adds the lane's place
+        w0 = static_cast<const uint16_t *>(g < p.E ? p.b0 : p.sb0) + gofs + (size_t)n0 * p.Kd;
+        if (DUAL) w1 = static_cast<const uint16_t *>(g < p.E ? p.b1 : p.sb1) + gofs + (size_t)n0 * p.Kd;
     }
+    u32x4 *wst = wstage + (PACKED ? 0 : wave * (DUAL ? 256 : 128));
     constexpr int PASS_ROWS = 16 * MAXNBT;
     for (int rb = row_begin; rb < row_end; rb += PASS_ROWS) {
         const int re = min(row_end, rb + PASS_ROWS);
         const int n_rows = re - rb;
-        if (MAXNBT == 1 || n_rows <= 16) skinny_lds_pass<DUAL, 1, PACKED>(p, w0, w1, xs, rb, re, k_begin, k_end, n0, kslice, active);
-        else if (MAXNBT == 2 || n_rows <= 32) skinny_lds_pass<DUAL, 2, PACKED>(p, w0, w1, xs, rb, re, k_begin, k_end, n0, kslice, active);
-        else skinny_lds_pass<DUAL, 4, PACKED>(p, w0, w1, xs, rb, re, k_begin, k_end, n0, kslice, active);
+        if (MAXNBT == 1 || n_rows <= 16) skinny_lds_pass<DUAL, 1, PACKED>(p, w0, w1, xs, wst, rb, re, k_begin, k_end, n0, kslice, active);
+        else if (MAXNBT == 2 || n_rows <= 32) skinny_lds_pass<DUAL, 2, PACKED>(p, w0, w1, xs, wst, rb, re, k_begin, k_end, n0, kslice, active);
+        else skinny_lds_pass<DUAL, 4, PACKED>(p, w0, w1, xs, wst, rb, re, k_begin, k_end, n0, kslice, active);
         __syncthreads();                              // the next pass restages the LDS buffers
     }
 }
@@ -467,9 +504,10 @@ __device__ __forceinline__ void skinny_lds_item(const SkinnyParams &p, u32x4 *xs
 template <bool DUAL, int MAXNBT, bool PACKED>
 __global__ void __launch_bounds__(256, 2) skinny_lds_bf16_kernel(SkinnyParams p) {
     __shared__ u32x4 xs[2 * SkinnyChunk<MAXNBT>::CH * MAXNBT * 64];
+    __shared__ u32x4 wstage[PACKED ? 1 : 4 * (DUAL ? 256 : 128)];    // public layout: 2 KB per wave and matrix
     const int gi = blockIdx.z;
     if (gi >= p.n_mtiles[0]) return;
-    skinny_lds_item<DUAL, MAXNBT, PACKED>(p, xs, p.mt_group[gi], blockIdx.x, blockIdx.y);
+    skinny_lds_item<DUAL, MAXNBT, PACKED>(p, xs, wstage, p.mt_group[gi], blockIdx.x, blockIdx.y);
 }
 
 bool skinny_lds_ok(int Kd, int ksplit) { return Kd % (KUNIT * ksplit) == 0; }
@@ -514,7 +552,7 @@ __device__ __forceinline__ PItem p_setup(const SkinnyParams &p, int it, int NRB,
         r.w0 = base + (((size_t)gl * NRB + rb) * (size_t)(p.Kd >> 5) + (k0 >> 5)) * (512 * NM) + (lk * 16 + lr) * 8;
         r.w1 = DUAL ? r.w0 + 512 : nullptr;
     } else {
-        const size_t rofs = (size_t)gl * p.N * p.Kd + (size_t)(r.n0 + lr) * p.Kd + lk * 8 + k0;
+        const size_t rofs = (size_t)gl * p.N * p.Kd + (size_t)r.n0 * p.Kd + k0;    // row n0; the kernel adds the lane's place
         r.w0 = static_cast<const uint16_t *>(r.g < p.E ? p.b0 : p.sb0) + rofs;
         r.w1 = DUAL ? static_cast<const uint16_t *>(r.g < p.E ? p.b1 : p.sb1) + rofs : nullptr;
     }
@@ -526,9 +564,24 @@ __global__ void __launch_bounds__(512) skinny_p_kernel(SkinnyParams p) {
     constexpr int NM = DUAL ? 2 : 1;
     constexpr int KSTEP = PACKED ? 512 * NM : 32;              // weight elements between consecutive k-steps
     constexpr int RED = 2 * 8 * NBT * NM * 64;                 // f32x4 entries of the reduction area
-    constexpr int PAD = RED * 16 < 84 * 1024 ? (84 * 1024 - RED * 16) / 16 : 0;
+    constexpr int WST = PACKED ? 0 : 8 * NM * 128;             // public layout: 2 KB per wave and matrix
+    constexpr int PAD = (RED + WST) * 16 < 84 * 1024 ? (84 * 1024 - (RED + WST) * 16) / 16 : 0;
     __shared__ f32x4 red[RED + PAD];                           // > half the LDS: one workgroup per compute unit
+    __shared__ u32x4 wstage[PACKED ? 1 : WST];
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, lr = lane & 15, lk = lane >> 4;
+    // Public layout: the weights come in as whole 128-byte lines - ring slots 2v and 2v + 1 hold rows 0-7 and
+    // 8-15 of line v of the chunk, lane l row l / 8, piece l % 8 - and reach the operand layout through the
+    // wave's own LDS area, as in the LDS-staged kernel above.
+    u32x4 *wst = wstage + (PACKED ? 0 : wave * NM * 128);
+    int lofs[2], wwr[2];
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+        const int r = 8 * j + (lane >> 3);
+        lofs[j] = PACKED ? 0 : r * p.Kd + (lane & 7) * 8;
+        wwr[j] = r * 8 + ((lane & 7) ^ (r & 7));
+    }
+    const int rrd = lr * 8, rx7 = lr & 7;
+#define BM_PW(wp_, u_) (PACKED ? (wp_) + (u_) * KSTEP : (wp_) + lofs[(u_) & 1] + ((u_) >> 1) * 64)
     const int NRB = p.N >> 4;
     const int n_items = p.n_mtiles[0] * NRB;
     if ((int)blockIdx.x >= n_items) return;
@@ -557,19 +610,34 @@ __global__ void __launch_bounds__(512) skinny_p_kernel(SkinnyParams p) {
     u32x4 s0[CH], s1[CH], sx[NBT][CH];
 #pragma unroll
     for (int u = 0; u < CH; ++u) {
-        s0[u] = ldg128_stream(cur.w0 + u * KSTEP);
-        if (DUAL) s1[u] = ldg128_stream(cur.w1 + u * KSTEP);
+        s0[u] = ldg128_stream(BM_PW(cur.w0, u));
+        if (DUAL) s1[u] = ldg128_stream(BM_PW(cur.w1, u));
 #pragma unroll
         for (int tb = 0; tb < NBT; ++tb) sx[tb][u] = ldg128(xa[tb] + u * 32);
     }
 
 #define BM_CONSUME(u_)                                                                                  \
-    _Pragma("unroll") for (int tb = 0; tb < NBT; ++tb) {                                                \
-        acc0[tb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(s0[u_]), as_bf16x8(sx[tb][u_]),    \
-                                                           acc0[tb], 0, 0, 0);                          \
-        if (DUAL)                                                                                       \
-            acc1[tb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(s1[u_]), as_bf16x8(sx[tb][u_]),\
-                                                               acc1[tb], 0, 0, 0);                      \
+    {                                                                                                   \
+        bf16x8 wa, wb;                                                                                  \
+        if (!PACKED && ((u_) & 1) == 0) {                                                               \
+            _Pragma("unroll") for (int j = 0; j < 2; ++j) {                                             \
+                wst[wwr[j]] = s0[(u_) + j];                                                             \
+                if (DUAL) wst[128 + wwr[j]] = s1[(u_) + j];                                             \
+            }                                                                                           \
+        }                                                                                               \
+        if (PACKED) {                                                                                   \
+            wa = as_bf16x8(s0[u_]);                                                                     \
+            wb = as_bf16x8(s1[DUAL ? (u_) : 0]);                                                        \
+        } else {                                                                                        \
+            const int rs_ = rrd + ((((u_) & 1) * 4 + lk) ^ rx7);                                        \
+            wa = as_bf16x8(wst[rs_]);                                                                   \
+            wb = as_bf16x8(wst[(DUAL ? 128 : 0) + rs_]);                                                \
+        }                                                                                               \
+        _Pragma("unroll") for (int tb = 0; tb < NBT; ++tb) {                                            \
+            acc0[tb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wa, as_bf16x8(sx[tb][u_]), acc0[tb], 0, 0, 0); \
+            if (DUAL)                                                                                   \
+                acc1[tb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wb, as_bf16x8(sx[tb][u_]), acc1[tb], 0, 0, 0); \
+        }                                                                                               \
     }
 // partial tiles -> LDS, barrier, every wave adds up and finishes an eighth of the outputs
 #define BM_FINALIZE()                                                                                   \
@@ -636,8 +704,13 @@ __global__ void __launch_bounds__(512) skinny_p_kernel(SkinnyParams p) {
 #pragma unroll
         for (int u = 0; u < CH; ++u) {
             BM_CONSUME(u);
-            s0[u] = ldg128_stream(rw0 + u * KSTEP);
-            if (DUAL) s1[u] = ldg128_stream(rw1 + u * KSTEP);
+            if (PACKED || (u & 1) == 1) {               // public layout: both slots of a line once it is used up
+#pragma unroll
+                for (int v = PACKED ? u : u - 1; v <= u; ++v) {
+                    s0[v] = ldg128_stream(BM_PW(rw0, v));
+                    if (DUAL) s1[v] = ldg128_stream(BM_PW(rw1, v));
+                }
+            }
 #pragma unroll
             for (int tb = 0; tb < NBT; ++tb) sx[tb][u] = ldg128(rx[tb] + u * 32);
             __builtin_amdgcn_sched_barrier(0);
@@ -657,9 +730,10 @@ __global__ void __launch_bounds__(512) skinny_p_kernel(SkinnyParams p) {
     BM_FINALIZE();
 #undef BM_CONSUME
 #undef BM_FINALIZE
+#undef BM_PW
 }
 
-bool skinny_p_ok(int Kd, int ch) { return Kd % (8 * 32 * ch) == 0; }
+bool skinny_p_ok(int Kd, int ch) { return ch % 2 == 0 && Kd % (8 * 32 * ch) == 0; }
 
 // launches the persistent kernel if a ring depth fits the shape; false otherwise
 template <bool DUAL>
