@@ -12,6 +12,7 @@ constexpr int TILE_T = 32;      // tokens per front-end tile (one MFMA row block
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(4))) float f32x4;
 typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;   // one 16-byte piece
+typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;   // four bf16 values
 typedef __attribute__((ext_vector_type(16))) float f32x16;
 
 __device__ __forceinline__ float bf16_to_f32(uint16_t b) {

@@ -462,7 +462,7 @@ __device__ __forceinline__ void skinny_lds_pass(const SkinnyParams &p, const uin
 // One item of the kernel below: 64 weight rows (a 16-row block per wave) of group g over reduction slice kslice.
 template <bool DUAL, int MAXNBT, bool PACKED>
 __device__ __forceinline__ void skinny_lds_item(const SkinnyParams &p, u32x4 *xs, u32x4 *wstage, int g, int blk, int kslice) {
-    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, lr = lane & 15, lk = lane >> 4;
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const int n0w = (blk * 4 + wave) * 16;
     const bool active = n0w < p.N;                    // a wave past the last weight row recomputes block 0 and stores nothing
     const int n0 = active ? n0w : 0;
