@@ -494,7 +494,8 @@ __global__ void __launch_bounds__(NW * 64) front_bf16_kernel(FrontParams p) {
     constexpr int NS_FIT = (68 * 1024) / (TILE * 4);
     constexpr int NS = NS_FIT >= NW ? NW : (NS_FIT < 1 ? 1 : NS_FIT);   // partial tiles kept side by side
     __shared__ float part[NS * TILE];
-    __shared__ u32x4 stage[NB == 1 && !FUSED ? NW * 256 : 1];   // 4 KB per wave (see the staged product below)
+    constexpr bool CAN_STAGE = !FUSED && U >= 2 && U % 2 == 0;
+    __shared__ u32x4 stage[CAN_STAGE ? NW * 256 : 1];            // 4 KB per wave (see the staged product below)
     __shared__ FrontLds s;
     __shared__ FusedLds fs_store[FUSED ? 1 : 0 + 1];
     FusedLds &fs = fs_store[0];
@@ -523,49 +524,71 @@ __global__ void __launch_bounds__(NW * 64) front_bf16_kernel(FrontParams p) {
 #pragma unroll
             for (int nb = 0; nb < NB; ++nb) acc[tb][nb] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-        // Tiles of at most 16 tokens and 16 experts: the operands are fetched as whole 128-byte lines (8
-        // rows per instruction, half as many lines touched as with 64 bytes per row) and turned into the
-        // MFMA operand order through a wave-private LDS area: stored 8 rows x 128 bytes per register,
-        // read back 16 rows x 16 bytes per fragment, the 16-byte pieces of a row rotated by the row index
-        // against bank conflicts.  No barrier: only the writing wave reads the area, and a wave's LDS
-        // operations stay in order.
+        // Staged product: the operands are fetched as whole 128-byte lines (8 rows per instruction, half as
+        // many lines touched as with 64 bytes per row - and with many experts the lines touched bound the
+        // kernel) and turned into the MFMA operand order through a wave-private LDS area of two 2 KB
+        // blocks: stored 8 rows x 128 bytes per register, read back 16 rows x 16 bytes per fragment, the
+        // 16-byte pieces of a row rotated by the row index against bank conflicts.  The blocks are reused
+        // operand block after operand block; no barrier: only the writing wave touches its area, and a
+        // wave's LDS operations stay in order.  A batch is LPB lines (two k-steps each) of every operand.
         // (not in the fused kernel, which has no registers to spare: it serves batches of a few tokens,
-        // whose direct loads touch few lines anyway)
-        const bool staged = NB == 1 && U == 4 && !FUSED && !two;
-        if (staged) {
-            u32x4 *area = stage + (NB == 1 && !FUSED ? wave : 0) * 256;   // [operand][row 0..15][piece 0..7]
+        // whose direct loads touch few lines anyway; not with 256 experts, whose batch would not fit)
+        const bool staged = CAN_STAGE;
+        int ks_done = nbatch * U;                                      // k-steps covered by the batched loops
+        if (CAN_STAGE) {
+            constexpr int LPB = U / 2 > 0 ? U / 2 : 1;
+            u32x4 *area = stage + (CAN_STAGE ? wave : 0) * 256;       // [block 0..1][row 0..15][piece 0..7]
             const int lrow = lane >> 3, lpiece = lane & 7;
-            const uint16_t *xs_[2], *ws_[2];
-            int wslot[2];
+            const uint16_t *xs_[2][2];
+            int woff[NB][2], wslot[2], rslot[2];
 #pragma unroll
             for (int j = 0; j < 2; ++j) {
                 const int r = 8 * j + lrow;
-                xs_[j] = x + (size_t)min(t0 + r, p.T - 1) * p.d + lpiece * 8;
-                ws_[j] = wr + (size_t)min(r, p.E - 1) * p.d + lpiece * 8;
+#pragma unroll
+                for (int tb = 0; tb < 2; ++tb) xs_[tb][j] = x + (size_t)min(t0 + tb * 16 + r, p.T - 1) * p.d + lpiece * 8;
+#pragma unroll
+                for (int nb = 0; nb < NB; ++nb) woff[nb][j] = min(nb * 16 + r, p.E - 1) * p.d + lpiece * 8;
                 wslot[j] = r * 8 + (lpiece ^ (r & 7));
+                rslot[j] = r16 * 8 + ((j * 4 + kq) ^ (r16 & 7));     // fragment of the line's k-step j
             }
-            for (int bt = wave; bt < nbatch; bt += NW) {
-                const int k0 = bt * 128;
-                u32x4 rx[2][2], rw[2][2];                           // [line of the 256-byte span][row group]
+            const int nlb = p.d / (64 * LPB);
+            ks_done = nlb * 2 * LPB;
+            for (int bt = wave; bt < nlb; bt += NW) {
+                const int k0 = bt * 64 * LPB;
+                u32x4 rx[LPB][2][2], rw[LPB][NB][2];                   // [line][operand block][row group]
 #pragma unroll
-                for (int h = 0; h < 2; ++h)
-#pragma unroll
-                    for (int j = 0; j < 2; ++j) {
-                        rx[h][j] = ldg128(xs_[j] + k0 + h * 64);
-                        rw[h][j] = ldg128(ws_[j] + k0 + h * 64);
-                    }
-#pragma unroll
-                for (int h = 0; h < 2; ++h) {
+                for (int h = 0; h < LPB; ++h)
 #pragma unroll
                     for (int j = 0; j < 2; ++j) {
-                        area[wslot[j]] = rx[h][j];
-                        area[128 + wslot[j]] = rw[h][j];
+                        rx[h][0][j] = ldg128(xs_[0][j] + k0 + h * 64);
+                        if (two) rx[h][1][j] = ldg128(xs_[1][j] + k0 + h * 64);
+#pragma unroll
+                        for (int nb = 0; nb < NB; ++nb) rw[h][nb][j] = ldg128(wr + woff[nb][j] + k0 + h * 64);
+                    }
+                __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                for (int h = 0; h < LPB; ++h) {
+                    bf16x8 fa[2][2];
+#pragma unroll
+                    for (int tb = 0; tb < 2; ++tb) {
+                        if (tb == 1 && !two) break;
+#pragma unroll
+                        for (int j = 0; j < 2; ++j) area[tb * 128 + wslot[j]] = rx[h][tb][j];
+#pragma unroll
+                        for (int ks = 0; ks < 2; ++ks) fa[tb][ks] = as_bf16x8(area[tb * 128 + rslot[ks]]);
                     }
 #pragma unroll
-                    for (int ks = 0; ks < 2; ++ks) {
-                        const int slot = r16 * 8 + ((ks * 4 + kq) ^ (r16 & 7));
-                        const bf16x8 a = as_bf16x8(area[slot]), b = as_bf16x8(area[128 + slot]);
-                        acc[0][0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, acc[0][0], 0, 0, 0);
+                    for (int nb = 0; nb < NB; ++nb) {
+                        u32x4 *ar = area + (nb & 1) * 128;
+#pragma unroll
+                        for (int j = 0; j < 2; ++j) ar[wslot[j]] = rw[h][nb][j];
+#pragma unroll
+                        for (int ks = 0; ks < 2; ++ks) {
+                            const bf16x8 b = as_bf16x8(ar[rslot[ks]]);
+                            acc[0][nb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fa[0][ks], b, acc[0][nb], 0, 0, 0);
+                            if (two)
+                                acc[1][nb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fa[1][ks], b, acc[1][nb], 0, 0, 0);
+                        }
                     }
                 }
             }
@@ -590,7 +613,7 @@ __global__ void __launch_bounds__(NW * 64) front_bf16_kernel(FrontParams p) {
                         acc[1][nb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(ra[1][u]), as_bf16x8(rb[nb][u]), acc[1][nb], 0, 0, 0);
                 }
         }
-        for (int ks = nbatch * U + wave; ks < ksteps; ks += NW) {       // k-steps past the last full batch
+        for (int ks = ks_done + wave; ks < ksteps; ks += NW) {          // k-steps past the last full batch
             const bf16x8 a0 = as_bf16x8(ldg128(xa[0] + ks * 32)), a1 = as_bf16x8(ldg128(xa[1] + ks * 32));
 #pragma unroll
             for (int nb = 0; nb < NB; ++nb) {
