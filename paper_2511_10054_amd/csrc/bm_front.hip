@@ -902,6 +902,134 @@ __global__ void __launch_bounds__(256) scatter_kernel(ScatterParams p) {
 }
 
 // ---------------------------------------------------------------------------
+// Scan and scatter in one launch for batches whose histogram (experts x tiles)
+// is small enough for every workgroup to sum it by itself: the workgroup of a
+// tile adds up, per expert, all tiles (group size) and the tiles before its
+// own (its base inside the group) - a wave per expert, lanes over the tiles,
+// the loads of EB experts going out together - scans the group sizes, and
+// places its assignments.  The workgroup of tile 0 also writes the offsets,
+// the row-tile table and the statistics.  Saves the one-workgroup scan launch,
+// a chain of dependent round trips to memory (11 us for 64-128 experts).
+// ---------------------------------------------------------------------------
+constexpr long long TILE_SUM_MAX = 32768;          // histogram entries every workgroup re-reads (128 KB)
+
+__global__ void __launch_bounds__(1024) group_tiles_kernel(ScanParams p, ScatterParams c) {
+    __shared__ int32_t total[BM_MAX_E + 8];
+    __shared__ int32_t before[BM_MAX_E];
+    __shared__ int32_t start[BM_MAX_E + 9];
+    __shared__ int32_t tstart[BM_MAX_E + 9];
+    __shared__ int32_t s_ids[TILE_T * BM_MAX_K];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, nw = blockDim.x >> 6;
+    const int tile = blockIdx.x, t0 = tile * c.tile_tokens;
+    const int K = c.K, E = p.E, G = p.E + p.n_shared;
+    const int ntok = min(c.tile_tokens, c.T - t0);
+    const int n = ntok * K;
+    for (int idx = tid; idx < n; idx += blockDim.x) {
+        const int e = c.ids[(size_t)t0 * K + idx];
+        s_ids[idx] = ((unsigned)e < (unsigned)E) ? e : -1;
+    }
+    constexpr int EB = 8, SB = 4;                         // every load is a round trip to memory: EB * SB go out together
+    for (int e0 = wave; e0 < E; e0 += nw * EB) {          // experts e0, e0 + nw, ..
+        int tot[EB], bef[EB];
+#pragma unroll
+        for (int j = 0; j < EB; ++j) tot[j] = bef[j] = 0;
+        for (int tb = 0; tb < p.n_tiles; tb += SB * WAVE) {
+            int cnt[EB][SB];
+#pragma unroll
+            for (int j = 0; j < EB; ++j)
+#pragma unroll
+                for (int i = 0; i < SB; ++i) {
+                    const int t = tb + i * WAVE + lane;
+                    cnt[j][i] = (e0 + j * nw < E && t < p.n_tiles) ? p.tile_counts[(size_t)(e0 + j * nw) * p.n_tiles + t] : 0;
+                }
+#pragma unroll
+            for (int j = 0; j < EB; ++j)
+#pragma unroll
+                for (int i = 0; i < SB; ++i) {
+                    tot[j] += cnt[j][i];
+                    bef[j] += tb + i * WAVE + lane < tile ? cnt[j][i] : 0;
+                }
+        }
+#pragma unroll
+        for (int j = 0; j < EB; ++j) {
+#pragma unroll
+            for (int m = 32; m >= 1; m >>= 1) {
+                tot[j] += __shfl_xor(tot[j], m, WAVE);
+                bef[j] += __shfl_xor(bef[j], m, WAVE);
+            }
+            if (lane == 0 && e0 + j * nw < E) { total[e0 + j * nw] = tot[j]; before[e0 + j * nw] = bef[j]; }
+        }
+    }
+    for (int g = E + tid; g < G; g += blockDim.x) total[g] = p.T;
+    __syncthreads();
+    if (wave == 0) {                               // exclusive scans over the groups, a few consecutive groups per lane
+        constexpr int PER = (BM_MAX_E + 8 + 63) / 64;
+        int cnt[PER], nt[PER], sum_c = 0, sum_t = 0;
+#pragma unroll
+        for (int i = 0; i < PER; ++i) {
+            const int g = lane * PER + i;
+            const int cg = g < G ? total[g] : 0;
+            cnt[i] = cg;
+            nt[i] = (cg + p.BM - 1) / p.BM;
+            sum_c += cg;
+            sum_t += nt[i];
+        }
+        int tot_c, tot_t;
+        int run_c = wave_excl_scan(sum_c, tot_c), run_t = wave_excl_scan(sum_t, tot_t);
+#pragma unroll
+        for (int i = 0; i < PER; ++i) {
+            const int g = lane * PER + i;
+            if (g <= G) { start[g] = run_c; tstart[g] = run_t; }
+            run_c += cnt[i];
+            run_t += nt[i];
+        }
+        if (tile == 0 && lane == 0) { p.n_mtiles[0] = tot_t; p.n_mtiles[1] = tot_c; }
+    }
+    __syncthreads();
+    if (tile == 0) {
+        for (int g = tid; g <= G; g += blockDim.x) p.offsets[g] = start[g];
+        for (int g = tid; g < G; g += blockDim.x) {
+            const int nt = tstart[g + 1] - tstart[g];
+            for (int i = 0; i < nt; ++i) {
+                p.mt_group[tstart[g] + i] = g;
+                p.mt_row0[tstart[g] + i] = start[g] + i * p.BM;
+            }
+        }
+        if (p.stats != nullptr && wave >= nw - 3) {    // one wave per counter, lanes over the tiles
+            const int k = wave - (nw - 3);
+            int sum = 0;
+            if (p.tile_stats != nullptr)
+                for (int t = lane; t < p.n_tiles; t += WAVE) sum += p.tile_stats[t * 4 + k];
+#pragma unroll
+            for (int m = 32; m >= 1; m >>= 1) sum += __shfl_xor(sum, m, WAVE);
+            if (lane == 0) { p.stats[k] = sum; p.stats[3 + k] = 0; }
+        }
+    }
+    // placement: group start + the tile's base inside the group + earlier assignments of the tile with the same expert
+    const int live = start[E];
+    for (int idx = tid; idx < n; idx += blockDim.x) {
+        const int e = s_ids[idx];
+        const int a = t0 * K + idx;
+        int pos = -1;
+        if (e >= 0) {
+            int rank = 0;
+            for (int j = 0; j < idx; ++j) rank += (s_ids[j] == e) ? 1 : 0;
+            pos = start[e] + before[e] + rank;
+            c.perm[pos] = a;
+            if (c.row_token) c.row_token[pos] = a / K;
+        }
+        c.inv_perm[a] = pos;
+    }
+    for (int idx = tid; idx < c.tile_tokens * K; idx += blockDim.x) {      // positions past the live count hold -1
+        const int pos = t0 * K + idx;
+        if (pos >= live && pos < c.T * K) c.perm[pos] = -1;
+    }
+    if (c.row_token)                                                         // rows of the shared experts map to their own token
+        for (int sidx = 0; sidx < c.n_shared; ++sidx)
+            for (int i = tid; i < ntok; i += blockDim.x) c.row_token[start[E + sidx] + t0 + i] = t0 + i;
+}
+
+// ---------------------------------------------------------------------------
 // Scan and scatter in one workgroup for small batches (at most SMALL_A
 // assignments): the substituted ids are staged in LDS, every expert's count
 // and the stable positions come from ballots over them (place_assignments).
@@ -1063,10 +1191,15 @@ int launch_scan(const ScanParams &p, hipStream_t st) {
 
 bool grouping_small(long long assignments) { return assignments <= SMALL_A; }
 
-// scan + scatter: one kernel for small batches
+// scan + scatter: one kernel for small batches and for small histograms
 int launch_grouping(const ScanParams &sp, const ScatterParams &cp, hipStream_t st) {
     if (grouping_small((long long)cp.T * cp.K)) {
         hipLaunchKernelGGL(group_small_kernel, dim3(1), dim3(1024), 0, st, sp, cp);   // also for an empty batch: offsets
+        return launch_status(__func__);
+    }
+    const int n_tiles = (cp.T + cp.tile_tokens - 1) / cp.tile_tokens;
+    if ((long long)sp.E * n_tiles <= TILE_SUM_MAX) {
+        hipLaunchKernelGGL(group_tiles_kernel, dim3(n_tiles), dim3(1024), 0, st, sp, cp);
         return launch_status(__func__);
     }
     const int rc = launch_scan(sp, st);

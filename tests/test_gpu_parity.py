@@ -128,7 +128,9 @@ def test_buddy_remap(T, E, K, R, n_res, unique):
 
 
 @pytest.mark.parametrize("T,K,E", [(0, 2, 8), (1, 2, 8), (57, 3, 11), (32, 32, 256), (128, 8, 200), (129, 8, 64),
-                                   (1000, 6, 64), (4096, 8, 128), (33, 32, 256)])
+                                   (1000, 6, 64), (4096, 8, 128), (33, 32, 256),
+                                   (2100, 4, 256),      # fused scan + placement per tile, ragged last tile
+                                   (8192, 8, 256)])     # histogram too large for that: separate scan and placement
 def test_permute_by_expert(T, K, E):
     torch = _torch()
     import paper_2511_10054_amd as bm
