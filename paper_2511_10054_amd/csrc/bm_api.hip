@@ -420,6 +420,11 @@ int bm_moe_forward(const bm_layer_desc *desc, const void *x, const bm_weights *w
         ScanParams sq = sp;
         sq.tile_stats = nullptr; sq.stats = nullptr;      // written by the substitution kernel
         err |= launch_grouping(sq, cp, st);
+    } else if (desc->dtype == BM_BF16 && sp.n_tiles == 1) {
+        fp.tail = 1;                           // a single tile: its workgroup finishes the grouping too
+        fp.scan = sp;
+        fp.scat = cp;
+        err |= launch_front(fp, desc->dtype, st);
     } else {
         err |= launch_front(fp, desc->dtype, st);
         err |= launch_grouping(sp, cp, st);

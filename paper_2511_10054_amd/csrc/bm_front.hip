@@ -417,6 +417,82 @@ __device__ void place_assignments(const int32_t *ids, int A, int E, int K, const
         if (ids[a] < 0) c.inv_perm[a] = -1;
 }
 
+// Everything after the per-expert counts of a batch whose substituted ids sit in LDS (one workgroup):
+// group offsets, the list of row tiles (or of live groups, largest first, for the decode projections),
+// statistics, stable placement.  counts: E entries in LDS; start / tstart: LDS scratch of G + 1 entries;
+// local_stats: the three substitution counters in LDS, or null to add up the per-tile ones.  Every thread of
+// the workgroup calls it, after a barrier behind the writes of ids and counts.
+__device__ void finish_groups(const ScanParams &p, const ScatterParams &c, const int32_t *ids, int A,
+                              const int32_t *counts, int32_t *start, int32_t *tstart, const int32_t *local_stats) {
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int E = p.E, G = p.E + p.n_shared, K = c.K;
+    if (wave == 0) {                               // exclusive scans over the groups, a few consecutive groups per lane
+        constexpr int PER = (BM_MAX_E + 8 + 63) / 64;
+        int cnt[PER], nt[PER], sum_c = 0, sum_t = 0;
+#pragma unroll
+        for (int i = 0; i < PER; ++i) {
+            const int g = lane * PER + i;
+            const int n = g < E ? counts[g] : (g < G ? p.T : 0);
+            cnt[i] = n;
+            nt[i] = (n + p.BM - 1) / p.BM;
+            sum_c += n;
+            sum_t += nt[i];
+        }
+        int tot_c, tot_t;
+        int run_c = wave_excl_scan(sum_c, tot_c), run_t = wave_excl_scan(sum_t, tot_t);
+#pragma unroll
+        for (int i = 0; i < PER; ++i) {
+            const int g = lane * PER + i;
+            if (g <= G) { start[g] = run_c; tstart[g] = run_t; }
+            run_c += cnt[i];
+            run_t += nt[i];
+        }
+        if (lane == 0) { p.n_mtiles[0] = tot_t; p.n_mtiles[1] = tot_c; }
+    }
+    __syncthreads();
+    for (int g = tid; g <= G; g += blockDim.x) p.offsets[g] = start[g];
+    if (p.largest_first) {
+        // decode projections: a group is one work-item column of the grid, and groups with more rows take
+        // longer per item; handing the big ones out first leaves the short items for the end of the launch
+        for (int g = tid; g < G; g += blockDim.x) {
+            const int n = start[g + 1] - start[g];
+            if (n == 0) continue;
+            int rank = 0;
+            for (int h = 0; h < G; ++h) {
+                const int m = start[h + 1] - start[h];
+                rank += (m > n || (m == n && h < g)) ? 1 : 0;
+            }
+            p.mt_group[rank] = g;
+            p.mt_row0[rank] = start[g];
+        }
+    } else {
+        for (int g = tid; g < G; g += blockDim.x) {
+            const int nt = tstart[g + 1] - tstart[g];
+            for (int i = 0; i < nt; ++i) {
+                p.mt_group[tstart[g] + i] = g;
+                p.mt_row0[tstart[g] + i] = start[g] + i * p.BM;
+            }
+        }
+    }
+    if (p.stats != nullptr && wave < 3) {          // one wave per counter
+        int sum = 0;
+        if (local_stats != nullptr) sum = local_stats[wave];
+        else {
+            if (p.tile_stats != nullptr)
+                for (int t = lane; t < p.n_tiles; t += WAVE) sum += p.tile_stats[t * 4 + wave];
+#pragma unroll
+            for (int m = 32; m >= 1; m >>= 1) sum += __shfl_xor(sum, m, WAVE);
+        }
+        if (lane == 0) { p.stats[wave] = sum; p.stats[3 + wave] = 0; }
+    }
+    place_assignments(ids, A, E, K, start, c);
+    const int live = start[E];
+    for (int pos = live + tid; pos < A; pos += blockDim.x) c.perm[pos] = -1;
+    if (c.row_token)
+        for (int sidx = 0; sidx < p.n_shared; ++sidx)
+            for (int t = tid; t < p.T; t += blockDim.x) c.row_token[start[E + sidx] + t] = t;
+}
+
 __device__ void fused_tail(const FrontParams &p, FusedLds &fs, int n_tiles) {
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int E = p.E, K = p.K, n_shared = p.scan.n_shared, G = E + n_shared, BM = p.scan.BM;
@@ -660,6 +736,12 @@ __global__ void __launch_bounds__(NW * 64) front_bf16_kernel(FrontParams p) {
         }
     }
     if (FUSED) fused_tail(p, fs, n_tiles);
+    // a batch of one tile: this workgroup holds every substituted id and the histogram, and finishes the
+    // grouping itself instead of leaving it to a launch of its own
+    if (!FUSED && p.tail) {
+        __syncthreads();
+        finish_groups(p.scan, p.scat, s.ids, p.T * p.K, s.counts, fs.start, fs.tstart, s.stats);
+    }
 }
 
 // ---------------------------------------------------------------------------
@@ -1043,7 +1125,7 @@ __global__ void __launch_bounds__(1024) group_small_kernel(ScanParams p, Scatter
     __shared__ int32_t start[BM_MAX_E + 9];
     __shared__ int32_t tstart[BM_MAX_E + 9];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, nw = blockDim.x >> 6;
-    const int E = p.E, G = p.E + p.n_shared, K = c.K, A = c.T * c.K;
+    const int E = p.E, A = c.T * c.K;
     for (int a = tid; a < A; a += blockDim.x) {
         const int e = c.ids[a];
         ids[a] = ((unsigned)e < (unsigned)E) ? e : -1;
@@ -1057,67 +1139,8 @@ __global__ void __launch_bounds__(1024) group_small_kernel(ScanParams p, Scatter
         }
         if (lane == 0) total[e] = cnt;
     }
-    for (int g = E + tid; g < G; g += blockDim.x) total[g] = p.T;
     __syncthreads();
-    if (wave == 0) {                               // exclusive scans over the groups, a few consecutive groups per lane
-        constexpr int PER = (BM_MAX_E + 8 + 63) / 64;
-        int cnt[PER], nt[PER], sum_c = 0, sum_t = 0;
-#pragma unroll
-        for (int i = 0; i < PER; ++i) {
-            const int g = lane * PER + i;
-            const int n = g < G ? total[g] : 0;
-            cnt[i] = n;
-            nt[i] = (n + p.BM - 1) / p.BM;
-            sum_c += n;
-            sum_t += nt[i];
-        }
-        int tot_c, tot_t;
-        int run_c = wave_excl_scan(sum_c, tot_c), run_t = wave_excl_scan(sum_t, tot_t);
-#pragma unroll
-        for (int i = 0; i < PER; ++i) {
-            const int g = lane * PER + i;
-            if (g <= G) { start[g] = run_c; tstart[g] = run_t; }
-            run_c += cnt[i];
-            run_t += nt[i];
-        }
-        if (lane == 0) { p.n_mtiles[0] = tot_t; p.n_mtiles[1] = tot_c; }
-    }
-    __syncthreads();
-    for (int g = tid; g <= G; g += blockDim.x) p.offsets[g] = start[g];
-    if (p.largest_first) {
-        // decode projections: a group is one work-item column of the grid, and groups with more rows take
-        // longer per item; handing the big ones out first leaves the short items for the end of the launch
-        for (int g = tid; g < G; g += blockDim.x) {
-            const int n = total[g];
-            if (n == 0) continue;
-            int rank = 0;
-            for (int h = 0; h < G; ++h) rank += (total[h] > n || (total[h] == n && h < g)) ? 1 : 0;
-            p.mt_group[rank] = g;
-            p.mt_row0[rank] = start[g];
-        }
-    } else {
-        for (int g = tid; g < G; g += blockDim.x) {
-            const int nt = tstart[g + 1] - tstart[g];
-            for (int i = 0; i < nt; ++i) {
-                p.mt_group[tstart[g] + i] = g;
-                p.mt_row0[tstart[g] + i] = start[g] + i * p.BM;
-            }
-        }
-    }
-    if (p.stats != nullptr && wave < 3) {          // one wave per counter, lanes over the tiles
-        int sum = 0;
-        if (p.tile_stats != nullptr)
-            for (int t = lane; t < p.n_tiles; t += WAVE) sum += p.tile_stats[t * 4 + wave];
-#pragma unroll
-        for (int m = 32; m >= 1; m >>= 1) sum += __shfl_xor(sum, m, WAVE);
-        if (lane == 0) { p.stats[wave] = sum; p.stats[3 + wave] = 0; }
-    }
-    place_assignments(ids, A, E, K, start, c);
-    const int live = start[E];
-    for (int pos = live + tid; pos < A; pos += blockDim.x) c.perm[pos] = -1;
-    if (c.row_token)
-        for (int sidx = 0; sidx < p.n_shared; ++sidx)
-            for (int t = tid; t < p.T; t += blockDim.x) c.row_token[start[E + sidx] + t] = t;
+    finish_groups(p, c, ids, A, total, start, tstart, nullptr);
 }
 
 // ---------------------------------------------------------------------------
@@ -1132,7 +1155,8 @@ static void launch_front_bf16(const FrontParams &p, int n_tiles, hipStream_t st)
 // One workgroup for the whole front end (router to placement): only with the distribution gate and a
 // batch of at most one tile - the gate's in-tile form needs the whole batch in one workgroup and saves two
 // launches.  Otherwise workgroups of 16 tokens plus the grouping kernel are faster at every batch size
-// (front end at 1 / 8 / 16 tokens: 13.8 / 13.6 / 14.2 us against 15.0 / 16.0 / 17.7 us).
+// (front end at 1 / 8 / 16 tokens: 13.8 / 13.6 / 14.2 us against 15.0 / 16.0 / 17.7 us); a batch of one such
+// workgroup finishes the grouping itself (FrontParams::tail).
 bool front_can_fuse(int T, int dtype, uint32_t flags) {
     return dtype == BM_BF16 && (flags & BM_GATE_DIST) && T > 0 && T <= TILE_T;
 }

@@ -65,9 +65,10 @@ struct FrontParams {
     int32_t *tile_counts;   // [E][n_tiles]
     int32_t *tile_stats;    // [n_tiles][4]
     int fused;              // one workgroup walks all tiles and also does the scan and the scatter
+    int tail;               // not fused, a single tile: the workgroup also finishes the grouping (bf16 kernel)
     int tile_tokens;        // tokens per workgroup: TILE_T, or 16 for small batches (bf16 kernel, see front_tile_tokens)
-    ScanParams scan;        // used when fused
-    ScatterParams scat;     // used when fused
+    ScanParams scan;        // used when fused or tail
+    ScatterParams scat;     // used when fused or tail
 };
 
 
