@@ -13,20 +13,25 @@ pytestmark = pytest.mark.gpu
 _cache = {}
 
 
-def _layers(name):
-    """Host + device weights of a config, built once per test session."""
+def _layers(name, pack=None):
+    """Host + device weights of a config, built once per test session.  pack: fragment-major copies of the
+    weights for the decode kernels (default: as bench.py does, for the decode config only)."""
+    if pack is None:
+        pack = name.startswith("c2")
     if name not in _cache:
         _cache.clear()                       # one big layer at a time
         spec = workloads.CONFIGS[name]
-        host = HostLayer(spec, 1, only_resident=True, poison=True)
-        _cache[name] = (host, DeviceLayer(host, pack=name.startswith("c2")))   # decode config: packed weights, as bench.py
-    return _cache[name]
+        _cache[name] = {"host": HostLayer(spec, 1, only_resident=True, poison=True)}
+    entry = _cache[name]
+    if pack not in entry:
+        entry[pack] = DeviceLayer(entry["host"], pack=pack)
+    return entry["host"], entry[pack]
 
 
-def _check(name, T, n_sample, unique=False, **gates):
+def _check(name, T, n_sample, unique=False, pack=None, **gates):
     spec = workloads.CONFIGS[name]
-    base_host, base_dev = _layers(name)
-    print(f"fullsize {name} T={T} unique={unique} {gates}", flush=True)
+    base_host, base_dev = _layers(name, pack)
+    print(f"fullsize {name} T={T} unique={unique} pack={pack} {gates}", flush=True)
     host = HostLayer(spec, T, base=base_host)
     dev = DeviceLayer(host, unique=unique, base=base_dev, **gates)
     out = dev.forward()
@@ -68,6 +73,12 @@ def _check(name, T, n_sample, unique=False, **gates):
 @pytest.mark.parametrize("T", [1, 8, 32, 64])
 def test_c2_mixtral_decode(T):
     _check("c2_mixtral_decode", T, 64)
+
+
+@pytest.mark.parametrize("T", [1, 16, 64])
+def test_c2_mixtral_decode_public_weight_layout(T):
+    """The same layer without the packed copies (bench.py --no-pack): the decode kernels read [N][K] rows."""
+    _check("c2_mixtral_decode", T, 64, pack=False)
 
 
 def test_c2_mixtral_decode_unique():
