@@ -241,7 +241,10 @@ int bm_moe_forward(const bm_layer_desc *desc, const void *x, const bm_weights *w
  * reference; the packed copy holds, for every block of 16 weight rows and every
  * 32 values of the reduction dimension, the 1 KB MFMA operand fragment
  * contiguously (gate and up fragments interleaved), so a wave streams its rows
- * as one contiguous run.  bf16 only; needs F % 32 == 0 and d % 32 == 0.
+ * as one contiguous run.  Optional: without it the decode kernels fetch the
+ * public layout as whole cache lines and re-order them on chip, a few per cent
+ * slower; the copy costs the memory of the resident experts once more.
+ * bf16 only; needs F % 32 == 0 and d % 32 == 0.
  * which: 0 routed gate+up, 1 routed down, 2 shared gate+up, 3 shared down. */
 size_t bm_packed_bytes(const bm_layer_desc *desc, int which);
 
