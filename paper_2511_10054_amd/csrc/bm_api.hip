@@ -19,19 +19,38 @@ using namespace bm;
 
 constexpr size_t ALIGN = 256;
 constexpr int MAX_SHARED = 8;
-constexpr int SKINNY_MAX_ROWS = 128;   // total rows up to which the weight-streaming path is used
+constexpr int SKINNY_MAX_ROWS = 256;   // total rows up to which the weight-streaming path is always used
+constexpr int SKINNY_AVG_ROWS = 8;     // ... and rows per group (averaged over all experts) with many experts
 constexpr int SKINNY_KSPLIT = 8;
 
-// Row-tile height of the grouped GEMM: 256 rows when the average group is large
-// (measured on routed experts; shared experts always have T rows), else 128.
+// Row-tile height of the grouped GEMM.  256 rows whenever both projections fit the persistent k-step-64
+// kernel (reduction widths that are multiples of 64 and at least 256, operands within 32-bit byte
+// offsets): even with groups of a few dozen rows its padded tiles beat the 128-row kernel (Mixtral-shaped
+// layer at 128 tokens 0.47 against 0.69 ms, Qwen3-shaped at 1024 tokens 0.22 against 0.30 ms).  Otherwise 256
+// rows when the average routed group is large, else 128.
 int gemm_tile_rows(const bm_layer_desc *d) {
+    const unsigned long long lim = 1ull << 32;
+    const unsigned long long rows = (unsigned long long)d->T * (d->K + (d->n_shared > 0 ? d->n_shared : 0)) +
+                                    256ull * (d->E + (d->n_shared > 0 ? d->n_shared : 0));
+    const bool k64 = d->d % 64 == 0 && d->F % 64 == 0 && d->d >= 256 && d->F >= 256 &&
+                     (unsigned long long)d->T * d->d * 2 < lim && rows * d->F * 2 < lim &&
+                     (unsigned long long)d->F * d->d * 2 < lim;
+    if (k64) return 256;
     return ((long long)d->T * d->K / d->E >= 128) ? 256 : 128;
 }
 
-// Few rows in total: every expert group is decode-sized and the projections
-// are bound by reading the weights once.
+// Few rows per group: every expert group is decode-sized and the projections are bound by reading the
+// weights once.  Up to 256 rows in all (Mixtral-shaped layer, 8 experts: 0.38 ms at 128 tokens against
+// 0.47 ms on the tiled path; at 192 tokens 0.56 against 0.47), or up to 8 rows per expert on average when
+// both widths fit the fast streaming kernels (Qwen3-shaped layer, 128 experts, 128 tokens: 0.17 against
+// 0.21 ms; the DeepSeek-shaped one, whose F = 1408 does not fit them and whose shared experts take every
+// token, is faster on the tiled path from 64 tokens on).
 bool use_skinny(const bm_layer_desc *d) {
-    return d->dtype == BM_BF16 && (long long)d->T * (d->K + (d->n_shared > 0 ? d->n_shared : 0)) <= SKINNY_MAX_ROWS;
+    if (d->dtype != BM_BF16) return false;
+    const int ns = d->n_shared > 0 ? d->n_shared : 0;
+    const long long rows = (long long)d->T * (d->K + ns);
+    if (rows <= SKINNY_MAX_ROWS) return true;
+    return rows <= (long long)SKINNY_AVG_ROWS * (d->E + ns) && d->d % 256 == 0 && d->F % 256 == 0;
 }
 // Reduction slices of the decode down projection (each slice is a workgroup
 // whose 4 waves split it once more): prefer a count that fits the
@@ -311,7 +330,7 @@ int bm_permute_by_expert(const bm_layer_desc *desc, const int32_t *ids_remapped,
     hipStream_t st = static_cast<hipStream_t>(stream);
     (void)hipGetLastError();
     int err = 0;
-    if (!grouping_small((long long)d2.T * d2.K))       // the small-batch kernel counts for itself
+    if (!grouping_small((long long)d2.T * d2.K, d2.E))       // the small-batch kernel counts for itself
         err = launch_count(ids_remapped, d2.T, d2.K, d2.E, TILE_T, at<int32_t>(workspace, L.tile_counts), st);
     ScanParams sp{};
     sp.T = d2.T; sp.E = d2.E; sp.n_shared = 0; sp.n_tiles = L.n_tiles; sp.BM = 128;
@@ -416,7 +435,7 @@ int bm_moe_forward(const bm_layer_desc *desc, const void *x, const bm_weights *w
         mp.q = fp.q; mp.eta = fp.eta; mp.probs = psi ? at<float>(ws, L.probs) : nullptr;
         mp.ids_in = fp.ids; mp.ids_out = fp.ids2; mp.w = fp.w; mp.stats = sp.stats;
         err |= launch_remap(mp, st);
-        if (!grouping_small((long long)T * K)) err |= launch_count(fp.ids2, T, K, E, fp.tile_tokens, fp.tile_counts, st);
+        if (!grouping_small((long long)T * K, E)) err |= launch_count(fp.ids2, T, K, E, fp.tile_tokens, fp.tile_counts, st);
         ScanParams sq = sp;
         sq.tile_stats = nullptr; sq.stats = nullptr;      // written by the substitution kernel
         err |= launch_grouping(sq, cp, st);

@@ -417,6 +417,36 @@ __device__ void place_assignments(const int32_t *ids, int A, int E, int K, const
         if (ids[a] < 0) c.inv_perm[a] = -1;
 }
 
+// Offsets and the list of row tiles from the group starts in LDS (start: G + 1 rows, tstart: G + 1 tiles);
+// every thread of one workgroup calls it.  For the decode projections (largest_first) the list holds the
+// live groups by falling row count: a group is one work-item column of their grid, groups with more rows take
+// longer per item, and handing the big ones out first leaves the short items for the end of the launch.
+__device__ void write_group_tables(const ScanParams &p, const int32_t *start, const int32_t *tstart) {
+    const int tid = threadIdx.x, G = p.E + p.n_shared;
+    for (int g = tid; g <= G; g += blockDim.x) p.offsets[g] = start[g];
+    if (p.largest_first) {
+        for (int g = tid; g < G; g += blockDim.x) {
+            const int n = start[g + 1] - start[g];
+            if (n == 0) continue;
+            int rank = 0;
+            for (int h = 0; h < G; ++h) {
+                const int m = start[h + 1] - start[h];
+                rank += (m > n || (m == n && h < g)) ? 1 : 0;
+            }
+            p.mt_group[rank] = g;
+            p.mt_row0[rank] = start[g];
+        }
+    } else {
+        for (int g = tid; g < G; g += blockDim.x) {
+            const int nt = tstart[g + 1] - tstart[g];
+            for (int i = 0; i < nt; ++i) {
+                p.mt_group[tstart[g] + i] = g;
+                p.mt_row0[tstart[g] + i] = start[g] + i * p.BM;
+            }
+        }
+    }
+}
+
 // Everything after the per-expert counts of a batch whose substituted ids sit in LDS (one workgroup):
 // group offsets, the list of row tiles (or of live groups, largest first, for the decode projections),
 // statistics, stable placement.  counts: E entries in LDS; start / tstart: LDS scratch of G + 1 entries;
@@ -450,30 +480,7 @@ __device__ void finish_groups(const ScanParams &p, const ScatterParams &c, const
         if (lane == 0) { p.n_mtiles[0] = tot_t; p.n_mtiles[1] = tot_c; }
     }
     __syncthreads();
-    for (int g = tid; g <= G; g += blockDim.x) p.offsets[g] = start[g];
-    if (p.largest_first) {
-        // decode projections: a group is one work-item column of the grid, and groups with more rows take
-        // longer per item; handing the big ones out first leaves the short items for the end of the launch
-        for (int g = tid; g < G; g += blockDim.x) {
-            const int n = start[g + 1] - start[g];
-            if (n == 0) continue;
-            int rank = 0;
-            for (int h = 0; h < G; ++h) {
-                const int m = start[h + 1] - start[h];
-                rank += (m > n || (m == n && h < g)) ? 1 : 0;
-            }
-            p.mt_group[rank] = g;
-            p.mt_row0[rank] = start[g];
-        }
-    } else {
-        for (int g = tid; g < G; g += blockDim.x) {
-            const int nt = tstart[g + 1] - tstart[g];
-            for (int i = 0; i < nt; ++i) {
-                p.mt_group[tstart[g] + i] = g;
-                p.mt_row0[tstart[g] + i] = start[g] + i * p.BM;
-            }
-        }
-    }
+    write_group_tables(p, start, tstart);
     if (p.stats != nullptr && wave < 3) {          // one wave per counter
         int sum = 0;
         if (local_stats != nullptr) sum = local_stats[wave];
@@ -1069,14 +1076,7 @@ __global__ void __launch_bounds__(1024) group_tiles_kernel(ScanParams p, Scatter
     }
     __syncthreads();
     if (tile == 0) {
-        for (int g = tid; g <= G; g += blockDim.x) p.offsets[g] = start[g];
-        for (int g = tid; g < G; g += blockDim.x) {
-            const int nt = tstart[g + 1] - tstart[g];
-            for (int i = 0; i < nt; ++i) {
-                p.mt_group[tstart[g] + i] = g;
-                p.mt_row0[tstart[g] + i] = start[g] + i * p.BM;
-            }
-        }
+        write_group_tables(p, start, tstart);
         if (p.stats != nullptr && wave >= nw - 3) {    // one wave per counter, lanes over the tiles
             const int k = wave - (nw - 3);
             int sum = 0;
@@ -1213,11 +1213,14 @@ int launch_scan(const ScanParams &p, hipStream_t st) {
     return launch_status(__func__);
 }
 
-bool grouping_small(long long assignments) { return assignments <= SMALL_A; }
+// The one-workgroup kernel walks every assignment once per expert (a wave per expert, 64 assignments a
+// step): fine for a few experts, slow for many (128 experts x 1024 assignments: 25 us against 12 us for the
+// per-tile kernel).
+bool grouping_small(long long assignments, int E) { return assignments <= SMALL_A && assignments * E <= 32768; }
 
 // scan + scatter: one kernel for small batches and for small histograms
 int launch_grouping(const ScanParams &sp, const ScatterParams &cp, hipStream_t st) {
-    if (grouping_small((long long)cp.T * cp.K)) {
+    if (grouping_small((long long)cp.T * cp.K, cp.E)) {
         hipLaunchKernelGGL(group_small_kernel, dim3(1), dim3(1024), 0, st, sp, cp);   // also for an empty batch: offsets
         return launch_status(__func__);
     }

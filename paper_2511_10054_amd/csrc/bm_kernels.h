@@ -127,7 +127,7 @@ int launch_count(const int32_t *ids, int T, int K, int E, int tile_tokens, int32
 int launch_scan(const ScanParams &p, hipStream_t st);
 int launch_scatter(const ScatterParams &p, hipStream_t st);
 int launch_grouping(const ScanParams &sp, const ScatterParams &cp, hipStream_t st);   // scan + scatter (one kernel for small batches)
-bool grouping_small(long long assignments);   // launch_grouping takes the one-kernel path (and needs no tile histograms)
+bool grouping_small(long long assignments, int E);   // launch_grouping takes the one-kernel path (and needs no tile histograms)
 
 // bf16 MFMA grouped projections (row tile height p.BM, which the row-tile table was built for)
 int launch_gateup_bf16(const GemmParams &p, hipStream_t st);   // c = silu(a b0^T) * (a b1^T), bf16

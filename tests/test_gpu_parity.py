@@ -214,6 +214,8 @@ DECODE_CASES = [
     ("c2_mixtral_decode", dict(d=2048, F=2048), 8),       # persistent kernel shapes
     ("c2_mixtral_decode", dict(d=2048, F=3584), 16),
     ("c2_mixtral_decode", dict(d=1024, F=2048), 64),      # LDS-staged kernel, several passes possible
+    ("c2_mixtral_decode", dict(d=1024, F=2048), 128),     # 256 rows over 5 groups: some groups take two passes
+    ("c4_qwen3", dict(d=256, F=256), 100),                # many experts, few rows each: streaming path past 256 rows
     ("c5_deepseek", dict(d=2048, F=1792, E=16, n_resident=4), 4),    # shared experts on the decode path
     ("c4_qwen3", dict(d=256, F=96), 12),                  # odd widths: generic decode kernel
 ]
