@@ -19,8 +19,9 @@ using namespace bm;
 
 constexpr size_t ALIGN = 256;
 constexpr int MAX_SHARED = 8;
-constexpr int SKINNY_MAX_ROWS = 256;   // total rows up to which the weight-streaming path is always used
-constexpr int SKINNY_AVG_ROWS = 8;     // ... and rows per group (averaged over all experts) with many experts
+constexpr int SKINNY_MAX_ROWS = 256;   // total rows up to which the weight-streaming path is always used,
+constexpr int SKINNY_FIT_ROWS = 512;   // ... up to which it is used when the widths fit its fast kernels,
+constexpr int SKINNY_AVG_ROWS = 8;     // ... and rows per group (averaged over all experts) likewise
 constexpr int SKINNY_KSPLIT = 8;
 
 // Row-tile height of the grouped GEMM.  256 rows whenever both projections fit the persistent k-step-64
@@ -40,17 +41,18 @@ int gemm_tile_rows(const bm_layer_desc *d) {
 }
 
 // Few rows per group: every expert group is decode-sized and the projections are bound by reading the
-// weights once.  Up to 256 rows in all (Mixtral-shaped layer, 8 experts: 0.38 ms at 128 tokens against
-// 0.47 ms on the tiled path; at 192 tokens 0.56 against 0.47), or up to 8 rows per expert on average when
-// both widths fit the fast streaming kernels (Qwen3-shaped layer, 128 experts, 128 tokens: 0.17 against
-// 0.21 ms; the DeepSeek-shaped one, whose F = 1408 does not fit them and whose shared experts take every
-// token, is faster on the tiled path from 64 tokens on).
+// weights once.  Up to 256 rows in all; up to 512 rows (Mixtral-shaped layer, 8 experts: 0.34 / 0.44 / 0.46 ms
+// at 128 / 192 / 256 tokens against 0.47 / 0.48 / 0.49 ms on the tiled path) or up to 8 rows per expert on
+// average (Qwen3-shaped layer, 128 experts, 128 tokens: 0.16 against 0.21 ms) when both widths fit the fast
+// streaming kernels - the DeepSeek-shaped layer, whose F = 1408 does not fit them and whose shared experts
+// take every token, is faster on the tiled path from 64 tokens (512 rows) on.
 bool use_skinny(const bm_layer_desc *d) {
     if (d->dtype != BM_BF16) return false;
     const int ns = d->n_shared > 0 ? d->n_shared : 0;
     const long long rows = (long long)d->T * (d->K + ns);
     if (rows <= SKINNY_MAX_ROWS) return true;
-    return rows <= (long long)SKINNY_AVG_ROWS * (d->E + ns) && d->d % 256 == 0 && d->F % 256 == 0;
+    const bool fit = d->d % 256 == 0 && d->F % 256 == 0;
+    return fit && (rows <= SKINNY_FIT_ROWS || rows <= (long long)SKINNY_AVG_ROWS * (d->E + ns));
 }
 // Reduction slices of the decode down projection (each slice is a workgroup
 // whose 4 waves split it once more): prefer a count that fits the
@@ -476,6 +478,7 @@ int bm_moe_forward(const bm_layer_desc *desc, const void *x, const bm_weights *w
         s1.c = gp.c; s1.N = desc->F; s1.Kd = desc->d; s1.E = E;
         s1.max_groups = G < L.mtiles_max ? G : L.mtiles_max;
         s1.ksplit = 1; s1.rows_max = L.rows_max; s1.max_rows_per_group = T * K;
+        s1.wide = (T > 64 && (long long)T * K >= 16ll * E) ? 1 : 0;   // big groups likely, not just many small ones
         s1.mt_group = sp.mt_group; s1.n_mtiles = sp.n_mtiles; s1.offsets = sp.offsets;
         SkinnyParams s2 = s1;
         s2.a = gp.c; s2.row_map = nullptr;

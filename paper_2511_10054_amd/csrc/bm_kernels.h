@@ -100,6 +100,7 @@ struct SkinnyParams {
     int max_groups;               // grid bound on live groups
     int ksplit, rows_max;
     int max_rows_per_group;       // launch-time bound: T*K routed rows (or T for a shared expert)
+    int wide;                     // groups of more than 64 rows are expected (more than 64 tokens): 128 rows per pass
     const int32_t *mt_group, *n_mtiles, *offsets;
 };
 

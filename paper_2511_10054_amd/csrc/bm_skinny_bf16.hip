@@ -489,7 +489,8 @@ __device__ __forceinline__ void skinny_lds_item(const SkinnyParams &p, u32x4 *xs
         const int n_rows = re - rb;
         if (MAXNBT == 1 || n_rows <= 16) skinny_lds_pass<DUAL, 1, PACKED>(p, w0, w1, xs, wst, rb, re, k_begin, k_end, n0, kslice, active);
         else if (MAXNBT == 2 || n_rows <= 32) skinny_lds_pass<DUAL, 2, PACKED>(p, w0, w1, xs, wst, rb, re, k_begin, k_end, n0, kslice, active);
-        else skinny_lds_pass<DUAL, 4, PACKED>(p, w0, w1, xs, wst, rb, re, k_begin, k_end, n0, kslice, active);
+        else if (MAXNBT == 4 || n_rows <= 64) skinny_lds_pass<DUAL, 4, PACKED>(p, w0, w1, xs, wst, rb, re, k_begin, k_end, n0, kslice, active);
+        else skinny_lds_pass<DUAL, MAXNBT, PACKED>(p, w0, w1, xs, wst, rb, re, k_begin, k_end, n0, kslice, active);
         __syncthreads();                              // the next pass restages the LDS buffers
     }
 }
@@ -502,7 +503,7 @@ __device__ __forceinline__ void skinny_lds_item(const SkinnyParams &p, u32x4 *xs
 // workgroups per unit walking the items with a stride took 117 us: the items left for its second
 // round sit on a quarter of the units, and a unit's streaming rate is capped.
 template <bool DUAL, int MAXNBT, bool PACKED>
-__global__ void __launch_bounds__(256, 2) skinny_lds_bf16_kernel(SkinnyParams p) {
+__global__ void __launch_bounds__(256, MAXNBT <= 4 ? 2 : 1) skinny_lds_bf16_kernel(SkinnyParams p) {
     __shared__ u32x4 xs[2 * SkinnyChunk<MAXNBT>::CH * MAXNBT * 64];
     __shared__ u32x4 wstage[PACKED ? 1 : 4 * (DUAL ? 256 : 128)];    // public layout: 2 KB per wave and matrix
     const int gi = blockIdx.z;
@@ -515,7 +516,11 @@ bool skinny_lds_ok(int Kd, int ksplit) { return Kd % (KUNIT * ksplit) == 0; }
 template <bool DUAL>
 static void launch_skinny_lds(const SkinnyParams &p, hipStream_t st) {
     dim3 grid((p.N / 16 + 3) / 4, p.ksplit, p.max_groups);
-    if (p.pk != nullptr) hipLaunchKernelGGL((skinny_lds_bf16_kernel<DUAL, 4, true>), grid, dim3(256), 0, st, p);
+    // groups of more than 64 rows (more than 64 tokens): 128 rows per pass over the weights, at one workgroup
+    // per compute unit (128 KB of staged activations), instead of two passes of 64
+    if (p.wide && p.pk != nullptr) hipLaunchKernelGGL((skinny_lds_bf16_kernel<DUAL, 8, true>), grid, dim3(256), 0, st, p);
+    else if (p.wide) hipLaunchKernelGGL((skinny_lds_bf16_kernel<DUAL, 8, false>), grid, dim3(256), 0, st, p);
+    else if (p.pk != nullptr) hipLaunchKernelGGL((skinny_lds_bf16_kernel<DUAL, 4, true>), grid, dim3(256), 0, st, p);
     else hipLaunchKernelGGL((skinny_lds_bf16_kernel<DUAL, 4, false>), grid, dim3(256), 0, st, p);
 }
 
