@@ -81,6 +81,13 @@ def test_c2_mixtral_decode_public_weight_layout(T):
     _check("c2_mixtral_decode", T, 64, pack=False)
 
 
+@pytest.mark.parametrize("T", [128, 256, 512])
+def test_c2_mixtral_between_decode_and_prefill(T):
+    """Batches between the benchmark points: 128-rows-per-pass streaming kernel (128), two such passes for the
+    largest groups (256), padded 256-row tiles of the prefill kernel (512)."""
+    _check("c2_mixtral_decode", T, 64)
+
+
 def test_c2_mixtral_decode_unique():
     _check("c2_mixtral_decode", 64, 64, unique=True)
 
