@@ -21,7 +21,7 @@ constexpr size_t ALIGN = 256;
 constexpr int MAX_SHARED = 8;
 constexpr int SKINNY_MAX_ROWS = 256;   // total rows up to which the weight-streaming path is always used,
 constexpr int SKINNY_FIT_ROWS = 512;   // ... up to which it is used when the widths fit its fast kernels,
-constexpr int SKINNY_AVG_ROWS = 8;     // ... and rows per group (averaged over all experts) likewise
+constexpr int SKINNY_AVG_ROWS = 16;    // ... and rows per group (averaged over all experts) likewise
 constexpr int SKINNY_KSPLIT = 8;
 
 // Row-tile height of the grouped GEMM.  256 rows whenever both projections fit the persistent k-step-64
@@ -42,8 +42,8 @@ int gemm_tile_rows(const bm_layer_desc *d) {
 
 // Few rows per group: every expert group is decode-sized and the projections are bound by reading the
 // weights once.  Up to 256 rows in all; up to 512 rows (Mixtral-shaped layer, 8 experts: 0.34 / 0.44 / 0.46 ms
-// at 128 / 192 / 256 tokens against 0.47 / 0.48 / 0.49 ms on the tiled path) or up to 8 rows per expert on
-// average (Qwen3-shaped layer, 128 experts, 128 tokens: 0.16 against 0.21 ms) when both widths fit the fast
+// at 128 / 192 / 256 tokens against 0.47 / 0.48 / 0.49 ms on the tiled path) or up to 16 rows per expert on
+// average (Qwen3-shaped layer, 128 experts, 128 / 256 tokens: 0.13 / 0.16 against 0.21 ms) when both widths fit the fast
 // streaming kernels - the DeepSeek-shaped layer, whose F = 1408 does not fit them and whose shared experts
 // take every token, is faster on the tiled path from 64 tokens (512 rows) on.
 bool use_skinny(const bm_layer_desc *d) {
@@ -69,6 +69,7 @@ int skinny_ksplit(const bm_layer_desc *d) {
             if (bm::skinny_lds_ok(d->F, s) && d->F / (512 * s) >= 2 && (d->d / 64) * groups * s >= 512) return s;
         for (int s = SKINNY_KSPLIT; s > 1; --s)
             if (bm::skinny_lds_ok(d->F, s) && d->F / (512 * s) >= 2) return s;
+        if (bm::skinny_lds_ok(d->F, 1)) return 1;       // short reduction (e.g. F = 768): unsplit, still the LDS-staged kernel
     }
     for (int s = SKINNY_KSPLIT; s >= 1; --s)
         if (bm::skinny_q_ok(d->F, s)) return s;
@@ -478,13 +479,16 @@ int bm_moe_forward(const bm_layer_desc *desc, const void *x, const bm_weights *w
         s1.c = gp.c; s1.N = desc->F; s1.Kd = desc->d; s1.E = E;
         s1.max_groups = G < L.mtiles_max ? G : L.mtiles_max;
         s1.ksplit = 1; s1.rows_max = L.rows_max; s1.max_rows_per_group = T * K;
-        s1.wide = (T > 64 && (long long)T * K >= 16ll * E) ? 1 : 0;   // big groups likely, not just many small ones
+        // 128 rows per pass when big groups are likely (measured on the 8- and the 128-expert layer: the gate/up
+        // projection gains from 8 rows per expert on average, the down projection from 16)
+        s1.wide = (T > 64 && (long long)T * K >= 8ll * E) ? 1 : 0;
         s1.mt_group = sp.mt_group; s1.n_mtiles = sp.n_mtiles; s1.offsets = sp.offsets;
         SkinnyParams s2 = s1;
         s2.a = gp.c; s2.row_map = nullptr;
         s2.b0 = wt->w_down; s2.b1 = nullptr; s2.sb0 = wt->ws_down; s2.sb1 = nullptr;
         s2.pk = pk_dn ? wt->wp_down : nullptr; s2.spk = pk_dn ? wt->wsp_down : nullptr;
         s2.c = dp.c; s2.N = desc->d; s2.Kd = desc->F; s2.ksplit = ksplit;
+        s2.wide = (T > 64 && (long long)T * K >= 16ll * E) ? 1 : 0;
         err |= launch_skinny_gateup_bf16(s1, st);
         mark(2);
         err |= launch_skinny_down_bf16(s2, st);

@@ -296,10 +296,10 @@ static void launch_skinny_q(const SkinnyParams &p, hipStream_t st) {
 // k-step and 16-row block: contiguous ds_read_b128), double-buffered, so they
 // cost each wave a quarter of the loads and no ring registers.  Weights run
 // through the same rotating register ring as above.
-// Needs Kd divisible by 512 * ksplit.
+// Needs Kd divisible by 256 * ksplit (chunks of 8 k-steps).
 // ---------------------------------------------------------------------------
 template <int NBT> struct SkinnyChunk { static constexpr int CH = 8; };
-constexpr int KUNIT = 512;
+constexpr int KUNIT = 256;                             // one chunk: SkinnyChunk::CH k-steps of 32
 
 // PACKED: the weights come from bm_pack_weights' fragment-major copy, where the 1 KB operand
 // fragment of every (16-row block, k-step) is contiguous (gate and up fragments interleaved), so a

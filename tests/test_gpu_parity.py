@@ -217,6 +217,7 @@ DECODE_CASES = [
     ("c2_mixtral_decode", dict(d=1024, F=2048), 128),     # 256 rows over 5 groups: passes of up to 128 rows
     ("c2_mixtral_decode", dict(d=512, F=1024), 250),      # 500 rows: some groups take two of those passes
     ("c4_qwen3", dict(d=256, F=256), 100),                # many experts, few rows each: streaming path past 256 rows
+    ("c4_qwen3", dict(d=512, F=768), 40),                 # reduction of three chunks in the down projection, unsplit
     ("c5_deepseek", dict(d=2048, F=1792, E=16, n_resident=4), 4),    # shared experts on the decode path
     ("c4_qwen3", dict(d=256, F=96), 12),                  # odd widths: generic decode kernel
 ]
