@@ -600,75 +600,92 @@ __global__ void __launch_bounds__(256) grouped_gemm256_k64w_bf16_kernel(GemmPara
         const bool t_partial = partial;
         const int t_kbeg = kbeg, t_kend = kend;
         bool more = false;                             // the loads have moved on to a next item (uniform)
-#pragma unroll
-        for (int i = 0; i < 8; ++i)
-#pragma unroll
-            for (int j = 0; j < 8; ++j)
-#pragma unroll
-                for (int v = 0; v < 4; ++v) acc[i][j][v] = 0.0f;
-        // Every wave's part of B(0), A(0) is in LDS (first tile: the wait above; later tiles: they were
-        // waited for in the middle of the previous tile's last k-step), and every wave is done with
-        // the write-out staging in the slot the first loads of this tile will fill.
-        BM_BARE_BARRIER();
-        {
-            const uint16_t *sa_ = smem + sA * P_PART + fa_off[0];
-            const uint16_t *sb_ = smem + sB * P_PART + fb_off[0];
-#pragma unroll
-            for (int d = 0; d < 16; ++d) BM_RD(d, f0a, f0b, sa_, sb_)
-        }
-
-        for (int kt = t_kbeg; kt < t_kend; ++kt) {
-            // k-step the loads of this trip fetch: two ahead, in the next item once this one is through
-            const int kl = more ? kbeg + (kt + 2 - t_kend) : kt + 2;
-            {
-                // first k slice of 32: 64 MFMAs; the second slice's fragments are read under MFMAs 0-31 (one
-                // read per two MFMAs), the 8 loads of B(kt+2) go into the slot A(kt-1) has left, one under
-                // every eighth MFMA (spread evenly: bunched loads hold up the MFMAs behind them at issue;
-                // measured 5 % on the whole kernel)
-                const uint16_t *sa_ = smem + sA * P_PART + fa_off[1];
-                const uint16_t *sb_ = smem + sB * P_PART + fb_off[1];
-#pragma unroll
-                for (int m = 0; m < 64; ++m) {
-                    BM_MFMA1(m, f0a, f0b);
-                    if (m < 32 && (m & 1) == 0) BM_RD(m >> 1, f1a, f1b, sa_, sb_)
-                    if ((m & 7) == 5) BM_DMA_B(sAp, kl, m >> 3);
-                    __builtin_amdgcn_sched_barrier(0);
-                }
-            }
-            // every fragment of B(kt), A(kt) is in registers; A(kt+1), B(kt+1) have landed (this wave's
-            // part: at most the 8 loads of B(kt+2) are outstanding - whatever was issued before them,
-            // the previous tile's stores included, is complete); after the barrier both hold for every wave
-            BM_WAIT_VM_LGKM(8, 0);
-            BM_BARE_BARRIER();
-            const int sBn = sB >= 3 ? sB - 3 : sB + 2, sAn = sA >= 3 ? sA - 3 : sA + 2;
-            {
-                // second slice: A(kt+2) goes into the slot B(kt) has left, one load under every eighth MFMA;
-                // the first fragments of k-step kt+1 are read under the first half, so that none of
-                // them is still in flight when the next k-step starts (after the last k-step of a tile
-                // they are the next tile's and are read again at its start: no register stays live
-                // across the write-out)
-                const uint16_t *sa_ = smem + sAn * P_PART + fa_off[0];
-                const uint16_t *sb_ = smem + sBn * P_PART + fb_off[0];
-#pragma unroll
-                for (int m = 0; m < 64; ++m) {
-                    BM_MFMA1(m, f1a, f1b);
-                    if ((m & 7) == 1) BM_DMA_A(sB, kl, m >> 3);
-                    if (m < 32 && (m & 1) == 0) BM_RD(m >> 1, f0a, f0b, sa_, sb_)
-                    __builtin_amdgcn_sched_barrier(0);
-                }
-            }
-            sAp = sA;
-            sB = sBn;
-            sA = sAn;
-            if (kt == t_kend - 3) {
-                // the loads of this item are all issued: from here on they fetch the next one
-                BM_NEXT_ITEM(more);
-                if (more) BM_SETUP(xcd * per_xcd + item_tile);
-            }
-        }
+        // One tile: accumulators cleared, then the k-steps.  Written as a macro so that the down projection
+        // can also instantiate it without the matrix work (COMPUTE_ = false, see below); the steps, in order:
+        //  - barrier: every wave's part of B(0), A(0) is in LDS (first tile: the wait above; later tiles: they
+        //    were waited for in the middle of the previous tile's last k-step), and every wave is done with the
+        //    write-out staging in the slot the first loads of this tile will fill; first fragments read.
+        //  - per k-step, kl = the k-step its loads fetch: two ahead, in the next item once this one is through.
+        //  - first k slice of 32: 64 MFMAs; the second slice's fragments are read under MFMAs 0-31 (one read
+        //    per two MFMAs), the 8 loads of B(kt+2) go into the slot A(kt-1) has left, one under every eighth
+        //    MFMA (spread evenly: bunched loads hold up the MFMAs behind them at issue; measured 5 % on the
+        //    whole kernel).
+        //  - wait + barrier: every fragment of B(kt), A(kt) is in registers; A(kt+1), B(kt+1) have landed (this
+        //    wave's part: at most the 8 loads of B(kt+2) are outstanding - whatever was issued before them, the
+        //    previous tile's stores included, is complete); after the barrier both hold for every wave.
+        //  - second slice: A(kt+2) goes into the slot B(kt) has left, one load under every eighth MFMA; the
+        //    first fragments of k-step kt+1 are read under the first half, so that none of them is still in
+        //    flight when the next k-step starts (after the last k-step of a tile they are the next tile's and
+        //    are read again at its start: no register stays live across the write-out).
+        //  - three k-steps before the end the loads of this item are all issued: from here on they fetch the
+        //    next one.
+#define BM_TILE_LOOP(COMPUTE_)                                                                                        \
+    {                                                                                                                 \
+        if (COMPUTE_) {                                                                                               \
+            _Pragma("unroll") for (int i = 0; i < 8; ++i)                                                             \
+                _Pragma("unroll") for (int j = 0; j < 8; ++j)                                                         \
+                    _Pragma("unroll") for (int v = 0; v < 4; ++v) acc[i][j][v] = 0.0f;                                \
+        }                                                                                                             \
+        BM_BARE_BARRIER();                                                                                            \
+        {                                                                                                             \
+            const uint16_t *sa_ = smem + sA * P_PART + fa_off[0];                                                     \
+            const uint16_t *sb_ = smem + sB * P_PART + fb_off[0];                                                     \
+        _Pragma("unroll")                                                                                             \
+            for (int d = 0; (COMPUTE_) && d < 16; ++d) BM_RD(d, f0a, f0b, sa_, sb_)                                   \
+        }                                                                                                             \
+        for (int kt = t_kbeg; kt < t_kend; ++kt) {                                                                    \
+            const int kl = more ? kbeg + (kt + 2 - t_kend) : kt + 2;                                                  \
+            {                                                                                                         \
+                const uint16_t *sa_ = smem + sA * P_PART + fa_off[1];                                                 \
+                const uint16_t *sb_ = smem + sB * P_PART + fb_off[1];                                                 \
+        _Pragma("unroll")                                                                                             \
+                for (int m = 0; m < 64; ++m) {                                                                        \
+                    if (COMPUTE_) BM_MFMA1(m, f0a, f0b);                                                              \
+                    if ((COMPUTE_) && m < 32 && (m & 1) == 0) BM_RD(m >> 1, f1a, f1b, sa_, sb_)                       \
+                    if ((m & 7) == 5) BM_DMA_B(sAp, kl, m >> 3);                                                      \
+                    __builtin_amdgcn_sched_barrier(0);                                                                \
+                }                                                                                                     \
+            }                                                                                                         \
+            BM_WAIT_VM_LGKM(8, 0);                                                                                    \
+            BM_BARE_BARRIER();                                                                                        \
+            const int sBn = sB >= 3 ? sB - 3 : sB + 2, sAn = sA >= 3 ? sA - 3 : sA + 2;                               \
+            {                                                                                                         \
+                const uint16_t *sa_ = smem + sAn * P_PART + fa_off[0];                                                \
+                const uint16_t *sb_ = smem + sBn * P_PART + fb_off[0];                                                \
+        _Pragma("unroll")                                                                                             \
+                for (int m = 0; m < 64; ++m) {                                                                        \
+                    if (COMPUTE_) BM_MFMA1(m, f1a, f1b);                                                              \
+                    if ((m & 7) == 1) BM_DMA_A(sB, kl, m >> 3);                                                       \
+                    if ((COMPUTE_) && m < 32 && (m & 1) == 0) BM_RD(m >> 1, f0a, f0b, sa_, sb_)                       \
+                    __builtin_amdgcn_sched_barrier(0);                                                                \
+                }                                                                                                     \
+            }                                                                                                         \
+            sAp = sA;                                                                                                 \
+            sB = sBn;                                                                                                 \
+            sA = sAn;                                                                                                 \
+            if (kt == t_kend - 3) {                                                                                   \
+                BM_NEXT_ITEM(more);                                                                                   \
+                if (more) BM_SETUP(xcd * per_xcd + item_tile);                                                        \
+            }                                                                                                         \
+        }                                                                                                             \
+    }
+        // Down projection: a tile of at most 128 rows leaves the two waves of the lower row half nothing but
+        // padding.  They keep their share of the loads, the waits and the barriers - the same instruction
+        // stream minus every MFMA and fragment read - and skip the write-out: the chip runs these kernels
+        // against its power limit, and what the idle matrix cores do not draw lets the others clock higher
+        // (Qwen3-shaped layer, 41 % padding: down projection -6 %).  The gate/up instantiation keeps the single
+        // loop (a second copy costs it registers and 2 % of its time).
+        const bool live = DUAL || !(wm == 1 && t_row_end - t_row0 <= 128);
+        if (DUAL || live) BM_TILE_LOOP(true)
+        else BM_TILE_LOOP(false)
+#undef BM_TILE_LOOP
         // The tile is done.  The slot A(last k-step) sat in is free for every wave since the barrier in
         // the middle of that k-step; it stages the write-out while the next tile's loads land elsewhere.
 
+        if (!live) {                                   // nothing but padding rows: nothing to write
+            if (!more) break;
+            continue;
+        }
         if (SPLIT && t_partial) {
             // chunk of a split tile: the fp32 accumulators go to this workgroup's scratch tile as they are
             // (accumulator tile, lane: 16-byte stores, contiguous over the lanes)
