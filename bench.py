@@ -34,9 +34,9 @@ PEAK_BF16_TFLOPS = 2500.0    # MI355X dense bf16 MFMA
 # first-resident mode only.  Re-measure after changing that kernel.
 TRAFFIC_BYTES = {
     "c2_mixtral_decode_T64": 1182.4e6,
-    "c3_mixtral_prefill_T4096": 4017.7e6,
-    "c4_qwen3_T2048": 590.9e6,
-    "c5_deepseek_T8192": 1751.8e6,
+    "c3_mixtral_prefill_T4096": 3979.2e6,
+    "c4_qwen3_T2048": 591.8e6,
+    "c5_deepseek_T8192": 1736.1e6,
 }
 
 WORKLOADS = {
