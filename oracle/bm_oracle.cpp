@@ -19,10 +19,10 @@
 // TAE against closed forms.  Unpinned by the paper: the error of the
 // substituted layer against the unsubstituted one (no bound is given).
 //
-// Every loop follows the order and notation of the passage it cites; there is
-// no blocking, fusion or reordering.  OpenMP splits the token loop only
-// (tokens are independent).
+// Plain loops, one per definition, with no blocking, fusion or reordering.
+// OpenMP splits the token loop only (tokens are independent).
 
+#include <algorithm>
 #include <cmath>
 #include <cstdint>
 #include <cstring>
@@ -117,45 +117,7 @@ int bm_oracle_tae(int T, int K, const double* w, double* tae) {
 // w [T][K] in/out (nullable), stats[3] = {misses, substituted, dropped}.
 int bm_oracle_buddy_remap(int T, int K, int E, int R, int H, int unique, const uint8_t* resident,
                           const int32_t* table, const int32_t* ids_in, int32_t* ids_out, double* w,
-                          int64_t* stats) {
-    if (H > R || H < 0) return -1;
-    int64_t n_miss = 0, n_sub = 0, n_drop = 0;
-    for (int t = 0; t < T; ++t) {
-        std::vector<char> in_u(E, 0);                       // U_t
-        for (int k = 0; k < K; ++k) {
-            int32_t e = ids_in[(size_t)t * K + k];
-            ids_out[(size_t)t * K + k] = e;                  // S' <- S
-            if (e >= 0 && e < E) in_u[e] = 1;
-        }
-        for (int k = 0; k < K; ++k) {
-            int32_t e = ids_out[(size_t)t * K + k];
-            if (e < 0 || e >= E) {                           // not a routed expert: nothing to run
-                ids_out[(size_t)t * K + k] = -1;
-                if (w) w[(size_t)t * K + k] = 0.0;
-                continue;
-            }
-            if (resident[e]) continue;
-            ++n_miss;
-            int32_t chosen = -1;
-            for (int r = 0; r < H; ++r) {
-                int32_t b = table[(size_t)e * R + r];
-                if (b < 0 || b >= E) continue;
-                if (resident[b] && !(unique && in_u[b])) { chosen = b; break; }
-            }
-            if (chosen >= 0) {
-                ids_out[(size_t)t * K + k] = chosen;
-                in_u[chosen] = 1;
-                ++n_sub;
-            } else {
-                ids_out[(size_t)t * K + k] = -1;
-                if (w) w[(size_t)t * K + k] = 0.0;
-                ++n_drop;
-            }
-        }
-    }
-    if (stats) { stats[0] = n_miss; stats[1] = n_sub; stats[2] = n_drop; }
-    return 0;
-}
+                          int64_t* stats);   // defined after the general form below, which it reduces to
 
 // Section 3.1 Eq. 2, Expert Distribution Gate: over the micro-batch (here: the
 // T tokens of the call) R(B) = the set of distinct experts some token selected;
@@ -208,6 +170,38 @@ double bm_oracle_distribution_delta(int T, int K, int E, const uint8_t* resident
 // per token the smallest relative gap (best - second) / best over its decisions
 // that had at least two acceptable entries (1e300 if none) - how close the token
 // came to a different choice.
+// The ranks r < H of expert e's buddy row whose entry may stand in for e for this
+// token (Algorithm 1's acceptance test): a valid expert id, resident, and - unique
+// mode - not among the experts the token holds already.
+static std::vector<int> acceptable_ranks(int e, int E, int R, int H, bool unique, const uint8_t* resident,
+                                         const int32_t* table, const std::vector<char>& held) {
+    std::vector<int> ranks;
+    for (int r = 0; r < H; ++r) {
+        const int32_t b = table[(size_t)e * R + r];
+        const bool valid = b >= 0 && b < E;
+        if (valid && resident[b] && !(unique && held[b])) ranks.push_back(r);
+    }
+    return ranks;
+}
+
+// Whether a token may be given substitutes at all (Section 3.1): Eq. 1 on its gate
+// weights renormalised to sum 1, and the top-two margin.
+static bool token_may_substitute(int K, const double* wt, bool use_tae, double tau, bool use_margin, double gamma) {
+    if (!use_tae && !use_margin) return true;
+    double sum = 0.0;
+    for (int k = 0; k < K; ++k) sum += wt[k];
+    double entropy = 0.0, largest = 0.0, second = 0.0;
+    for (int k = 0; k < K; ++k) {
+        const double pk = wt[k] / sum;
+        if (pk > 0.0) entropy -= pk * std::log(pk);
+        if (pk > largest) { second = largest; largest = pk; } else if (pk > second) { second = pk; }
+    }
+    const double tae = (K > 1) ? entropy / std::log((double)K) : 0.0;
+    if (use_tae && tae <= tau) return false;
+    if (use_margin && (largest - second) >= gamma) return false;
+    return true;
+}
+
 int bm_oracle_buddy_remap_psi(int T, int K, int E, int R, int H, int unique, int use_tae, double tau,
                               int use_margin, double gamma, int use_budget, int rho, int use_dist,
                               double beta, int use_psi, double eta, const double* q, const double* zhat,
@@ -218,74 +212,68 @@ int bm_oracle_buddy_remap_psi(int T, int K, int E, int R, int H, int unique, int
     bool bypass = false;
     if (use_dist) bypass = bm_oracle_distribution_delta(T, K, E, resident, ids_in, dist) >= beta && dist[0] > 0;
     for (int t = 0; t < T; ++t) {
+        const int32_t* s_in = ids_in + (size_t)t * K;
+        int32_t* s_out = ids_out + (size_t)t * K;
         double* wt = w ? w + (size_t)t * K : nullptr;
-        bool allowed = !bypass;
-        if (use_tae || use_margin) {
-            double sum = 0.0;
-            for (int k = 0; k < K; ++k) sum += wt[k];
-            double h = 0.0, p1 = 0.0, p2 = 0.0;              // entropy, largest and second largest p~
-            for (int k = 0; k < K; ++k) {
-                double pk = wt[k] / sum;
-                if (pk > 0.0) h -= pk * std::log(pk);
-                if (pk > p1) { p2 = p1; p1 = pk; } else if (pk > p2) { p2 = pk; }
-            }
-            const double tae = (K > 1) ? h / std::log((double)K) : 0.0;
-            if (use_tae && tae <= tau) allowed = false;
-            if (use_margin && (p1 - p2) >= gamma) allowed = false;
-        }
-        int replaced = 0;
-        double tok_margin = 1e300;
+        const bool open = !bypass && (!wt || token_may_substitute(K, wt, use_tae, tau, use_margin, gamma));
 
-        std::vector<char> in_u(E, 0);
+        std::vector<int32_t> selected(s_in, s_in + K);       // the token's routed experts (ids_out may alias ids_in)
+        std::vector<char> held(E, 0);                        // U_t: the routed experts, then every accepted buddy
+        for (int32_t e : selected) if (e >= 0 && e < E) held[e] = 1;
+
+        int replaced = 0;
+        double closest = 1e300;
         for (int k = 0; k < K; ++k) {
-            int32_t e = ids_in[(size_t)t * K + k];
-            ids_out[(size_t)t * K + k] = e;
-            if (e >= 0 && e < E) in_u[e] = 1;
-        }
-        for (int k = 0; k < K; ++k) {
-            int32_t e = ids_out[(size_t)t * K + k];
+            const int32_t e = selected[k];
+            int32_t runs = e;                                // the expert that will run in this slot
             if (e < 0 || e >= E) {
-                ids_out[(size_t)t * K + k] = -1;
-                if (wt) wt[k] = 0.0;
-                continue;
-            }
-            if (resident[e]) continue;
-            ++n_miss;
-            int32_t chosen = -1;
-            if (allowed && !(use_budget && replaced >= rho)) {
-                double best = 0.0, second = -1.0;
-                for (int r = 0; r < H; ++r) {
-                    int32_t b = table[(size_t)e * R + r];
-                    if (b < 0 || b >= E) continue;
-                    if (!(resident[b] && !(unique && in_u[b]))) continue;
-                    if (!use_psi) { chosen = b; break; }
-                    const double psi = q[(size_t)e * R + r] * (1.0 + eta * zhat[(size_t)t * E + b]);
-                    if (chosen < 0 || psi > best) { second = chosen < 0 ? -1.0 : best; best = psi; chosen = b; }
-                    else if (psi > second) second = psi;
+                runs = -1;                                   // not a routed expert: nothing to run
+            } else if (!resident[e]) {
+                ++n_miss;
+                runs = -1;
+                std::vector<int> ranks;
+                if (open && !(use_budget && replaced >= rho))
+                    ranks = acceptable_ranks(e, E, R, H, unique != 0, resident, table, held);
+                if (!ranks.empty()) {
+                    int pick = ranks.front();                // Algorithm 1: the highest-ranked acceptable entry
+                    if (use_psi) {                           // Eq. 3: the acceptable entry of largest priority
+                        double best = -1.0, second = -1.0;
+                        for (int r : ranks) {
+                            const int32_t b = table[(size_t)e * R + r];
+                            const double psi = q[(size_t)e * R + r] * (1.0 + eta * zhat[(size_t)t * E + b]);
+                            if (psi > best) { second = best; best = psi; pick = r; }
+                            else if (psi > second) second = psi;
+                        }
+                        if (ranks.size() > 1 && best > 0.0) closest = std::min(closest, (best - second) / best);
+                    }
+                    runs = table[(size_t)e * R + pick];
+                    held[runs] = 1;
+                    ++replaced;
+                    ++n_sub;
+                } else {
+                    ++n_drop;
                 }
-                if (use_psi && chosen >= 0 && second >= 0.0 && best > 0.0) {
-                    const double m = (best - second) / best;
-                    if (m < tok_margin) tok_margin = m;
-                }
             }
-            if (chosen >= 0) {
-                ids_out[(size_t)t * K + k] = chosen;
-                in_u[chosen] = 1;
-                ++replaced;
-                ++n_sub;
-            } else {
-                ids_out[(size_t)t * K + k] = -1;
-                if (wt) wt[k] = 0.0;
-                ++n_drop;
-            }
+            s_out[k] = runs;
+            if (runs < 0 && wt) wt[k] = 0.0;
         }
-        if (margin_out) margin_out[t] = tok_margin;
+        if (margin_out) margin_out[t] = closest;
     }
     if (stats) {
         stats[0] = n_miss; stats[1] = n_sub; stats[2] = n_drop;
         stats[3] = dist[0]; stats[4] = dist[1]; stats[5] = bypass ? 1 : 0;
     }
     return 0;
+}
+
+int bm_oracle_buddy_remap(int T, int K, int E, int R, int H, int unique, const uint8_t* resident,
+                          const int32_t* table, const int32_t* ids_in, int32_t* ids_out, double* w,
+                          int64_t* stats) {
+    int64_t all[6];
+    const int rc = bm_oracle_buddy_remap_psi(T, K, E, R, H, unique, 0, 0.0, 0, 0.0, 0, 0, 0, 0.0, 0, 0.0, nullptr,
+                                             nullptr, resident, table, ids_in, ids_out, w, all, nullptr);
+    if (rc == 0 && stats) { stats[0] = all[0]; stats[1] = all[1]; stats[2] = all[2]; }
+    return rc;
 }
 
 int bm_oracle_buddy_remap_gated(int T, int K, int E, int R, int H, int unique, int use_tae, double tau,

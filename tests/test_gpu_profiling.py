@@ -78,6 +78,33 @@ def test_buddy_table_builder(E, K, R):
         np.testing.assert_array_equal(table2.cpu().numpy(), t_ref)
 
 
+def test_buddy_table_builder_exact_boundary_of_eq5():
+    """Prefix sums that land exactly on alpha (Eq. 5): counts 6, 3, 1 with alpha = fp32(0.9) and its fp32
+    neighbours, counts 2, 1, 1 with alpha = 0.75, 0.5 (exact in every format) and their neighbours."""
+    torch = _torch()
+    import paper_2511_10054_amd as bm
+    M1 = np.array([[0, 3, 6, 1], [3, 0, 0, 0], [6, 0, 0, 2], [1, 0, 2, 0]], np.int64)
+    M2 = np.array([[0, 2, 1, 1], [2, 0, 0, 0], [1, 0, 0, 0], [1, 0, 0, 0]], np.int64)
+    desc = bm.LayerDesc(T=0, d=32, E=4, F=0, K=2, n_shared=0, R=3, H=3, dtype=bm.BM_BF16, flags=0)
+    seen = set()
+    for M_ref, alphas in ((M1, (0.9, 0.6)), (M2, (0.75, 0.5))):
+        M = to_device(M_ref)
+        for a in alphas:
+            a = np.float32(a)
+            for a32 in (np.nextafter(a, np.float32(0)), a, np.nextafter(a, np.float32(1))):
+                print("eq5 boundary", float(a32), flush=True)
+                t_ref, l_ref, _ = oracle.build_buddy_lists(M_ref, float(a32), 3)
+                table = torch.full((4, 3), -9, dtype=torch.int32, device="cuda")
+                length = torch.full((4,), -9, dtype=torch.int32, device="cuda")
+                bm.bm_build_buddy_table(desc, M, float(a32), table, length)
+                torch.cuda.synchronize()
+                np.testing.assert_array_equal(table.cpu().numpy(), t_ref, err_msg=str(float(a32)))
+                np.testing.assert_array_equal(length.cpu().numpy(), l_ref)
+                seen.add((float(a), int(l_ref[0])))
+    # the list length does change across each boundary (the cases are not vacuous)
+    assert {(float(np.float32(0.9)), 2), (float(np.float32(0.9)), 3), (0.75, 2), (0.75, 3), (0.5, 1), (0.5, 2)} <= seen
+
+
 @pytest.mark.parametrize("name,over,T", [("c5_deepseek", dict(d=256, F=352), 1500),
                                          ("c4_qwen3", dict(d=256, F=384), 900)])
 def test_profile_then_serve(name, over, T):

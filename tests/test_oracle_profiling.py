@@ -60,6 +60,27 @@ def test_buddy_lists_hand_case():
     np.testing.assert_array_equal(t0[3], [-1, -1, -1]); assert l0[3] == 0
 
 
+def test_buddy_lists_exact_boundary_of_eq5():
+    # Eq. 5 when a prefix sum lands exactly on alpha.  Counts 6, 3, 1 of 10: the prefix {.6, .3} is .9.
+    M = np.array([[0, 3, 6, 1], [3, 0, 0, 0], [6, 0, 0, 2], [1, 0, 2, 0]], np.int64)
+    # alpha = 0.9 as an fp64 number: 0.9 * 10 rounds to 9.0 exactly, 9 >= 9.0 holds, the prefix of two is enough
+    np.testing.assert_array_equal(oracle.build_buddy_lists(M, 0.9, 3)[0][0], [2, 1, -1])
+    # alpha = 0.9 as the fp32 number a C caller passes is 0.89999998: still two entries; the next fp32 value
+    # up, 0.90000004, is past the prefix sum and needs the third
+    a32 = np.float32(0.9)
+    assert float(a32) < 0.9 < float(np.nextafter(a32, np.float32(1)))
+    np.testing.assert_array_equal(oracle.build_buddy_lists(M, float(a32), 3)[0][0], [2, 1, -1])
+    np.testing.assert_array_equal(oracle.build_buddy_lists(M, float(np.nextafter(a32, np.float32(1))), 3)[0][0], [2, 1, 3])
+    # and just past 0.9 in fp64
+    np.testing.assert_array_equal(oracle.build_buddy_lists(M, float(np.nextafter(0.9, 1.0)), 3)[0][0], [2, 1, 3])
+    # a boundary every format represents exactly: counts 2, 1, 1 of 4 and alpha = 0.75 (prefix {.5, .25})
+    M2 = np.array([[0, 2, 1, 1], [2, 0, 0, 0], [1, 0, 0, 0], [1, 0, 0, 0]], np.int64)
+    np.testing.assert_array_equal(oracle.build_buddy_lists(M2, 0.75, 3)[0][0], [1, 2, -1])       # ">=" includes equality
+    np.testing.assert_array_equal(oracle.build_buddy_lists(M2, 0.5, 3)[0][0], [1, -1, -1])
+    np.testing.assert_array_equal(oracle.build_buddy_lists(M2, float(np.nextafter(np.float32(0.75), np.float32(1))), 3)[0][0],
+                                  [1, 2, 3])
+
+
 def test_buddy_lists_against_numpy_ranking():
     ids = _ids(5, 3000, 32, 6)
     _, M = oracle.coactivation(ids, 32)

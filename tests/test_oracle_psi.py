@@ -1,5 +1,6 @@
 """Pins for the oracle's token-aware buddy priority (Section 3.1, Eq. 3 with kappa = 0).  CPU only."""
 import numpy as np
+import pytest
 
 import oracle
 from tests.test_oracle_remap import _random_problem
@@ -84,3 +85,61 @@ def test_gates_still_apply():
     np.testing.assert_array_equal(got[0], none[0])
     got = oracle.buddy_remap_psi(ids, res, table, q, zhat, 2.0, w=w, beta=0.0)
     np.testing.assert_array_equal(got[0], none[0])
+
+
+def _layer_case(T=48, seed=4):
+    import workloads
+    from workloads.harness import HostLayer
+    h = HostLayer(workloads.scaled("c1_tiny"), T)
+    g = np.random.default_rng(seed)
+    q = -np.sort(-g.dirichlet(np.ones(h.spec.R), size=h.spec.E), axis=1)
+    return h, q
+
+
+@pytest.mark.parametrize("unique", [False, True])
+@pytest.mark.parametrize("gates", [dict(), dict(rho=1), dict(tau=0.55)])
+def test_layer_with_token_aware_priority_equals_stages(unique, gates):
+    # the layer wrapper == routing -> softmax over ALL experts as z-hat -> Eq. 3 substitution -> experts,
+    # chained by hand from the separately pinned stages (Section 3 "Notation", Section 3.1 Eq. 3)
+    h, q = _layer_case()
+    f, K, eta = h.f32, h.spec.K, 40.0
+    out = oracle.moe_forward(f(h.x), f(h.w_router), h.bias, f(h.wg), f(h.wu), f(h.wd), h.mask, h.table, K,
+                             H=3, unique=unique, eta=eta, q=q, **gates)
+    z = oracle.router_logits(f(h.x), f(h.w_router), h.bias)
+    ids, w = oracle.topk_gates(z, K)
+    zhat = oracle.softmax_all(z)
+    ids2, w2, st, margin = oracle.buddy_remap_psi(ids, h.mask, h.table, q, zhat, eta, w=w, H=3, unique=unique, **gates)
+    y = oracle.experts_combine(f(h.x), ids2, w2, f(h.wg), f(h.wu), f(h.wd))
+    np.testing.assert_array_equal(out["ids"], ids)
+    np.testing.assert_array_equal(out["ids_remapped"], ids2)
+    np.testing.assert_array_equal(out["w"], w2)
+    np.testing.assert_array_equal(out["y"], y)
+    np.testing.assert_array_equal(out["margin"], margin)
+    assert out["stats"] == st and st["n_substituted"] > 0
+    if not gates:
+        # the case discriminates: raw logits as z-hat, or eta = 0 (the table order), choose differently
+        raw = oracle.buddy_remap_psi(ids, h.mask, h.table, q, z, eta, w=w, H=3, unique=unique)[0]
+        assert (raw != ids2).any()
+        plain = oracle.buddy_remap(ids, h.mask, h.table, H=3, unique=unique)[0]
+        assert (plain != ids2).any()
+
+
+def test_layer_with_token_aware_priority_shared_experts_and_bias():
+    # every pointer of the long argument list lands where it should: shared experts, bias, a q that is not
+    # row-constant, no renormalisation
+    import workloads
+    from workloads.harness import HostLayer
+    h = HostLayer(workloads.scaled("c5_deepseek", d=32, F=64), 40)
+    f, K = h.f32, h.spec.K
+    g = np.random.default_rng(2)
+    q = -np.sort(-g.dirichlet(np.ones(h.spec.R), size=h.spec.E), axis=1)
+    out = oracle.moe_forward(f(h.x), f(h.w_router), h.bias, f(h.wg), f(h.wu), f(h.wd), h.mask, h.table, K,
+                             renorm=False, unique=True, eta=25.0, q=q, ws_gate=f(h.sg), ws_up=f(h.su), ws_down=f(h.sd))
+    z = oracle.router_logits(f(h.x), f(h.w_router), h.bias)
+    ids, w = oracle.topk_gates(z, K, renorm=False)
+    ids2, w2, st, _ = oracle.buddy_remap_psi(ids, h.mask, h.table, q, oracle.softmax_all(z), 25.0, w=w, unique=True)
+    y = oracle.experts_combine(f(h.x), ids2, w2, f(h.wg), f(h.wu), f(h.wd), f(h.sg), f(h.su), f(h.sd))
+    np.testing.assert_array_equal(out["ids_remapped"], ids2)
+    np.testing.assert_array_equal(out["w"], w2)
+    np.testing.assert_array_equal(out["y"], y)
+    assert out["stats"] == st and st["n_substituted"] > 0 and st["n_dropped"] > 0

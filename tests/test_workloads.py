@@ -87,3 +87,18 @@ def test_c5_drops_some_assignments():
     ids, w = oracle.route_topk(lay.as_f32(x), lay.as_f32(lay.w_router), lay.router_bias, spec.K)
     _, _, st = oracle.buddy_remap(ids, lay.resident_mask, lay.buddy_table, H=spec.H)
     assert st["n_dropped"] > 0 and st["n_substituted"] > st["n_dropped"]
+
+
+@pytest.mark.parametrize("name", list(CONFIGS))
+def test_fp64_topk_definition_gives_the_oracles_ids(name):
+    # The oracle takes its top-k decision on logits rounded to fp32.  On the generated inputs (full hidden
+    # size, the token counts the configs are quoted on, capped at 2048) the plain definition - the K largest
+    # fp64 logits in descending order - selects the same ids in the same slots, so the rounding is immaterial.
+    spec = CONFIGS[name].replace(F=32)
+    lay = workloads.get_layer(spec)
+    for T in sorted({min(t, 2048) for t in spec.T}):
+        x, _ = lay.tokens(T)
+        z = oracle.router_logits(lay.as_f32(x), lay.as_f32(lay.w_router), lay.router_bias)
+        ids, _ = oracle.topk_gates(z, spec.K)
+        want = np.argsort(-z, axis=1, kind="stable")[:, : spec.K]
+        np.testing.assert_array_equal(ids, want)
