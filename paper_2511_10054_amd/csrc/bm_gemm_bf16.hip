@@ -875,10 +875,12 @@ int launch_gateup_bf16(const GemmParams &p, hipStream_t st) {
     return launch_status(__func__);
 }
 
+// the reduction-split tail (see TailSplit) pays only for long reductions
+bool down_split_tail(int Kd) { return Kd / 64 >= 64; }
+
 int launch_down_bf16(const GemmParams &p, hipStream_t st) {
     if (k64_ok(p)) {
-        // the reduction-split tail (see TailSplit) pays only for long reductions
-        if (p.splitk != nullptr && p.Kd / 64 >= 64) {
+        if (p.splitk != nullptr && down_split_tail(p.Kd)) {
             GemmParams q = p;
             q.splitk_stride = persistent_grid(p, false) >> 3;
             hipLaunchKernelGGL((BM_K64_DOWN_SPLIT), dim3(persistent_grid(p, false)), dim3(256), 0, st, q);

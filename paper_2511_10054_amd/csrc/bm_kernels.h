@@ -133,6 +133,7 @@ bool grouping_small(long long assignments, int E);   // launch_grouping takes th
 // bf16 MFMA grouped projections (row tile height p.BM, which the row-tile table was built for)
 int launch_gateup_bf16(const GemmParams &p, hipStream_t st);   // c = silu(a b0^T) * (a b1^T), bf16
 int launch_down_bf16(const GemmParams &p, hipStream_t st);     // c = a b0^T, bf16
+bool down_split_tail(int Kd);   // the down projection of this reduction width may use p.splitk (its split tail)
 
 // fp32 FMA projections (one workgroup per row)
 int launch_gateup_f32(const GemmParams &p, int max_rows, hipStream_t st);
