@@ -236,6 +236,25 @@ int bm_moe_forward(const bm_layer_desc *desc, const void *x, const bm_weights *w
                    void *workspace, size_t workspace_bytes, const bm_debug_out *dbg,
                    void *stream);
 
+/* bm_moe_forward for callers that cannot allocate device memory or carry a
+ * workspace: code running under HIP graph capture, tight serving loops, harnesses
+ * that forbid hipMalloc.  Same arguments, kernels and results as bm_moe_forward,
+ * but the scratch is a BM_STATIC_WORKSPACE_BYTES array built into the library's
+ * device code (each GPU the library is loaded on holds one copy until the process
+ * ends); the call allocates and frees nothing.  A desc whose
+ * bm_workspace_bytes exceeds BM_STATIC_WORKSPACE_BYTES is refused with
+ * BM_ERR_WORKSPACE before anything is launched (decode-sized batches of the large
+ * layers and small prefill batches fit; use bm_moe_forward beyond that).  Every
+ * call on a GPU shares that GPU's array: calls that overlap on one GPU (different
+ * streams or threads) race - serialise them.  Nothing in the array has to survive
+ * between calls and every kernel writes what it later reads, so no clearing is
+ * needed and none is done.  The array's address is looked up once per device, on
+ * the first call with that device current (BM_ERR_HIP if the lookup fails). */
+#define BM_STATIC_WORKSPACE_BYTES (32u << 20)
+int bm_moe_forward_static(const bm_layer_desc *desc, const void *x, const bm_weights *weights,
+                          const uint64_t *residency_bitmap, const int32_t *buddy_table, void *y,
+                          const bm_debug_out *dbg, void *stream);
+
 /* One-time repacking of the expert weights for decode-sized batches (model
  * load time, not part of the forward pass).  The public layout above stays the
  * reference; the packed copy holds, for every block of 16 weight rows and every

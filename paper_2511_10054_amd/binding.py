@@ -70,6 +70,9 @@ def load_library() -> ctypes.CDLL:
         lib.bm_permute_by_expert.argtypes = [ctypes.POINTER(LayerDesc), vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
         lib.bm_moe_forward.argtypes = [ctypes.POINTER(LayerDesc), vp, ctypes.POINTER(Weights), vp, vp, vp, vp,
                                        ctypes.c_size_t, ctypes.POINTER(DebugOut), vp]
+        lib.bm_moe_forward_static.argtypes = [ctypes.POINTER(LayerDesc), vp, ctypes.POINTER(Weights), vp, vp, vp,
+                                              ctypes.POINTER(DebugOut), vp]
+        lib.bm_moe_forward_static.restype = i32
         lib.bm_stream_read.argtypes = [vp, ctypes.c_size_t, vp, vp]
         lib.bm_stream_read.restype = i32
         for f in (lib.bm_validate_tables, lib.bm_route_topk, lib.bm_buddy_remap, lib.bm_permute_by_expert,
@@ -151,16 +154,33 @@ def bm_moe_forward(desc: LayerDesc, x, weights: Weights, bitmap, table, y, works
                    stream: Optional[int] = None):
     """dbg: optional dict of device tensors keyed by bm_debug_out member names;
     the key "stage_events" takes a sequence of 5 hipEvent_t handles (ints)."""
-    d = None
-    if dbg:
-        d = DebugOut(**{k: _ptr(v) for k, v in dbg.items() if k != "stage_events"})
-        if dbg.get("stage_events") is not None:
-            d.stage_events = (ctypes.c_void_p * 5)(*dbg["stage_events"])
+    d = _debug_struct(dbg)
     _check(load_library().bm_moe_forward(ctypes.byref(desc), _ptr(x), ctypes.byref(weights), _ptr(bitmap),
                                          _ptr(table), _ptr(y), _ptr(workspace),
                                          workspace.numel() * workspace.element_size(),
                                          ctypes.byref(d) if d is not None else None,
                                          _stream() if stream is None else stream), "bm_moe_forward")
+
+
+def _debug_struct(dbg: Optional[dict]):
+    d = None
+    if dbg:
+        d = DebugOut(**{k: _ptr(v) for k, v in dbg.items() if k != "stage_events"})
+        if dbg.get("stage_events") is not None:
+            d.stage_events = (ctypes.c_void_p * 5)(*dbg["stage_events"])
+    return d
+
+
+BM_STATIC_WORKSPACE_BYTES = 32 << 20
+
+
+def bm_moe_forward_static(desc: LayerDesc, x, weights: Weights, bitmap, table, y, dbg: Optional[dict] = None,
+                          stream: Optional[int] = None):
+    """bm_moe_forward on the library's built-in scratch array: no workspace argument, nothing allocated."""
+    d = _debug_struct(dbg)
+    _check(load_library().bm_moe_forward_static(ctypes.byref(desc), _ptr(x), ctypes.byref(weights), _ptr(bitmap),
+                                                _ptr(table), _ptr(y), ctypes.byref(d) if d is not None else None,
+                                                _stream() if stream is None else stream), "bm_moe_forward_static")
 
 
 def make_weights(w_router, router_bias, w_gate, w_up, w_down, ws_gate=None, ws_up=None, ws_down=None,

@@ -1,8 +1,16 @@
 // C ABI of the library: argument checks, workspace carving, kernel sequencing.
-// Nothing here allocates, synchronises or keeps state between calls.
+// Nothing here allocates or synchronises; the only state kept between calls is the
+// per-device address of the built-in scratch array of bm_moe_forward_static.
 #include "bm_kernels.h"
 
+#include <atomic>
 #include <cstdio>
+#include <mutex>
+
+// Built-in workspace of bm_moe_forward_static: every device the library runs on holds its own copy
+// until the process ends.  Host code never uses this name as an address - it is a host-side stand-in;
+// the device address comes from hipGetSymbolAddress (static_scratch_ptr below).
+static __device__ __align__(256) unsigned char scratch[BM_STATIC_WORKSPACE_BYTES];
 
 namespace bm {
 int launch_status(const char *what) {
@@ -145,10 +153,25 @@ Layout make_layout(const bm_layer_desc *d) {
     L.h = take((size_t)L.rows_max * F * esz);
     L.o = take(use_skinny(d) ? (size_t)skinny_ksplit(d) * L.rows_max * d->d * 4 : (size_t)L.rows_max * d->d * esz);
     // fp32 partial tiles of the down projection's split tail: one 256 x 256 tile per workgroup of the launch
-    L.has_splitk = !use_skinny(d) && d->dtype == BM_BF16 && gemm_tile_rows(d) == 256;
+    L.has_splitk = !use_skinny(d) && d->dtype == BM_BF16 && gemm_tile_rows(d) == 256 && down_split_tail(d->F);
     L.splitk = take(L.has_splitk ? (size_t)256 * 256 * 256 * 4 : 0);
     L.total = off;
     return L;
+}
+
+// Argument checks of the whole-layer entry points (everything but the workspace).
+int check_moe_args(const bm_layer_desc *desc, const void *x, const bm_weights *wt, const uint64_t *residency_bitmap,
+                   const int32_t *buddy_table, const void *y) {
+    int rc = check_desc(desc, true);
+    if (rc) return rc;
+    rc = check_remap_desc(desc);
+    if (rc) return rc;
+    if (desc->T == 0) return BM_OK;
+    if (!x || !wt || !residency_bitmap || !y || (!buddy_table && desc->R > 0)) return BM_ERR_NULL;
+    if (!wt->w_router || !wt->w_gate || !wt->w_up || !wt->w_down) return BM_ERR_NULL;
+    if (desc->n_shared > 0 && (!wt->ws_gate || !wt->ws_up || !wt->ws_down)) return BM_ERR_NULL;
+    if ((desc->flags & BM_PSI_TOKEN) && !wt->buddy_q) return BM_ERR_NULL;
+    return BM_OK;
 }
 
 template <typename T>
@@ -168,6 +191,31 @@ __global__ void copy_ints_kernel(const int32_t *src, int32_t *dst, size_t n) {
 void copy_ints(const void *src, void *dst, size_t n, hipStream_t st) {
     if (n) hipLaunchKernelGGL(copy_ints_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st,
                               static_cast<const int32_t *>(src), static_cast<int32_t *>(dst), n);
+}
+
+// Device address of `scratch` on the current device, looked up once per device.
+constexpr int MAX_DEVICES = 64;
+std::atomic<void *> g_scratch_ptr[MAX_DEVICES];
+std::mutex g_scratch_mutex;
+
+int static_scratch_ptr(void **out) {
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= MAX_DEVICES) return BM_ERR_HIP;
+    void *p = g_scratch_ptr[dev].load(std::memory_order_acquire);
+    if (!p) {
+        std::lock_guard<std::mutex> lock(g_scratch_mutex);
+        p = g_scratch_ptr[dev].load(std::memory_order_relaxed);
+        if (!p) {
+            const hipError_t e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+            if (e != hipSuccess || !p) {
+                std::fprintf(stderr, "buddymoe: hipGetSymbolAddress(scratch): %s\n", hipGetErrorString(e));
+                return BM_ERR_HIP;
+            }
+            g_scratch_ptr[dev].store(p, std::memory_order_release);
+        }
+    }
+    *out = p;
+    return BM_OK;
 }
 
 }  // namespace
@@ -353,18 +401,25 @@ int bm_permute_by_expert(const bm_layer_desc *desc, const int32_t *ids_remapped,
     return err ? BM_ERR_HIP : BM_OK;
 }
 
+int bm_moe_forward_static(const bm_layer_desc *desc, const void *x, const bm_weights *wt,
+                          const uint64_t *residency_bitmap, const int32_t *buddy_table, void *y,
+                          const bm_debug_out *dbg, void *stream) {
+    int rc = check_moe_args(desc, x, wt, residency_bitmap, buddy_table, y);
+    if (rc) return rc;
+    if (desc->T == 0) return BM_OK;
+    if (make_layout(desc).total > (size_t)BM_STATIC_WORKSPACE_BYTES) return BM_ERR_WORKSPACE;
+    void *ws = nullptr;
+    rc = static_scratch_ptr(&ws);
+    if (rc) return rc;
+    return bm_moe_forward(desc, x, wt, residency_bitmap, buddy_table, y, ws, BM_STATIC_WORKSPACE_BYTES, dbg, stream);
+}
+
 int bm_moe_forward(const bm_layer_desc *desc, const void *x, const bm_weights *wt,
                    const uint64_t *residency_bitmap, const int32_t *buddy_table, void *y, void *workspace,
                    size_t workspace_bytes, const bm_debug_out *dbg, void *stream) {
-    int rc = check_desc(desc, true);
-    if (rc) return rc;
-    rc = check_remap_desc(desc);
+    int rc = check_moe_args(desc, x, wt, residency_bitmap, buddy_table, y);
     if (rc) return rc;
     if (desc->T == 0) return BM_OK;
-    if (!x || !wt || !residency_bitmap || !y || (!buddy_table && desc->R > 0)) return BM_ERR_NULL;
-    if (!wt->w_router || !wt->w_gate || !wt->w_up || !wt->w_down) return BM_ERR_NULL;
-    if (desc->n_shared > 0 && (!wt->ws_gate || !wt->ws_up || !wt->ws_down)) return BM_ERR_NULL;
-    if ((desc->flags & BM_PSI_TOKEN) && !wt->buddy_q) return BM_ERR_NULL;
     Layout L;
     rc = check_ws(desc, workspace, workspace_bytes, L);
     if (rc) return rc;

@@ -24,7 +24,7 @@ def test_library_exports_every_declared_symbol():
     names = set(re.findall(r"\b(bm_[a-z_]+)\s*\(", header))
     assert {"bm_route_topk", "bm_buddy_remap", "bm_permute_by_expert", "bm_moe_forward",
             "bm_workspace_bytes", "bm_validate_tables", "bm_strerror", "bm_coactivation_accumulate",
-            "bm_build_buddy_table"} <= names
+            "bm_build_buddy_table", "bm_moe_forward_static"} <= names
     lib = bm.load_library()
     for n in names:
         assert hasattr(lib, n), n
@@ -136,6 +136,13 @@ def test_host_side_argument_errors_launch_nothing():
     assert lib.bm_moe_forward(ctypes.byref(d), one, None, one, one, one, one, 1 << 30, None, None) == -1
     assert lib.bm_moe_forward(ctypes.byref(_desc(n_shared=9)), one, ctypes.byref(w), one, one, one, one, 1 << 30, None, None) == -2
     assert lib.bm_moe_forward(ctypes.byref(_desc(T=0)), None, None, None, None, None, None, 0, None, None) == 0
+    # the entry point on the built-in scratch array: same checks, and a layer whose scratch does not fit
+    assert lib.bm_moe_forward_static(ctypes.byref(d), one, None, one, one, one, None, None) == -1
+    assert lib.bm_moe_forward_static(ctypes.byref(_desc(n_shared=9)), one, ctypes.byref(w), one, one, one, None, None) == -2
+    assert lib.bm_moe_forward_static(ctypes.byref(_desc(T=0)), None, None, None, None, None, None, None) == 0
+    big = _desc(T=4096, d=4096, E=8, F=14336, K=2, R=7, H=7, dtype=bm.BM_BF16)
+    assert bm.bm_workspace_bytes(big) > bm.BM_STATIC_WORKSPACE_BYTES
+    assert lib.bm_moe_forward_static(ctypes.byref(big), one, ctypes.byref(w), one, one, one, None, None) == -4
     psi = _desc(flags=bm.BM_PSI_TOKEN, psi_eta=1.0)
     assert lib.bm_moe_forward(ctypes.byref(psi), one, ctypes.byref(w), one, one, one, one, 1 << 30, None, None) == -1  # no q
     assert lib.bm_buddy_remap(ctypes.byref(psi), one, one, one, one, one, None, None) == -2
