@@ -285,17 +285,6 @@ size_t bm_workspace_bytes(const bm_layer_desc *desc);
 int bm_validate_tables(const bm_layer_desc *desc, const uint64_t *bitmap_host,
                        const int32_t *table_host);
 
-/* Measurement aid, not part of the layer: reads `bytes` bytes (a multiple of 16,
- * device memory, 16-byte aligned) once with the access pattern of the decode
- * weight stream - every wave instruction a contiguous kilobyte, eight in flight
- * per wave, non-temporal - and discards them.  Its throughput is the HBM read
- * rate a kernel can reach on this device, the practical ceiling beside the
- * datasheet figure the roofline fractions are quoted against.  sink: one
- * device uint32 the kernel may write (it keeps the loads alive).  bytes = 0
- * does nothing (src may then be NULL).
- * BM_ERR_NULL, BM_ERR_SHAPE (bytes not a multiple of 16), BM_ERR_HIP. */
-int bm_stream_read(const void *src, size_t bytes, uint32_t *sink, void *stream);
-
 /* Static string for a bm_status. */
 const char *bm_strerror(int status);
 

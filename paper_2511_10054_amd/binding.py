@@ -1,4 +1,4 @@
-"""ctypes binding of include/buddymoe.h.  Argument marshalling only."""
+"""ctypes binding of include/buddymoe.h (and the bench aid of include/buddymoe_bench.h).  Argument marshalling only."""
 from __future__ import annotations
 
 import ctypes
@@ -190,7 +190,7 @@ def make_weights(w_router, router_bias, w_gate, w_up, w_down, ws_gate=None, ws_u
 
 
 def bm_stream_read(src, sink, stream: Optional[int] = None):
-    """Measurement aid: one streaming read of the whole tensor `src` (see include/buddymoe.h)."""
+    """Measurement aid: one streaming read of the whole tensor `src` (see include/buddymoe_bench.h)."""
     _check(load_library().bm_stream_read(_ptr(src), src.numel() * src.element_size(), _ptr(sink),
                                          _stream() if stream is None else stream), "bm_stream_read")
 

@@ -2,6 +2,7 @@
 // translation units.  Parameter blocks are plain structs passed by value.
 #pragma once
 #include "../../include/buddymoe.h"
+#include "../../include/buddymoe_bench.h"
 #include "bm_device.h"
 
 namespace bm {

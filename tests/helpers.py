@@ -1,4 +1,4 @@
-from workloads.harness import DeviceLayer, HostLayer, err_metric, to_device  # noqa: F401
+from workloads.harness import DeviceLayer, HostLayer, edge_tokens, err_metric, err_unfloored, to_device  # noqa: F401
 
 import numpy as np
 

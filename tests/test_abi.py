@@ -20,8 +20,11 @@ def _desc(**kw):
 
 
 def test_library_exports_every_declared_symbol():
-    header = open(os.path.join(ROOT, "include", "buddymoe.h")).read()
+    inc = os.path.join(ROOT, "include")
+    assert sorted(os.listdir(inc)) == ["buddymoe.h", "buddymoe_bench.h"]
+    header = "".join(open(os.path.join(inc, f)).read() for f in os.listdir(inc))
     names = set(re.findall(r"\b(bm_[a-z_]+)\s*\(", header))
+    assert "bm_stream_read" not in open(os.path.join(inc, "buddymoe.h")).read()      # a bench aid, not the layer's ABI
     assert {"bm_route_topk", "bm_buddy_remap", "bm_permute_by_expert", "bm_moe_forward",
             "bm_workspace_bytes", "bm_validate_tables", "bm_strerror", "bm_coactivation_accumulate",
             "bm_build_buddy_table", "bm_moe_forward_static"} <= names

@@ -6,7 +6,7 @@ import pytest
 
 import oracle
 import workloads
-from helpers import DeviceLayer, HostLayer, err_metric, safe_threshold, tae_margin
+from helpers import DeviceLayer, HostLayer, edge_tokens, err_metric, err_unfloored, safe_threshold, tae_margin
 
 pytestmark = pytest.mark.gpu
 
@@ -50,12 +50,15 @@ def _check(name, T, n_sample, unique=False, pack=None, **gates):
     np.testing.assert_array_equal(out["perm"], perm_ref)
     np.testing.assert_array_equal(out["inv_perm"], inv_ref)
     assert host.mask[ids2_ref[ids2_ref >= 0]].all()
-    # outputs on a seeded sample that touches every expert in use
+    # outputs on a seeded sample of tokens plus the tokens whose rows sit at tile edges: the first and the
+    # last row of every expert group and one row from each 128-row half of every 256-row tile
     g = np.random.default_rng(1234 + T)
     rows = g.permutation(T)[: min(T, n_sample)]
-    used = np.unique(ids2_ref[ids2_ref >= 0])
-    extra = [int(np.nonzero((ids2_ref == e).any(1))[0][0]) for e in used]
-    rows = np.unique(np.concatenate([rows, np.array(extra, dtype=rows.dtype)]))
+    edges = edge_tokens(off_ref, perm_ref, spec.K, cap=max(2 * n_sample, 2 * int((np.diff(off_ref) > 0).sum())), seed=T)
+    rows = np.unique(np.concatenate([rows, edges]))
+    for e in np.unique(ids2_ref[ids2_ref >= 0]):                 # the sample does hold every group's two end rows
+        for pos in (off_ref[e], off_ref[e + 1] - 1):
+            assert perm_ref[pos] // spec.K in rows
     if gates:      # the distribution gate sees the whole batch: feed the sampled tokens' final ids and weights
         f = host.f32
         y_ref = oracle.experts_combine(f(host.x)[rows], ids2_ref[rows], w2_ref[rows], f(host.wg), f(host.wu),
@@ -65,7 +68,8 @@ def _check(name, T, n_sample, unique=False, pack=None, **gates):
         np.testing.assert_array_equal(ref["ids_remapped"], ids2_ref[rows])
         y_ref = ref["y"]
     err = err_metric(out["y"][rows], y_ref)
-    print(f"   sample {len(rows)} tokens, err {err:.3e}, stats {st}", flush=True)
+    print(f"   sample {len(rows)} tokens ({len(edges)} at group / tile edges), err {err:.3e}, "
+          f"unfloored elementwise {err_unfloored(out['y'][rows], y_ref):.3e}, stats {st}", flush=True)
     assert np.isfinite(out["y"]).all()
     assert err <= 2e-2, err
 

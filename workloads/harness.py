@@ -16,6 +16,42 @@ def err_metric(y, ref):
     return float(np.max(np.abs(y - ref) / np.maximum(np.abs(ref), rms)))
 
 
+def err_unfloored(y, ref):
+    """max_i |y_i - ref_i| / |ref_i| over the entries with ref_i != 0: the plain elementwise relative error
+    (dominated by outputs that cancel to almost nothing); reported beside err_metric, not bounded."""
+    y = np.asarray(y, np.float64)
+    ref = np.asarray(ref, np.float64)
+    nz = ref != 0
+    return float(np.max(np.abs(y - ref)[nz] / np.abs(ref)[nz])) if nz.any() else 0.0
+
+
+def edge_tokens(offsets, perm, K, tile_rows=256, cap=None, seed=0):
+    """Tokens whose rows sit where tiling mistakes hide, from the grouping (offsets [E+1], perm): the first and
+    last row of every expert group, and one seeded row from each 128-row half of every `tile_rows`-row tile of
+    every group (the second half of a group's last tile may be partial or empty).  With `cap`, the tile-half
+    rows are thinned to keep about `cap` tokens; the group-edge tokens always stay."""
+    offsets = np.asarray(offsets, np.int64)
+    perm = np.asarray(perm, np.int64)
+    g = np.random.default_rng(seed)
+    edge, inner = [], []
+    for e in range(len(offsets) - 1):
+        lo, hi = int(offsets[e]), int(offsets[e + 1])
+        if hi <= lo:
+            continue
+        edge += [lo, hi - 1]
+        for t0 in range(lo, hi, tile_rows):
+            for h0 in (t0, t0 + 128):
+                h1 = min(h0 + 128, hi, t0 + tile_rows)
+                if h1 > h0:
+                    inner.append(int(g.integers(h0, h1)))
+    edge = np.unique(perm[np.array(edge, np.int64)] // K) if edge else np.zeros(0, np.int64)
+    inner = np.unique(perm[np.array(inner, np.int64)] // K) if inner else np.zeros(0, np.int64)
+    inner = np.setdiff1d(inner, edge)
+    if cap is not None and len(edge) + len(inner) > cap:
+        inner = g.permutation(inner)[: max(cap - len(edge), 0)]
+    return np.unique(np.concatenate([edge, inner])).astype(np.int64)
+
+
 class HostLayer:
     """Host-side view of one workload: storage arrays and fp32 views for the oracle."""
 
