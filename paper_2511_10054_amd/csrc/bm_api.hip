@@ -37,6 +37,9 @@ constexpr int SKINNY_KSPLIT = 8;
 // offsets): even with groups of a few dozen rows its padded tiles beat the 128-row kernel (Mixtral-shaped
 // layer at 128 tokens 0.47 against 0.69 ms, Qwen3-shaped at 1024 tokens 0.22 against 0.30 ms).  Otherwise 256
 // rows when the average routed group is large, else 128.
+#ifndef BM_TILE128_AVG_ROWS
+#define BM_TILE128_AVG_ROWS 192   // routed rows per expert (averaged over all E) below which the k-step-64 kernel runs 128-row tiles
+#endif
 int gemm_tile_rows(const bm_layer_desc *d) {
     const unsigned long long lim = 1ull << 32;
     const unsigned long long rows = (unsigned long long)d->T * (d->K + (d->n_shared > 0 ? d->n_shared : 0)) +
@@ -44,7 +47,7 @@ int gemm_tile_rows(const bm_layer_desc *d) {
     const bool k64 = d->d % 64 == 0 && d->F % 64 == 0 && d->d >= 256 && d->F >= 256 &&
                      (unsigned long long)d->T * d->d * 2 < lim && rows * d->F * 2 < lim &&
                      (unsigned long long)d->F * d->d * 2 < lim;
-    if (k64) return 256;
+    if (k64) return ((long long)d->T * d->K < (long long)BM_TILE128_AVG_ROWS * d->E) ? 128 : 256;
     return ((long long)d->T * d->K / d->E >= 128) ? 256 : 128;
 }
 

@@ -444,8 +444,17 @@ constexpr int SPLIT_TILE_FLOATS = 256 * 256;
 
 // SPLIT: compile the reduction-split tail in (kept out of the other instantiations: its write-out of raw
 // accumulators costs registers that short tiles cannot afford to spill around)
-template <bool DUAL, bool SPLIT>
+// MI: 16-row blocks per wave.  MI = 8 is the 256-row tile described above; MI = 4 is a 128-row tile on the
+// same ring (the activation part fills half of its slot: four loads per wave and k-step instead of eight,
+// 32 MFMAs per k slice instead of 64, the weight part unchanged), for layers whose groups are mostly
+// smaller than a 256-row tile.
+template <bool DUAL, bool SPLIT, int MI = 8>
 __global__ void __launch_bounds__(256) grouped_gemm256_k64w_bf16_kernel(GemmParams p) {
+    static_assert(MI == 8 || MI == 4, "tile height is 256 or 128 rows");
+    static_assert(!SPLIT || MI == 8, "the reduction-split tail exists for 256-row tiles only");
+    constexpr int TM = MI * 32;                            // rows per tile
+    constexpr int NM = MI * 8;                             // MFMAs per k slice of 32
+    constexpr int NR = MI + 8;                             // fragment reads per k slice
     __shared__ __attribute__((aligned(1024))) uint16_t smem[5 * P_PART];         // 160 KB: the whole LDS
     const int tid = threadIdx.x, lane = tid & 63;
     // the wave index as a scalar: everything derived from it (LDS targets of the loads, tile halves) then
@@ -501,12 +510,12 @@ __global__ void __launch_bounds__(256) grouped_gemm256_k64w_bf16_kernel(GemmPara
 #pragma unroll
     for (int s = 0; s < 2; ++s) {
         const int pc = ((4 * s + quad) ^ ((r16 >> 1) & 7)) << 3;
-        fa_off[s] = (wm * 128 + r16) * 64 + pc;
+        fa_off[s] = (wm * (MI * 16) + r16) * 64 + pc;
         fb_off[s] = (DUAL ? (wn * 64 + r16) : (wn * 128 + r16)) * 64 + pc;
     }
 
-    f32x4 acc[8][8];                                   // 16 x 16 tiles: rows i*16.., columns j*16..
-    bf16x8 f0a[8], f0b[8], f1a[8], f1b[8];
+    f32x4 acc[MI][8];                                  // 16 x 16 tiles: rows i*16.., columns j*16..
+    bf16x8 f0a[MI], f0b[8], f1a[MI], f1b[8];
     // Load addresses are (uniform base + k offset) + a 32-bit byte offset per lane, so that the k advance
     // is scalar arithmetic and a load needs no vector address computation.
     uint32_t oa[8], ob[8];
@@ -534,9 +543,11 @@ __global__ void __launch_bounds__(256) grouped_gemm256_k64w_bf16_kernel(GemmPara
         _Pragma("unroll") for (int j = 0; j < 8; ++j) {                                            \
             const int r_ = 8 * (4 * j + wave) + (lane >> 3);                                       \
             const int piece_ = (lane & 7) ^ ((r_ >> 1) & 7);                                       \
-            const int pos_ = min(row0 + r_, row_end - 1);                                          \
-            const int src_ = p.row_map ? p.row_map[pos_] : pos_;                                   \
-            oa[j] = ((uint32_t)src_ * (uint32_t)Kd + piece_ * 8) * 2u;                             \
+            if (j < MI) {                                                                          \
+                const int pos_ = min(row0 + r_, row_end - 1);                                      \
+                const int src_ = p.row_map ? p.row_map[pos_] : pos_;                               \
+                oa[j] = ((uint32_t)src_ * (uint32_t)Kd + piece_ * 8) * 2u;                         \
+            }                                                                                      \
             /* DUAL: rows 0-127 of the part are W_gate rows (loads 0-3), rows 128-255 W_up rows (4-7) */ \
             const int n_ = DUAL ? min(n0 + (r_ & 127), N - 1) : min(n0 + r_, N - 1);               \
             ob[j] = ((uint32_t)n_ * (uint32_t)Kd + piece_ * 8) * 2u;                               \
@@ -553,14 +564,14 @@ __global__ void __launch_bounds__(256) grouped_gemm256_k64w_bf16_kernel(GemmPara
 #define BM_PROLOGUE()                                                                              \
     {                                                                                              \
         _Pragma("unroll") for (int j = 0; j < 8; ++j) BM_DMA_B(0, kbeg, j);                        \
-        _Pragma("unroll") for (int j = 0; j < 8; ++j) BM_DMA_A(1, kbeg, j);                        \
+        _Pragma("unroll") for (int j = 0; j < MI; ++j) BM_DMA_A(1, kbeg, j);                       \
         _Pragma("unroll") for (int j = 0; j < 8; ++j) BM_DMA_B(2, kbeg + 1, j);                    \
-        _Pragma("unroll") for (int j = 0; j < 8; ++j) BM_DMA_A(3, kbeg + 1, j);                    \
+        _Pragma("unroll") for (int j = 0; j < MI; ++j) BM_DMA_A(3, kbeg + 1, j);                   \
     }
 #define BM_LD(ptr_) as_bf16x8(*reinterpret_cast<const u32x4 *>(ptr_))
 // weight fragment j of 8: 16 weight rows; DUAL: fragments 0-3 are W_gate rows, 4-7 the same rows of W_up
 #define BM_BOFF(j_) (DUAL ? (((j_) >> 2) * 8192 + ((j_) & 3) * 1024) : (j_) * 1024)
-// fragment read d_ of 16, in the order the MFMAs need them: a0 b0..b7 a1..a7
+// fragment read d_ of NR, in the order the MFMAs need them: a0 b0..b7 a1..a(MI-1)
 #define BM_RD(d_, fa_, fb_, sa_, sb_)                                                              \
     {                                                                                              \
         if ((d_) == 0) fa_[0] = BM_LD(sa_);                                                        \
@@ -593,8 +604,8 @@ __global__ void __launch_bounds__(256) grouped_gemm256_k64w_bf16_kernel(GemmPara
     // tile starts with its operands in LDS and nothing is drained in between.
     int sB = 0, sA = 1, sAp = 4;                       // slots of B(kt), A(kt), and of A(kt-1) (free)
     // first tile: B(0) and A(0) have landed - vector memory operations complete in issue order and only
-    // the 16 loads of B(1), A(1) are younger
-    BM_WAIT_VMCNT(16);
+    // the loads of B(1), A(1) are younger
+    BM_WAIT_VMCNT(8 + MI);
     for (;;) {
         const int t_row0 = row0, t_row_end = row_end, t_n0 = n0;    // the tile being multiplied
         const bool t_partial = partial;
@@ -622,7 +633,7 @@ __global__ void __launch_bounds__(256) grouped_gemm256_k64w_bf16_kernel(GemmPara
 #define BM_TILE_LOOP(COMPUTE_)                                                                                        \
     {                                                                                                                 \
         if (COMPUTE_) {                                                                                               \
-            _Pragma("unroll") for (int i = 0; i < 8; ++i)                                                             \
+            _Pragma("unroll") for (int i = 0; i < MI; ++i)                                                            \
                 _Pragma("unroll") for (int j = 0; j < 8; ++j)                                                         \
                     _Pragma("unroll") for (int v = 0; v < 4; ++v) acc[i][j][v] = 0.0f;                                \
         }                                                                                                             \
@@ -631,7 +642,7 @@ __global__ void __launch_bounds__(256) grouped_gemm256_k64w_bf16_kernel(GemmPara
             const uint16_t *sa_ = smem + sA * P_PART + fa_off[0];                                                     \
             const uint16_t *sb_ = smem + sB * P_PART + fb_off[0];                                                     \
         _Pragma("unroll")                                                                                             \
-            for (int d = 0; (COMPUTE_) && d < 16; ++d) BM_RD(d, f0a, f0b, sa_, sb_)                                   \
+            for (int d = 0; (COMPUTE_) && d < NR; ++d) BM_RD(d, f0a, f0b, sa_, sb_)                                   \
         }                                                                                                             \
         for (int kt = t_kbeg; kt < t_kend; ++kt) {                                                                    \
             const int kl = more ? kbeg + (kt + 2 - t_kend) : kt + 2;                                                  \
@@ -639,10 +650,10 @@ __global__ void __launch_bounds__(256) grouped_gemm256_k64w_bf16_kernel(GemmPara
                 const uint16_t *sa_ = smem + sA * P_PART + fa_off[1];                                                 \
                 const uint16_t *sb_ = smem + sB * P_PART + fb_off[1];                                                 \
         _Pragma("unroll")                                                                                             \
-                for (int m = 0; m < 64; ++m) {                                                                        \
+                for (int m = 0; m < NM; ++m) {                                                                        \
                     if (COMPUTE_) BM_MFMA1(m, f0a, f0b);                                                              \
-                    if ((COMPUTE_) && m < 32 && (m & 1) == 0) BM_RD(m >> 1, f1a, f1b, sa_, sb_)                       \
-                    if ((m & 7) == 5) BM_DMA_B(sAp, kl, m >> 3);                                                      \
+                    if ((COMPUTE_) && m < 2 * NR && (m & 1) == 0) BM_RD(m >> 1, f1a, f1b, sa_, sb_)                   \
+                    if (MI == 8 ? (m & 7) == 5 : (m & 3) == 1) BM_DMA_B(sAp, kl, MI == 8 ? m >> 3 : m >> 2);          \
                     __builtin_amdgcn_sched_barrier(0);                                                                \
                 }                                                                                                     \
             }                                                                                                         \
@@ -653,10 +664,10 @@ __global__ void __launch_bounds__(256) grouped_gemm256_k64w_bf16_kernel(GemmPara
                 const uint16_t *sa_ = smem + sAn * P_PART + fa_off[0];                                                \
                 const uint16_t *sb_ = smem + sBn * P_PART + fb_off[0];                                                \
         _Pragma("unroll")                                                                                             \
-                for (int m = 0; m < 64; ++m) {                                                                        \
+                for (int m = 0; m < NM; ++m) {                                                                        \
                     if (COMPUTE_) BM_MFMA1(m, f1a, f1b);                                                              \
                     if ((m & 7) == 1) BM_DMA_A(sB, kl, m >> 3);                                                       \
-                    if ((COMPUTE_) && m < 32 && (m & 1) == 0) BM_RD(m >> 1, f0a, f0b, sa_, sb_)                       \
+                    if ((COMPUTE_) && m < 2 * NR && (m & 1) == 0) BM_RD(m >> 1, f0a, f0b, sa_, sb_)                   \
                     __builtin_amdgcn_sched_barrier(0);                                                                \
                 }                                                                                                     \
             }                                                                                                         \
@@ -675,7 +686,7 @@ __global__ void __launch_bounds__(256) grouped_gemm256_k64w_bf16_kernel(GemmPara
         // against its power limit, and what the idle matrix cores do not draw lets the others clock higher
         // (Qwen3-shaped layer, 41 % padding: down projection -6 %).  The gate/up instantiation keeps the single
         // loop (a second copy costs it registers and 2 % of its time).
-        const bool live = DUAL || !(wm == 1 && t_row_end - t_row0 <= 128);
+        const bool live = DUAL || !(wm == 1 && t_row_end - t_row0 <= MI * 16);
         if (DUAL || live) BM_TILE_LOOP(true)
         else BM_TILE_LOOP(false)
 #undef BM_TILE_LOOP
@@ -693,7 +704,7 @@ __global__ void __launch_bounds__(256) grouped_gemm256_k64w_bf16_kernel(GemmPara
             // up front cost registers, and the spills land in the main loop)
             float *dst = p.splitk + (size_t)(xcd * stride + slot) * SPLIT_TILE_FLOATS + wave * (64 * 256) + lane * 4;
 #pragma unroll
-            for (int i = 0; i < 8; ++i)
+            for (int i = 0; i < MI; ++i)
 #pragma unroll
                 for (int j = 0; j < 8; ++j) {
                     *(BM_GLOBAL f32x4 *)dst = acc[i][j];
@@ -717,7 +728,7 @@ __global__ void __launch_bounds__(256) grouped_gemm256_k64w_bf16_kernel(GemmPara
             uint32_t *stage = reinterpret_cast<uint32_t *>(smem + sAp * P_PART) + wave * 2048;
             const bool odd = lane & 1;
 #pragma unroll
-            for (int i = 0; i < 8; ++i) {
+            for (int i = 0; i < MI; ++i) {
 #pragma unroll
                 for (int j = 0; j < OC; ++j) {
 #pragma unroll
@@ -739,7 +750,7 @@ __global__ void __launch_bounds__(256) grouped_gemm256_k64w_bf16_kernel(GemmPara
                     const int q = lane + 64 * t;
                     const int lrow = q / PR, pc = q % PR;
                     const u32x4 val = *reinterpret_cast<const u32x4 *>(stage + lrow * SD + pc * 4);
-                    const int row = t_row0 + wm * 128 + i * 16 + lrow;
+                    const int row = t_row0 + wm * (MI * 16) + i * 16 + lrow;
                     const int col = t_n0 + wn * (OC * 16) + pc * 8;
                     if (row < t_row_end && col < N) stg128(&c[(size_t)row * N + col], val);
                 }
@@ -753,7 +764,7 @@ __global__ void __launch_bounds__(256) grouped_gemm256_k64w_bf16_kernel(GemmPara
             constexpr int PR = OC * 2;                  // 16-byte pieces per output row
             uint32_t *stage = reinterpret_cast<uint32_t *>(smem + sAp * P_PART) + wave * 2048;
 #pragma unroll
-            for (int i = 0; i < 8; ++i) {
+            for (int i = 0; i < MI; ++i) {
 #pragma unroll
                 for (int j = 0; j < OC; ++j) {
                     float x[4];
@@ -769,7 +780,7 @@ __global__ void __launch_bounds__(256) grouped_gemm256_k64w_bf16_kernel(GemmPara
                     const int q = lane + 64 * t;
                     const int lrow = q / PR, pc = q % PR;
                     const u32x4 val = *reinterpret_cast<const u32x4 *>(stage + lrow * SD + pc * 4);
-                    const int row = t_row0 + wm * 128 + i * 16 + lrow;
+                    const int row = t_row0 + wm * (MI * 16) + i * 16 + lrow;
                     const int col = t_n0 + wn * (OC * 16) + pc * 8;
                     if (row < t_row_end && col < N) stg128(&c[(size_t)row * N + col], val);
                 }
@@ -843,6 +854,8 @@ __global__ void __launch_bounds__(256) splitk_fixup_kernel(GemmParams p) {
 #define BM_K64_GATEUP grouped_gemm256_k64w_bf16_kernel<true, false>
 #define BM_K64_DOWN grouped_gemm256_k64w_bf16_kernel<false, false>
 #define BM_K64_DOWN_SPLIT grouped_gemm256_k64w_bf16_kernel<false, true>
+#define BM_K64_GATEUP_128 grouped_gemm256_k64w_bf16_kernel<true, false, 4>
+#define BM_K64_DOWN_128 grouped_gemm256_k64w_bf16_kernel<false, false, 4>
 
 static int grid_for(const GemmParams &p, bool dual) {
     const int n_nt = dual ? (p.N + 127) / 128 : (p.N + 255) / 256;
@@ -861,12 +874,14 @@ static int persistent_grid(const GemmParams &p, bool dual) {
 static bool k64_ok(const GemmParams &p) {
     const unsigned long long lim = 1ull << 32;
     // (and hands the loads over to the next tile three k-steps before a tile ends)
-    return p.BM == 256 && p.Kd % 64 == 0 && p.Kd >= 256 && (unsigned long long)p.a_rows * p.Kd * 2 < lim &&
+    return (p.BM == 256 || p.BM == 128) && p.Kd % 64 == 0 && p.Kd >= 256 && (unsigned long long)p.a_rows * p.Kd * 2 < lim &&
            (unsigned long long)p.N * p.Kd * 2 < lim;
 }
 
 int launch_gateup_bf16(const GemmParams &p, hipStream_t st) {
-    if (k64_ok(p))
+    if (k64_ok(p) && p.BM == 128)
+        hipLaunchKernelGGL((BM_K64_GATEUP_128), dim3(persistent_grid(p, true)), dim3(256), 0, st, p);
+    else if (k64_ok(p))
         hipLaunchKernelGGL((BM_K64_GATEUP), dim3(persistent_grid(p, true)), dim3(256), 0, st, p);
     else if (p.BM == 256)
         hipLaunchKernelGGL((grouped_gemm256_dma_bf16_kernel<true>), dim3(grid_for(p, true)), dim3(256), 0, st, p);
@@ -879,7 +894,9 @@ int launch_gateup_bf16(const GemmParams &p, hipStream_t st) {
 bool down_split_tail(int Kd) { return Kd / 64 >= 64; }
 
 int launch_down_bf16(const GemmParams &p, hipStream_t st) {
-    if (k64_ok(p)) {
+    if (k64_ok(p) && p.BM == 128) {
+        hipLaunchKernelGGL((BM_K64_DOWN_128), dim3(persistent_grid(p, false)), dim3(256), 0, st, p);
+    } else if (k64_ok(p)) {
         if (p.splitk != nullptr && down_split_tail(p.Kd)) {
             GemmParams q = p;
             q.splitk_stride = persistent_grid(p, false) >> 3;

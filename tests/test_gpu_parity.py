@@ -209,6 +209,42 @@ def test_layer_matches_oracle(name, over, T, unique):
     _check_layer(host, unique)
 
 
+def _host_with_group_sizes(spec, sizes, n_dropped=3, pool=16000):
+    """A HostLayer (K = 1) whose tokens are picked from a pool so that, after substitution, the expert groups
+    have exactly the row counts in `sizes` (largest to the expert that attracts most tokens)."""
+    assert spec.K == 1
+    big = HostLayer(spec, pool, stream=3)
+    ids, _ = oracle.route_topk(big.f32(big.x), big.f32(big.w_router), big.bias, 1)
+    final = oracle.buddy_remap(ids, big.mask, big.table, H=spec.H)[0][:, 0]
+    have = sorted(((int((final == e).sum()), e) for e in range(spec.E)), reverse=True)
+    pick = []
+    for want, (n, e) in zip(sorted(sizes, reverse=True), have):
+        assert n >= want, (n, want)
+        pick.append(np.flatnonzero(final == e)[:want])
+    pick.append(np.flatnonzero(final < 0)[:n_dropped])
+    sel = np.random.default_rng(len(sizes)).permutation(np.concatenate(pick))
+    host = HostLayer(spec, len(sel), base=big)
+    host.x = big.x[sel]
+    return host
+
+
+@pytest.mark.parametrize("sizes", [
+    [1, 64, 65, 127, 128, 129, 255, 256],                 # 128-row tiles (fewer than 192 rows per expert)
+    [2, 16, 17, 130, 384, 385],
+    [1, 128, 129, 255, 256, 257, 513, 1600],              # 256-row tiles
+])
+def test_tile_heights_at_exact_group_sizes(sizes):
+    """Row tiles of the grouped projections at group sizes around their edges: a group of exactly one tile, one
+    row more, one row less, a single row, for both tile heights of the persistent kernel."""
+    spec = workloads.scaled("c4_qwen3", d=256, F=384, K=1, E=16, n_resident=8)
+    _say("tile heights", sizes)
+    host = _host_with_group_sizes(spec, sizes)
+    out, ref, _ = _check_layer(host, unique=False)
+    got = np.sort(np.diff(out["offsets"]))[::-1]
+    np.testing.assert_array_equal(got[:len(sizes)], np.sort(sizes)[::-1])
+    assert (got[len(sizes):] == 0).all()
+
+
 DECODE_CASES = [
     ("c2_mixtral_decode", dict(d=512, F=1024), 1),
     ("c2_mixtral_decode", dict(d=2048, F=2048), 8),       # persistent kernel shapes
