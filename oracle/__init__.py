@@ -29,11 +29,24 @@ def build(force: bool = False) -> str:
     return _LIB
 
 
+def build_sanitized(out_path: str) -> str:
+    """The same source with AddressSanitizer and UndefinedBehaviorSanitizer (tests load it in a child process
+    through BM_ORACLE_LIBRARY, with the sanitizer runtime preloaded)."""
+    cmd = ["g++", "-O1", "-g", "-fno-omit-frame-pointer", "-fsanitize=address,undefined", "-fno-sanitize-recover=undefined",
+           "-fopenmp", "-fPIC", "-shared", "-std=c++17", "-o", out_path, _SRC]
+    subprocess.run(cmd, check=True)
+    return out_path
+
+
 def lib() -> ctypes.CDLL:
     global _lib
     if _lib is None:
-        build()
-        _lib = ctypes.CDLL(_LIB)
+        override = os.environ.get("BM_ORACLE_LIBRARY")     # a differently built copy of the same source (sanitizer run)
+        if override:
+            _lib = ctypes.CDLL(override)
+        else:
+            build()
+            _lib = ctypes.CDLL(_LIB)
     return _lib
 
 

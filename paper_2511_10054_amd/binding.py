@@ -6,7 +6,8 @@ import os
 from typing import Optional
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-_LIB_PATH = os.path.join(_HERE, "libbuddymoe.so")
+# BUDDYMOE_LIBRARY: another build of the same library (e.g. one with host-side sanitizers) instead of the in-tree one
+_LIB_PATH = os.environ.get("BUDDYMOE_LIBRARY") or os.path.join(_HERE, "libbuddymoe.so")
 _lib = None
 
 BM_F32, BM_BF16 = 0, 1

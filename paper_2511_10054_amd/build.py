@@ -18,8 +18,13 @@ FLAGS = [
 ]
 
 
-def build_library(verbose: bool = False, extra=()) -> str:
-    objdir = os.path.join(HERE, "_build")
+# host-side AddressSanitizer + UndefinedBehaviorSanitizer (device code is not instrumented)
+HOST_SANITIZE = ["-Xarch_host", "-fsanitize=address", "-Xarch_host", "-fsanitize=undefined",
+                 "-Xarch_host", "-fno-sanitize-recover=undefined", "-Xarch_host", "-fno-omit-frame-pointer", "-g"]
+
+
+def build_library(verbose: bool = False, extra=(), lib: str = LIB, objdir: str = None, link_extra=()) -> str:
+    objdir = objdir or os.path.join(HERE, "_build")
     os.makedirs(objdir, exist_ok=True)
 
     def compile_one(src):
@@ -34,12 +39,12 @@ def build_library(verbose: bool = False, extra=()) -> str:
 
     with ThreadPoolExecutor(max_workers=4) as ex:
         objs = list(ex.map(compile_one, SOURCES))
-    r = subprocess.run([HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB, *objs],
+    r = subprocess.run([HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", *link_extra, "-o", lib, *objs],
                        capture_output=True, text=True)
     if r.returncode != 0:
         sys.stderr.write(r.stdout + r.stderr)
         raise RuntimeError("link failed")
-    return LIB
+    return lib
 
 
 if __name__ == "__main__":
