@@ -170,10 +170,13 @@ int bm_route_topk(const bm_layer_desc *desc, const void *x, const void *w_router
  * buddy_table [E][R] int32 (device), best buddy first, short rows padded -1.
  * ids_in [T][K] (device); ids_out [T][K] (device, may alias ids_in);
  * w [T][K] fp32 in/out (device, nullable); stats (device, nullable, written).
- * With BM_GATE_TAE / BM_GATE_MARGIN / BM_REPLACE_BUDGET (Section 3.1, Section 5.1)
- * the gates are evaluated per token in fp32 from w as passed in (w is then
- * required: BM_ERR_NULL without it); a miss of a gated token, or one beyond the
- * token's budget, counts as a miss and as dropped.  BM_GATE_DIST takes the
+ * With BM_GATE_TAE / BM_GATE_MARGIN (Section 3.1) the gates are evaluated per
+ * token in fp32 from w as passed in (w is then required: BM_ERR_NULL without it;
+ * BM_REPLACE_BUDGET, Section 5.1, counts substitutions and does not read w); a miss
+ * of a gated token, or one beyond the token's budget, counts as a miss and as
+ * dropped.  TAE and the margin are fp32 values compared with fp32 thresholds: a
+ * token whose exact TAE (or margin) lies within about 2e-5 of the threshold may
+ * fall on either side of it.  BM_GATE_DIST takes the
  * T tokens of the call as the batch; with it and ids_out == ids_in the call
  * runs in a single workgroup (the request set has to be read before any id is
  * overwritten).  BM_PSI_TOKEN needs the router's probabilities and is refused
@@ -217,8 +220,10 @@ int bm_build_buddy_table(const bm_layer_desc *desc, const int64_t *coactivations
  *   offsets [E+1]: first position of each expert, offsets[E] = live count
  *   perm [T*K]: perm[pos] = a for pos < live count, -1 after
  *   inv_perm [T*K]: position of assignment a, -1 if dropped
- * All device int32.  workspace: device scratch of at least
- * bm_workspace_bytes(desc) bytes, 256-byte aligned.  Uses T, E, K of desc.
+ * All device int32.  Uses T, E, K of desc only.  workspace: device scratch,
+ * 256-byte aligned, of at least bm_workspace_bytes of a desc with the same T, E, K
+ * and d = F = 0 (a few hundred bytes to a few hundred KB: per-tile histograms);
+ * the size of a whole layer's desc is always enough as well.
  * T = 0 writes offsets (all zero) only; the other arrays may then be NULL. */
 int bm_permute_by_expert(const bm_layer_desc *desc, const int32_t *ids_remapped,
                          int32_t *offsets, int32_t *perm, int32_t *inv_perm,
@@ -275,8 +280,10 @@ size_t bm_packed_bytes(const bm_layer_desc *desc, int which);
 int bm_pack_weights(const bm_layer_desc *desc, const bm_weights *weights,
                     const uint64_t *residency_bitmap, void *stream);
 
-/* Bytes of device scratch bm_moe_forward / bm_permute_by_expert need for
- * this desc (host, pure function of desc; 0 if desc is invalid). */
+/* Bytes of device scratch bm_moe_forward needs for this desc (host, pure function
+ * of desc: T, d, E, F, K, n_shared, dtype and flags enter; 0 if desc is invalid).
+ * With d = 0 and F = 0 it is the scratch of bm_permute_by_expert alone, a function
+ * of T, E and K. */
 size_t bm_workspace_bytes(const bm_layer_desc *desc);
 
 /* Host-side check of a residency bitmap and buddy table (host pointers):

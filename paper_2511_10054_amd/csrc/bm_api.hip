@@ -2,6 +2,7 @@
 // Nothing here allocates or synchronises; the only state kept between calls is the
 // per-device address of the built-in scratch array of bm_moe_forward_static.
 #include "bm_kernels.h"
+#include "bm_device_shape.h"
 
 #include <atomic>
 #include <cstdio>
@@ -157,7 +158,7 @@ Layout make_layout(const bm_layer_desc *d) {
     L.o = take(use_skinny(d) ? (size_t)skinny_ksplit(d) * L.rows_max * d->d * 4 : (size_t)L.rows_max * d->d * esz);
     // fp32 partial tiles of the down projection's split tail: one 256 x 256 tile per workgroup of the launch
     L.has_splitk = !use_skinny(d) && d->dtype == BM_BF16 && gemm_tile_rows(d) == 256 && down_split_tail(d->F);
-    L.splitk = take(L.has_splitk ? (size_t)256 * 256 * 256 * 4 : 0);
+    L.splitk = take(L.has_splitk ? (size_t)K64_CUS * 256 * 256 * 4 : 0);   // a launch has at most K64_CUS workgroups
     L.total = off;
     return L;
 }
@@ -174,6 +175,33 @@ int check_moe_args(const bm_layer_desc *desc, const void *x, const bm_weights *w
     if (!wt->w_router || !wt->w_gate || !wt->w_up || !wt->w_down) return BM_ERR_NULL;
     if (desc->n_shared > 0 && (!wt->ws_gate || !wt->ws_up || !wt->ws_down)) return BM_ERR_NULL;
     if ((desc->flags & BM_PSI_TOKEN) && !wt->buddy_q) return BM_ERR_NULL;
+    return BM_OK;
+}
+
+// Scratch of bm_permute_by_expert: the per-tile histograms and bases and the row-tile table the grouping
+// kernels write on the way.  A pure function of T and E.
+struct GroupLayout {
+    size_t tile_counts, tile_base, mt_group, mt_row0, n_mtiles, total;
+    int n_tiles;
+};
+
+GroupLayout make_group_layout(int T, int E) {
+    GroupLayout L{};
+    L.n_tiles = (T + TILE_T - 1) / TILE_T;
+    size_t off = 0;
+    auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes); return o; };
+    L.tile_counts = take((size_t)L.n_tiles * E * 4);
+    L.tile_base = take((size_t)L.n_tiles * E * 4);
+    L.mt_group = take((size_t)E * 4);            // one entry per live group (the table is built with a tile height no group reaches)
+    L.mt_row0 = take((size_t)E * 4);
+    L.n_mtiles = take(16);
+    L.total = off;
+    return L;
+}
+
+int check_group_desc(const bm_layer_desc *d) {
+    if (d->T < 0 || d->E <= 0 || d->K <= 0 || d->E > BM_MAX_E || d->K > BM_MAX_K || d->K > d->E) return BM_ERR_SHAPE;
+    if ((long long)d->T * d->K > (1ll << 30)) return BM_ERR_SHAPE;
     return BM_OK;
 }
 
@@ -246,6 +274,11 @@ const char *bm_strerror(int status) {
 }
 
 size_t bm_workspace_bytes(const bm_layer_desc *desc) {
+    if (!desc) return 0;
+    if (desc->d == 0 && desc->F == 0) {          // grouping only: a function of T, E and K
+        if (check_group_desc(desc) != BM_OK) return 0;
+        return make_group_layout(desc->T, desc->E).total;
+    }
     if (check_desc(desc, false) != BM_OK) return 0;
     return make_layout(desc).total;
 }
@@ -373,21 +406,20 @@ int bm_permute_by_expert(const bm_layer_desc *desc, const int32_t *ids_remapped,
                          int32_t *perm, int32_t *inv_perm, void *workspace, size_t workspace_bytes,
                          void *stream) {
     if (!desc) return BM_ERR_NULL;
-    if (desc->T < 0 || desc->E <= 0 || desc->K <= 0 || desc->E > BM_MAX_E || desc->K > BM_MAX_K) return BM_ERR_SHAPE;
-    if ((long long)desc->T * desc->K > (1ll << 30)) return BM_ERR_SHAPE;
-    if (!offsets || (desc->T > 0 && (!ids_remapped || !perm || !inv_perm))) return BM_ERR_NULL;   // empty batch: offsets only
-    bm_layer_desc d2 = *desc;
-    d2.n_shared = 0;
-    Layout L;
-    int rc = check_ws(&d2, workspace, workspace_bytes, L);
+    int rc = check_group_desc(desc);
     if (rc) return rc;
+    if (!offsets || (desc->T > 0 && (!ids_remapped || !perm || !inv_perm))) return BM_ERR_NULL;   // empty batch: offsets only
+    const int T = desc->T, K = desc->K, E = desc->E;
+    const GroupLayout L = make_group_layout(T, E);
+    if (!workspace || (reinterpret_cast<uintptr_t>(workspace) % ALIGN) || workspace_bytes < L.total) return BM_ERR_WORKSPACE;
     hipStream_t st = static_cast<hipStream_t>(stream);
     (void)hipGetLastError();
     int err = 0;
-    if (!grouping_small((long long)d2.T * d2.K, d2.E))       // the small-batch kernel counts for itself
-        err = launch_count(ids_remapped, d2.T, d2.K, d2.E, TILE_T, at<int32_t>(workspace, L.tile_counts), st);
+    if (!grouping_small((long long)T * K, E))       // the small-batch kernel counts for itself
+        err = launch_count(ids_remapped, T, K, E, TILE_T, at<int32_t>(workspace, L.tile_counts), st);
     ScanParams sp{};
-    sp.T = d2.T; sp.E = d2.E; sp.n_shared = 0; sp.n_tiles = L.n_tiles; sp.BM = 128;
+    sp.T = T; sp.E = E; sp.n_shared = 0; sp.n_tiles = L.n_tiles;
+    sp.BM = 1 << 30;                                // one table entry per live group: the table is not an output
     sp.tile_counts = at<int32_t>(workspace, L.tile_counts);
     sp.tile_base = at<int32_t>(workspace, L.tile_base);
     sp.tile_stats = nullptr;
@@ -397,7 +429,7 @@ int bm_permute_by_expert(const bm_layer_desc *desc, const int32_t *ids_remapped,
     sp.n_mtiles = at<int32_t>(workspace, L.n_mtiles);
     sp.stats = nullptr;
     ScatterParams cp{};
-    cp.T = d2.T; cp.K = d2.K; cp.E = d2.E; cp.n_shared = 0; cp.tile_tokens = TILE_T;
+    cp.T = T; cp.K = K; cp.E = E; cp.n_shared = 0; cp.tile_tokens = TILE_T;
     cp.ids = ids_remapped; cp.offsets = offsets; cp.tile_base = sp.tile_base;
     cp.perm = perm; cp.inv_perm = inv_perm; cp.row_token = nullptr;
     err |= launch_grouping(sp, cp, st);

@@ -23,6 +23,7 @@
 // p ^ ((r >> 1) & 7); the 16 lanes of one ds_read_b128 pass (16 rows, same p) then hit 16 distinct
 // 16-byte slots (measured: zero bank-conflict cycles).
 #include "bm_kernels.h"
+#include "bm_device_shape.h"
 
 namespace bm {
 
@@ -580,9 +581,18 @@ __global__ void __launch_bounds__(256) grouped_gemm256_k64w_bf16_kernel(GemmPara
     }
 // For the down projection the MFMA is written as an assembly statement with the accumulator tied to an
 // AGPR tile as input and output: with the builtin the register allocator lets accumulator tiles change
-// registers across the loop and fills the loop with copies (measured 70 % slower).  No accumulator is
-// touched again within 63 MFMAs, and a barrier and the tile bookkeeping lie between the loop and the
-// first read of an accumulator, so the wait states the compiler cannot see here are always met.
+// registers across the loop and fills the loop with copies (measured 70 % slower).  The compiler's hazard
+// recogniser does not see inside the statement, so the two distances it would otherwise guarantee are put
+// in by hand, as s_nop statements that carry a data dependency on the accumulator concerned (an
+// instruction-scheduling fence in those places makes the register allocator spill about 200 registers):
+//   - accumulator zeroing (VALU writes of the AGPRs) -> first MFMA, which reads acc[0][0] as its third
+//     operand: at most 2 wait states are required on this family; 8 are inserted behind the zeroing
+//     (a barrier and the first 16 fragment reads follow before that MFMA can issue anyway);
+//   - last MFMA of a tile (acc[MI - 1][7]) -> first read of an accumulator by another instruction (write-out,
+//     partial-tile store): an 8-pass MFMA result needs 11 wait states (18 for a 16-pass one); 32 are
+//     inserted where the write-out starts.  Every other accumulator's MFMA is at least 16 cycles older.
+// Inside the loop an accumulator is next touched by its own MFMA 63 instructions later (same register as
+// destination and third operand), which the MFMA pipeline interlocks by itself.
 // There the weight fragment is the first operand: the product comes out transposed, i.e. a lane holds four
 // consecutive output columns (4 * quad ...) of one output row (r16), which pack into 8 contiguous bytes
 // (down projection 3-9 % faster through the shorter write-out; the gate/up projection measured 1-3 %
@@ -636,6 +646,7 @@ __global__ void __launch_bounds__(256) grouped_gemm256_k64w_bf16_kernel(GemmPara
             _Pragma("unroll") for (int i = 0; i < MI; ++i)                                                            \
                 _Pragma("unroll") for (int j = 0; j < 8; ++j)                                                         \
                     _Pragma("unroll") for (int v = 0; v < 4; ++v) acc[i][j][v] = 0.0f;                                \
+            if (!DUAL) asm volatile("s_nop 7" : "+a"(acc[0][0]));  /* acc[0][0]: the first MFMA's accumulator */       \
         }                                                                                                             \
         BM_BARE_BARRIER();                                                                                            \
         {                                                                                                             \
@@ -697,6 +708,9 @@ __global__ void __launch_bounds__(256) grouped_gemm256_k64w_bf16_kernel(GemmPara
             if (!more) break;
             continue;
         }
+        // last MFMA of the tile -> first read of an accumulator (see BM_MFMA1): acc[MI - 1][7] is the last MFMA's
+        // accumulator, every other one is at least one MFMA (16 cycles) older
+        if (!DUAL) asm volatile("s_nop 15\n\ts_nop 15" : "+a"(acc[MI - 1][7]));
         if (SPLIT && t_partial) {
             // chunk of a split tile: the fp32 accumulators go to this workgroup's scratch tile as they are
             // (accumulator tile, lane: 16-byte stores, contiguous over the lanes)
@@ -867,21 +881,35 @@ static int grid_for(const GemmParams &p, bool dual) {
 // always a multiple of 8 so that every XCD gets the same number.
 static int persistent_grid(const GemmParams &p, bool dual) {
     const int g = grid_for(p, dual);
-    return g < 256 ? g : 256;
+    return g < K64_CUS ? g : K64_CUS;
 }
 
-// the k-step-64 kernel addresses rows by 32-bit byte offsets from a uniform base
+// compute units and XCDs of the current device (0, 0 if the queries fail)
+static void device_shape(int &cus, int &xcds) {
+    int dev = 0;
+    cus = xcds = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return;
+    if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) cus = 0;
+    if (hipDeviceGetAttribute(&xcds, hipDeviceAttributeNumberOfXccs, dev) != hipSuccess) xcds = 0;
+}
+
+// the k-step-64 kernel addresses rows by 32-bit byte offsets from a uniform base, and its schedule is laid
+// out for the full part (see bm_device_shape.h)
 static bool k64_ok(const GemmParams &p) {
     const unsigned long long lim = 1ull << 32;
+    int cus, xcds;
+    device_shape(cus, xcds);
+    if (!persistent_schedule_fits(cus, xcds)) return false;
     // (and hands the loads over to the next tile three k-steps before a tile ends)
     return (p.BM == 256 || p.BM == 128) && p.Kd % 64 == 0 && p.Kd >= 256 && (unsigned long long)p.a_rows * p.Kd * 2 < lim &&
            (unsigned long long)p.N * p.Kd * 2 < lim;
 }
 
 int launch_gateup_bf16(const GemmParams &p, hipStream_t st) {
-    if (k64_ok(p) && p.BM == 128)
+    const bool k64 = k64_ok(p);
+    if (k64 && p.BM == 128)
         hipLaunchKernelGGL((BM_K64_GATEUP_128), dim3(persistent_grid(p, true)), dim3(256), 0, st, p);
-    else if (k64_ok(p))
+    else if (k64)
         hipLaunchKernelGGL((BM_K64_GATEUP), dim3(persistent_grid(p, true)), dim3(256), 0, st, p);
     else if (p.BM == 256)
         hipLaunchKernelGGL((grouped_gemm256_dma_bf16_kernel<true>), dim3(grid_for(p, true)), dim3(256), 0, st, p);
@@ -894,9 +922,10 @@ int launch_gateup_bf16(const GemmParams &p, hipStream_t st) {
 bool down_split_tail(int Kd) { return Kd / 64 >= 64; }
 
 int launch_down_bf16(const GemmParams &p, hipStream_t st) {
-    if (k64_ok(p) && p.BM == 128) {
+    const bool k64 = k64_ok(p);
+    if (k64 && p.BM == 128) {
         hipLaunchKernelGGL((BM_K64_DOWN_128), dim3(persistent_grid(p, false)), dim3(256), 0, st, p);
-    } else if (k64_ok(p)) {
+    } else if (k64) {
         if (p.splitk != nullptr && down_split_tail(p.Kd)) {
             GemmParams q = p;
             q.splitk_stride = persistent_grid(p, false) >> 3;

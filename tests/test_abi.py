@@ -66,6 +66,10 @@ def test_strerror_and_workspace_bytes():
     big = bm.bm_workspace_bytes(_desc(T=4096))
     assert 0 < small < big and small % 256 == 0
     assert bm.bm_workspace_bytes(_desc(K=9)) == 0          # K > E
+    # grouping only (d = F = 0): a function of T, E, K - per-tile histograms, no activations
+    g = bm.bm_workspace_bytes(_desc(T=4096, d=0, F=0))
+    assert 0 < g < 64 * 1024 and g % 256 == 0 and g == bm.bm_workspace_bytes(_desc(T=4096, d=0, F=0, dtype=7, R=99))
+    assert bm.bm_workspace_bytes(_desc(T=4096, d=0, F=0, K=9)) == 0
     assert bm.bm_workspace_bytes(_desc(dtype=7)) == 0
     # DeepSeek-shaped layer: h and o for 8192*6 + 2*8192 rows
     n = bm.bm_workspace_bytes(_desc(T=8192, d=2048, E=64, F=1408, K=6, n_shared=2, R=8, H=8, dtype=bm.BM_BF16))
@@ -172,3 +176,23 @@ def test_stream_read_rejects_bad_arguments_on_the_host():
     assert lib.bm_stream_read(None, 1024, one, None) == -1
     assert lib.bm_stream_read(one, 1024, None, None) == -1
     assert lib.bm_stream_read(one, 1000, one, None) == -2          # not a multiple of 16 bytes
+
+
+def test_persistent_schedule_is_taken_only_on_the_full_part(tmp_path):
+    """The device-shape rule of the persistent prefill kernel (csrc/bm_device_shape.h, plain C++): exactly
+    256 compute units in 8 XCDs; a partitioned or different device, or a failed query (0), takes the
+    fallback kernels."""
+    import subprocess
+    src = tmp_path / "shape.cpp"
+    src.write_text('#include "bm_device_shape.h"\n#include <cstdio>\nint main() {\n'
+                   '  using bm::persistent_schedule_fits;\n'
+                   '  int bad = 0;\n'
+                   '  bad += !persistent_schedule_fits(256, 8);\n'
+                   '  bad += persistent_schedule_fits(0, 0) + persistent_schedule_fits(256, 0) + persistent_schedule_fits(0, 8);\n'
+                   '  bad += persistent_schedule_fits(128, 4) + persistent_schedule_fits(64, 2) + persistent_schedule_fits(32, 1);\n'
+                   '  bad += persistent_schedule_fits(304, 8) + persistent_schedule_fits(256, 4) + persistent_schedule_fits(255, 8);\n'
+                   '  std::printf("%d\\n", bad);\n  return bad;\n}\n')
+    exe = tmp_path / "shape"
+    subprocess.run(["g++", "-std=c++17", "-I", os.path.join(ROOT, "paper_2511_10054_amd", "csrc"), "-o", str(exe), str(src)],
+                   check=True)
+    assert subprocess.run([str(exe)], capture_output=True, text=True).stdout.strip() == "0"

@@ -140,8 +140,10 @@ def test_permute_by_expert(T, K, E):
     ids[g.random((T, K)) < 0.2] = -1
     ids[:, 0] = np.minimum(ids[:, 0], 2)               # skew: a few very large groups
     off_ref, perm_ref, inv_ref = oracle.permute(ids, E)
-    desc = bm.LayerDesc(T=T, d=32, E=E, F=0, K=K, n_shared=0, R=0, H=0, dtype=bm.BM_BF16, flags=0)
-    ws = torch.empty(bm.bm_workspace_bytes(desc), dtype=torch.uint8, device="cuda")
+    desc = bm.LayerDesc(T=T, d=0, E=E, F=0, K=K, n_shared=0, R=0, H=0, dtype=bm.BM_BF16, flags=0)   # T, E, K only
+    nbytes = bm.bm_workspace_bytes(desc)
+    assert 0 < nbytes <= 2 * 4 * E * (T // 32 + 1) + 2 * 4 * E + 6 * 256
+    ws = torch.full((nbytes,), 0xA5, dtype=torch.uint8, device="cuda")
     off = torch.full((E + 1,), -9, dtype=torch.int32, device="cuda")
     perm = torch.full((T * K,), -9, dtype=torch.int32, device="cuda")
     inv = torch.full((T * K,), -9, dtype=torch.int32, device="cuda")
