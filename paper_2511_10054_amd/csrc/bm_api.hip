@@ -33,22 +33,34 @@ constexpr int SKINNY_FIT_ROWS = 512;   // ... up to which it is used when the wi
 constexpr int SKINNY_AVG_ROWS = 16;    // ... and rows per group (averaged over all experts) likewise
 constexpr int SKINNY_KSPLIT = 8;
 
-// Row-tile height of the grouped GEMM.  256 rows whenever both projections fit the persistent k-step-64
-// kernel (reduction widths that are multiples of 64 and at least 256, operands within 32-bit byte
-// offsets): even with groups of a few dozen rows its padded tiles beat the 128-row kernel (Mixtral-shaped
-// layer at 128 tokens 0.47 against 0.69 ms, Qwen3-shaped at 1024 tokens 0.22 against 0.30 ms).  Otherwise 256
-// rows when the average routed group is large, else 128.
+// Row-tile height of a grouped projection (down: the down projection, else gate/up).  When both
+// projections fit the persistent k-step-64 kernel (reduction widths that are multiples of 64 and at least
+// 256, operands within 32-bit byte offsets) it runs 256- or 128-row tiles, chosen per projection; a 128-row
+// tile costs about 0.65 of a 256-row one, so it pays when padding and the rounding of tiles to whole rounds
+// of 256 workgroups outweigh that.  Measured ms (gate/up, down) with 128- | 256-row tiles: Mixtral-shaped
+// layer, 5 of 8 experts resident, 384 tokens .27 .22 | .32 .19, 512 tokens .32 .21 | .33 .19, 768 tokens
+// .44 .24 | .43 .20; DeepSeek-shaped 1024 tokens .10 .08 | .12 .08, 2048 tokens .20 .12 | .18 .12;
+// Qwen3-shaped 1024 tokens .11 .07 | .13 .08, 2048 tokens .14 .10 | .16 .09.  The down projection of a long
+// reduction keeps 256 rows: its partial last round is split along the reduction instead.
+// Other shapes: 256 rows when the average routed group is large, else 128 (the register-staged kernel).
 #ifndef BM_TILE128_AVG_ROWS
-#define BM_TILE128_AVG_ROWS 192   // routed rows per expert (averaged over all E) below which the k-step-64 kernel runs 128-row tiles
+#define BM_TILE128_AVG_ROWS 192   // gate/up: routed rows per expert (averaged over all E) below which tiles are 128 rows
 #endif
-int gemm_tile_rows(const bm_layer_desc *d) {
+#ifndef BM_TILE128_AVG_ROWS_DOWN
+#define BM_TILE128_AVG_ROWS_DOWN 48   // down projection: rows per group (shared experts included) likewise
+#endif
+int gemm_tile_rows(const bm_layer_desc *d, bool down) {
     const unsigned long long lim = 1ull << 32;
-    const unsigned long long rows = (unsigned long long)d->T * (d->K + (d->n_shared > 0 ? d->n_shared : 0)) +
-                                    256ull * (d->E + (d->n_shared > 0 ? d->n_shared : 0));
+    const int ns = d->n_shared > 0 ? d->n_shared : 0;
+    const unsigned long long rows = (unsigned long long)d->T * (d->K + ns) + 256ull * (d->E + ns);
     const bool k64 = d->d % 64 == 0 && d->F % 64 == 0 && d->d >= 256 && d->F >= 256 &&
                      (unsigned long long)d->T * d->d * 2 < lim && rows * d->F * 2 < lim &&
                      (unsigned long long)d->F * d->d * 2 < lim;
-    if (k64) return ((long long)d->T * d->K < (long long)BM_TILE128_AVG_ROWS * d->E) ? 128 : 256;
+    if (k64) {
+        if (!down) return ((long long)d->T * d->K < (long long)BM_TILE128_AVG_ROWS * d->E) ? 128 : 256;
+        if (down_split_tail(d->F)) return 256;
+        return ((long long)d->T * (d->K + ns) < (long long)BM_TILE128_AVG_ROWS_DOWN * (d->E + ns)) ? 128 : 256;
+    }
     return ((long long)d->T * d->K / d->E >= 128) ? 256 : 128;
 }
 
@@ -77,6 +89,9 @@ int skinny_ksplit(const bm_layer_desc *d) {
         // rows each) - longer weight streams per workgroup and fewer fp32 partial outputs beat a finer
         // split (measured on the Mixtral-shaped layer at 64 tokens: 2 slices 99 us, 4: 111, 7: 115; unsplit 147)
         const long long groups = d->E + d->n_shared < (long long)d->T * d->K ? d->E + d->n_shared : (long long)d->T * d->K;
+#ifdef BM_FORCE_KSPLIT
+        if (bm::skinny_lds_ok(d->F, BM_FORCE_KSPLIT)) return BM_FORCE_KSPLIT;
+#endif
         for (int s = 2; s <= SKINNY_KSPLIT; ++s)
             if (bm::skinny_lds_ok(d->F, s) && d->F / (512 * s) >= 2 && (d->d / 64) * groups * s >= 512) return s;
         for (int s = SKINNY_KSPLIT; s > 1; --s)
@@ -95,7 +110,7 @@ size_t align_up(size_t v) { return (v + ALIGN - 1) / ALIGN * ALIGN; }
 // Workspace carving: a pure function of desc.
 struct Layout {
     size_t ids, ids2, w, tile_counts, tile_base, tile_stats, offsets, perm, inv_perm, row_token;
-    size_t mt_group, mt_row0, n_mtiles, stats, probs, h, o, splitk, total;
+    size_t mt_group, mt_row0, n_mtiles, mt_group2, mt_row02, n_mtiles2, stats, probs, h, o, splitk, total;
     int n_tiles, rows_max, mtiles_max;
     bool has_splitk;
 };
@@ -150,6 +165,11 @@ Layout make_layout(const bm_layer_desc *d) {
     L.mt_group = take((size_t)L.mtiles_max * 4);
     L.mt_row0 = take((size_t)L.mtiles_max * 4);
     L.n_mtiles = take(16);
+    // second row-tile table: the down projection on another tile height than the gate/up projection
+    const bool two = !use_skinny(d) && d->dtype == BM_BF16 && gemm_tile_rows(d, false) != gemm_tile_rows(d, true);
+    L.mt_group2 = take(two ? (size_t)L.mtiles_max * 4 : 0);
+    L.mt_row02 = take(two ? (size_t)L.mtiles_max * 4 : 0);
+    L.n_mtiles2 = take(two ? 16 : 0);
     L.stats = take(32);
     // every expert's probability per token: only when the substitution runs apart from the router kernel
     L.probs = take(((d->flags & BM_PSI_TOKEN) && (d->flags & BM_GATE_DIST)) ? (size_t)d->T * d->E * 4 : 0);
@@ -157,7 +177,7 @@ Layout make_layout(const bm_layer_desc *d) {
     L.h = take((size_t)L.rows_max * F * esz);
     L.o = take(use_skinny(d) ? (size_t)skinny_ksplit(d) * L.rows_max * d->d * 4 : (size_t)L.rows_max * d->d * esz);
     // fp32 partial tiles of the down projection's split tail: one 256 x 256 tile per workgroup of the launch
-    L.has_splitk = !use_skinny(d) && d->dtype == BM_BF16 && gemm_tile_rows(d) == 256 && down_split_tail(d->F);
+    L.has_splitk = !use_skinny(d) && d->dtype == BM_BF16 && gemm_tile_rows(d, true) == 256 && down_split_tail(d->F);
     L.splitk = take(L.has_splitk ? (size_t)K64_CUS * 256 * 256 * 4 : 0);   // a launch has at most K64_CUS workgroups
     L.total = off;
     return L;
@@ -493,7 +513,13 @@ int bm_moe_forward(const bm_layer_desc *desc, const void *x, const bm_weights *w
     const bool skinny = use_skinny(desc);
     sp.T = T; sp.E = E; sp.n_shared = desc->n_shared;
     sp.n_tiles = (T + fp.tile_tokens - 1) / fp.tile_tokens;   // tiles of the front kernel (per-tile statistics)
-    sp.BM = skinny ? (1 << 20) : gemm_tile_rows(desc);   // skinny: one table entry per live group
+    sp.BM = skinny ? (1 << 20) : gemm_tile_rows(desc, false);   // skinny: one table entry per live group
+    const int bm_down = skinny ? sp.BM : (bf16 ? gemm_tile_rows(desc, true) : sp.BM);
+    if (bm_down != sp.BM) {                         // the down projection walks its own table
+        sp.BM2 = bm_down;
+        sp.mt_group2 = at<int32_t>(ws, L.mt_group2); sp.mt_row02 = at<int32_t>(ws, L.mt_row02);
+        sp.n_mtiles2 = at<int32_t>(ws, L.n_mtiles2);
+    }
     sp.largest_first = skinny ? 1 : 0;
     sp.tile_counts = fp.tile_counts; sp.tile_base = at<int32_t>(ws, L.tile_base);
     sp.tile_stats = fp.tile_stats;
@@ -555,6 +581,7 @@ int bm_moe_forward(const bm_layer_desc *desc, const void *x, const bm_weights *w
     dp.b0 = wt->w_down; dp.b1 = nullptr; dp.sb0 = wt->ws_down; dp.sb1 = nullptr;
     dp.c = at<void>(ws, L.o);
     dp.N = desc->d; dp.Kd = desc->F;
+    if (sp.BM2) { dp.BM = sp.BM2; dp.mt_group = sp.mt_group2; dp.mt_row0 = sp.mt_row02; dp.n_mtiles = sp.n_mtiles2; }
     dp.splitk = L.has_splitk ? at<float>(ws, L.splitk) : nullptr;
     int ksplit = 1;
     if (skinny) {

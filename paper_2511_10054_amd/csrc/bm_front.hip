@@ -417,6 +417,38 @@ __device__ void place_assignments(const int32_t *ids, int A, int E, int K, const
         if (ids[a] < 0) c.inv_perm[a] = -1;
 }
 
+// A second list of row tiles, of height p.BM2, for the projection that runs on another tile height than the
+// first list (0: none).  Called by every thread of the workgroup once `start` (G + 1 group starts in LDS) is
+// valid; the last wave does the work - a scan over the groups in registers, a few consecutive groups per
+// lane - while the others go on.
+__device__ void write_second_tile_table(const ScanParams &p, const int32_t *start) {
+    if (p.BM2 <= 0) return;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nw = blockDim.x >> 6;
+    if (wave != nw - 1) return;
+    const int G = p.E + p.n_shared;
+    constexpr int PER = (BM_MAX_E + 8 + 63) / 64;
+    int nt[PER], sum = 0;
+#pragma unroll
+    for (int i = 0; i < PER; ++i) {
+        const int g = lane * PER + i;
+        const int n = g < G ? start[g + 1] - start[g] : 0;
+        nt[i] = (n + p.BM2 - 1) / p.BM2;
+        sum += nt[i];
+    }
+    int total;
+    int run = wave_excl_scan(sum, total);
+#pragma unroll
+    for (int i = 0; i < PER; ++i) {
+        const int g = lane * PER + i;
+        for (int j = 0; j < nt[i]; ++j) {
+            p.mt_group2[run + j] = g;
+            p.mt_row02[run + j] = start[g] + j * p.BM2;
+        }
+        run += nt[i];
+    }
+    if (lane == 0) { p.n_mtiles2[0] = total; p.n_mtiles2[1] = start[G]; }
+}
+
 // Offsets and the list of row tiles from the group starts in LDS (start: G + 1 rows, tstart: G + 1 tiles);
 // every thread of one workgroup calls it.  For the decode projections (largest_first) the list holds the
 // live groups by falling row count: a group is one work-item column of their grid, groups with more rows take
@@ -481,6 +513,7 @@ __device__ void finish_groups(const ScanParams &p, const ScatterParams &c, const
     }
     __syncthreads();
     write_group_tables(p, start, tstart);
+    write_second_tile_table(p, start);
     if (p.stats != nullptr && wave < 3) {          // one wave per counter
         int sum = 0;
         if (local_stats != nullptr) sum = local_stats[wave];
@@ -538,6 +571,7 @@ __device__ void fused_tail(const FrontParams &p, FusedLds &fs, int n_tiles) {
             p.scan.mt_row0[fs.tstart[g] + i] = fs.start[g] + i * BM;
         }
     }
+    write_second_tile_table(p.scan, fs.start);
     if (p.scan.stats != nullptr && tid < 3) {
         int sum = 0;
         for (int t = 0; t < n_tiles; ++t) sum += fs.stats[t][tid];
@@ -937,6 +971,7 @@ __global__ void __launch_bounds__(1024) scan_kernel(ScanParams p) {
             p.mt_row0[tstart[g] + i] = start[g] + i * p.BM;
         }
     }
+    write_second_tile_table(p, start);
     if (p.stats != nullptr && wave < 3) {          // one wave per counter, lanes over the tiles
         int sum = 0;
         if (p.tile_stats != nullptr)
@@ -1077,6 +1112,7 @@ __global__ void __launch_bounds__(1024) group_tiles_kernel(ScanParams p, Scatter
     __syncthreads();
     if (tile == 0) {
         write_group_tables(p, start, tstart);
+        write_second_tile_table(p, start);
         if (p.stats != nullptr && wave >= nw - 3) {    // one wave per counter, lanes over the tiles
             const int k = wave - (nw - 3);
             int sum = 0;

@@ -33,6 +33,8 @@ struct ScanParams {
     int32_t *offsets;             // [E + n_shared + 1]
     int32_t *mt_group, *mt_row0;  // row-tile table
     int32_t *n_mtiles;            // [2]: number of row tiles, total rows
+    int BM2;                      // height of a second row-tile table (the two projections differ), 0: none
+    int32_t *mt_group2, *mt_row02, *n_mtiles2;
     int32_t *stats;               // 3 ints or null
 };
 

@@ -178,6 +178,10 @@ LAYER_CASES = [
     # long reduction of the down projection (the reduction-split tail itself needs more than 256 tiles: it is
     # covered by the full-size Mixtral prefill test)
     ("c3_mixtral_prefill", dict(d=256, F=4096), 2300),
+    # the two projections on different tile heights (each walks its own row-tile table): 128-row gate/up tiles
+    # with 256-row down tiles, short and long reduction
+    ("c4_qwen3", dict(d=256, F=384), 1000),
+    ("c3_mixtral_prefill", dict(d=256, F=4096), 600),
 ]
 
 
@@ -231,7 +235,8 @@ def _host_with_group_sizes(spec, sizes, n_dropped=3, pool=16000):
 
 
 @pytest.mark.parametrize("sizes", [
-    [1, 64, 65, 127, 128, 129, 255, 256],                 # 128-row tiles (fewer than 192 rows per expert)
+    [1, 64, 65, 127, 128, 129],                           # 128-row tiles in both projections
+    [1, 64, 65, 127, 128, 129, 255, 256],                 # 128-row gate/up tiles, 256-row down tiles
     [2, 16, 17, 130, 384, 385],
     [1, 128, 129, 255, 256, 257, 513, 1600],              # 256-row tiles
 ])
