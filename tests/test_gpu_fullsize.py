@@ -85,10 +85,11 @@ def test_c2_mixtral_decode_public_weight_layout(T):
     _check("c2_mixtral_decode", T, 64, pack=False)
 
 
-@pytest.mark.parametrize("T", [128, 256, 512])
+@pytest.mark.parametrize("T", [128, 256, 512, 1024, 2048])
 def test_c2_mixtral_between_decode_and_prefill(T):
     """Batches between the benchmark points: 128-rows-per-pass streaming kernel (128), two such passes for the
-    largest groups (256), padded 256-row tiles of the prefill kernel (512)."""
+    largest groups (256), 128-row gate/up tiles with 256-row down tiles of the prefill kernels (512), 256-row
+    tiles in both with a last round of few tiles (1024, 2048)."""
     _check("c2_mixtral_decode", T, 64)
 
 
