@@ -33,33 +33,30 @@ constexpr int SKINNY_FIT_ROWS = 512;   // ... up to which it is used when the wi
 constexpr int SKINNY_AVG_ROWS = 16;    // ... and rows per group (averaged over all experts) likewise
 constexpr int SKINNY_KSPLIT = 8;
 
-// Row-tile height of a grouped projection (down: the down projection, else gate/up).  When both
-// projections fit the persistent k-step-64 kernel (reduction widths that are multiples of 64 and at least
-// 256, operands within 32-bit byte offsets) it runs 256- or 128-row tiles, chosen per projection; a 128-row
-// tile costs about 0.65 of a 256-row one, so it pays when padding and the rounding of tiles to whole rounds
-// of 256 workgroups outweigh that.  Measured ms (gate/up, down) with 128- | 256-row tiles: Mixtral-shaped
-// layer, 5 of 8 experts resident, 384 tokens .27 .22 | .32 .19, 512 tokens .32 .21 | .33 .19, 768 tokens
-// .44 .24 | .43 .20; DeepSeek-shaped 1024 tokens .10 .08 | .12 .08, 2048 tokens .20 .12 | .18 .12;
-// Qwen3-shaped 1024 tokens .11 .07 | .13 .08, 2048 tokens .14 .10 | .16 .09.  The down projection of a long
-// reduction keeps 256 rows: its partial last round is split along the reduction instead.
-// Other shapes: 256 rows when the average routed group is large, else 128 (the register-staged kernel).
-#ifndef BM_TILE128_AVG_ROWS
-#define BM_TILE128_AVG_ROWS 192   // gate/up: routed rows per expert (averaged over all E) below which tiles are 128 rows
-#endif
-#ifndef BM_TILE128_AVG_ROWS_DOWN
-#define BM_TILE128_AVG_ROWS_DOWN 48   // down projection: rows per group (shared experts included) likewise
-#endif
-int gemm_tile_rows(const bm_layer_desc *d, bool down) {
+// Shapes both projections of which fit the persistent k-step-64 kernel: reduction widths that are multiples
+// of 64 and at least 256, operands within 32-bit byte offsets.
+bool k64_shape(const bm_layer_desc *d) {
     const unsigned long long lim = 1ull << 32;
     const int ns = d->n_shared > 0 ? d->n_shared : 0;
     const unsigned long long rows = (unsigned long long)d->T * (d->K + ns) + 256ull * (d->E + ns);
-    const bool k64 = d->d % 64 == 0 && d->F % 64 == 0 && d->d >= 256 && d->F >= 256 &&
-                     (unsigned long long)d->T * d->d * 2 < lim && rows * d->F * 2 < lim &&
-                     (unsigned long long)d->F * d->d * 2 < lim;
-    if (k64) {
-        if (!down) return ((long long)d->T * d->K < (long long)BM_TILE128_AVG_ROWS * d->E) ? 128 : 256;
-        if (down_split_tail(d->F)) return 256;
-        return ((long long)d->T * (d->K + ns) < (long long)BM_TILE128_AVG_ROWS_DOWN * (d->E + ns)) ? 128 : 256;
+    return d->dtype == BM_BF16 && d->d % 64 == 0 && d->F % 64 == 0 && d->d >= 256 && d->F >= 256 &&
+           (unsigned long long)d->T * d->d * 2 < lim && rows * d->F * 2 < lim && (unsigned long long)d->F * d->d * 2 < lim;
+}
+
+// Row tiles of a grouped projection (down: the down projection, else gate/up): TILES_MIXED, or the single
+// tile height 256 / 128.  On the persistent kernel (k64_shape on a device of the expected shape) a launch
+// runs both heights: a group's rows go into 256-row tiles and a rest of at most 128 rows into one 128-row
+// tile, which costs 0.65 of a 256-row tile's time.  Measured against single heights, ms (gate/up, down) with
+// 128- | 256-row tiles only: Mixtral-shaped layer, 5 of 8 experts resident, 384 tokens .27 .22 | .32 .19,
+// 1024 tokens .55 .41 | .50 .30; DeepSeek-shaped 1024 tokens .10 .08 | .12 .08, 2048 tokens .20 .12 | .18 .12;
+// Qwen3-shaped 1024 tokens .11 .07 | .13 .08, 2048 tokens .14 .10 | .16 .09: neither height wins everywhere.
+// The down projection of a long reduction keeps 256 rows: its partial last round is split along the
+// reduction instead (down_split_tail).  Other shapes: 256 rows when the average routed group is large, else 128.
+constexpr int TILES_MIXED = 0;
+int tile_mode(const bm_layer_desc *d, bool down, bool persistent) {
+    if (k64_shape(d)) {
+        if (!persistent) return 256;
+        return (down && down_split_tail(d->F)) ? 256 : TILES_MIXED;
     }
     return ((long long)d->T * d->K / d->E >= 128) ? 256 : 128;
 }
@@ -110,7 +107,8 @@ size_t align_up(size_t v) { return (v + ALIGN - 1) / ALIGN * ALIGN; }
 // Workspace carving: a pure function of desc.
 struct Layout {
     size_t ids, ids2, w, tile_counts, tile_base, tile_stats, offsets, perm, inv_perm, row_token;
-    size_t mt_group, mt_row0, n_mtiles, mt_group2, mt_row02, n_mtiles2, stats, probs, h, o, splitk, total;
+    size_t mt_group, mt_row0, n_mtiles, mt_group_b, mt_row0_b, n_mtiles_b, mt_group_s, mt_row0_s, n_mtiles_s;
+    size_t stats, probs, h, o, splitk, total;
     int n_tiles, rows_max, mtiles_max;
     bool has_splitk;
 };
@@ -165,11 +163,14 @@ Layout make_layout(const bm_layer_desc *d) {
     L.mt_group = take((size_t)L.mtiles_max * 4);
     L.mt_row0 = take((size_t)L.mtiles_max * 4);
     L.n_mtiles = take(16);
-    // second row-tile table: the down projection on another tile height than the gate/up projection
-    const bool two = !use_skinny(d) && d->dtype == BM_BF16 && gemm_tile_rows(d, false) != gemm_tile_rows(d, true);
-    L.mt_group2 = take(two ? (size_t)L.mtiles_max * 4 : 0);
-    L.mt_row02 = take(two ? (size_t)L.mtiles_max * 4 : 0);
-    L.n_mtiles2 = take(two ? 16 : 0);
+    // the two row-tile lists of a launch that runs 256- and 128-row tiles (at most rows / 256 + G and G entries)
+    const bool mixed = !use_skinny(d) && k64_shape(d);
+    L.mt_group_b = take(mixed ? (size_t)L.mtiles_max * 4 : 0);
+    L.mt_row0_b = take(mixed ? (size_t)L.mtiles_max * 4 : 0);
+    L.n_mtiles_b = take(mixed ? 16 : 0);
+    L.mt_group_s = take(mixed ? (size_t)G * 4 : 0);
+    L.mt_row0_s = take(mixed ? (size_t)G * 4 : 0);
+    L.n_mtiles_s = take(mixed ? 16 : 0);
     L.stats = take(32);
     // every expert's probability per token: only when the substitution runs apart from the router kernel
     L.probs = take(((d->flags & BM_PSI_TOKEN) && (d->flags & BM_GATE_DIST)) ? (size_t)d->T * d->E * 4 : 0);
@@ -177,7 +178,7 @@ Layout make_layout(const bm_layer_desc *d) {
     L.h = take((size_t)L.rows_max * F * esz);
     L.o = take(use_skinny(d) ? (size_t)skinny_ksplit(d) * L.rows_max * d->d * 4 : (size_t)L.rows_max * d->d * esz);
     // fp32 partial tiles of the down projection's split tail: one 256 x 256 tile per workgroup of the launch
-    L.has_splitk = !use_skinny(d) && d->dtype == BM_BF16 && gemm_tile_rows(d, true) == 256 && down_split_tail(d->F);
+    L.has_splitk = !use_skinny(d) && k64_shape(d) && down_split_tail(d->F);
     L.splitk = take(L.has_splitk ? (size_t)K64_CUS * 256 * 256 * 4 : 0);   // a launch has at most K64_CUS workgroups
     L.total = off;
     return L;
@@ -513,12 +514,17 @@ int bm_moe_forward(const bm_layer_desc *desc, const void *x, const bm_weights *w
     const bool skinny = use_skinny(desc);
     sp.T = T; sp.E = E; sp.n_shared = desc->n_shared;
     sp.n_tiles = (T + fp.tile_tokens - 1) / fp.tile_tokens;   // tiles of the front kernel (per-tile statistics)
-    sp.BM = skinny ? (1 << 20) : gemm_tile_rows(desc, false);   // skinny: one table entry per live group
-    const int bm_down = skinny ? sp.BM : (bf16 ? gemm_tile_rows(desc, true) : sp.BM);
-    if (bm_down != sp.BM) {                         // the down projection walks its own table
-        sp.BM2 = bm_down;
-        sp.mt_group2 = at<int32_t>(ws, L.mt_group2); sp.mt_row02 = at<int32_t>(ws, L.mt_row02);
-        sp.n_mtiles2 = at<int32_t>(ws, L.n_mtiles2);
+    const bool persistent = !skinny && bf16 && persistent_device();
+    const int mode_gu = skinny ? (1 << 20) : tile_mode(desc, false, persistent);   // skinny: one table entry per live group
+    const int mode_dn = skinny ? (1 << 20) : tile_mode(desc, true, persistent);
+    // the plain table serves whichever projection runs a single tile height (both, unless one is mixed)
+    sp.BM = mode_gu != TILES_MIXED ? mode_gu : (mode_dn != TILES_MIXED ? mode_dn : 256);
+    if (mode_gu == TILES_MIXED || mode_dn == TILES_MIXED) {
+        sp.mixed = 1;
+        sp.mt_group_b = at<int32_t>(ws, L.mt_group_b); sp.mt_row0_b = at<int32_t>(ws, L.mt_row0_b);
+        sp.n_mtiles_b = at<int32_t>(ws, L.n_mtiles_b);
+        sp.mt_group_s = at<int32_t>(ws, L.mt_group_s); sp.mt_row0_s = at<int32_t>(ws, L.mt_row0_s);
+        sp.n_mtiles_s = at<int32_t>(ws, L.n_mtiles_s);
     }
     sp.largest_first = skinny ? 1 : 0;
     sp.tile_counts = fp.tile_counts; sp.tile_base = at<int32_t>(ws, L.tile_base);
@@ -577,11 +583,17 @@ int bm_moe_forward(const bm_layer_desc *desc, const void *x, const bm_weights *w
     gp.N = desc->F; gp.Kd = desc->d; gp.E = E; gp.n_groups = G; gp.max_mtiles = L.mtiles_max; gp.BM = sp.BM;
     gp.mt_group = sp.mt_group; gp.mt_row0 = sp.mt_row0; gp.n_mtiles = sp.n_mtiles; gp.offsets = sp.offsets;
     GemmParams dp = gp;
+    auto use_mixed = [&](GemmParams &q) {
+        q.mixed = 1; q.BM = 256;
+        q.mt_group = sp.mt_group_b; q.mt_row0 = sp.mt_row0_b; q.n_mtiles = sp.n_mtiles_b;
+        q.mt_group_s = sp.mt_group_s; q.mt_row0_s = sp.mt_row0_s; q.n_mtiles_s = sp.n_mtiles_s;
+    };
+    if (mode_gu == TILES_MIXED) use_mixed(gp);
+    if (mode_dn == TILES_MIXED) use_mixed(dp);
     dp.a = gp.c; dp.row_map = nullptr; dp.a_rows = L.rows_max;
     dp.b0 = wt->w_down; dp.b1 = nullptr; dp.sb0 = wt->ws_down; dp.sb1 = nullptr;
     dp.c = at<void>(ws, L.o);
     dp.N = desc->d; dp.Kd = desc->F;
-    if (sp.BM2) { dp.BM = sp.BM2; dp.mt_group = sp.mt_group2; dp.mt_row0 = sp.mt_row02; dp.n_mtiles = sp.n_mtiles2; }
     dp.splitk = L.has_splitk ? at<float>(ws, L.splitk) : nullptr;
     int ksplit = 1;
     if (skinny) {

@@ -417,36 +417,48 @@ __device__ void place_assignments(const int32_t *ids, int A, int E, int K, const
         if (ids[a] < 0) c.inv_perm[a] = -1;
 }
 
-// A second list of row tiles, of height p.BM2, for the projection that runs on another tile height than the
-// first list (0: none).  Called by every thread of the workgroup once `start` (G + 1 group starts in LDS) is
-// valid; the last wave does the work - a scan over the groups in registers, a few consecutive groups per
+// The two row-tile lists of a projection that runs both tile heights in one launch (p.mixed): a group of n rows
+// gives n / 256 tiles of 256 rows, and its rest one more of them when it exceeds 128 rows, else (when there is
+// a rest) one 128-row tile.  Called by every thread of the workgroup once `start` (G + 1 group starts in LDS)
+// is valid; the last wave does the work - scans over the groups in registers, a few consecutive groups per
 // lane - while the others go on.
-__device__ void write_second_tile_table(const ScanParams &p, const int32_t *start) {
-    if (p.BM2 <= 0) return;
+__device__ void write_mixed_tile_tables(const ScanParams &p, const int32_t *start) {
+    if (!p.mixed) return;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nw = blockDim.x >> 6;
     if (wave != nw - 1) return;
     const int G = p.E + p.n_shared;
     constexpr int PER = (BM_MAX_E + 8 + 63) / 64;
-    int nt[PER], sum = 0;
+    int nb[PER], ns[PER], sum_b = 0, sum_s = 0;
 #pragma unroll
     for (int i = 0; i < PER; ++i) {
         const int g = lane * PER + i;
         const int n = g < G ? start[g + 1] - start[g] : 0;
-        nt[i] = (n + p.BM2 - 1) / p.BM2;
-        sum += nt[i];
+        const int rest = n & 255;
+        nb[i] = (n >> 8) + (rest > 128 ? 1 : 0);
+        ns[i] = (rest >= 1 && rest <= 128) ? 1 : 0;
+        sum_b += nb[i];
+        sum_s += ns[i];
     }
-    int total;
-    int run = wave_excl_scan(sum, total);
+    int tot_b, tot_s;
+    int run_b = wave_excl_scan(sum_b, tot_b), run_s = wave_excl_scan(sum_s, tot_s);
 #pragma unroll
     for (int i = 0; i < PER; ++i) {
         const int g = lane * PER + i;
-        for (int j = 0; j < nt[i]; ++j) {
-            p.mt_group2[run + j] = g;
-            p.mt_row02[run + j] = start[g] + j * p.BM2;
+        for (int j = 0; j < nb[i]; ++j) {
+            p.mt_group_b[run_b + j] = g;
+            p.mt_row0_b[run_b + j] = start[g] + j * 256;
         }
-        run += nt[i];
+        if (ns[i]) {
+            p.mt_group_s[run_s] = g;
+            p.mt_row0_s[run_s] = start[g] + nb[i] * 256;
+        }
+        run_b += nb[i];
+        run_s += ns[i];
     }
-    if (lane == 0) { p.n_mtiles2[0] = total; p.n_mtiles2[1] = start[G]; }
+    if (lane == 0) {
+        p.n_mtiles_b[0] = tot_b; p.n_mtiles_b[1] = start[G];
+        p.n_mtiles_s[0] = tot_s; p.n_mtiles_s[1] = start[G];
+    }
 }
 
 // Offsets and the list of row tiles from the group starts in LDS (start: G + 1 rows, tstart: G + 1 tiles);
@@ -513,7 +525,7 @@ __device__ void finish_groups(const ScanParams &p, const ScatterParams &c, const
     }
     __syncthreads();
     write_group_tables(p, start, tstart);
-    write_second_tile_table(p, start);
+    write_mixed_tile_tables(p, start);
     if (p.stats != nullptr && wave < 3) {          // one wave per counter
         int sum = 0;
         if (local_stats != nullptr) sum = local_stats[wave];
@@ -571,7 +583,7 @@ __device__ void fused_tail(const FrontParams &p, FusedLds &fs, int n_tiles) {
             p.scan.mt_row0[fs.tstart[g] + i] = fs.start[g] + i * BM;
         }
     }
-    write_second_tile_table(p.scan, fs.start);
+    write_mixed_tile_tables(p.scan, fs.start);
     if (p.scan.stats != nullptr && tid < 3) {
         int sum = 0;
         for (int t = 0; t < n_tiles; ++t) sum += fs.stats[t][tid];
@@ -971,7 +983,7 @@ __global__ void __launch_bounds__(1024) scan_kernel(ScanParams p) {
             p.mt_row0[tstart[g] + i] = start[g] + i * p.BM;
         }
     }
-    write_second_tile_table(p, start);
+    write_mixed_tile_tables(p, start);
     if (p.stats != nullptr && wave < 3) {          // one wave per counter, lanes over the tiles
         int sum = 0;
         if (p.tile_stats != nullptr)
@@ -1112,7 +1124,7 @@ __global__ void __launch_bounds__(1024) group_tiles_kernel(ScanParams p, Scatter
     __syncthreads();
     if (tile == 0) {
         write_group_tables(p, start, tstart);
-        write_second_tile_table(p, start);
+        write_mixed_tile_tables(p, start);
         if (p.stats != nullptr && wave >= nw - 3) {    // one wave per counter, lanes over the tiles
             const int k = wave - (nw - 3);
             int sum = 0;

@@ -12,13 +12,15 @@
 // operand (8 consecutive k) is one 16-byte piece of a row.
 //
 // Kernels, in the order the launchers prefer them:
-//   grouped_gemm256_k64w         BM = 256, persistent, k-steps of 64 with whole-line direct-to-LDS
-//                                loads, v_mfma_f32_16x16x32_bf16; the down projection with a
-//                                reduction-split tail for long reductions
-//   grouped_gemm256_dma          BM = 256, k-steps of 32 (reduction not a multiple of 64, or offsets
-//                                beyond 32 bits)
+//   grouped_gemm_mixed_k64w      persistent, k-steps of 64 with whole-line direct-to-LDS loads,
+//                                v_mfma_f32_16x16x32_bf16; 256-row tiles plus one 128-row tile for a group's
+//                                rest of at most 128 rows, both heights in one launch
+//   grouped_gemm256_k64w         the same tile loop on 256-row tiles only, with a reduction-split tail: the
+//                                down projection of long reductions
+//   grouped_gemm256_dma          BM = 256, k-steps of 32 (reduction not a multiple of 64, offsets beyond
+//                                32 bits, or a device that is not the full part)
 //   grouped_gemm_bf16_kernel     BM = 128, 4 waves, register-staged double buffer, for groups too small
-//                                for 256-row tiles
+//                                for 256-row tiles on those shapes
 // LDS rows of 128 bytes: the 64 banks span two rows, so piece p of row r is stored at slot
 // p ^ ((r >> 1) & 7); the 16 lanes of one ds_read_b128 pass (16 rows, same p) then hit 16 distinct
 // 16-byte slots (measured: zero bank-conflict cycles).
@@ -449,14 +451,49 @@ constexpr int SPLIT_TILE_FLOATS = 256 * 256;
 // same ring (the activation part fills half of its slot: four loads per wave and k-step instead of eight,
 // 32 MFMAs per k slice instead of 64, the weight part unchanged), for layers whose groups are mostly
 // smaller than a 256-row tile.
-template <bool DUAL, bool SPLIT, int MI = 8>
-__global__ void __launch_bounds__(256) grouped_gemm256_k64w_bf16_kernel(GemmParams p) {
+//
+// PHASE: 0 - every row tile of the table has the height of this instantiation.  1 and 2 - one launch runs
+// both heights (grouped_gemm_mixed_k64w_bf16_kernel): a group's rows are cut into 256-row tiles, and a rest
+// of at most 128 rows becomes a 128-row tile; every workgroup first takes its share of the 256-row tiles
+// (phase 1, the plain persistent order), then its share of the 128-row tiles (phase 2), which are dealt out
+// so that the workgroups that got one 256-row tile fewer catch up first (next_small_tile).
+__shared__ __attribute__((aligned(1024))) uint16_t k64w_smem[5 * P_PART];        // 160 KB: the whole LDS
+
+// Deals an XCD's 128-row tiles (ids 0 .. n_small - 1) to its `stride` workgroups after the 256-row tiles:
+// the first R workgroups (the "heavy" ones) hold one 256-row tile more than the other L = stride - R.  The
+// tiles go out in batches, each batch to the class with the smaller load so far, one tile per workgroup of
+// the class; a 256-row tile counts 20, a 128-row tile 13 (measured tile times 53 and 35 us).  Every
+// workgroup replays the same sequence and picks out its own tiles, so no memory is shared.
+struct SmallTileDealer {
+    int base, load_l, load_h, R, L, n_small, slot;
+    __device__ __forceinline__ void init(int n_big, int n_small_, int stride, int slot_) {
+        R = n_big % stride; L = stride - R; n_small = n_small_; slot = slot_; base = 0;
+        load_l = 20 * (n_big / stride);
+        load_h = load_l + 20;
+    }
+    __device__ __forceinline__ bool next(int &tile) {
+        while (base < n_small) {
+            const bool to_light = R == 0 || load_l <= load_h;
+            const int cnt = to_light ? L : R;
+            const int mine = to_light ? slot - R : (slot < R ? slot : -1);
+            const int id = base + mine;
+            base += cnt;
+            if (to_light) load_l += 13; else load_h += 13;
+            if (mine >= 0 && id < n_small) { tile = id; return true; }
+        }
+        return false;
+    }
+};
+
+template <bool DUAL, bool SPLIT, int MI, int PHASE>
+__device__ __forceinline__ void k64w_body(const GemmParams &p) {
+    uint16_t *const smem = k64w_smem;
     static_assert(MI == 8 || MI == 4, "tile height is 256 or 128 rows");
+    static_assert(PHASE == 0 || (!SPLIT && MI == (PHASE == 1 ? 8 : 4)), "mixed heights: 256-row tiles first, then 128-row tiles");
     static_assert(!SPLIT || MI == 8, "the reduction-split tail exists for 256-row tiles only");
     constexpr int TM = MI * 32;                            // rows per tile
     constexpr int NM = MI * 8;                             // MFMAs per k slice of 32
     constexpr int NR = MI + 8;                             // fragment reads per k slice
-    __shared__ __attribute__((aligned(1024))) uint16_t smem[5 * P_PART];         // 160 KB: the whole LDS
     const int tid = threadIdx.x, lane = tid & 63;
     // the wave index as a scalar: everything derived from it (LDS targets of the loads, tile halves) then
     // stays in scalar registers and costs no vector instructions in the main loop
@@ -468,7 +505,9 @@ __global__ void __launch_bounds__(256) grouped_gemm256_k64w_bf16_kernel(GemmPara
     // logical tiles with stride (workgroups per XCD), so the workgroups that run together on an XCD work
     // on consecutive logical tiles (see tile_of) and a workgroup keeps its compute unit: the next tile's
     // first loads fly while the finished tile is written out, and nothing is relaunched.
-    const int n_mt = p.n_mtiles[0];
+    const int32_t *const mt_group = PHASE == 2 ? p.mt_group_s : p.mt_group;
+    const int32_t *const mt_row0 = PHASE == 2 ? p.mt_row0_s : p.mt_row0;
+    const int n_mt = PHASE == 2 ? p.n_mtiles_s[0] : p.n_mtiles[0];
     const int n_nt = DUAL ? (p.N + 127) / 128 : (p.N + 255) / 256;
     const int total = n_mt * n_nt;
     const int per_xcd = (total + 7) >> 3;
@@ -476,6 +515,12 @@ __global__ void __launch_bounds__(256) grouped_gemm256_k64w_bf16_kernel(GemmPara
     const int N = p.N, Kd = p.Kd;
     const int KT = Kd / 64;
     const TailSplit ts = tail_split(total, per_xcd, xcd, stride, KT, SPLIT && p.splitk != nullptr);
+    SmallTileDealer dealer;
+    if (PHASE == 2) {
+        const int total_big = p.n_mtiles[0] * n_nt, per_xcd_big = (total_big + 7) >> 3;
+        dealer.init(max(0, min(per_xcd_big, total_big - xcd * per_xcd_big)), max(0, min(per_xcd, total - xcd * per_xcd)),
+                    stride, slot);
+    }
     int idx = slot;                                    // next tile of the complete rounds
     bool tail_pending = ts.rem > 0;
     int kbeg = 0, kend = KT;                           // k-steps of the item whose loads are being issued
@@ -485,7 +530,10 @@ __global__ void __launch_bounds__(256) grouped_gemm256_k64w_bf16_kernel(GemmPara
 #define BM_NEXT_ITEM(ok_)                                                                          \
     {                                                                                              \
         ok_ = false;                                                                               \
-        if (idx < ts.full) {                                                                       \
+        if (PHASE == 2) {                                                                          \
+            ok_ = dealer.next(item_tile);                                                          \
+            kbeg = 0; kend = KT; partial = false;                                                  \
+        } else if (idx < ts.full) {                                                                       \
             item_tile = idx; kbeg = 0; kend = KT; partial = false; idx += stride; ok_ = true;      \
         } else if (tail_pending) {                                                                 \
             tail_pending = false;                                                                  \
@@ -530,8 +578,8 @@ __global__ void __launch_bounds__(256) grouped_gemm256_k64w_bf16_kernel(GemmPara
     {                                                                                              \
         int mt_, nt_;                                                                              \
         tile_of((lid_), n_mt, n_nt, mt_, nt_);                                                     \
-        const int g_ = p.mt_group[mt_];                                                            \
-        row0 = p.mt_row0[mt_];                                                                     \
+        const int g_ = mt_group[mt_];                                                              \
+        row0 = mt_row0[mt_];                                                                       \
         row_end = p.offsets[g_ + 1];                                                               \
         n0 = nt_ * (DUAL ? 128 : 256);                                                             \
         if (g_ < p.E) {                                                                            \
@@ -817,6 +865,33 @@ __global__ void __launch_bounds__(256) grouped_gemm256_k64w_bf16_kernel(GemmPara
 #undef BM_MFMA1
 }
 
+template <bool DUAL, bool SPLIT, int MI = 8>
+__global__ void __launch_bounds__(256) grouped_gemm256_k64w_bf16_kernel(GemmParams p) {
+    k64w_body<DUAL, SPLIT, MI, 0>(p);
+}
+
+// Both tile heights in one launch (see k64w_body): p.mt_group / mt_row0 / n_mtiles list the 256-row tiles,
+// p.mt_group_s / mt_row0_s / n_mtiles_s the 128-row tiles.
+template <bool DUAL>
+__global__ void __launch_bounds__(256) grouped_gemm_mixed_k64w_bf16_kernel(GemmParams p) {
+    // A 128-row tile is the only user of its weight panel (a group has at most one), so it streams from
+    // memory at a third of a 256-row tile's arithmetic intensity.  When there are many of them (at least a
+    // quarter of the 256-row tiles' number) every other workgroup takes its 128-row tiles first, so that the
+    // streaming is spread over the launch instead of bunched at its end (Qwen3-shaped layer, 2048 tokens:
+    // gate/up 141 -> 133 us); with few of them that order only delays 256-row tiles (Mixtral-shaped prefill
+    // + 1 %, 1024 tokens + 3 %).
+    const bool small_first = p.n_mtiles_s[0] * 4 >= p.n_mtiles[0] && ((blockIdx.x >> 3) & 1);
+    if (small_first) {
+        k64w_body<DUAL, false, 4, 2>(p);
+        __syncthreads();      // the last write-out's staging area becomes the next phase's first load target
+        k64w_body<DUAL, false, 8, 1>(p);
+    } else {
+        k64w_body<DUAL, false, 8, 1>(p);
+        __syncthreads();
+        k64w_body<DUAL, false, 4, 2>(p);
+    }
+}
+
 // Adds the chunks of every split tail tile in chunk order and writes the bf16 result (see TailSplit).
 // Grid (16 tail tiles, 8 XCDs, 16 slices of a tile): a workgroup handles one sixteenth of a tile - the
 // accumulator tiles (i, j) with i * 8 + j in [4 * blockIdx.z, 4 * blockIdx.z + 4) - with the chunk
@@ -865,12 +940,6 @@ __global__ void __launch_bounds__(256) splitk_fixup_kernel(GemmParams p) {
     }
 }
 
-#define BM_K64_GATEUP grouped_gemm256_k64w_bf16_kernel<true, false>
-#define BM_K64_DOWN grouped_gemm256_k64w_bf16_kernel<false, false>
-#define BM_K64_DOWN_SPLIT grouped_gemm256_k64w_bf16_kernel<false, true>
-#define BM_K64_GATEUP_128 grouped_gemm256_k64w_bf16_kernel<true, false, 4>
-#define BM_K64_DOWN_128 grouped_gemm256_k64w_bf16_kernel<false, false, 4>
-
 static int grid_for(const GemmParams &p, bool dual) {
     const int n_nt = dual ? (p.N + 127) / 128 : (p.N + 255) / 256;
     const int total = p.max_mtiles * n_nt;
@@ -893,24 +962,27 @@ static void device_shape(int &cus, int &xcds) {
     if (hipDeviceGetAttribute(&xcds, hipDeviceAttributeNumberOfXccs, dev) != hipSuccess) xcds = 0;
 }
 
+bool persistent_device() {
+    int cus, xcds;
+    device_shape(cus, xcds);
+    return persistent_schedule_fits(cus, xcds);
+}
+
 // the k-step-64 kernel addresses rows by 32-bit byte offsets from a uniform base, and its schedule is laid
 // out for the full part (see bm_device_shape.h)
 static bool k64_ok(const GemmParams &p) {
     const unsigned long long lim = 1ull << 32;
-    int cus, xcds;
-    device_shape(cus, xcds);
-    if (!persistent_schedule_fits(cus, xcds)) return false;
+    if (!persistent_device()) return false;
     // (and hands the loads over to the next tile three k-steps before a tile ends)
-    return (p.BM == 256 || p.BM == 128) && p.Kd % 64 == 0 && p.Kd >= 256 && (unsigned long long)p.a_rows * p.Kd * 2 < lim &&
+    return p.BM == 256 && p.Kd % 64 == 0 && p.Kd >= 256 && (unsigned long long)p.a_rows * p.Kd * 2 < lim &&
            (unsigned long long)p.N * p.Kd * 2 < lim;
 }
 
 int launch_gateup_bf16(const GemmParams &p, hipStream_t st) {
-    const bool k64 = k64_ok(p);
-    if (k64 && p.BM == 128)
-        hipLaunchKernelGGL((BM_K64_GATEUP_128), dim3(persistent_grid(p, true)), dim3(256), 0, st, p);
-    else if (k64)
-        hipLaunchKernelGGL((BM_K64_GATEUP), dim3(persistent_grid(p, true)), dim3(256), 0, st, p);
+    if (p.mixed && k64_ok(p))
+        hipLaunchKernelGGL((grouped_gemm_mixed_k64w_bf16_kernel<true>), dim3(persistent_grid(p, true)), dim3(256), 0, st, p);
+    else if (p.mixed)
+        return -1;                // the caller asks for both tile heights only where the persistent kernel runs
     else if (p.BM == 256)
         hipLaunchKernelGGL((grouped_gemm256_dma_bf16_kernel<true>), dim3(grid_for(p, true)), dim3(256), 0, st, p);
     else
@@ -922,23 +994,20 @@ int launch_gateup_bf16(const GemmParams &p, hipStream_t st) {
 bool down_split_tail(int Kd) { return Kd / 64 >= 64; }
 
 int launch_down_bf16(const GemmParams &p, hipStream_t st) {
-    const bool k64 = k64_ok(p);
-    if (k64 && p.BM == 128) {
-        hipLaunchKernelGGL((BM_K64_DOWN_128), dim3(persistent_grid(p, false)), dim3(256), 0, st, p);
-    } else if (k64) {
-        if (p.splitk != nullptr && down_split_tail(p.Kd)) {
-            GemmParams q = p;
-            q.splitk_stride = persistent_grid(p, false) >> 3;
-            hipLaunchKernelGGL((BM_K64_DOWN_SPLIT), dim3(persistent_grid(p, false)), dim3(256), 0, st, q);
-            hipLaunchKernelGGL(splitk_fixup_kernel, dim3(16, 8, 16), dim3(256), 0, st, q);
-        } else {
-            hipLaunchKernelGGL((BM_K64_DOWN), dim3(persistent_grid(p, false)), dim3(256), 0, st, p);
-        }
-    }
-    else if (p.BM == 256)
+    if (p.mixed && k64_ok(p)) {
+        hipLaunchKernelGGL((grouped_gemm_mixed_k64w_bf16_kernel<false>), dim3(persistent_grid(p, false)), dim3(256), 0, st, p);
+    } else if (p.mixed) {
+        return -1;
+    } else if (p.BM == 256 && p.splitk != nullptr && down_split_tail(p.Kd) && k64_ok(p)) {
+        GemmParams q = p;
+        q.splitk_stride = persistent_grid(p, false) >> 3;
+        hipLaunchKernelGGL((grouped_gemm256_k64w_bf16_kernel<false, true>), dim3(persistent_grid(p, false)), dim3(256), 0, st, q);
+        hipLaunchKernelGGL(splitk_fixup_kernel, dim3(16, 8, 16), dim3(256), 0, st, q);
+    } else if (p.BM == 256) {
         hipLaunchKernelGGL((grouped_gemm256_dma_bf16_kernel<false>), dim3(grid_for(p, false)), dim3(256), 0, st, p);
-    else
+    } else {
         hipLaunchKernelGGL((grouped_gemm_bf16_kernel<false, 128>), dim3(grid_for(p, false)), dim3(256), 0, st, p);
+    }
     return launch_status(__func__);
 }
 

@@ -33,8 +33,9 @@ struct ScanParams {
     int32_t *offsets;             // [E + n_shared + 1]
     int32_t *mt_group, *mt_row0;  // row-tile table
     int32_t *n_mtiles;            // [2]: number of row tiles, total rows
-    int BM2;                      // height of a second row-tile table (the two projections differ), 0: none
-    int32_t *mt_group2, *mt_row02, *n_mtiles2;
+    int mixed;                    // also write the two lists of a projection that runs 256- and 128-row tiles in one launch
+    int32_t *mt_group_b, *mt_row0_b, *n_mtiles_b;   // its 256-row tiles
+    int32_t *mt_group_s, *mt_row0_s, *n_mtiles_s;   // its 128-row tiles
     int32_t *stats;               // 3 ints or null
 };
 
@@ -88,6 +89,8 @@ struct GemmParams {
     int max_mtiles;               // grid bound on row tiles
     int BM;                       // rows per tile of the row-tile table: 128 or 256
     const int32_t *mt_group, *mt_row0, *n_mtiles, *offsets;
+    int mixed;                    // both tile heights in one launch: the table above lists the 256-row tiles and
+    const int32_t *mt_group_s, *mt_row0_s, *n_mtiles_s;   // ... this one the 128-row tiles
     float *splitk;                // scratch for the reduction-split tail of the down projection (or null)
     int splitk_stride;            // workgroups per XCD of the launch that wrote it
 };
@@ -136,6 +139,7 @@ bool grouping_small(long long assignments, int E);   // launch_grouping takes th
 // bf16 MFMA grouped projections (row tile height p.BM, which the row-tile table was built for)
 int launch_gateup_bf16(const GemmParams &p, hipStream_t st);   // c = silu(a b0^T) * (a b1^T), bf16
 int launch_down_bf16(const GemmParams &p, hipStream_t st);     // c = a b0^T, bf16
+bool persistent_device();       // the current device has the shape the persistent prefill kernels are laid out for
 bool down_split_tail(int Kd);   // the down projection of this reduction width may use p.splitk (its split tail)
 
 // fp32 FMA projections (one workgroup per row)
