@@ -29,8 +29,8 @@ using namespace bm;
 constexpr size_t ALIGN = 256;
 constexpr int MAX_SHARED = 8;
 constexpr int SKINNY_MAX_ROWS = 256;   // total rows up to which the weight-streaming path is always used,
-constexpr int SKINNY_FIT_ROWS = 512;   // ... up to which it is used when the widths fit its fast kernels,
 constexpr int SKINNY_AVG_ROWS = 16;    // ... and rows per group (averaged over all experts) likewise
+constexpr int SKINNY_UNFIT_ROWS = 16;  // total rows when the widths do not fit its fast kernels but do fit the persistent tiled kernel
 constexpr int SKINNY_KSPLIT = 8;
 
 // Shapes both projections of which fit the persistent k-step-64 kernel: reduction widths that are multiples
@@ -62,18 +62,22 @@ int tile_mode(const bm_layer_desc *d, bool down, bool persistent) {
 }
 
 // Few rows per group: every expert group is decode-sized and the projections are bound by reading the
-// weights once.  Up to 256 rows in all; up to 512 rows (Mixtral-shaped layer, 8 experts: 0.34 / 0.44 / 0.46 ms
-// at 128 / 192 / 256 tokens against 0.47 / 0.48 / 0.49 ms on the tiled path) or up to 16 rows per expert on
-// average (Qwen3-shaped layer, 128 experts, 128 / 256 tokens: 0.13 / 0.16 against 0.21 ms) when both widths fit the fast
-// streaming kernels - the DeepSeek-shaped layer, whose F = 1408 does not fit them and whose shared experts
-// take every token, is faster on the tiled path from 64 tokens (512 rows) on.
+// weights once.  Up to 256 rows in all, or up to 16 rows per expert on average (Qwen3-shaped layer, 128
+// experts, 64 / 128 / 256 tokens: 0.11 / 0.13 / 0.16 ms against 0.14 / 0.15 / 0.16 ms on the tiled path), when
+// both widths fit the fast streaming kernels (multiples of 256).  Widths that do not (DeepSeek-shaped layer,
+// F = 1408, whose shared experts take every token as well) leave the streaming path to its slower
+// fallbacks: there the persistent tiled kernel is faster from 4 tokens on (4 / 8 / 32 tokens: 0.064 / 0.071 /
+// 0.089 against 0.068 / 0.082 / 0.101 ms), so the streaming path keeps only batches of at most 16 rows.
+// Mixtral-shaped layer, 8 experts, streaming | tiled, ms: 128 tokens 0.40 | 0.44, 192 tokens 0.55 | 0.47,
+// 256 tokens 0.59 | 0.48 (public weight layout; 0.48 | 0.47 and 0.52 | 0.48 on the packed copies).
 bool use_skinny(const bm_layer_desc *d) {
     if (d->dtype != BM_BF16) return false;
     const int ns = d->n_shared > 0 ? d->n_shared : 0;
     const long long rows = (long long)d->T * (d->K + ns);
-    if (rows <= SKINNY_MAX_ROWS) return true;
     const bool fit = d->d % 256 == 0 && d->F % 256 == 0;
-    return fit && (rows <= SKINNY_FIT_ROWS || rows <= (long long)SKINNY_AVG_ROWS * (d->E + ns));
+    if (!fit && k64_shape(d)) return rows <= SKINNY_UNFIT_ROWS;
+    if (rows <= SKINNY_MAX_ROWS) return true;
+    return fit && rows <= (long long)SKINNY_AVG_ROWS * (d->E + ns);
 }
 // Reduction slices of the decode down projection (each slice is a workgroup
 // whose 4 waves split it once more): prefer a count that fits the
@@ -84,11 +88,9 @@ int skinny_ksplit(const bm_layer_desc *d) {
     if ((long long)d->T * d->K > 32) {
         // LDS-staged kernel: the fewest slices that still give every compute unit two workgroups (64 weight
         // rows each) - longer weight streams per workgroup and fewer fp32 partial outputs beat a finer
-        // split (measured on the Mixtral-shaped layer at 64 tokens: 2 slices 99 us, 4: 111, 7: 115; unsplit 147)
+        // split (measured on the Mixtral-shaped layer at 64 tokens: 2 slices 99 us, 4: 111, 7: 115-119, 8: 114; unsplit 147;
+        // the aggregation kernel grows with the slices as well, 8 -> 11 -> 15 -> 16 us)
         const long long groups = d->E + d->n_shared < (long long)d->T * d->K ? d->E + d->n_shared : (long long)d->T * d->K;
-#ifdef BM_FORCE_KSPLIT
-        if (bm::skinny_lds_ok(d->F, BM_FORCE_KSPLIT)) return BM_FORCE_KSPLIT;
-#endif
         for (int s = 2; s <= SKINNY_KSPLIT; ++s)
             if (bm::skinny_lds_ok(d->F, s) && d->F / (512 * s) >= 2 && (d->d / 64) * groups * s >= 512) return s;
         for (int s = SKINNY_KSPLIT; s > 1; --s)
