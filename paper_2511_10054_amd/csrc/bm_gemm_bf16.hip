@@ -26,6 +26,7 @@
 // 16-byte slots (measured: zero bank-conflict cycles).
 #include "bm_kernels.h"
 #include "bm_device_shape.h"
+#include "bm_tile_dealer.h"
 
 namespace bm {
 
@@ -459,32 +460,6 @@ constexpr int SPLIT_TILE_FLOATS = 256 * 256;
 // so that the workgroups that got one 256-row tile fewer catch up first (next_small_tile).
 __shared__ __attribute__((aligned(1024))) uint16_t k64w_smem[5 * P_PART];        // 160 KB: the whole LDS
 
-// Deals an XCD's 128-row tiles (ids 0 .. n_small - 1) to its `stride` workgroups after the 256-row tiles:
-// the first R workgroups (the "heavy" ones) hold one 256-row tile more than the other L = stride - R.  The
-// tiles go out in batches, each batch to the class with the smaller load so far, one tile per workgroup of
-// the class; a 256-row tile counts 20, a 128-row tile 13 (measured tile times 53 and 35 us).  Every
-// workgroup replays the same sequence and picks out its own tiles, so no memory is shared.
-struct SmallTileDealer {
-    int base, load_l, load_h, R, L, n_small, slot;
-    __device__ __forceinline__ void init(int n_big, int n_small_, int stride, int slot_) {
-        R = n_big % stride; L = stride - R; n_small = n_small_; slot = slot_; base = 0;
-        load_l = 20 * (n_big / stride);
-        load_h = load_l + 20;
-    }
-    __device__ __forceinline__ bool next(int &tile) {
-        while (base < n_small) {
-            const bool to_light = R == 0 || load_l <= load_h;
-            const int cnt = to_light ? L : R;
-            const int mine = to_light ? slot - R : (slot < R ? slot : -1);
-            const int id = base + mine;
-            base += cnt;
-            if (to_light) load_l += 13; else load_h += 13;
-            if (mine >= 0 && id < n_small) { tile = id; return true; }
-        }
-        return false;
-    }
-};
-
 template <bool DUAL, bool SPLIT, int MI, int PHASE>
 __device__ __forceinline__ void k64w_body(const GemmParams &p) {
     uint16_t *const smem = k64w_smem;
@@ -635,7 +610,12 @@ __device__ __forceinline__ void k64w_body(const GemmParams &p) {
 // instruction-scheduling fence in those places makes the register allocator spill about 200 registers):
 //   - accumulator zeroing (VALU writes of the AGPRs) -> first MFMA, which reads acc[0][0] as its third
 //     operand: at most 2 wait states are required on this family; 8 are inserted behind the zeroing
-//     (a barrier and the first 16 fragment reads follow before that MFMA can issue anyway);
+//     (a barrier and the first 16 fragment reads follow before that MFMA can issue anyway).  The zeroing of
+//     the other accumulators cannot move closer to their first MFMA than that because the k-steps of a tile
+//     form ONE loop and the zeroing stays in front of it.  Do not peel the first k-step off that loop in
+//     this instantiation: in straight-line code the compiler sinks each accumulator's zeroing to right in
+//     front of its first MFMA, which then reads the stale register (every 128-row tile came out wrong when
+//     this was tried; tying a wait to all 64 accumulators instead made the allocator spill 128 registers);
 //   - last MFMA of a tile (acc[MI - 1][7]) -> first read of an accumulator by another instruction (write-out,
 //     partial-tile store): an 8-pass MFMA result needs 11 wait states (18 for a 16-pass one); 32 are
 //     inserted where the write-out starts.  Every other accumulator's MFMA is at least 16 cycles older.

@@ -196,3 +196,50 @@ def test_persistent_schedule_is_taken_only_on_the_full_part(tmp_path):
     subprocess.run(["g++", "-std=c++17", "-I", os.path.join(ROOT, "paper_2511_10054_amd", "csrc"), "-o", str(exe), str(src)],
                    check=True)
     assert subprocess.run([str(exe)], capture_output=True, text=True).stdout.strip() == "0"
+
+
+def test_small_tile_dealer_hands_out_every_tile_exactly_once(tmp_path):
+    """The dealing of 128-row tiles among an XCD's workgroups (csrc/bm_tile_dealer.h, plain C++): for every
+    number of 256-row tiles, 128-row tiles and workgroups in a range, each tile goes to exactly one workgroup,
+    a workgroup's tiles come in increasing order, and no workgroup ends more than one 256-row tile's worth
+    above the lightest one."""
+    import subprocess
+    src = tmp_path / "dealer.cpp"
+    src.write_text(r'''
+#include "bm_tile_dealer.h"
+#include <cstdio>
+#include <vector>
+int main() {
+    long checked = 0;
+    for (int stride = 1; stride <= 32; ++stride)
+        for (int n_big = 0; n_big <= 70; ++n_big)
+            for (int n_small = 0; n_small <= 90; ++n_small) {
+                std::vector<int> owner(n_small, -1), load(stride);
+                for (int slot = 0; slot < stride; ++slot) {
+                    bm::SmallTileDealer d;
+                    d.init(n_big, n_small, stride, slot);
+                    load[slot] = 20 * (n_big / stride + (slot < n_big % stride ? 1 : 0));
+                    int tile = -1, last = -1, guard = 0;
+                    while (d.next(tile)) {
+                        if (tile < 0 || tile >= n_small || owner[tile] != -1 || tile <= last || ++guard > n_small) {
+                            std::printf("bad deal stride %d big %d small %d slot %d tile %d\n", stride, n_big, n_small, slot, tile);
+                            return 1;
+                        }
+                        owner[tile] = slot; last = tile; load[slot] += 13;
+                    }
+                }
+                int lo = 1 << 30, hi = 0;
+                for (int t = 0; t < n_small; ++t) if (owner[t] < 0) { std::printf("tile %d not dealt (%d %d %d)\n", t, stride, n_big, n_small); return 1; }
+                for (int v : load) { lo = v < lo ? v : lo; hi = v > hi ? v : hi; }
+                if (hi - lo > 20) { std::printf("unbalanced %d..%d (%d %d %d)\n", lo, hi, stride, n_big, n_small); return 1; }
+                ++checked;
+            }
+    std::printf("ok %ld\n", checked);
+    return 0;
+}
+''')
+    exe = tmp_path / "dealer"
+    subprocess.run(["g++", "-O1", "-std=c++17", "-I", os.path.join(ROOT, "paper_2511_10054_amd", "csrc"), "-o", str(exe), str(src)],
+                   check=True)
+    r = subprocess.run([str(exe)], capture_output=True, text=True)
+    assert r.returncode == 0 and r.stdout.startswith("ok"), r.stdout
