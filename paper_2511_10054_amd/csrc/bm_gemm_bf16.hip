@@ -446,6 +446,17 @@ __device__ __forceinline__ TailSplit tail_split(int total, int per_xcd, int xcd,
 }
 constexpr int SPLIT_TILE_FLOATS = 256 * 256;
 
+// table[idx] for a wave-uniform idx through the scalar cache.  Written out by hand because the compiler
+// uses scalar loads only for memory it can prove unwritten since the kernel began; behind the first
+// output store it reads such tables with vector loads, and waiting for one of those means waiting for
+// every direct-to-LDS load issued before it.  The tables are written by an earlier launch.
+__device__ __forceinline__ int scalar_load_i32(const int32_t *table, int idx) {
+    int v;
+    const int off = __builtin_amdgcn_readfirstlane(idx) * 4;
+    asm volatile("s_load_dword %0, %1, %2\n\ts_waitcnt lgkmcnt(0)" : "=s"(v) : "s"(table), "s"(off) : "memory");
+    return v;
+}
+
 // SPLIT: compile the reduction-split tail in (kept out of the other instantiations: its write-out of raw
 // accumulators costs registers that short tiles cannot afford to spill around)
 // MI: 16-row blocks per wave.  MI = 8 is the 256-row tile described above; MI = 4 is a 128-row tile on the
@@ -545,31 +556,66 @@ __device__ __forceinline__ void k64w_body(const GemmParams &p) {
     uint32_t oa[8], ob[8];
     const uint16_t *base_b0, *base_b1;
     int row0, row_end, n0;                             // of the tile whose loads are being issued
+    int g_n, row0_n, row_end_n, n0_n;                  // of the tile looked up last (BM_LOOKUP)
+                                                       // (the source rows of its activation loads: in v255)
+    bool n_more = false, n_partial = false;            // the item the loads move on to next, found a k-step
+    int n_kbeg = 0, n_kend = 0;                        // before they do
 
-// Pointers of logical tile lid_.  Load instruction j of this wave fills the 1 KB block (4*j + wave) of a
-// part: 8 tile rows of 128 bytes.  Lane i supplies row 8*block + i/8 and LDS slot i%8 of it, i.e.
-// global piece (i % 8) ^ ((row >> 1) & 7).
-#define BM_SETUP(lid_)                                                                             \
+// Load instruction j of a wave fills the 1 KB block (4*j + wave) of a part: 8 tile rows of 128 bytes.  Lane i
+// supplies row 8*block + i/8 and LDS slot i%8 of it, i.e. global piece (i % 8) ^ ((row >> 1) & 7).
+// Moving the loads on to another tile takes two steps, a k-step apart:
+// BM_LOOKUP(lid_): the tables of logical tile lid_ (scalar loads) and the source rows of the wave's
+//   activation loads: 64 tile rows per wave, one per lane (lane l: the row load l/8 fetches for lanes
+//   8 * (l%8) ..), ONE vector load of row_map.  Nothing the running loads use is touched.
+// BM_ADOPT(): the load addresses of the tile looked up last; every lane picks up its eight source rows
+//   from the lanes that loaded them (a lane permute; it moves data through the LDS crossbar and uses no
+//   LDS memory).
+// The row_map load is an assembly statement into a register the compiler does not manage (v255, named as
+// clobbered so that it is allocated to the kernel; the compiler's own values stay far below it), i.e. the
+// compiler neither waits for the result nor moves it.  Vector memory operations complete in issue order, so
+// a wait for this load is a wait for every direct-to-LDS load issued before it; left to the compiler,
+// look-up and use drained the load pipeline up to three times per tile (tile index -> group -> rows,
+// dependent round trips), and given a k-step of distance it copied the pending value out of the result
+// register at once and waited at the top of EVERY k-step.  By hand nothing waits at all: the look-up runs
+// at the end of k-step kend - 4, BM_ADOPT at the end of k-step kend - 3, whose own wait in the middle (at
+// most the 8 weight loads of its first half outstanding) has covered the row_map load.
+// The lane index goes through an empty assembly statement in both: otherwise the compiler keeps the sixteen
+// per-load row numbers of a lane alive across the whole tile loop, and spills them.
+#define BM_LOOKUP(lid_)                                                                            \
     {                                                                                              \
         int mt_, nt_;                                                                              \
         tile_of((lid_), n_mt, n_nt, mt_, nt_);                                                     \
-        const int g_ = mt_group[mt_];                                                              \
-        row0 = mt_row0[mt_];                                                                       \
-        row_end = p.offsets[g_ + 1];                                                               \
-        n0 = nt_ * (DUAL ? 128 : 256);                                                             \
-        if (g_ < p.E) {                                                                            \
-            base_b0 = static_cast<const uint16_t *>(p.b0) + (size_t)g_ * N * Kd;                   \
-            base_b1 = DUAL ? static_cast<const uint16_t *>(p.b1) + (size_t)g_ * N * Kd : base_b0;  \
+        g_n = scalar_load_i32(mt_group, mt_);                                                      \
+        row0_n = scalar_load_i32(mt_row0, mt_);                                                    \
+        row_end_n = scalar_load_i32(p.offsets, g_n + 1);                                           \
+        n0_n = __builtin_amdgcn_readfirstlane(nt_) * (DUAL ? 128 : 256);                           \
+        int lane_ = lane;                                                                          \
+        asm volatile("" : "+v"(lane_));                                                            \
+        const int r_ = 8 * (4 * (lane_ >> 3) + wave) + (lane_ & 7);                                \
+        const int pos_ = min(row0_n + r_, row_end_n - 1);                                          \
+        if (p.row_map)                                                                             \
+            asm volatile("global_load_dword v255, %0, %1" : : "v"(pos_ * 4), "s"(p.row_map) : "v255", "memory"); \
+        else                                                                                       \
+            asm volatile("v_mov_b32 v255, %0" : : "v"(pos_) : "v255");                             \
+    }
+#define BM_ADOPT()                                                                                 \
+    {                                                                                              \
+        row0 = row0_n; row_end = row_end_n; n0 = n0_n;                                             \
+        if (g_n < p.E) {                                                                           \
+            base_b0 = static_cast<const uint16_t *>(p.b0) + (size_t)g_n * N * Kd;                  \
+            base_b1 = DUAL ? static_cast<const uint16_t *>(p.b1) + (size_t)g_n * N * Kd : base_b0; \
         } else {                                                                                   \
-            base_b0 = static_cast<const uint16_t *>(p.sb0) + (size_t)(g_ - p.E) * N * Kd;          \
-            base_b1 = DUAL ? static_cast<const uint16_t *>(p.sb1) + (size_t)(g_ - p.E) * N * Kd : base_b0; \
+            base_b0 = static_cast<const uint16_t *>(p.sb0) + (size_t)(g_n - p.E) * N * Kd;         \
+            base_b1 = DUAL ? static_cast<const uint16_t *>(p.sb1) + (size_t)(g_n - p.E) * N * Kd : base_b0; \
         }                                                                                          \
+        int lane_ = lane, rmv_;                                                                    \
+        asm volatile("" : "+v"(lane_));                                                            \
+        asm volatile("v_mov_b32 %0, v255" : "=v"(rmv_));                                           \
         _Pragma("unroll") for (int j = 0; j < 8; ++j) {                                            \
-            const int r_ = 8 * (4 * j + wave) + (lane >> 3);                                       \
-            const int piece_ = (lane & 7) ^ ((r_ >> 1) & 7);                                       \
+            const int r_ = 8 * (4 * j + wave) + (lane_ >> 3);                                      \
+            const int piece_ = (lane_ & 7) ^ ((r_ >> 1) & 7);                                      \
             if (j < MI) {                                                                          \
-                const int pos_ = min(row0 + r_, row_end - 1);                                      \
-                const int src_ = p.row_map ? p.row_map[pos_] : pos_;                               \
+                const int src_ = __builtin_amdgcn_ds_bpermute(4 * (8 * j + (lane_ >> 3)), rmv_);   \
                 oa[j] = ((uint32_t)src_ * (uint32_t)Kd + piece_ * 8) * 2u;                         \
             }                                                                                      \
             /* DUAL: rows 0-127 of the part are W_gate rows (loads 0-3), rows 128-255 W_up rows (4-7) */ \
@@ -602,40 +648,45 @@ __device__ __forceinline__ void k64w_body(const GemmParams &p) {
         else if ((d_) <= 8) fb_[(d_) - 1] = BM_LD((sb_) + BM_BOFF((d_) - 1));                      \
         else fa_[(d_) - 8] = BM_LD((sa_) + ((d_) - 8) * 1024);                                     \
     }
-// For the down projection the MFMA is written as an assembly statement with the accumulator tied to an
-// AGPR tile as input and output: with the builtin the register allocator lets accumulator tiles change
-// registers across the loop and fills the loop with copies (measured 70 % slower).  The compiler's hazard
-// recogniser does not see inside the statement, so the two distances it would otherwise guarantee are put
-// in by hand, as s_nop statements that carry a data dependency on the accumulator concerned (an
-// instruction-scheduling fence in those places makes the register allocator spill about 200 registers):
+// The MFMA is written as an assembly statement with the accumulator tied to an AGPR tile as input and
+// output.  With the builtin the register allocator lets accumulator tiles change registers across the loop
+// (down projection: a loop full of copies, measured 70 % slower) and copies all 256 accumulator values to
+// vector registers where the loop ends (gate/up projection: up to 48 registers spilled around the
+// write-out, and every reload from scratch memory waits for all loads and stores in flight).  The
+// compiler's hazard recogniser does not see inside the statement, so the two distances it would otherwise
+// guarantee are put in by hand, as s_nop statements that carry a data dependency on the accumulator
+// concerned (an instruction-scheduling fence in those places makes the register allocator spill about 200
+// registers):
 //   - accumulator zeroing (VALU writes of the AGPRs) -> first MFMA, which reads acc[0][0] as its third
 //     operand: at most 2 wait states are required on this family; 8 are inserted behind the zeroing
 //     (a barrier and the first 16 fragment reads follow before that MFMA can issue anyway).  The zeroing of
 //     the other accumulators cannot move closer to their first MFMA than that because the k-steps of a tile
-//     form ONE loop and the zeroing stays in front of it.  Do not peel the first k-step off that loop in
-//     this instantiation: in straight-line code the compiler sinks each accumulator's zeroing to right in
-//     front of its first MFMA, which then reads the stale register (every 128-row tile came out wrong when
-//     this was tried; tying a wait to all 64 accumulators instead made the allocator spill 128 registers);
+//     form ONE loop and the zeroing stays in front of it.  Do not peel the first k-step off that loop: in
+//     straight-line code the compiler sinks each accumulator's zeroing to right in front of its first MFMA,
+//     which then reads the stale register (every 128-row tile came out wrong when this was tried; tying a
+//     wait to all 64 accumulators instead made the allocator spill 128 registers);
 //   - last MFMA of a tile (acc[MI - 1][7]) -> first read of an accumulator by another instruction (write-out,
 //     partial-tile store): an 8-pass MFMA result needs 11 wait states (18 for a 16-pass one); 32 are
 //     inserted where the write-out starts.  Every other accumulator's MFMA is at least 16 cycles older.
 // Inside the loop an accumulator is next touched by its own MFMA 63 instructions later (same register as
 // destination and third operand), which the MFMA pipeline interlocks by itself.
-// There the weight fragment is the first operand: the product comes out transposed, i.e. a lane holds four
-// consecutive output columns (4 * quad ...) of one output row (r16), which pack into 8 contiguous bytes
-// (down projection 3-9 % faster through the shorter write-out; the gate/up projection measured 1-3 %
+// Down projection: the weight fragment is the first operand, so the product comes out transposed, i.e. a
+// lane holds four consecutive output columns (4 * quad ...) of one output row (r16), which pack into 8
+// contiguous bytes (3-9 % faster through the shorter write-out; the gate/up projection measured 1-3 %
 // slower with that order and keeps activations first).
 #define BM_MFMA1(m_, fa_, fb_)                                                                     \
     {                                                                                              \
         if (DUAL)                                                                                  \
-            acc[(m_) >> 3][(m_) & 7] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(                    \
-                fa_[(m_) >> 3], fb_[(m_) & 7], acc[(m_) >> 3][(m_) & 7], 0, 0, 0);                 \
+            asm("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0"                                          \
+                : "+a"(acc[(m_) >> 3][(m_) & 7]) : "v"(fa_[(m_) >> 3]), "v"(fb_[(m_) & 7]));       \
         else                                                                                       \
             asm("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0"                                          \
                 : "+a"(acc[(m_) >> 3][(m_) & 7]) : "v"(fb_[(m_) & 7]), "v"(fa_[(m_) >> 3]));       \
     }
 
-    BM_SETUP(xcd * per_xcd + item_tile);
+    BM_LOOKUP(xcd * per_xcd + item_tile);
+    BM_WAIT_VM_LGKM(0, 0);                             // the row_map load, which the compiler does not wait for
+    BM_ADOPT();
     BM_PROLOGUE();
     // The ring runs on across tiles: during the last two k-steps of a tile the loads already fetch the
     // first two k-steps of the workgroup's next item (instead of repeats of the last k-step), so a new
@@ -667,14 +718,14 @@ __device__ __forceinline__ void k64w_body(const GemmParams &p) {
         //    flight when the next k-step starts (after the last k-step of a tile they are the next tile's and
         //    are read again at its start: no register stays live across the write-out).
         //  - three k-steps before the end the loads of this item are all issued: from here on they fetch the
-        //    next one.
+        //    next one, which was looked up a k-step earlier (BM_LOOKUP, BM_ADOPT).
 #define BM_TILE_LOOP(COMPUTE_)                                                                                        \
     {                                                                                                                 \
         if (COMPUTE_) {                                                                                               \
             _Pragma("unroll") for (int i = 0; i < MI; ++i)                                                            \
                 _Pragma("unroll") for (int j = 0; j < 8; ++j)                                                         \
                     _Pragma("unroll") for (int v = 0; v < 4; ++v) acc[i][j][v] = 0.0f;                                \
-            if (!DUAL) asm volatile("s_nop 7" : "+a"(acc[0][0]));  /* acc[0][0]: the first MFMA's accumulator */       \
+            asm volatile("s_nop 7" : "+a"(acc[0][0]));  /* acc[0][0]: the first MFMA's accumulator */       \
         }                                                                                                             \
         BM_BARE_BARRIER();                                                                                            \
         {                                                                                                             \
@@ -685,6 +736,10 @@ __device__ __forceinline__ void k64w_body(const GemmParams &p) {
         }                                                                                                             \
         for (int kt = t_kbeg; kt < t_kend; ++kt) {                                                                    \
             const int kl = more ? kbeg + (kt + 2 - t_kend) : kt + 2;                                                  \
+            /* no LDS read is pending here (the last ones were issued half a k-step ago); said explicitly,  */        \
+            /* because the compiler otherwise puts its own wait for the loop-carried fragments behind this */        \
+            /* k-step's first read and the first MFMA stalls for an LDS round trip */                                 \
+            BM_WAIT_VM_LGKM(63, 0);                                                                                   \
             {                                                                                                         \
                 const uint16_t *sa_ = smem + sA * P_PART + fa_off[1];                                                 \
                 const uint16_t *sb_ = smem + sB * P_PART + fb_off[1];                                                 \
@@ -714,8 +769,18 @@ __device__ __forceinline__ void k64w_body(const GemmParams &p) {
             sB = sBn;                                                                                                 \
             sA = sAn;                                                                                                 \
             if (kt == t_kend - 3) {                                                                                   \
-                BM_NEXT_ITEM(more);                                                                                   \
-                if (more) BM_SETUP(xcd * per_xcd + item_tile);                                                        \
+                more = n_more;                                                                                        \
+                if (more) {                                                                                           \
+                    kbeg = n_kbeg; kend = n_kend; partial = n_partial;                                                \
+                    BM_ADOPT();                                                                                       \
+                }                                                                                                     \
+            } else if (kt == t_kend - 4) {    /* every item has at least 4 k-steps */                                  \
+                const int kb_ = kbeg, ke_ = kend;                                                                     \
+                const bool pa_ = partial;                                                                             \
+                BM_NEXT_ITEM(n_more);                                                                                 \
+                n_kbeg = kbeg; n_kend = kend; n_partial = partial;                                                    \
+                kbeg = kb_; kend = ke_; partial = pa_;                                                                \
+                if (n_more) BM_LOOKUP(xcd * per_xcd + item_tile);                                                     \
             }                                                                                                         \
         }                                                                                                             \
     }
@@ -738,7 +803,7 @@ __device__ __forceinline__ void k64w_body(const GemmParams &p) {
         }
         // last MFMA of the tile -> first read of an accumulator (see BM_MFMA1): acc[MI - 1][7] is the last MFMA's
         // accumulator, every other one is at least one MFMA (16 cycles) older
-        if (!DUAL) asm volatile("s_nop 15\n\ts_nop 15" : "+a"(acc[MI - 1][7]));
+        asm volatile("s_nop 15\n\ts_nop 15" : "+a"(acc[MI - 1][7]));
         if (SPLIT && t_partial) {
             // chunk of a split tile: the fp32 accumulators go to this workgroup's scratch tile as they are
             // (accumulator tile, lane: 16-byte stores, contiguous over the lanes)
@@ -768,15 +833,27 @@ __device__ __forceinline__ void k64w_body(const GemmParams &p) {
             constexpr int SD = 36;                      // LDS row stride in dwords (padded against conflicts)
             constexpr int PR = OC * 2;                  // 16-byte pieces per output row
             uint32_t *stage = reinterpret_cast<uint32_t *>(smem + sAp * P_PART) + wave * 2048;
-            const bool odd = lane & 1;
+            // The accumulators are read one pair of values at a time, by hand and behind scheduling fences:
+            // left to itself the compiler copies all 256 of them to vector registers where the loop ends
+            // and spills what does not fit, and every reload waits for all stores issued so far.  The lane
+            // index is hidden from it for the same reason (its derived constants stayed live across tiles).
+            int lane_w = lane;
+            asm volatile("" : "+v"(lane_w));
+            const int r16 = lane_w & 15, quad = lane_w >> 4;
+            const bool odd = lane_w & 1;
 #pragma unroll
             for (int i = 0; i < MI; ++i) {
 #pragma unroll
                 for (int j = 0; j < OC; ++j) {
 #pragma unroll
                     for (int v = 0; v < 4; v += 2) {
-                        const float x0 = silu(acc[i][j][v]) * acc[i][4 + j][v];
-                        const float x1 = silu(acc[i][j][v + 1]) * acc[i][4 + j][v + 1];
+                        float g0, g1, u0, u1;
+                        asm volatile("v_accvgpr_read_b32 %0, %1" : "=v"(g0) : "a"(acc[i][j][v]));
+                        asm volatile("v_accvgpr_read_b32 %0, %1" : "=v"(g1) : "a"(acc[i][j][v + 1]));
+                        asm volatile("v_accvgpr_read_b32 %0, %1" : "=v"(u0) : "a"(acc[i][4 + j][v]));
+                        asm volatile("v_accvgpr_read_b32 %0, %1" : "=v"(u1) : "a"(acc[i][4 + j][v + 1]));
+                        const float x0 = silu(g0) * u0;
+                        const float x1 = silu(g1) * u1;
                         // even lane keeps row v and gets the right-hand neighbour's value of that row;
                         // odd lane keeps row v+1 and gets the left-hand neighbour's
                         const float send = odd ? x0 : x1;
@@ -786,16 +863,18 @@ __device__ __forceinline__ void k64w_body(const GemmParams &p) {
                         const int lrow = 4 * quad + v + (odd ? 1 : 0);
                         stage[lrow * SD + j * 8 + (r16 >> 1)] = pk;
                     }
+                    __builtin_amdgcn_sched_barrier(0);
                 }
 #pragma unroll
                 for (int t = 0; t < PR / 4; ++t) {
-                    const int q = lane + 64 * t;
+                    const int q = lane_w + 64 * t;
                     const int lrow = q / PR, pc = q % PR;
                     const u32x4 val = *reinterpret_cast<const u32x4 *>(stage + lrow * SD + pc * 4);
                     const int row = t_row0 + wm * (MI * 16) + i * 16 + lrow;
                     const int col = t_n0 + wn * (OC * 16) + pc * 8;
                     if (row < t_row_end && col < N) stg128(&c[(size_t)row * N + col], val);
                 }
+                __builtin_amdgcn_sched_barrier(0);
             }
         } else {
             // Down projection (weights as the first MFMA operand): an accumulator tile holds, per lane, four
@@ -833,7 +912,8 @@ __device__ __forceinline__ void k64w_body(const GemmParams &p) {
     // the last tile's loads ran past its end (repeats of its last k-step): nothing may still be landing in
     // LDS when the workgroup ends
     BM_WAIT_VM_LGKM(0, 0);
-#undef BM_SETUP
+#undef BM_LOOKUP
+#undef BM_ADOPT
 #undef BM_NEXT_ITEM
 #undef BM_PROLOGUE
 #undef BM_DMA_AT

@@ -243,3 +243,31 @@ int main() {
                    check=True)
     r = subprocess.run([str(exe)], capture_output=True, text=True)
     assert r.returncode == 0 and r.stdout.startswith("ok"), r.stdout
+
+
+def test_prefill_kernels_keep_the_hand_managed_register_to_themselves(tmp_path):
+    """The persistent prefill kernels park the pending result of one vector load in v255, a register the
+    compiler does not manage (csrc/bm_gemm_bf16.hip, BM_LOOKUP / BM_ADOPT): the compiler's own values must
+    stay below it, and it may appear in the hand-written statements only.  The same kernels must not spill:
+    a reload from scratch memory waits for every load and store in flight.  Checked on the assembly the
+    build's compiler emits for the build's flags (own code, device side only)."""
+    import re
+    import subprocess
+    from paper_2511_10054_amd import build
+    out = tmp_path / "gemm.s"
+    flags = [f for f in build.FLAGS if f != "-fPIC"]
+    subprocess.run([build.HIPCC, *flags, "-S", "--cuda-device-only", "-o", str(out),
+                    os.path.join(build.CSRC, "bm_gemm_bf16.hip")], check=True, capture_output=True)
+    text = out.read_text()
+    kernels = re.findall(r"^(_ZN2bm\w*k64w\w*):[^\n]*\n(.*?)\.end_amdhsa_kernel", text, flags=re.S | re.M)
+    assert len(kernels) >= 3, [k for k, _ in kernels]
+    allowed = (r"global_load_dword v255, v\d+, s\[\d+:\d+\]", r"v_mov_b32 v255, v\d+", r"v_mov_b32 v\d+, v255")
+    for name, body in kernels:
+        assert "scratch_" not in body, name + " spills vector registers"
+        assert "global_load_dword v255" in body and "v255" in body, name
+        for line in body.split("\n"):
+            code = line.split(";")[0].strip()
+            if re.search(r"\bv255\b|v\[\d+:255\]", code):
+                assert any(re.fullmatch(a, code) for a in allowed), (name, code)
+        used = [int(m) for m in re.findall(r"\bv(\d+)\b", body)] + [int(m) for m in re.findall(r"\bv\[\d+:(\d+)\]", body)]
+        assert max(u for u in used if u != 255) < 240, name
