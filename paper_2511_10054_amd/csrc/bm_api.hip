@@ -598,6 +598,7 @@ int bm_moe_forward(const bm_layer_desc *desc, const void *x, const bm_weights *w
     dp.N = desc->d; dp.Kd = desc->F;
     dp.splitk = L.has_splitk ? at<float>(ws, L.splitk) : nullptr;
     int ksplit = 1;
+    bool combined = false;                              // the down projection has written y itself
     if (skinny) {
         ksplit = skinny_ksplit(desc);
         SkinnyParams s1{};
@@ -620,6 +621,12 @@ int bm_moe_forward(const bm_layer_desc *desc, const void *x, const bm_weights *w
         s2.pk = pk_dn ? wt->wp_down : nullptr; s2.spk = pk_dn ? wt->wsp_down : nullptr;
         s2.c = dp.c; s2.N = desc->d; s2.Kd = desc->F; s2.ksplit = ksplit;
         s2.wide = (T > 64 && (long long)T * K >= 16ll * E) ? 1 : 0;
+        // small batches on a matrix as many 16-row blocks wide as the device has units: the down kernel
+        // aggregates its own results (null y: it writes them out for launch_combine below)
+        s2.y = y; s2.w = fp.w; s2.inv_perm = cp.inv_perm; s2.T = T; s2.K = K; s2.n_shared = desc->n_shared;
+        s2.y_f32 = (desc->flags & BM_Y_F32) ? 1 : 0;
+        combined = skinny_down_fuses_combine(s2);
+        if (!combined) s2.y = nullptr;
         err |= launch_skinny_gateup_bf16(s1, st);
         mark(2);
         err |= launch_skinny_down_bf16(s2, st);
@@ -640,7 +647,7 @@ int bm_moe_forward(const bm_layer_desc *desc, const void *x, const bm_weights *w
     mp.ksplit = ksplit; mp.slice_stride = (size_t)L.rows_max * desc->d;
     mp.o = dp.c; mp.w = fp.w; mp.inv_perm = cp.inv_perm; mp.offsets = sp.offsets;
     mp.y = y; mp.y_f32 = (!bf16 || (desc->flags & BM_Y_F32)) ? 1 : 0;
-    err |= launch_combine(mp, bf16 && !skinny, st);
+    if (!combined) err |= launch_combine(mp, bf16 && !skinny, st);
     mark(4);
 
     if (dbg) {

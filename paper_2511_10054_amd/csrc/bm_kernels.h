@@ -108,6 +108,11 @@ struct SkinnyParams {
     int max_rows_per_group;       // launch-time bound: T*K routed rows (or T for a shared expert)
     int wide;                     // groups of more than 64 rows are expected (more than 64 tokens): 128 rows per pass
     const int32_t *mt_group, *n_mtiles, *offsets;
+    // down projection of the persistent kernel with the aggregation fused in (skinny_down_fuses_combine):
+    void *y;                      // [T][N] layer output, or null: write c and leave the aggregation to launch_combine
+    const float *w;               // [T][K] gate weights
+    const int32_t *inv_perm;      // [T*K]
+    int T, K, n_shared, y_f32;
 };
 
 struct CombineParams {
@@ -151,6 +156,8 @@ bool skinny_lds_ok(int Kd, int ksplit); // shape fits the LDS-staged decode kern
 bool skinny_q_ok(int Kd, int ksplit);   // shape fits the quarter-split decode kernel
 int launch_skinny_gateup_bf16(const SkinnyParams &p, hipStream_t st);
 int launch_skinny_down_bf16(const SkinnyParams &p, hipStream_t st);
+// launch_skinny_down_bf16(p) with p.y set will write the layer output itself (no launch_combine needed)
+bool skinny_down_fuses_combine(const SkinnyParams &p);
 
 int launch_combine(const CombineParams &p, bool o_bf16, hipStream_t st);
 int launch_stream_read(const void *src, size_t bytes, uint32_t *sink, hipStream_t st);

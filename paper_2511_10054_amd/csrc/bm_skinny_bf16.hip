@@ -564,8 +564,19 @@ __device__ __forceinline__ PItem p_setup(const SkinnyParams &p, int it, int NRB,
     return r;
 }
 
-template <bool DUAL, int NBT, int CH, bool PACKED>
+// COMBINE (down projection only; the grid is as wide as the matrix has 16-row blocks, or divides that
+// number): the stride of the item walk is then a multiple of the blocks per group, so a workgroup meets the
+// same 16-row blocks - 16 columns of the layer output each - in every live group.  It keeps its finished
+// 16-column slices of every row in LDS instead of writing them out, and once through adds them up per token
+// the way combine_kernel does (slot order, then the shared experts: the same operations in the same order,
+// so the same bits) and writes the layer output: no launch, and no round trip through memory, for the
+// aggregation.
+constexpr int P_COMB_ROWS = 160;                       // rows (assignments + shared-expert rows) the fused form holds
+constexpr int P_COMB_BLOCKS = 2;                       // 16-row blocks per workgroup it holds
+
+template <bool DUAL, int NBT, int CH, bool PACKED, bool COMBINE = false>
 __global__ void __launch_bounds__(512) skinny_p_kernel(SkinnyParams p) {
+    static_assert(!COMBINE || !DUAL, "the aggregation follows the down projection");
     constexpr int NM = DUAL ? 2 : 1;
     constexpr int KSTEP = PACKED ? 512 * NM : 32;              // weight elements between consecutive k-steps
     constexpr int RED = 2 * 8 * NBT * NM * 64;                 // f32x4 entries of the reduction area
@@ -589,7 +600,30 @@ __global__ void __launch_bounds__(512) skinny_p_kernel(SkinnyParams p) {
 #define BM_PW(wp_, u_) (PACKED ? (wp_) + (u_) * KSTEP : (wp_) + lofs[(u_) & 1] + ((u_) >> 1) * 64)
     const int NRB = p.N >> 4;
     const int n_items = p.n_mtiles[0] * NRB;
-    if ((int)blockIdx.x >= n_items) return;
+    __shared__ float comb[COMBINE ? P_COMB_BLOCKS * P_COMB_ROWS * 16 : 1];   // [block][row][16 columns]
+// the layer output for this workgroup's 16-column blocks from the slices in comb (see combine_kernel)
+#define BM_COMBINE_OUT(HAVE_)                                                                           \
+    {                                                                                                   \
+        const int nbl_ = NRB / (int)gridDim.x;                                                          \
+        for (int idx = threadIdx.x; idx < nbl_ * p.T * 16; idx += blockDim.x) {                         \
+            const int col = idx & 15, t = (idx >> 4) % p.T, bl = (idx >> 4) / p.T;                      \
+            float acc = 0.0f;                                                                           \
+            for (int k = 0; (HAVE_) && k < p.K + p.n_shared; ++k) {                                     \
+                const int pos = k < p.K ? p.inv_perm[(size_t)t * p.K + k] : p.offsets[p.E + (k - p.K)] + t; \
+                if (pos < 0) continue;                                                                  \
+                const float wk = k < p.K ? p.w[(size_t)t * p.K + k] : 1.0f;                             \
+                const float o = 0.0f + comb[(bl * P_COMB_ROWS + pos) * 16 + col];                       \
+                acc = fmaf(wk, o, acc);                                                                 \
+            }                                                                                           \
+            const size_t at = (size_t)t * p.N + ((size_t)blockIdx.x + (size_t)bl * gridDim.x) * 16 + col; \
+            if (p.y_f32) static_cast<float *>(p.y)[at] = acc;                                           \
+            else stg16(static_cast<uint16_t *>(p.y) + at, f32_to_bf16(acc));                            \
+        }                                                                                               \
+    }
+    if ((int)blockIdx.x >= n_items) {
+        if (COMBINE) BM_COMBINE_OUT(false)             // no live group at all: the output is zero
+        return;
+    }
     const int my_items = (n_items - 1 - (int)blockIdx.x) / (int)gridDim.x + 1;
     const int kq = p.Kd >> 3;
     const int k0 = wave * kq;
@@ -669,6 +703,9 @@ __global__ void __launch_bounds__(512) skinny_p_kernel(SkinnyParams p) {
                     u16x4 h;                                                                            \
                     _Pragma("unroll") for (int i = 0; i < 4; ++i) h[i] = f32_to_bf16(silu(t0[i]) * t1[i]); \
                     *(BM_GLOBAL u16x4 *)(static_cast<uint16_t *>(p.c) + (size_t)pos * p.N + n) = h;     \
+                } else if (COMBINE) {                                                                   \
+                    const int bl_ = (cur.n0 >> 4) / (int)gridDim.x;                                     \
+                    *reinterpret_cast<f32x4 *>(&comb[(bl_ * P_COMB_ROWS + pos) * 16 + (ln >> 4) * 4]) = t0; \
                 } else {                                                                                \
                     *(BM_GLOBAL f32x4 *)(static_cast<float *>(p.c) + (size_t)pos * p.N + n) = t0;       \
                 }                                                                                       \
@@ -733,6 +770,11 @@ __global__ void __launch_bounds__(512) skinny_p_kernel(SkinnyParams p) {
 #pragma unroll
     for (int u = 0; u < CH; ++u) { BM_CONSUME(u); }
     BM_FINALIZE();
+    if (COMBINE) {
+        __syncthreads();
+        BM_COMBINE_OUT(true)
+    }
+#undef BM_COMBINE_OUT
 #undef BM_CONSUME
 #undef BM_FINALIZE
 #undef BM_PW
@@ -740,19 +782,36 @@ __global__ void __launch_bounds__(512) skinny_p_kernel(SkinnyParams p) {
 
 bool skinny_p_ok(int Kd, int ch) { return ch % 2 == 0 && Kd % (8 * 32 * ch) == 0; }
 
+static int device_cus() {
+    int dev = 0, cus = 0;
+    if (hipGetDevice(&dev) != hipSuccess ||
+        hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0)
+        return 0;
+    return cus;
+}
+
+// the persistent kernel takes the down projection of this call and can hold every row's slices (see COMBINE)
+bool skinny_down_fuses_combine(const SkinnyParams &p) {
+    const int cus = device_cus();
+    return p.y != nullptr && p.ksplit == 1 && p.max_rows_per_group <= 32 && (skinny_p_ok(p.Kd, 14) || skinny_p_ok(p.Kd, 8)) &&
+           cus > 0 && (p.N / 16) % cus == 0 && (p.N / 16) / cus <= P_COMB_BLOCKS && p.rows_max <= P_COMB_ROWS && p.T > 0;
+}
+
 // launches the persistent kernel if a ring depth fits the shape; false otherwise
 template <bool DUAL>
 static bool launch_skinny_p(const SkinnyParams &p, hipStream_t st) {
     if (p.max_rows_per_group > 32) return false;
-    int dev = 0, cus = 0;
-    if (hipGetDevice(&dev) != hipSuccess ||
-        hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0)
-        return false;
+    const int cus = device_cus();
+    if (cus <= 0) return false;
     const dim3 grid(cus), block(512);
     const bool one = p.max_rows_per_group <= 16;
+    const bool comb = !DUAL && skinny_down_fuses_combine(p);
 #define BM_LAUNCH_P(D_, NBT_, CH_)                                                                         \
     {                                                                                                      \
-        if (p.pk != nullptr) hipLaunchKernelGGL((skinny_p_kernel<D_, NBT_, CH_, true>), grid, block, 0, st, p); \
+        if (!D_ && comb) {                                                                                 \
+            if (p.pk != nullptr) hipLaunchKernelGGL((skinny_p_kernel<false, NBT_, CH_, true, true>), grid, block, 0, st, p); \
+            else hipLaunchKernelGGL((skinny_p_kernel<false, NBT_, CH_, false, true>), grid, block, 0, st, p); \
+        } else if (p.pk != nullptr) hipLaunchKernelGGL((skinny_p_kernel<D_, NBT_, CH_, true>), grid, block, 0, st, p); \
         else hipLaunchKernelGGL((skinny_p_kernel<D_, NBT_, CH_, false>), grid, block, 0, st, p);           \
     }
     if (DUAL) {

@@ -93,6 +93,29 @@ def test_c2_mixtral_between_decode_and_prefill(T):
     _check("c2_mixtral_decode", T, 64)
 
 
+def test_c2_small_batches_aggregated_by_the_down_kernel():
+    """Up to 16 tokens on this layer (hidden size = 16 x the device's 256 units) the persistent down kernel
+    adds up its own results and writes the layer output; checked here on the fp32 output as well, on a batch
+    size that is no multiple of anything, and with nothing resident (no live group: the output is zero)."""
+    spec = workloads.CONFIGS["c2_mixtral_decode"]
+    base_host, base_dev = _layers("c2_mixtral_decode", pack=False)
+    for T in (3, 16):
+        print(f"fullsize c2 T={T} fp32 output", flush=True)
+        host = HostLayer(spec, T, base=base_host)
+        out = DeviceLayer(host, y_f32=True, base=base_dev).forward()
+        ref = host.oracle_forward(oracle, rows=np.arange(T))
+        np.testing.assert_array_equal(out["ids_remapped"], ref["ids_remapped"])
+        err = err_metric(out["y"], ref["y"])
+        print(f"   err {err:.3e}", flush=True)
+        assert err <= 2e-2, err
+    print("fullsize c2 T=5 nothing resident", flush=True)
+    host = HostLayer(spec, 5, mask=np.zeros(spec.E, bool), base=base_host)
+    dev = DeviceLayer(host, base=base_dev)
+    dev.y.fill_(7.0)
+    out = dev.forward()
+    assert (out["ids_remapped"] == -1).all() and (out["y"] == 0).all()
+
+
 def test_c2_mixtral_decode_unique():
     _check("c2_mixtral_decode", 64, 64, unique=True)
 
