@@ -169,12 +169,14 @@ LAYER_CASES = [
     ("c4_qwen3", dict(d=256, F=384), 300),
     ("c5_deepseek", dict(d=256, F=352), 500),
     # 256-row tiles at short reductions: below four k-steps of 64 the fallback kernel runs, four and five are
-    # the persistent kernel's shortest tiles (its loads move on to the next tile three k-steps before the end);
-    # and with shared experts
+    # the persistent kernel's shortest tiles (it looks the next tile up four k-steps before a tile's end, i.e.
+    # at the first k-step of a four-step tile, and its loads move on three k-steps before the end); and with
+    # shared experts
     ("c3_mixtral_prefill", dict(d=64, F=256), 600),
     ("c3_mixtral_prefill", dict(d=128, F=64), 520),
     ("c3_mixtral_prefill", dict(d=256, F=320), 600),
     ("c5_deepseek", dict(d=256, F=384, E=16, n_resident=6), 700),
+    ("c5_deepseek", dict(d=256, F=256, E=16, n_resident=6), 900),     # four k-steps in both projections
     # long reduction of the down projection (the reduction-split tail itself needs more than 256 tiles: it is
     # covered by the full-size Mixtral prefill test)
     ("c3_mixtral_prefill", dict(d=256, F=4096), 2300),
