@@ -271,3 +271,17 @@ def test_prefill_kernels_keep_the_hand_managed_register_to_themselves(tmp_path):
                 assert any(re.fullmatch(a, code) for a in allowed), (name, code)
         used = [int(m) for m in re.findall(r"\bv(\d+)\b", body)] + [int(m) for m in re.findall(r"\bv\[\d+:(\d+)\]", body)]
         assert max(u for u in used if u != 255) < 240, name
+        # every MFMA sits in the k-step loop (depth 2 inside the tile loop): were the first k-step ever peeled
+        # into straight-line code, the compiler would sink the accumulator zeroing to right in front of the
+        # hand-written MFMA statements, inside their wait-state window
+        depth, n_mfma = 0, 0
+        for line in body.split("\n"):
+            if re.match(r"^(\.LBB\S+:|; %bb\.\d+:)", line):          # a block: "... in Loop: Header=BBn_m Depth=N"
+                m = re.search(r"in Loop: Header=\S+ Depth=(\d+)", line)
+                depth = int(m.group(1)) if m else 0
+            elif re.match(r"^\s*;.*Loop Header: Depth=(\d+)", line):   # ... or a loop header, its depth on the next line
+                depth = int(re.search(r"Loop Header: Depth=(\d+)", line).group(1))
+            elif "v_mfma" in line:
+                n_mfma += 1
+                assert depth >= 2, (name, "MFMA outside the k-step loop")
+        assert n_mfma >= 128, name
