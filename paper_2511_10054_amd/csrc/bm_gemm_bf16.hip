@@ -453,7 +453,8 @@ constexpr int SPLIT_TILE_FLOATS = 256 * 256;
 __device__ __forceinline__ int scalar_load_i32(const int32_t *table, int idx) {
     int v;
     const int off = __builtin_amdgcn_readfirstlane(idx) * 4;
-    asm volatile("s_load_dword %0, %1, %2\n\ts_waitcnt lgkmcnt(0)" : "=s"(v) : "s"(table), "s"(off) : "memory");
+    // (early clobber: the result register is none of the address registers, as a replayed load would need)
+    asm volatile("s_load_dword %0, %1, %2\n\ts_waitcnt lgkmcnt(0)" : "=&s"(v) : "s"(table), "s"(off) : "memory");
     return v;
 }
 

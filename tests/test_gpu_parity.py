@@ -265,6 +265,9 @@ DECODE_CASES = [
     ("c4_qwen3", dict(d=512, F=768), 40),                 # reduction of three chunks in the down projection, unsplit
     ("c5_deepseek", dict(d=2048, F=1792, E=16, n_resident=4), 4),    # shared experts on the decode path
     ("c4_qwen3", dict(d=256, F=96), 12),                  # odd widths: generic decode kernel
+    # hidden size 16 x 256 units: the persistent down kernel aggregates its own results, here with shared
+    # experts (their rows follow the routed ones) and with slots dropped
+    ("c5_deepseek", dict(d=4096, F=512, E=16, n_resident=4), 5),
 ]
 
 
